@@ -1,0 +1,38 @@
+"""CPU oracle for the data-parallel hot path of Synkhronos (arXiv 1710.04162).
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product path may import this package:
+only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg use it.
+It shares no code with the HIP library and never imports it.
+
+Everything here is plain NumPy in float64 (or exact integer work), written as
+the definition of what each step of the path computes:
+
+  split       Sec. 3.2 "Function Calling" step 1 (inputs scattered equally, as
+              possible, over workers) and Sec. 5.1 (a worker's share is cut
+              into slices the same way); Sec. 4.1 (first tensor dimension =
+              independent data points).
+  gather      Sec. 5.2 (a list of row indexes selects the minibatch; each
+              worker excerpts its own contiguous share of the list).
+  mlp         the "function" of Sec. 2 / Sec. 3.3 step 1: loss and gradient of
+              a ReLU MLP with softmax cross-entropy on a set of rows, the
+              sliced/aggregated evaluation of Sec. 5.1 and the worker reduce of
+              Sec. 3.2 step 3.
+  reduce      Sec. 3.1 "Build Functions" (a reduce/gather op per output),
+              Sec. 3.3 step 2 (all-reduce of the flat gradient).
+  update      Sec. 3.3 step 3 (momentum update applied with the combined
+              gradient on the flat parameter array).
+  evalops     a six-output evaluation function, each output with its own
+              reduce op, aggregated over slices (Sec. 3.1, Sec. 5.1).
+  brute       pure-Python-loop twins used only to pin the NumPy code at tiny
+              sizes.
+
+Pins (tests/test_oracle_*.py): finite differences, closed forms, brute-force
+loops, library routines (np.array_split, np.take, scipy logsumexp,
+torch.optim.SGD on CPU, torch.bfloat16 casts) and the paper's defining
+invariant (Sec. 1.1): aggregating independent calls over any subdivision of
+the data equals the one full-batch call.
+
+Parity unpinned: mlp.function(..., bf16_points=True) beyond (a) its rounding
+primitive, pinned against torch.bfloat16, and (b) staying close to the float64
+result (loss within 2e-2, gradient within 1e-1 in the Frobenius norm).
+"""

@@ -1,0 +1,355 @@
+"""Pins of the CPU oracle to things other than itself: library routines,
+closed forms, finite differences, brute-force loops, autograd on CPU, exact
+rational arithmetic and the paper's defining invariant (Sec. 1.1: reducing the
+results of independent calls over arbitrary subdivisions of the data gives the
+result of the one call)."""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import brute, evalops, gather, mlp, reduce as oreduce, split, update
+
+
+# ----------------------------------------------------------------- split
+@pytest.mark.parametrize("count,parts", [(0, 3), (1, 4), (7, 3), (256, 2), (1024, 8), (13, 13), (5, 8), (100, 7)])
+def test_split_matches_array_split(count, parts):
+    ref = [len(a) for a in np.array_split(np.arange(count), parts)]
+    assert split.share_sizes(count, parts) == ref
+    b = split.share_bounds(count, parts)
+    assert b[0][0] == 0 and b[-1][1] == count
+    assert all(b[i][1] == b[i + 1][0] for i in range(parts - 1))
+
+
+def test_worker_slice_bounds_tile_the_range():
+    for count, n, s in [(256, 2, 4), (10, 3, 4), (3, 4, 2), (1000, 7, 5)]:
+        flat = [ab for w in split.worker_slice_bounds(count, n, s) for ab in w]
+        assert flat[0][0] == 0 and flat[-1][1] == count
+        assert all(flat[i][1] == flat[i + 1][0] for i in range(len(flat) - 1))
+        ref = [len(x) for part in np.array_split(np.arange(count), n) for x in np.array_split(part, s)]
+        assert [b - a for a, b in flat] == ref
+
+
+# ---------------------------------------------------------------- gather
+def test_gather_matches_take_and_identity():
+    rng = np.random.default_rng(0)
+    data = rng.standard_normal((50, 7)).astype(np.float32)
+    idx = rng.integers(0, 50, 33)
+    assert np.array_equal(gather.gather_rows(data, idx), np.take(data, idx, axis=0))
+    assert np.array_equal(gather.gather_rows(data, np.arange(50)), data)
+    shares = gather.gather_shares(data, idx, 4)
+    assert np.array_equal(np.concatenate(shares), np.take(data, idx, axis=0))
+    assert [len(s) for s in shares] == [9, 8, 8, 8]
+    with pytest.raises(IndexError):
+        gather.gather_rows(data, np.array([50]))
+    with pytest.raises(IndexError):
+        gather.gather_rows(data, np.array([-1]))
+
+
+def test_normalise_u8_exact_rational():
+    mean = np.array([0.485 * 255, 0.456 * 255, 103.53], dtype=np.float32)
+    std = np.array([0.229 * 255, 57.12, 0.225 * 255], dtype=np.float32)
+    x = np.arange(256, dtype=np.uint8).reshape(1, 1, 256).repeat(3, axis=1)  # [1,3,256]
+    got = gather.normalise_u8(x, mean, std)
+    assert got.dtype == np.float32
+    for c in range(3):
+        for val in range(256):
+            exact = (Fraction(val) - Fraction(float(mean[c]))) / Fraction(float(std[c]))
+            assert got[0, c, val] == np.float32(float(exact))
+    # special cases with obvious answers
+    one = gather.normalise_u8(x, np.zeros(3, np.float32), np.ones(3, np.float32))
+    assert np.array_equal(one[0, 0], np.arange(256, dtype=np.float32))
+    pm = gather.normalise_u8(x, np.full(3, 127.5, np.float32), np.full(3, 127.5, np.float32))
+    assert pm[0, 1, 0] == -1.0 and pm[0, 1, 255] == 1.0
+
+
+def test_bf16_rounding_matches_torch_cast():
+    rng = np.random.default_rng(1)
+    a = np.concatenate([
+        rng.standard_normal(20000).astype(np.float32) * np.float32(3.0),
+        (rng.standard_normal(2000).astype(np.float32) * np.float32(1e-20)),
+        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 1.0078125, 3.3895314e38, 1e-40], np.float32),
+        # exact ties: 1 + k/256 for odd k sit half-way between bf16 neighbours
+        (1.0 + np.arange(1, 64, 2) / 256.0).astype(np.float32),
+    ])
+    ref = torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
+    got = gather.round_to_bf16(a)
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+# ------------------------------------------------------------------- mlp
+def _tiny(dims, rows, seed):
+    rng = np.random.default_rng(seed)
+    P = mlp.param_count(dims)
+    theta = rng.standard_normal(P) * 0.5
+    X = rng.standard_normal((rows, dims[0]))
+    y = rng.integers(0, dims[-1], rows)
+    return theta, X, y
+
+
+def test_hand_worked_example():
+    # x=[1,2]; W1=[[1,-1],[.5,1]] -> z1=[2,1]; W2=I -> logits [2,1]; y=0
+    dims = [2, 2, 2]
+    theta = np.array([1, -1, .5, 1, 0, 0, 1, 0, 0, 1, 0, 0], dtype=np.float64)
+    loss, g = mlp.function(theta, dims, np.array([[1.0, 2.0]]), np.array([0]))
+    s = 1.0 / (1.0 + math.e)                      # softmax prob of class 1
+    assert loss == pytest.approx(math.log1p(math.exp(-1.0)), abs=1e-15)
+    exp = [-s, s, -2 * s, 2 * s, -s, s,           # dW1 = x^T dz1, db1
+           -2 * s, 2 * s, -s, s, -s, s]           # dW2 = h^T dz2, db2
+    assert np.allclose(g, exp, atol=1e-15)
+
+
+def test_uniform_logits_give_ln_C():
+    dims = [5, 4, 10]
+    theta, X, y = _tiny(dims, 9, 2)
+    (W1, b1), (W2, b2) = mlp.unpack(theta, dims)
+    W2[...] = 0.0
+    b2[...] = 0.25           # any constant row of logits
+    loss, g = mlp.function(theta, dims, X, y)
+    assert loss == pytest.approx(math.log(10.0), abs=1e-14)
+
+
+def test_last_bias_gradient_sums_to_zero():
+    dims = [6, 5, 4, 3]
+    theta, X, y = _tiny(dims, 11, 3)
+    _, g = mlp.function(theta, dims, X, y)
+    gb_last = mlp.unpack(g, dims)[-1][1]
+    assert abs(gb_last.sum()) < 1e-15
+
+
+@pytest.mark.parametrize("dims", [[4, 3, 2], [5, 4, 3, 6], [3, 7]])
+def test_gradient_finite_differences(dims):
+    theta, X, y = _tiny(dims, 6, 4)
+    _, g = mlp.function(theta, dims, X, y)
+    h = 1e-5
+    for k in range(theta.size):
+        tp = theta.copy(); tp[k] += h
+        tm = theta.copy(); tm[k] -= h
+        fd = (mlp.function(tp, dims, X, y)[0] - mlp.function(tm, dims, X, y)[0]) / (2 * h)
+        assert abs(fd - g[k]) < 1e-6 * max(1.0, abs(g[k])), (k, fd, g[k])
+
+
+def test_loss_and_gradient_match_scalar_loops():
+    dims = [4, 5, 3]
+    theta, X, y = _tiny(dims, 7, 5)
+    loss, g = mlp.function(theta, dims, X, y)
+    assert loss == pytest.approx(brute.mlp_loss(theta, dims, X, y), abs=1e-13)
+    assert np.allclose(g, brute.mlp_grad_two_layer(theta, dims, X, y), atol=1e-13)
+    dims3 = [3, 4, 4, 2]
+    theta, X, y = _tiny(dims3, 5, 6)
+    assert mlp.function(theta, dims3, X, y)[0] == pytest.approx(brute.mlp_loss(theta, dims3, X, y), abs=1e-13)
+
+
+def test_gradient_matches_cpu_autograd():
+    dims = [12, 9, 8, 5]
+    theta, X, y = _tiny(dims, 17, 7)
+    t = torch.tensor(theta, dtype=torch.float64, requires_grad=True)
+    h = torch.tensor(X)
+    at = 0
+    for l in range(len(dims) - 1):
+        k, n = dims[l], dims[l + 1]
+        W = t[at:at + k * n].view(k, n); at += k * n
+        b = t[at:at + n]; at += n
+        h = h @ W + b
+        if l < len(dims) - 2:
+            h = torch.relu(h)
+    loss = torch.nn.functional.cross_entropy(h, torch.tensor(y), reduction="mean")
+    loss.backward()
+    ol, og = mlp.function(theta, dims, X, y)
+    assert ol == pytest.approx(loss.item(), abs=1e-13)
+    assert np.allclose(og, t.grad.numpy(), atol=1e-13)
+
+
+@pytest.mark.parametrize("B,N,S", [(24, 1, 1), (24, 2, 4), (25, 3, 4), (7, 4, 3), (5, 8, 2), (31, 5, 7), (16, 8, 4)])
+def test_defining_invariant_sliced_equals_full(B, N, S):
+    dims = [6, 5, 4]
+    rng = np.random.default_rng(8)
+    data = rng.standard_normal((40, 6)); labels = rng.integers(0, 4, 40)
+    idx = rng.integers(0, 40, B)
+    theta = rng.standard_normal(mlp.param_count(dims)) * 0.4
+    fl, fg = mlp.full(theta, dims, data, labels, idx)
+    r = mlp.sliced(theta, dims, data, labels, idx, N, S, "mean", worker_weights="rows")
+    assert r["loss"] == pytest.approx(fl, abs=1e-13)
+    assert np.allclose(r["grad"], fg, atol=1e-13)
+    if B % N == 0:     # plain 1/N average is the same thing when shares are equal
+        r2 = mlp.sliced(theta, dims, data, labels, idx, N, S, "mean")
+        assert np.allclose(r2["grad"], fg, atol=1e-13)
+    if N == 1 and S == 1:
+        assert np.array_equal(r["grad"], fg)
+
+
+def test_sum_aggregation_is_the_sum_of_slice_results():
+    dims = [4, 3, 3]
+    rng = np.random.default_rng(9)
+    data = rng.standard_normal((20, 4)); labels = rng.integers(0, 3, 20)
+    idx = rng.permutation(20)[:10]
+    theta = rng.standard_normal(mlp.param_count(dims))
+    r = mlp.sliced(theta, dims, data, labels, idx, 1, 3, "sum")
+    tot_g = 0.0; tot_l = 0.0
+    for (a, b) in split.share_bounds(10, 3):
+        l, g = mlp.function(theta, dims, data[idx[a:b]], labels[idx[a:b]])
+        tot_g = tot_g + g; tot_l += l
+    assert np.allclose(r["worker_grads"][0], tot_g, atol=1e-14)
+    assert r["worker_losses"][0] == pytest.approx(tot_l, abs=1e-14)
+
+
+def test_index_permutation_invariance():
+    dims = [5, 6, 3]
+    rng = np.random.default_rng(10)
+    data = rng.standard_normal((30, 5)); labels = rng.integers(0, 3, 30)
+    idx = rng.integers(0, 30, 12)
+    theta = rng.standard_normal(mlp.param_count(dims))
+    a = mlp.sliced(theta, dims, data, labels, idx, 3, 2, worker_weights="rows")
+    b = mlp.sliced(theta, dims, data, labels, rng.permutation(idx), 3, 2, worker_weights="rows")
+    assert np.allclose(a["grad"], b["grad"], atol=1e-13) and a["loss"] == pytest.approx(b["loss"], abs=1e-13)
+
+
+def test_bf16_points_mode_stays_near_float64():
+    dims = [64, 48, 32, 10]
+    rng = np.random.default_rng(11)
+    theta = np.concatenate([np.r_[(rng.standard_normal(dims[l] * dims[l + 1]) * np.sqrt(2 / dims[l])),
+                                  np.zeros(dims[l + 1])] for l in range(3)]).astype(np.float32)
+    X = rng.random((32, 64)).astype(np.float32); y = rng.integers(0, 10, 32)
+    l0, g0 = mlp.function(theta, dims, X, y)
+    l1, g1 = mlp.function(theta, dims, X, y, bf16_points=True)
+    assert abs(l1 - l0) < 2e-2 * abs(l0)
+    # bf16 inputs move individual gradient entries by a few percent (relu
+    # masks of near-zero units change); the band is on the whole array
+    assert np.linalg.norm(g1 - g0) < 1e-1 * np.linalg.norm(g0)
+    assert np.abs(g1 - g0).max() > 0      # the mode does something
+
+
+def test_relu_tie_flag_changes_only_near_zero_units():
+    dims = [3, 2, 2]
+    theta = np.array([1, 1, -1, 1, 0, 0.5,   0, 0,   1, -1, 2, 1,   0, 0], dtype=np.float64)
+    X = np.array([[1.0, 1.0, 0.0]])            # z1 = [0, 2]: unit 0 sits exactly on the kink
+    y = np.array([1])
+    tr = []
+    _, g = mlp.function(theta, dims, X, y, trace=tr)
+    assert np.array_equal(tr[0], [[0.0, 2.0]])
+    _, gf = mlp.function(theta, dims, X, y, tie_eps=1e-12, flip_ties=True)
+    gW1 = mlp.unpack(g, dims)[0][0]; gW1f = mlp.unpack(gf, dims)[0][0]
+    assert np.all(gW1[:, 0] == 0) and np.any(gW1f[:, 0] != 0)      # column of the tied unit
+    assert np.array_equal(gW1[:, 1], gW1f[:, 1])
+    assert np.array_equal(mlp.unpack(g, dims)[1][0], mlp.unpack(gf, dims)[1][0])
+
+
+# ---------------------------------------------------------------- reduce
+def test_reduce_ops_against_numpy():
+    rng = np.random.default_rng(12)
+    f = [rng.uniform(0.5, 2.0, 100).astype(np.float32) for _ in range(5)]
+    i = [rng.integers(-1000, 1000, 100).astype(np.int32) for _ in range(5)]
+    st = np.stack(f).astype(np.float64)
+    assert np.allclose(oreduce.reduce_buffers(f, "sum"), st.sum(0), rtol=1e-15)
+    assert np.allclose(oreduce.reduce_buffers(f, "mean"), st.mean(0), rtol=1e-15)
+    assert np.allclose(oreduce.reduce_buffers(f, "prod"), st.prod(0), rtol=1e-14)
+    assert np.array_equal(oreduce.reduce_buffers(f, "max"), st.max(0))
+    assert np.array_equal(oreduce.reduce_buffers(f, "min"), st.min(0))
+    si = np.stack(i).astype(np.int64)
+    assert np.array_equal(oreduce.reduce_buffers(i, "sum"), si.sum(0))
+    assert np.array_equal(oreduce.reduce_buffers(i, "max"), si.max(0))
+    assert np.array_equal(oreduce.reduce_buffers(i, "min"), si.min(0))
+    assert np.array_equal(oreduce.reduce_buffers([f[0][:3], f[1][:5]], "concat"), np.r_[f[0][:3], f[1][:5]])
+    with pytest.raises(TypeError):
+        oreduce.reduce_buffers(i, "mean")
+
+
+def test_mean_of_equal_buffers_is_bit_exact_and_pairs_cancel():
+    rng = np.random.default_rng(13)
+    x = rng.standard_normal(257).astype(np.float32)
+    for n in (1, 2, 4, 8):
+        out = oreduce.reduce_buffers([x] * n, "mean")
+        assert np.array_equal(out.astype(np.float32), x)
+    assert np.array_equal(oreduce.reduce_buffers([x, -x, x, -x], "mean"), np.zeros(257))
+    x64 = x.astype(np.float64)
+    w = oreduce.reduce_buffers([x64, 3 * x64], "mean", weights=[0.25, 0.75])
+    assert np.allclose(w, 2.5 * x64, rtol=1e-15)
+
+
+# ---------------------------------------------------------------- update
+def test_sgd_zero_momentum_and_closed_form():
+    rng = np.random.default_rng(14)
+    p = rng.standard_normal(50); g = rng.standard_normal(50); v = np.zeros(50)
+    p1, v1 = update.sgd_momentum(p, v, g, 0.1, 0.0)
+    assert np.allclose(p1, p - 0.1 * g, rtol=0, atol=1e-16)
+    pk, vk = p.copy(), v.copy()
+    for k in range(1, 8):
+        pk, vk = update.sgd_momentum(pk, vk, g, 0.05, 0.9)
+        assert np.allclose(pk, brute.momentum_closed_form(p, g, 0.05, 0.9, k), atol=1e-13)
+
+
+def test_sgd_trajectory_matches_torch_optim():
+    rng = np.random.default_rng(15)
+    p0 = rng.standard_normal(64)
+    grads = [rng.standard_normal(64) for _ in range(6)]
+    t = torch.nn.Parameter(torch.tensor(p0))
+    opt = torch.optim.SGD([t], lr=0.1, momentum=0.9, dampening=0.0, weight_decay=1e-2)
+    p, v = p0.copy(), np.zeros(64)
+    for g in grads:
+        t.grad = torch.tensor(g)
+        opt.step()
+        p, v = update.sgd_momentum(p, v, g, 0.1, 0.9, 1e-2)
+        assert np.allclose(p, t.detach().numpy(), atol=1e-13)
+
+
+def test_whole_step_independent_of_worker_count():
+    # App. A: averaging over workers "preserves the algorithm" for plain SGD.
+    dims = [6, 8, 3]
+    rng = np.random.default_rng(16)
+    data = rng.standard_normal((64, 6)); labels = rng.integers(0, 3, 64)
+    idx = rng.permutation(64)[:24]
+    theta = rng.standard_normal(mlp.param_count(dims)) * 0.3
+    outs = []
+    for n, s in [(1, 1), (2, 3), (4, 2), (8, 1)]:
+        r = mlp.sliced(theta, dims, data, labels, idx, n, s)
+        p2, v2, G, loss = update.reduce_and_update(theta, np.zeros_like(theta), r["worker_grads"],
+                                                   0.01, 0.9, 0.0, None, r["worker_losses"])
+        outs.append((p2, loss))
+    for p2, loss in outs[1:]:
+        assert np.allclose(p2, outs[0][0], atol=1e-14) and loss == pytest.approx(outs[0][1], abs=1e-14)
+
+
+# --------------------------------------------------------------- evalops
+def test_evalops_against_library_routines():
+    rng = np.random.default_rng(17)
+    logits = (rng.standard_normal((200, 37)) * 2).astype(np.float32)
+    logits[5, 3] = logits[5, 9] = logits[5].max() + 1.0          # a tie: lowest index wins
+    y = rng.integers(0, 37, 200).astype(np.int32)
+    r = evalops.function(logits, y)
+    am = np.argmax(logits, axis=1)
+    assert r["argmax"][5] == 3
+    assert np.array_equal(r["argmax"], am)
+    assert np.array_equal(r["counts"], np.bincount(am, minlength=37)) and r["counts"].sum() == 200
+    assert r["n_correct"][0] == int((am == y).sum())
+    assert r["max_logit"][0] == logits.max() and r["min_logit"][0] == logits.min()
+    assert r["max_logit"][0] == logits[np.arange(200), am].max()
+    ce = (scipy.special.logsumexp(logits.astype(np.float64), axis=1) - logits[np.arange(200), y]).sum()
+    assert r["ce_sum"][0] == pytest.approx(ce, rel=1e-14)
+
+
+@pytest.mark.parametrize("rows,S", [(200, 1), (200, 7), (64, 64), (5, 8), (130, 3)])
+def test_evalops_sliced_equals_full(rows, S):
+    rng = np.random.default_rng(18)
+    logits = (rng.standard_normal((rows, 11)) * 2).astype(np.float32)
+    y = rng.integers(0, 11, rows).astype(np.int32)
+    a = evalops.function(logits, y); b = evalops.sliced(logits, y, S)
+    for k in a:
+        if k == "ce_sum":
+            assert b[k][0] == pytest.approx(a[k][0], rel=1e-14)
+        else:
+            assert np.array_equal(a[k], b[k]), k
+
+
+def test_evalops_permutation_moves_only_the_concat_output():
+    rng = np.random.default_rng(19)
+    logits = (rng.standard_normal((90, 13)) * 2).astype(np.float32)
+    y = rng.integers(0, 13, 90).astype(np.int32)
+    perm = rng.permutation(90)
+    a = evalops.sliced(logits, y, 4); b = evalops.sliced(logits[perm], y[perm], 4)
+    for k in ("counts", "max_logit", "min_logit", "n_correct"):
+        assert np.array_equal(a[k], b[k])
+    assert np.array_equal(a["argmax"][perm], b["argmax"])
+    assert b["ce_sum"][0] == pytest.approx(a["ce_sum"][0], rel=1e-13)
