@@ -1,0 +1,271 @@
+/*
+ * synk.h - C ABI of libsynk: the data-parallel hot path of Synkhronos
+ * (arXiv 1710.04162) as hand-written HIP kernels for AMD MI355X (gfx950).
+ *
+ * One synchronous-SGD step of the paper (Sec. 3.3) on one GPU, with the N
+ * workers of Sec. 3.1-3.2 emulated as N device buffers:
+ *
+ *   synk_gather_rows        input indexing (Sec. 5.2) + scatter of the index
+ *                           list over workers (Sec. 3.2 step 1)
+ *   synk_sliced_grad        the gradient function run over every worker's
+ *                           share in slices, slice results aggregated on the
+ *                           GPU (Sec. 5.1), one flat gradient per worker
+ *                           (Sec. 3.3 step 1)
+ *   synk_sliced_eval        a function with six outputs, one reduce/gather op
+ *                           each (Sec. 3.1), evaluated in slices (Sec. 5.1)
+ *   synk_reduce_buffers     reduce/gather of N worker results (Sec. 3.2 step
+ *                           3, Sec. 3.3 step 2)
+ *   synk_sgd_update         momentum update on the flat array (Sec. 3.3 step 3)
+ *   synk_reduce_sgd_update  the last two fused into one pass over memory
+ *
+ * Conventions common to every call
+ * --------------------------------
+ * - Returns SYNK_OK (0) or a negative SYNK_ERR_* code; never throws, keeps no
+ *   global state, and may be called from several host threads.
+ * - All argument checks run on the host BEFORE the first HIP call, so a call
+ *   with invalid arguments returns its error code without touching a device.
+ * - "device" pointers are device memory owned by the caller and stay owned by
+ *   the caller.  "host" pointers (pointer tables, small descriptor arrays) are
+ *   read during the call and may be freed when it returns.
+ * - The library allocates nothing.  Scratch memory is a caller-provided
+ *   workspace (ws, ws_bytes), sized by the matching *_workspace_bytes call,
+ *   256-byte aligned; its contents are undefined between calls.
+ * - Kernels are launched asynchronously on `stream` (a hipStream_t passed as
+ *   void*; NULL = the default stream).  No call synchronises except
+ *   synk_poll_error.  Calls on one stream execute in call order.
+ * - At most SYNK_MAX_WORKERS workers / buffers per call.
+ * - Splitting `count` data points over `parts` workers or slices always uses
+ *   the same rule (the paper says "equally (as possible)"): contiguous runs,
+ *   share i has count/parts + (i < count%parts ? 1 : 0) points; shares may be
+ *   empty.
+ * - Float results are run-to-run reproducible: no floating-point atomics.
+ */
+#ifndef SYNK_H
+#define SYNK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SYNK_VERSION 100
+#define SYNK_MAX_WORKERS 64
+#define SYNK_MAX_LAYERS 8
+#define SYNK_MAX_CHANNELS 16
+
+/* status codes */
+#define SYNK_OK 0
+#define SYNK_ERR_NULL (-1)        /* a required pointer is NULL */
+#define SYNK_ERR_SHAPE (-2)       /* a size/count is negative, zero where it may not be, or inconsistent */
+#define SYNK_ERR_DTYPE (-3)       /* dtype code unknown or not supported by this call */
+#define SYNK_ERR_OP (-4)          /* op code unknown or not defined for the dtype */
+#define SYNK_ERR_ALIGN (-5)       /* a device pointer is not aligned as documented */
+#define SYNK_ERR_WORKSPACE (-6)   /* ws is NULL/misaligned or ws_bytes too small */
+#define SYNK_ERR_INDEX (-7)       /* an index was out of range (synk_poll_error) */
+#define SYNK_ERR_HIP (-8)         /* a HIP runtime call failed */
+#define SYNK_ERR_UNSUPPORTED (-9) /* valid request outside what is implemented */
+
+/* element types */
+#define SYNK_U8 0
+#define SYNK_I32 1
+#define SYNK_F32 2
+#define SYNK_BF16 3
+
+/* reduce / gather ops (Sec. 3.1: one per function output) */
+#define SYNK_SUM 0
+#define SYNK_MEAN 1
+#define SYNK_MAX 2
+#define SYNK_MIN 3
+#define SYNK_PROD 4
+#define SYNK_CONCAT 5
+
+/* flags */
+#define SYNK_FLAG_CHECK_INDEX 1u /* record out-of-range indexes in ws (see synk_poll_error) */
+
+int synk_version(void);
+const char* synk_status_string(int status);
+
+/* Host-side helper: the split rule above.  Writes parts+1 offsets
+ * (start[0] = 0, start[parts] = count) into `start` (host). */
+int synk_split(int64_t count, int parts, int64_t* start);
+
+/* ------------------------------------------------------------------ gather
+ * Input indexing, Sec. 5.2: the minibatch is data[idx[0..n_idx)], duplicates
+ * allowed; Sec. 3.2 step 1: the index list is split over n_workers by the
+ * split rule and worker w receives its rows, in list order, densely packed in
+ * dst[w] ([share_w x row_elems], row-major).
+ *
+ *   data        device, [n_rows x row_elems] of src_dtype, row-major, dense
+ *   idx         device, int32[n_idx], each in [0, n_rows)
+ *   dst         host array[n_workers] of device pointers, each large enough
+ *               for its share; dst[w] may be NULL only if share w is empty
+ *   dst_dtype   == src_dtype: bit-exact copy (any dtype);
+ *               SYNK_BF16 from SYNK_F32: round-to-nearest-even;
+ *               SYNK_F32 from SYNK_U8: out = lut[c*256 + x] with channel
+ *               c = element_index / (row_elems/channels): needs `lut`
+ *               (device float[channels*256], see synk_build_norm_lut) and
+ *               row_elems % channels == 0, channels <= SYNK_MAX_CHANNELS
+ *   labels      device int32[n_rows] or NULL; if given, dst_labels is a host
+ *               array[n_workers] of device int32 buffers receiving
+ *               labels[idx[j]] in the same order
+ *   flags       SYNK_FLAG_CHECK_INDEX: needs ws of
+ *               synk_gather_workspace_bytes(); whether this call met an
+ *               out-of-range index is recorded there.  With or without the flag a row whose index
+ *               is out of range is skipped (its destination is left
+ *               untouched) rather than read out of bounds.
+ * Alignment: none required; 16-byte aligned data/dst and a row pitch that is
+ * a multiple of 16 bytes select the widest copy path.
+ * Errors: NULL -> ERR_NULL; n_rows<0, row_elems<=0, n_idx<0, n_workers out of
+ * [1,SYNK_MAX_WORKERS], row_elems%channels -> ERR_SHAPE; dtype pair not
+ * listed -> ERR_DTYPE; flag set with no/small ws -> ERR_WORKSPACE.
+ * n_idx == 0 is a no-op.
+ */
+size_t synk_gather_workspace_bytes(void);
+int synk_gather_rows(const void* data, int64_t n_rows, int64_t row_elems, int src_dtype,
+                     const int32_t* idx, int64_t n_idx,
+                     void* const* dst, int n_workers, int dst_dtype,
+                     const float* lut, int channels,
+                     const int32_t* labels, int32_t* const* dst_labels,
+                     uint32_t flags, void* ws, size_t ws_bytes, void* stream);
+
+/* Builds on the device the table used by the U8->F32 gather:
+ * lut[c*256 + x] = (float)(((double)x - (double)mean[c]) / (double)std[c]),
+ * i.e. the float64 quotient rounded once to float32.  mean, std: host
+ * float[channels] on the 0..255 scale, std != 0; lut: device
+ * float[channels*256]. */
+int synk_build_norm_lut(const float* mean, const float* std, int channels, float* lut, void* stream);
+
+/* Synchronises `stream`, reads and clears the error word the most recent call
+ * with SYNK_FLAG_CHECK_INDEX left in ws.  Returns SYNK_OK, SYNK_ERR_INDEX, or
+ * SYNK_ERR_HIP. */
+int synk_poll_error(void* ws, void* stream);
+
+/* ------------------------------------------------------------- sliced grad
+ * The gradient function of synchronous SGD (Sec. 3.3 step 1) for a ReLU MLP
+ * with softmax cross-entropy, called the way Sec. 3.2 and 5.1 describe: every
+ * worker runs it on its own rows, cut into n_slices slices by the split rule;
+ * all slices see the same parameter values (Sec. 5.1: updates are applied
+ * once, afterwards); a worker's slice results are aggregated on the GPU with
+ * grad_op and land in that worker's own flat gradient array and loss.
+ *
+ * Function on a row set R: h_0 = X_R; h_l = relu(h_{l-1} W_l + b_l) for
+ * l < L; logits = h_{L-1} W_L + b_L; l_i = logsumexp(logits_i) -
+ * logits_i[y_i]; outputs loss_R = mean_i l_i and g_R = d loss_R / d params.
+ * relu'(0) = 0.  Aggregation over a worker's slices s with |R_s| rows:
+ *   SYNK_MEAN  sum_s (|R_s|/|R_w|) out_s  (= the unsliced call on the share)
+ *   SYNK_SUM   sum_s out_s
+ *
+ *   m.dims          host int64[n_layers+1]: d_0 (features) .. d_L (classes)
+ *   m.compute_dtype SYNK_F32: fp32 GEMM operands; SYNK_BF16: X, W_l, hidden
+ *                   activations and dZ_l are rounded (nearest-even) to bf16
+ *                   where they enter a GEMM, products accumulate in fp32,
+ *                   everything else is fp32
+ *   params          device float[P], P = sum_l d_{l-1} d_l + d_l, layout
+ *                   W_1, b_1, W_2, b_2, ...; W_l is [d_{l-1} x d_l] row-major
+ *   params_lp       device bf16[P], the same array rounded to bf16 (as
+ *                   written by synk_sgd_update / synk_cast_bf16); required
+ *                   for SYNK_BF16, ignored for SYNK_F32
+ *   x               host array[n_workers] of device [rows[w] x d_0] buffers
+ *                   in compute_dtype (as written by synk_gather_rows)
+ *   y               host array[n_workers] of device int32[rows[w]], each in
+ *                   [0, d_L); a label outside that range contributes as if no
+ *                   class were the target (never reads out of bounds)
+ *   rows            host int64[n_workers], >= 0, not all zero; rows and layer
+ *                   widths are limited to 2^21 each
+ *   grad            host array[n_workers] of device float[P]; fully
+ *                   overwritten (a worker with no rows gets zeros)
+ *   loss            device float[n_workers]
+ *   ws              synk_sliced_grad_workspace_bytes(m, rows, n_workers, &b)
+ * Errors: NULL -> ERR_NULL; n_layers out of [1,SYNK_MAX_LAYERS], dims <= 0,
+ * rows < 0, all rows zero, n_workers out of range, n_slices <= 0 -> ERR_SHAPE;
+ * compute_dtype -> ERR_DTYPE; grad_op not SUM/MEAN -> ERR_OP; params, x[w] or
+ * grad[w] not 4-byte (F32) / 2-byte (BF16) aligned -> ERR_ALIGN; ws ->
+ * ERR_WORKSPACE.  16-byte aligned x[w], grad[w], params, params_lp and layer
+ * widths that are multiples of 8 select the vector load paths.
+ */
+typedef struct {
+  int n_layers;
+  const int64_t* dims;
+  int compute_dtype;
+} synk_mlp_desc;
+
+int synk_mlp_param_count(const synk_mlp_desc* m, int64_t* count);
+int synk_sliced_grad_workspace_bytes(const synk_mlp_desc* m, const int64_t* rows, int n_workers,
+                                     size_t* bytes);
+int synk_sliced_grad(const synk_mlp_desc* m, const float* params, const void* params_lp,
+                     const void* const* x, const int32_t* const* y, const int64_t* rows,
+                     int n_workers, int n_slices, int grad_op,
+                     float* const* grad, float* loss,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* out[i] = bf16(in[i]), round-to-nearest-even; device float[len] -> device
+ * bf16[len].  Makes the params_lp array for a first step. */
+int synk_cast_bf16(const float* in, void* out, int64_t len, void* stream);
+
+/* ------------------------------------------------------------- sliced eval
+ * A function with six outputs, each with its own reduce/gather op (Sec. 3.1),
+ * evaluated over n_slices contiguous slices of the rows (split rule) whose
+ * results are aggregated on the GPU (Sec. 5.1).  With a_i = argmax_c
+ * logits[i,c] (lowest c on ties):
+ *   ce_sum       float[1]      sum_i logsumexp(logits_i) - logits_i[y_i]  SUM
+ *   class_counts int32[classes] #{i : a_i = c}                            SUM
+ *   max_logit    float[1]      max over all entries                       MAX
+ *   min_logit    float[1]      min over all entries                       MIN
+ *   n_correct    int32[1]      #{i : a_i = y_i}                           SUM
+ *   argmax       int32[rows]   a_i                                        CONCAT
+ * logits: device float[rows x classes] row-major; labels: device int32[rows]
+ * (a label outside [0,classes) adds only the logsumexp term and never counts
+ * as correct).  Inputs must be finite.  All outputs are device pointers and
+ * are fully overwritten.  rows >= 1, classes in [1, 4096], n_slices >= 1.
+ */
+int synk_sliced_eval_workspace_bytes(int64_t rows, int64_t classes, int n_slices, size_t* bytes);
+int synk_sliced_eval(const float* logits, const int32_t* labels, int64_t rows, int64_t classes,
+                     int n_slices,
+                     float* ce_sum, int32_t* class_counts, float* max_logit, float* min_logit,
+                     int32_t* n_correct, int32_t* argmax,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------ reduce
+ * Reduce or gather N equally long worker results (Sec. 3.2 step 3; Sec. 3.3
+ * step 2 for the flat gradient): out[i] = op_w bufs[w][i].
+ *   bufs     host array[n] of device buffers of `dtype` (F32 or I32)
+ *   op       SUM, MAX, MIN, PROD: folded in buffer order;
+ *            MEAN (F32 only): sum_w weights[w]*bufs[w][i], weights = 1/n when
+ *            NULL (host float[n] otherwise);
+ *            CONCAT: out = bufs[0] ++ bufs[1] ++ ..., buffer w having lens[w]
+ *            elements (host int64[n]; `len` is ignored)
+ *   out      device, len elements (CONCAT: sum of lens); may alias bufs[0]
+ *            except for CONCAT
+ * Errors: MEAN on I32 -> ERR_OP; weights with an op other than MEAN ->
+ * ERR_OP; CONCAT without lens -> ERR_NULL; n out of [1,SYNK_MAX_WORKERS],
+ * len < 0 -> ERR_SHAPE.  len == 0 is a no-op.
+ */
+int synk_reduce_buffers(const void* const* bufs, int n, int64_t len, int dtype, int op,
+                        const float* weights, const int64_t* lens, void* out, void* stream);
+
+/* ------------------------------------------------------------------ update
+ * Momentum update with the combined gradient (Sec. 3.3 step 3; the paper
+ * names the rule, the formula is this library's reading):
+ *   g = G[i] + weight_decay * p[i];  v[i] = momentum * v[i] - lr * g;
+ *   p[i] = p[i] + v[i];  if p_lp: p_lp[i] = bf16(p[i]) (nearest-even)
+ * p, v: device float[len], updated in place; g: device float[len];
+ * p_lp: device bf16[len] or NULL.
+ */
+int synk_sgd_update(float* p, float* v, const float* g, int64_t len,
+                    float lr, float momentum, float weight_decay, void* p_lp, void* stream);
+
+/* Sec. 3.3 steps 2 and 3 in one pass: G[i] = sum_w weights[w]*grads[w][i]
+ * (weights NULL = 1/n), then the update above; G is never written to memory.
+ * Optionally also the mean of the per-worker scalar losses (Sec. 3.2 step 3):
+ * loss_out[0] = sum_w weights[w]*loss_in[w] (both device; both NULL to skip).
+ * Same results as synk_reduce_buffers(MEAN) followed by synk_sgd_update. */
+int synk_reduce_sgd_update(const float* const* grads, int n, int64_t len, const float* weights,
+                           float* p, float* v, float lr, float momentum, float weight_decay,
+                           void* p_lp, const float* loss_in, float* loss_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SYNK_H */

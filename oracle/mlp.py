@@ -59,7 +59,8 @@ def function(theta, dims, X, y, bf16_points=False, tie_eps=0.0, flip_ties=False,
     The derivative of relu at a pre-activation of exactly 0 is taken as 0.  A
     pre-activation that is 0 up to rounding (|z| <= tie_eps) has two valid
     derivatives; flip_ties=True takes the other one for every such entry, so
-    that a caller can accept either.  `trace`, if a list, receives the hidden
+    that a caller can accept either (tie_eps: one bound, or one per hidden
+    layer).  `trace`, if a list, receives the hidden
     pre-activations z_1 .. z_{L-1}."""
     theta = np.asarray(theta, dtype=np.float64)
     X = np.asarray(X, dtype=np.float64)
@@ -79,7 +80,8 @@ def function(theta, dims, X, y, bf16_points=False, tie_eps=0.0, flip_ties=False,
             a = np.maximum(z, 0.0)
             mask = a > 0.0             # derivative of relu at 0 taken as 0
             if flip_ties:
-                mask = mask ^ (np.abs(z) <= tie_eps)
+                eps = tie_eps[l] if isinstance(tie_eps, (list, tuple)) else tie_eps
+                mask = mask ^ (np.abs(z) <= eps)
             pre_mask.append(mask)
             if trace is not None:
                 trace.append(z)

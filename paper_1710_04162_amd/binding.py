@@ -1,0 +1,227 @@
+"""ctypes binding of libsynk.so.  Argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/synk.h has
+the semantics).  Tensors must already live on the GPU; lists of tensors become
+host pointer tables.  A negative status raises SynkError.  Launches go on
+torch's current stream unless `stream` (a raw hipStream_t integer) is given.
+"""
+import ctypes
+import os
+
+import torch
+
+__all__ = [
+    "SynkError", "lib", "LIB_PATH", "DTYPE", "OP",
+    "SYNK_U8", "SYNK_I32", "SYNK_F32", "SYNK_BF16",
+    "SYNK_SUM", "SYNK_MEAN", "SYNK_MAX", "SYNK_MIN", "SYNK_PROD", "SYNK_CONCAT",
+    "SYNK_FLAG_CHECK_INDEX", "SYNK_MAX_WORKERS",
+    "synk_version", "synk_status_string", "synk_split", "synk_gather_workspace_bytes",
+    "synk_gather_rows", "synk_build_norm_lut", "synk_poll_error", "synk_mlp_param_count",
+    "synk_sliced_grad_workspace_bytes", "synk_sliced_grad", "synk_cast_bf16",
+    "synk_sliced_eval_workspace_bytes", "synk_sliced_eval", "synk_reduce_buffers",
+    "synk_sgd_update", "synk_reduce_sgd_update",
+]
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsynk.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError("libsynk.so is not built: run `python -m paper_1710_04162_amd.build` "
+                      "(there is no fallback path)")
+lib = ctypes.CDLL(LIB_PATH)
+
+SYNK_U8, SYNK_I32, SYNK_F32, SYNK_BF16 = 0, 1, 2, 3
+SYNK_SUM, SYNK_MEAN, SYNK_MAX, SYNK_MIN, SYNK_PROD, SYNK_CONCAT = 0, 1, 2, 3, 4, 5
+SYNK_FLAG_CHECK_INDEX = 1
+SYNK_MAX_WORKERS = 64
+DTYPE = {torch.uint8: SYNK_U8, torch.int32: SYNK_I32, torch.float32: SYNK_F32,
+         torch.bfloat16: SYNK_BF16}
+OP = dict(sum=SYNK_SUM, mean=SYNK_MEAN, max=SYNK_MAX, min=SYNK_MIN, prod=SYNK_PROD,
+          concat=SYNK_CONCAT)
+
+_vp, _i64, _int, _f32, _sz = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float,
+                              ctypes.c_size_t)
+_pp = ctypes.POINTER(ctypes.c_void_p)
+_pi64 = ctypes.POINTER(ctypes.c_int64)
+_pf32 = ctypes.POINTER(ctypes.c_float)
+
+
+class MlpDesc(ctypes.Structure):
+    _fields_ = [("n_layers", _int), ("dims", _pi64), ("compute_dtype", _int)]
+
+
+lib.synk_version.restype = _int
+lib.synk_status_string.restype = ctypes.c_char_p
+lib.synk_status_string.argtypes = [_int]
+lib.synk_split.argtypes = [_i64, _int, _pi64]
+lib.synk_gather_workspace_bytes.restype = _sz
+lib.synk_gather_rows.argtypes = [_vp, _i64, _i64, _int, _vp, _i64, _pp, _int, _int, _vp, _int, _vp,
+                                 _pp, ctypes.c_uint32, _vp, _sz, _vp]
+lib.synk_build_norm_lut.argtypes = [_pf32, _pf32, _int, _vp, _vp]
+lib.synk_poll_error.argtypes = [_vp, _vp]
+lib.synk_mlp_param_count.argtypes = [ctypes.POINTER(MlpDesc), _pi64]
+lib.synk_sliced_grad_workspace_bytes.argtypes = [ctypes.POINTER(MlpDesc), _pi64, _int,
+                                                 ctypes.POINTER(_sz)]
+lib.synk_sliced_grad.argtypes = [ctypes.POINTER(MlpDesc), _vp, _vp, _pp, _pp, _pi64, _int, _int,
+                                 _int, _pp, _vp, _vp, _sz, _vp]
+lib.synk_cast_bf16.argtypes = [_vp, _vp, _i64, _vp]
+lib.synk_sliced_eval_workspace_bytes.argtypes = [_i64, _i64, _int, ctypes.POINTER(_sz)]
+lib.synk_sliced_eval.argtypes = [_vp, _vp, _i64, _i64, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
+                                 _vp]
+lib.synk_reduce_buffers.argtypes = [_pp, _int, _i64, _int, _int, _pf32, _pi64, _vp, _vp]
+lib.synk_sgd_update.argtypes = [_vp, _vp, _vp, _i64, _f32, _f32, _f32, _vp, _vp]
+lib.synk_reduce_sgd_update.argtypes = [_pp, _int, _i64, _pf32, _vp, _vp, _f32, _f32, _f32, _vp, _vp,
+                                       _vp, _vp]
+for _n in ("synk_split", "synk_gather_rows", "synk_build_norm_lut", "synk_poll_error",
+           "synk_mlp_param_count", "synk_sliced_grad_workspace_bytes", "synk_sliced_grad",
+           "synk_cast_bf16", "synk_sliced_eval_workspace_bytes", "synk_sliced_eval",
+           "synk_reduce_buffers", "synk_sgd_update", "synk_reduce_sgd_update"):
+    getattr(lib, _n).restype = _int
+
+
+class SynkError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, lib.synk_status_string(status).decode(), status))
+
+
+def _check(status, where):
+    if status != 0:
+        raise SynkError(status, where)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("libsynk takes device tensors only")
+    if not t.is_contiguous():
+        raise ValueError("libsynk takes dense (contiguous) tensors only")
+    return t.data_ptr()
+
+
+def _table(tensors):
+    arr = (ctypes.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = _ptr(t) or None      # an empty tensor may have no storage: NULL
+    return arr
+
+
+def _stream(stream):
+    return torch.cuda.current_stream().cuda_stream if stream is None else stream
+
+
+def _ws(ws):
+    return (None, 0) if ws is None else (_ptr(ws), ws.numel() * ws.element_size())
+
+
+def _desc(dims, compute_dtype):
+    arr = (ctypes.c_int64 * len(dims))(*[int(d) for d in dims])
+    d = MlpDesc(len(dims) - 1, arr, compute_dtype)
+    d._keep = arr
+    return d
+
+
+def synk_version():
+    return lib.synk_version()
+
+
+def synk_status_string(status):
+    return lib.synk_status_string(status).decode()
+
+
+def synk_split(count, parts):
+    out = (ctypes.c_int64 * (parts + 1))()
+    _check(lib.synk_split(count, parts, out), "synk_split")
+    return list(out)
+
+
+def synk_gather_workspace_bytes():
+    return lib.synk_gather_workspace_bytes()
+
+
+def synk_gather_rows(data, idx, dst, lut=None, channels=0, labels=None, dst_labels=None, flags=0,
+                     ws=None, stream=None):
+    n_rows = data.shape[0]
+    row_elems = data.numel() // max(n_rows, 1) if n_rows else int(torch.tensor(data.shape[1:]).prod())
+    wsp, wsb = _ws(ws)
+    _check(lib.synk_gather_rows(_ptr(data), n_rows, row_elems, DTYPE[data.dtype], _ptr(idx),
+                                idx.numel(), _table(dst), len(dst), DTYPE[dst[0].dtype], _ptr(lut),
+                                channels, _ptr(labels),
+                                _table(dst_labels) if dst_labels is not None else None, flags, wsp,
+                                wsb, _stream(stream)), "synk_gather_rows")
+
+
+def synk_build_norm_lut(mean, std, lut, stream=None):
+    c = len(mean)
+    m = (ctypes.c_float * c)(*[float(x) for x in mean])
+    s = (ctypes.c_float * c)(*[float(x) for x in std])
+    _check(lib.synk_build_norm_lut(m, s, c, _ptr(lut), _stream(stream)), "synk_build_norm_lut")
+
+
+def synk_poll_error(ws, stream=None):
+    return lib.synk_poll_error(_ptr(ws), _stream(stream))
+
+
+def synk_mlp_param_count(dims, compute_dtype=SYNK_F32):
+    out = ctypes.c_int64(0)
+    _check(lib.synk_mlp_param_count(ctypes.byref(_desc(dims, compute_dtype)), ctypes.byref(out)),
+           "synk_mlp_param_count")
+    return out.value
+
+
+def synk_sliced_grad_workspace_bytes(dims, compute_dtype, rows):
+    out = _sz(0)
+    r = (ctypes.c_int64 * len(rows))(*[int(x) for x in rows])
+    _check(lib.synk_sliced_grad_workspace_bytes(ctypes.byref(_desc(dims, compute_dtype)), r, len(rows),
+                                                ctypes.byref(out)), "synk_sliced_grad_workspace_bytes")
+    return out.value
+
+
+def synk_sliced_grad(dims, compute_dtype, params, params_lp, x, y, rows, n_slices, grad_op, grad, loss,
+                     ws, stream=None):
+    r = (ctypes.c_int64 * len(rows))(*[int(v) for v in rows])
+    wsp, wsb = _ws(ws)
+    _check(lib.synk_sliced_grad(ctypes.byref(_desc(dims, compute_dtype)), _ptr(params), _ptr(params_lp),
+                                _table(x), _table(y), r, len(rows), n_slices, grad_op, _table(grad),
+                                _ptr(loss), wsp, wsb, _stream(stream)), "synk_sliced_grad")
+
+
+def synk_cast_bf16(src, dst, stream=None):
+    _check(lib.synk_cast_bf16(_ptr(src), _ptr(dst), src.numel(), _stream(stream)), "synk_cast_bf16")
+
+
+def synk_sliced_eval_workspace_bytes(rows, classes, n_slices):
+    out = _sz(0)
+    _check(lib.synk_sliced_eval_workspace_bytes(rows, classes, n_slices, ctypes.byref(out)),
+           "synk_sliced_eval_workspace_bytes")
+    return out.value
+
+
+def synk_sliced_eval(logits, labels, n_slices, ce_sum, class_counts, max_logit, min_logit, n_correct,
+                     argmax, ws, stream=None):
+    rows, classes = logits.shape
+    wsp, wsb = _ws(ws)
+    _check(lib.synk_sliced_eval(_ptr(logits), _ptr(labels), rows, classes, n_slices, _ptr(ce_sum),
+                                _ptr(class_counts), _ptr(max_logit), _ptr(min_logit), _ptr(n_correct),
+                                _ptr(argmax), wsp, wsb, _stream(stream)), "synk_sliced_eval")
+
+
+def synk_reduce_buffers(bufs, op, out, weights=None, stream=None):
+    n = len(bufs)
+    w = (ctypes.c_float * n)(*[float(x) for x in weights]) if weights is not None else None
+    lens = (ctypes.c_int64 * n)(*[b.numel() for b in bufs]) if op == SYNK_CONCAT else None
+    _check(lib.synk_reduce_buffers(_table(bufs), n, bufs[0].numel(), DTYPE[bufs[0].dtype], op, w, lens,
+                                   _ptr(out), _stream(stream)), "synk_reduce_buffers")
+
+
+def synk_sgd_update(p, v, g, lr, momentum, weight_decay=0.0, p_lp=None, stream=None):
+    _check(lib.synk_sgd_update(_ptr(p), _ptr(v), _ptr(g), p.numel(), lr, momentum, weight_decay,
+                               _ptr(p_lp), _stream(stream)), "synk_sgd_update")
+
+
+def synk_reduce_sgd_update(grads, p, v, lr, momentum, weight_decay=0.0, weights=None, p_lp=None,
+                           loss_in=None, loss_out=None, stream=None):
+    n = len(grads)
+    w = (ctypes.c_float * n)(*[float(x) for x in weights]) if weights is not None else None
+    _check(lib.synk_reduce_sgd_update(_table(grads), n, p.numel(), w, _ptr(p), _ptr(v), lr, momentum,
+                                      weight_decay, _ptr(p_lp), _ptr(loss_in), _ptr(loss_out),
+                                      _stream(stream)), "synk_reduce_sgd_update")

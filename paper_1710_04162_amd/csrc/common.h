@@ -1,0 +1,75 @@
+// Internal helpers shared by the kernels of libsynk (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/synk.h"
+
+#define SYNK_HIP_TRY(expr)                         \
+  do {                                             \
+    if ((expr) != hipSuccess) return SYNK_ERR_HIP; \
+  } while (0)
+
+// Kernel launches report configuration errors through hipGetLastError.
+#define SYNK_LAUNCH_CHECK()                                   \
+  do {                                                        \
+    if (hipGetLastError() != hipSuccess) return SYNK_ERR_HIP; \
+  } while (0)
+
+namespace synk {
+
+// Native vector types (what the nontemporal builtins and MFMA builtins take).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWave = 64;
+constexpr int kNumCU = 256;
+
+static inline bool aligned_to(const void* p, size_t a) {
+  return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0;
+}
+
+static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// share i of `count` points over `parts`: [start, start+size)
+static inline void share(int64_t count, int parts, int i, int64_t* start, int64_t* size) {
+  const int64_t base = count / parts, extra = count % parts;
+  *size = base + (i < extra ? 1 : 0);
+  *start = base * i + (i < extra ? i : extra);
+}
+
+// float -> bfloat16 bits, round to nearest even (finite inputs; NaN kept quiet)
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) {
+  return __uint_as_float(((uint32_t)h) << 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// Device-side form of the split rule: which share holds point j, and where
+// that share starts.
+__device__ __forceinline__ void share_of(int64_t count, int parts, int64_t j, int* which,
+                                         int64_t* start) {
+  const int64_t base = count / parts, extra = count % parts;
+  const int64_t big = extra * (base + 1);
+  if (j < big) {
+    const int64_t w = j / (base + 1);
+    *which = (int)w;
+    *start = w * (base + 1);
+  } else {
+    const int64_t w = extra + (base > 0 ? (j - big) / base : 0);
+    *which = (int)w;
+    *start = big + (w - extra) * base;
+  }
+}
+
+}  // namespace synk

@@ -1,0 +1,318 @@
+// Input indexing (Sec. 5.2) fused with the scatter of the index list over
+// workers (Sec. 3.2 step 1): batch row j = data[idx[j]] lands, densely packed,
+// in the buffer of the worker whose share holds j.  Pure data movement, bound
+// by HBM bandwidth: one workgroup per (batch row, row chunk), every load and
+// store coalesced across the wavefront.
+#include "common.h"
+
+namespace synk {
+
+struct DstTable {
+  void* dst[SYNK_MAX_WORKERS];
+  int32_t* lab[SYNK_MAX_WORKERS];
+};
+
+constexpr int kGBlock = 256;
+
+struct RowRef {
+  int64_t src_row;   // idx[j], or -1 when out of range
+  int worker;
+  int64_t local;     // row inside the worker's buffer
+};
+
+__device__ __forceinline__ RowRef locate(const int32_t* __restrict__ idx, int64_t n_idx,
+                                         int n_workers, int64_t n_rows, int64_t j,
+                                         uint32_t* err_word) {
+  RowRef r;
+  const int64_t src = idx[j];
+  int64_t start;
+  share_of(n_idx, n_workers, j, &r.worker, &start);
+  r.local = j - start;
+  r.src_row = (src >= 0 && src < n_rows) ? src : -1;
+  if (r.src_row < 0 && err_word && threadIdx.x == 0 && blockIdx.y == 0) atomicOr(err_word, 1u);
+  return r;
+}
+
+__device__ __forceinline__ void copy_label(const DstTable& t, const int32_t* __restrict__ labels,
+                                           const RowRef& r) {
+  if (labels && blockIdx.y == 0 && threadIdx.x == 0) t.lab[r.worker][r.local] = labels[r.src_row];
+}
+
+// Bit-exact copy in units of V (16, 4 or 1 bytes).  grid = (n_idx, chunks).
+template <typename V>
+__global__ __launch_bounds__(kGBlock) void gather_copy_kernel(
+    const V* __restrict__ data, int64_t n_rows, int64_t row_units, const int32_t* __restrict__ idx,
+    int64_t n_idx, DstTable t, int n_workers, const int32_t* __restrict__ labels,
+    uint32_t* err_word, int units_per_block) {
+  const int64_t j = blockIdx.x;
+  const RowRef r = locate(idx, n_idx, n_workers, n_rows, j, err_word);
+  if (r.src_row < 0) return;
+  copy_label(t, labels, r);
+  const V* src = data + r.src_row * row_units;
+  V* dst = reinterpret_cast<V*>(t.dst[r.worker]) + r.local * row_units;
+  const int64_t u0 = (int64_t)blockIdx.y * units_per_block;
+  int64_t u1 = u0 + units_per_block;
+  if (u1 > row_units) u1 = row_units;
+  for (int64_t u = u0 + threadIdx.x; u < u1; u += kGBlock) dst[u] = src[u];
+}
+
+// float32 -> bfloat16 (nearest-even).  VEC: 4 floats in, 8 bytes out per lane.
+template <bool VEC>
+__global__ __launch_bounds__(kGBlock) void gather_bf16_kernel(
+    const float* __restrict__ data, int64_t n_rows, int64_t row_elems,
+    const int32_t* __restrict__ idx, int64_t n_idx, DstTable t, int n_workers,
+    const int32_t* __restrict__ labels, uint32_t* err_word, int units_per_block) {
+  const int64_t j = blockIdx.x;
+  const RowRef r = locate(idx, n_idx, n_workers, n_rows, j, err_word);
+  if (r.src_row < 0) return;
+  copy_label(t, labels, r);
+  const float* src = data + r.src_row * row_elems;
+  uint16_t* dst = reinterpret_cast<uint16_t*>(t.dst[r.worker]) + r.local * row_elems;
+  const int64_t units = VEC ? (row_elems >> 2) : row_elems;
+  const int64_t u0 = (int64_t)blockIdx.y * units_per_block;
+  int64_t u1 = u0 + units_per_block;
+  if (u1 > units) u1 = units;
+  for (int64_t u = u0 + threadIdx.x; u < u1; u += kGBlock) {
+    if (VEC) {
+      const f32x4 a = reinterpret_cast<const f32x4*>(src)[u];
+      u32x2 q;
+      q.x = pack_bf16x2(a.x, a.y);
+      q.y = pack_bf16x2(a.z, a.w);
+      reinterpret_cast<u32x2*>(dst)[u] = q;
+    } else {
+      dst[u] = f32_to_bf16(src[u]);
+    }
+  }
+}
+
+// uint8 -> float32 through a per-channel table held in LDS.  VEC: each lane
+// loads 4 pixels (one dword) and stores one 16-byte vector, so both the load
+// and the store of a wavefront are contiguous.
+template <bool VEC>
+__global__ __launch_bounds__(kGBlock) void gather_u8_lut_kernel(
+    const uint8_t* __restrict__ data, int64_t n_rows, int64_t row_elems, int64_t plane,
+    const int32_t* __restrict__ idx, int64_t n_idx, DstTable t, int n_workers,
+    const float* __restrict__ lut, int channels, const int32_t* __restrict__ labels,
+    uint32_t* err_word, int units_per_block) {
+  __shared__ float s_lut[SYNK_MAX_CHANNELS * 256];
+  const int64_t j = blockIdx.x;
+  const RowRef r = locate(idx, n_idx, n_workers, n_rows, j, err_word);
+  if (r.src_row < 0) return;   // uniform per block: before the barrier is fine
+  for (int i = threadIdx.x; i < channels * 256; i += kGBlock) s_lut[i] = lut[i];
+  __syncthreads();
+  copy_label(t, labels, r);
+  const uint8_t* src = data + r.src_row * row_elems;
+  float* dst = reinterpret_cast<float*>(t.dst[r.worker]) + r.local * row_elems;
+  const int64_t units = VEC ? (row_elems >> 2) : row_elems;
+  const int64_t u0 = (int64_t)blockIdx.y * units_per_block;
+  int64_t u1 = u0 + units_per_block;
+  if (u1 > units) u1 = units;
+  if (VEC) {
+    // plane % 4 == 0 here, so the 4 pixels of a unit share a channel
+    constexpr int UNROLL = 4;
+    int64_t u = u0 + threadIdx.x;
+    for (; u + (UNROLL - 1) * kGBlock < u1; u += UNROLL * kGBlock) {
+      uint32_t px[UNROLL];
+#pragma unroll
+      for (int k = 0; k < UNROLL; ++k)
+        px[k] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(src) + u + k * kGBlock);
+#pragma unroll
+      for (int k = 0; k < UNROLL; ++k) {
+        const int64_t uu = u + k * kGBlock;
+        const float* l = s_lut + ((uu << 2) / plane) * 256;
+        f32x4 o;
+        o.x = l[px[k] & 0xffu];
+        o.y = l[(px[k] >> 8) & 0xffu];
+        o.z = l[(px[k] >> 16) & 0xffu];
+        o.w = l[px[k] >> 24];
+        __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst) + uu);
+      }
+    }
+    for (; u < u1; u += kGBlock) {
+      const uint32_t px = reinterpret_cast<const uint32_t*>(src)[u];
+      const float* l = s_lut + ((u << 2) / plane) * 256;
+      f32x4 o;
+      o.x = l[px & 0xffu];
+      o.y = l[(px >> 8) & 0xffu];
+      o.z = l[(px >> 16) & 0xffu];
+      o.w = l[px >> 24];
+      reinterpret_cast<f32x4*>(dst)[u] = o;
+    }
+  } else {
+    for (int64_t u = u0 + threadIdx.x; u < u1; u += kGBlock)
+      dst[u] = s_lut[(u / plane) * 256 + src[u]];
+  }
+}
+
+struct LutArgs {
+  double v[2 * SYNK_MAX_CHANNELS];
+};
+
+__global__ void norm_lut_kernel_args(float* __restrict__ lut, int channels, LutArgs a) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < channels * 256) {
+    const int c = i >> 8;
+    lut[i] = (float)(((double)(i & 255) - a.v[c]) / a.v[SYNK_MAX_CHANNELS + c]);
+  }
+}
+
+__global__ void clear_word_kernel(uint32_t* w) { *w = 0u; }
+
+static int chunking(int64_t units, int* units_per_block, int* chunks) {
+  // up to 16 units per thread per block; at least one block per row
+  int64_t upb = (int64_t)kGBlock * 16;
+  if (units < upb) upb = (units + kGBlock - 1) / kGBlock * kGBlock;
+  if (upb < kGBlock) upb = kGBlock;
+  *units_per_block = (int)upb;
+  const int64_t c = (units + upb - 1) / upb;
+  if (c > 65535) return SYNK_ERR_UNSUPPORTED;   // grid.y limit: rows beyond 4 Gi units
+  *chunks = c < 1 ? 1 : (int)c;
+  return SYNK_OK;
+}
+
+}  // namespace synk
+
+using namespace synk;
+
+extern "C" size_t synk_gather_workspace_bytes(void) { return 256; }
+
+extern "C" int synk_gather_rows(const void* data, int64_t n_rows, int64_t row_elems, int src_dtype,
+                                const int32_t* idx, int64_t n_idx, void* const* dst, int n_workers,
+                                int dst_dtype, const float* lut, int channels,
+                                const int32_t* labels, int32_t* const* dst_labels, uint32_t flags,
+                                void* ws, size_t ws_bytes, void* stream) {
+  if (!data || !idx || !dst) return SYNK_ERR_NULL;
+  if (labels && !dst_labels) return SYNK_ERR_NULL;
+  if (n_rows < 0 || row_elems <= 0 || n_idx < 0) return SYNK_ERR_SHAPE;
+  if (n_workers < 1 || n_workers > SYNK_MAX_WORKERS) return SYNK_ERR_SHAPE;
+  if (n_idx > 0x7fffffffLL) return SYNK_ERR_SHAPE;   // grid.x limit
+  if (src_dtype < SYNK_U8 || src_dtype > SYNK_BF16 || dst_dtype < SYNK_U8 || dst_dtype > SYNK_BF16)
+    return SYNK_ERR_DTYPE;
+  enum { COPY, TO_BF16, U8_LUT } mode;
+  if (dst_dtype == src_dtype) mode = COPY;
+  else if (src_dtype == SYNK_F32 && dst_dtype == SYNK_BF16) mode = TO_BF16;
+  else if (src_dtype == SYNK_U8 && dst_dtype == SYNK_F32) mode = U8_LUT;
+  else return SYNK_ERR_DTYPE;
+  if (mode == U8_LUT) {
+    if (!lut) return SYNK_ERR_NULL;
+    if (channels < 1 || channels > SYNK_MAX_CHANNELS || row_elems % channels != 0)
+      return SYNK_ERR_SHAPE;
+  }
+  static const int kElemBytes[4] = {1, 4, 4, 2};
+  const int src_b = kElemBytes[src_dtype], dst_b = kElemBytes[dst_dtype];
+  if (!aligned_to(data, src_b)) return SYNK_ERR_ALIGN;
+  uint32_t* err_word = nullptr;
+  if (flags & SYNK_FLAG_CHECK_INDEX) {
+    if (!ws || ws_bytes < synk_gather_workspace_bytes() || !aligned_to(ws, 256))
+      return SYNK_ERR_WORKSPACE;
+    err_word = reinterpret_cast<uint32_t*>(ws);
+  }
+  DstTable t;
+  bool dst16 = true;
+  for (int w = 0; w < n_workers; ++w) {
+    int64_t s, n;
+    share(n_idx, n_workers, w, &s, &n);
+    if (n > 0 && (!dst[w] || (labels && !dst_labels[w]))) return SYNK_ERR_NULL;
+    if (n > 0 && !aligned_to(dst[w], dst_b)) return SYNK_ERR_ALIGN;
+    if (n > 0) dst16 = dst16 && aligned_to(dst[w], 16);
+    t.dst[w] = dst[w];
+    t.lab[w] = labels ? dst_labels[w] : nullptr;
+  }
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  if (err_word) {
+    hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, s, err_word);
+    SYNK_LAUNCH_CHECK();
+  }
+  if (n_idx == 0) return SYNK_OK;
+
+  int upb, chunks;
+  if (mode == COPY) {
+    const int64_t row_bytes = row_elems * src_b;
+    if (row_bytes % 16 == 0 && aligned_to(data, 16) && dst16) {
+      if (int rc = chunking(row_bytes / 16, &upb, &chunks)) return rc;
+      hipLaunchKernelGGL((gather_copy_kernel<u32x4>), dim3((unsigned)n_idx, chunks), dim3(kGBlock), 0,
+                         s, reinterpret_cast<const u32x4*>(data), n_rows, row_bytes / 16, idx, n_idx,
+                         t, n_workers, labels, err_word, upb);
+    } else if (row_bytes % 4 == 0 && aligned_to(data, 4)) {
+      // every dst is at least element aligned; 4-byte rows keep dwords aligned
+      bool dst4 = true;
+      for (int w = 0; w < n_workers; ++w) dst4 = dst4 && aligned_to(t.dst[w], 4);
+      if (dst4) {
+        if (int rc = chunking(row_bytes / 4, &upb, &chunks)) return rc;
+        hipLaunchKernelGGL((gather_copy_kernel<uint32_t>), dim3((unsigned)n_idx, chunks),
+                           dim3(kGBlock), 0, s, reinterpret_cast<const uint32_t*>(data), n_rows,
+                           row_bytes / 4, idx, n_idx, t, n_workers, labels, err_word, upb);
+      } else {
+        if (int rc = chunking(row_bytes, &upb, &chunks)) return rc;
+        hipLaunchKernelGGL((gather_copy_kernel<uint8_t>), dim3((unsigned)n_idx, chunks),
+                           dim3(kGBlock), 0, s, reinterpret_cast<const uint8_t*>(data), n_rows,
+                           row_bytes, idx, n_idx, t, n_workers, labels, err_word, upb);
+      }
+    } else {
+      if (int rc = chunking(row_bytes, &upb, &chunks)) return rc;
+      hipLaunchKernelGGL((gather_copy_kernel<uint8_t>), dim3((unsigned)n_idx, chunks), dim3(kGBlock),
+                         0, s, reinterpret_cast<const uint8_t*>(data), n_rows, row_bytes, idx, n_idx,
+                         t, n_workers, labels, err_word, upb);
+    }
+  } else if (mode == TO_BF16) {
+    bool dst8 = true;
+    for (int w = 0; w < n_workers; ++w) dst8 = dst8 && aligned_to(t.dst[w], 8);
+    if (row_elems % 4 == 0 && aligned_to(data, 16) && dst8) {
+      if (int rc = chunking(row_elems / 4, &upb, &chunks)) return rc;
+      hipLaunchKernelGGL((gather_bf16_kernel<true>), dim3((unsigned)n_idx, chunks), dim3(kGBlock), 0,
+                         s, reinterpret_cast<const float*>(data), n_rows, row_elems, idx, n_idx, t,
+                         n_workers, labels, err_word, upb);
+    } else {
+      if (int rc = chunking(row_elems, &upb, &chunks)) return rc;
+      hipLaunchKernelGGL((gather_bf16_kernel<false>), dim3((unsigned)n_idx, chunks), dim3(kGBlock), 0,
+                         s, reinterpret_cast<const float*>(data), n_rows, row_elems, idx, n_idx, t,
+                         n_workers, labels, err_word, upb);
+    }
+  } else {
+    const int64_t plane = row_elems / channels;
+    if (plane % 4 == 0 && aligned_to(data, 4) && dst16) {
+      if (int rc = chunking(row_elems / 4, &upb, &chunks)) return rc;
+      hipLaunchKernelGGL((gather_u8_lut_kernel<true>), dim3((unsigned)n_idx, chunks), dim3(kGBlock),
+                         0, s, reinterpret_cast<const uint8_t*>(data), n_rows, row_elems, plane, idx,
+                         n_idx, t, n_workers, lut, channels, labels, err_word, upb);
+    } else {
+      if (int rc = chunking(row_elems, &upb, &chunks)) return rc;
+      hipLaunchKernelGGL((gather_u8_lut_kernel<false>), dim3((unsigned)n_idx, chunks), dim3(kGBlock),
+                         0, s, reinterpret_cast<const uint8_t*>(data), n_rows, row_elems, plane, idx,
+                         n_idx, t, n_workers, lut, channels, labels, err_word, upb);
+    }
+  }
+  SYNK_LAUNCH_CHECK();
+  return SYNK_OK;
+}
+
+extern "C" int synk_build_norm_lut(const float* mean, const float* std, int channels, float* lut,
+                                   void* stream) {
+  if (!mean || !std || !lut) return SYNK_ERR_NULL;
+  if (channels < 1 || channels > SYNK_MAX_CHANNELS) return SYNK_ERR_SHAPE;
+  if (!aligned_to(lut, 4)) return SYNK_ERR_ALIGN;
+  LutArgs a;
+  for (int c = 0; c < SYNK_MAX_CHANNELS; ++c) {
+    a.v[c] = c < channels ? (double)mean[c] : 0.0;
+    a.v[SYNK_MAX_CHANNELS + c] = c < channels ? (double)std[c] : 1.0;
+    if (c < channels && std[c] == 0.0f) return SYNK_ERR_SHAPE;
+  }
+  hipLaunchKernelGGL(norm_lut_kernel_args, dim3(channels), dim3(256), 0,
+                     reinterpret_cast<hipStream_t>(stream), lut, channels, a);
+  SYNK_LAUNCH_CHECK();
+  return SYNK_OK;
+}
+
+extern "C" int synk_poll_error(void* ws, void* stream) {
+  if (!ws) return SYNK_ERR_NULL;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  uint32_t word = 0;
+  SYNK_HIP_TRY(hipMemcpyAsync(&word, ws, sizeof(word), hipMemcpyDeviceToHost, s));
+  SYNK_HIP_TRY(hipStreamSynchronize(s));
+  if (word) {
+    hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, s, reinterpret_cast<uint32_t*>(ws));
+    SYNK_LAUNCH_CHECK();
+    return SYNK_ERR_INDEX;
+  }
+  return SYNK_OK;
+}

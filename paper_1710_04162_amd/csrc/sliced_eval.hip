@@ -1,0 +1,284 @@
+// Six-output evaluation over slices with on-GPU aggregation (Sec. 3.1: one
+// reduce/gather op per output; Sec. 5.1: slice results aggregated in place).
+//
+// Stage 1 (one pass over the logits, bound by HBM bandwidth): one wavefront
+// per row computes arg-max, max, min and the log-sum-exp with a running
+// (max, sum) pair, merged across the 64 lanes with shuffles; a workgroup covers
+// a run of rows of ONE slice and leaves per-(slice, chunk) partial results.
+// Stage 2 folds chunk partials into slice results and slice results into the
+// outputs with each output's op, in a fixed order (no float atomics).
+#include <math.h>
+
+#include "common.h"
+
+namespace synk {
+
+constexpr int kEBlock = 256;
+constexpr int kEWaves = kEBlock / kWave;
+constexpr int kRowsPerBlock = 32;
+
+struct EvalWs {
+  float* part_ce;        // [S x CH]
+  float* part_max;       // [S x CH]
+  float* part_min;       // [S x CH]
+  int32_t* part_correct; // [S x CH]
+  int32_t* slice_counts; // [S x C]
+};
+
+static inline size_t eval_chunks(int64_t rows, int n_slices) {
+  const int64_t longest = (rows + n_slices - 1) / n_slices;
+  int64_t ch = (longest + kRowsPerBlock - 1) / kRowsPerBlock;
+  return (size_t)(ch < 1 ? 1 : ch);
+}
+
+static inline size_t eval_ws_layout(int64_t rows, int64_t classes, int n_slices, void* ws,
+                                    EvalWs* out) {
+  const size_t ch = eval_chunks(rows, n_slices);
+  const size_t part = round_up((size_t)n_slices * ch * 4, 256);
+  const size_t counts = round_up((size_t)n_slices * (size_t)classes * 4, 256);
+  if (out) {
+    char* b = reinterpret_cast<char*>(ws);
+    out->part_ce = reinterpret_cast<float*>(b);
+    out->part_max = reinterpret_cast<float*>(b + part);
+    out->part_min = reinterpret_cast<float*>(b + 2 * part);
+    out->part_correct = reinterpret_cast<int32_t*>(b + 3 * part);
+    out->slice_counts = reinterpret_cast<int32_t*>(b + 4 * part);
+  }
+  return 4 * part + counts;
+}
+
+__global__ __launch_bounds__(kEBlock) void zero_i32_kernel(int32_t* __restrict__ p, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * kEBlock;
+  for (int64_t i = (int64_t)blockIdx.x * kEBlock + threadIdx.x; i < n; i += stride) p[i] = 0;
+}
+
+struct RowStat {
+  float m;     // running max (also the row max)
+  float s;     // sum of exp(x - m)
+  float mn;    // row min
+  int arg;     // index of the first maximum
+  float xy;    // logit of the label class (0 if the label is out of range)
+};
+
+__device__ __forceinline__ void take(RowStat& st, float x, int c, int y) {
+  if (x > st.m) {
+    st.s = st.s * __expf(st.m - x) + 1.0f;
+    st.m = x;
+    st.arg = c;
+  } else {
+    st.s += __expf(x - st.m);
+  }
+  st.mn = fminf(st.mn, x);
+  if (c == y) st.xy = x;
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kEBlock) void eval_stage1_kernel(
+    const float* __restrict__ logits, const int32_t* __restrict__ labels, int64_t rows, int classes,
+    int n_slices, int chunks, EvalWs ws, int32_t* __restrict__ argmax_out) {
+  const int slice = blockIdx.y, chunk = blockIdx.x;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  // rows of this slice (split rule), then this block's run inside it
+  const int64_t base = rows / n_slices, extra = rows % n_slices;
+  const int64_t s_rows = base + (slice < extra ? 1 : 0);
+  const int64_t s_start = base * slice + (slice < extra ? slice : extra);
+  const int64_t r0 = (int64_t)chunk * kRowsPerBlock;
+  int64_t r1 = r0 + kRowsPerBlock;
+  if (r1 > s_rows) r1 = s_rows;
+
+  float w_ce = 0.0f, w_max = -INFINITY, w_min = INFINITY;
+  int w_correct = 0;
+  for (int64_t r = r0 + wave; r < r1; r += kEWaves) {
+    const int64_t row = s_start + r;
+    const float* x = logits + row * classes;
+    const int y = labels[row];
+    RowStat st{-INFINITY, 0.0f, INFINITY, 0x7fffffff, 0.0f};
+    if (VEC) {
+      const int units = classes >> 2;
+      for (int u0 = 0; u0 < units; u0 += 4 * kWave) {
+        f32x4 q[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int u = u0 + k * kWave + lane;
+          if (u < units) q[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(x) + u);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int u = u0 + k * kWave + lane;
+          if (u < units) {
+            const int c = u << 2;
+            take(st, q[k].x, c, y);
+            take(st, q[k].y, c + 1, y);
+            take(st, q[k].z, c + 2, y);
+            take(st, q[k].w, c + 3, y);
+          }
+        }
+      }
+    } else {
+      for (int c = lane; c < classes; c += kWave) take(st, x[c], c, y);
+    }
+    // merge the 64 lanes: larger max wins, equal maxima keep the lower index
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+      const float om = __shfl_xor(st.m, off);
+      const float os = __shfl_xor(st.s, off);
+      const float omn = __shfl_xor(st.mn, off);
+      const int oarg = __shfl_xor(st.arg, off);
+      const float oxy = __shfl_xor(st.xy, off);
+      const float nm = fmaxf(st.m, om);
+      // exp(-inf - finite) = 0 covers lanes that saw no element
+      const float sa = (st.m == nm) ? st.s : st.s * __expf(st.m - nm);
+      const float sb = (om == nm) ? os : os * __expf(om - nm);
+      if (om > st.m || (om == st.m && oarg < st.arg)) st.arg = oarg;
+      st.s = sa + sb;
+      st.m = nm;
+      st.mn = fminf(st.mn, omn);
+      st.xy += oxy;   // exactly one lane holds a non-zero value
+    }
+    if (lane == 0) {
+      w_ce += (__logf(st.s) + st.m) - st.xy;
+      w_max = fmaxf(w_max, st.m);
+      w_min = fminf(w_min, st.mn);
+      w_correct += (st.arg == y) ? 1 : 0;
+      argmax_out[row] = st.arg;
+      atomicAdd(ws.slice_counts + (int64_t)slice * classes + st.arg, 1);
+    }
+  }
+  __shared__ float s_ce[kEWaves], s_max[kEWaves], s_min[kEWaves];
+  __shared__ int s_cor[kEWaves];
+  if (lane == 0) {
+    s_ce[wave] = w_ce;
+    s_max[wave] = w_max;
+    s_min[wave] = w_min;
+    s_cor[wave] = w_correct;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float ce = s_ce[0], mx = s_max[0], mn = s_min[0];
+    int cor = s_cor[0];
+    for (int w = 1; w < kEWaves; ++w) {
+      ce += s_ce[w];
+      mx = fmaxf(mx, s_max[w]);
+      mn = fminf(mn, s_min[w]);
+      cor += s_cor[w];
+    }
+    const int64_t o = (int64_t)slice * chunks + chunk;
+    ws.part_ce[o] = ce;
+    ws.part_max[o] = mx;
+    ws.part_min[o] = mn;
+    ws.part_correct[o] = cor;
+  }
+}
+
+// Stage 2.  Block 0: chunk partials -> slice results (in chunk order) -> the
+// four scalar outputs with their ops over slices (fixed-shape tree).  All
+// blocks: class_counts[c] = sum over slices of the slice's count, in slice
+// order.
+__global__ __launch_bounds__(kEBlock) void eval_stage2_kernel(
+    EvalWs ws, int n_slices, int chunks, int classes, float* __restrict__ ce_sum,
+    int32_t* __restrict__ class_counts, float* __restrict__ max_logit,
+    float* __restrict__ min_logit, int32_t* __restrict__ n_correct) {
+  const int64_t stride = (int64_t)gridDim.x * kEBlock;
+  for (int64_t c = (int64_t)blockIdx.x * kEBlock + threadIdx.x; c < classes; c += stride) {
+    int32_t acc = 0;
+    for (int s = 0; s < n_slices; ++s) acc += ws.slice_counts[(int64_t)s * classes + c];
+    class_counts[c] = acc;
+  }
+  if (blockIdx.x != 0) return;
+  __shared__ float s_ce[kEBlock], s_max[kEBlock], s_min[kEBlock];
+  __shared__ int s_cor[kEBlock];
+  float ce = 0.0f, mx = -INFINITY, mn = INFINITY;
+  int cor = 0;
+  for (int s = threadIdx.x; s < n_slices; s += kEBlock) {
+    float sce = 0.0f, smx = -INFINITY, smn = INFINITY;
+    int scor = 0;
+    for (int k = 0; k < chunks; ++k) {
+      const int64_t o = (int64_t)s * chunks + k;
+      sce += ws.part_ce[o];
+      smx = fmaxf(smx, ws.part_max[o]);
+      smn = fminf(smn, ws.part_min[o]);
+      scor += ws.part_correct[o];
+    }
+    ce += sce;              // op SUM over slices
+    mx = fmaxf(mx, smx);    // op MAX
+    mn = fminf(mn, smn);    // op MIN
+    cor += scor;            // op SUM (int)
+  }
+  s_ce[threadIdx.x] = ce;
+  s_max[threadIdx.x] = mx;
+  s_min[threadIdx.x] = mn;
+  s_cor[threadIdx.x] = cor;
+  __syncthreads();
+  for (int off = kEBlock / 2; off > 0; off >>= 1) {
+    if (threadIdx.x < off) {
+      s_ce[threadIdx.x] += s_ce[threadIdx.x + off];
+      s_max[threadIdx.x] = fmaxf(s_max[threadIdx.x], s_max[threadIdx.x + off]);
+      s_min[threadIdx.x] = fminf(s_min[threadIdx.x], s_min[threadIdx.x + off]);
+      s_cor[threadIdx.x] += s_cor[threadIdx.x + off];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    ce_sum[0] = s_ce[0];
+    max_logit[0] = s_max[0];
+    min_logit[0] = s_min[0];
+    n_correct[0] = s_cor[0];
+  }
+}
+
+}  // namespace synk
+
+using namespace synk;
+
+static int eval_check(int64_t rows, int64_t classes, int n_slices) {
+  if (rows < 1 || classes < 1 || classes > 4096 || n_slices < 1) return SYNK_ERR_SHAPE;
+  if (n_slices > 65535) return SYNK_ERR_UNSUPPORTED;
+  if (eval_chunks(rows, n_slices) > 0x7fffffffULL) return SYNK_ERR_UNSUPPORTED;
+  return SYNK_OK;
+}
+
+extern "C" int synk_sliced_eval_workspace_bytes(int64_t rows, int64_t classes, int n_slices,
+                                                size_t* bytes) {
+  if (!bytes) return SYNK_ERR_NULL;
+  if (int rc = eval_check(rows, classes, n_slices)) return rc;
+  *bytes = eval_ws_layout(rows, classes, n_slices, nullptr, nullptr);
+  return SYNK_OK;
+}
+
+extern "C" int synk_sliced_eval(const float* logits, const int32_t* labels, int64_t rows,
+                                int64_t classes, int n_slices, float* ce_sum,
+                                int32_t* class_counts, float* max_logit, float* min_logit,
+                                int32_t* n_correct, int32_t* argmax, void* ws, size_t ws_bytes,
+                                void* stream) {
+  if (!logits || !labels || !ce_sum || !class_counts || !max_logit || !min_logit || !n_correct ||
+      !argmax)
+    return SYNK_ERR_NULL;
+  if (int rc = eval_check(rows, classes, n_slices)) return rc;
+  if (!aligned_to(logits, 4) || !aligned_to(labels, 4) || !aligned_to(argmax, 4) ||
+      !aligned_to(class_counts, 4) || !aligned_to(ce_sum, 4) || !aligned_to(max_logit, 4) ||
+      !aligned_to(min_logit, 4) || !aligned_to(n_correct, 4))
+    return SYNK_ERR_ALIGN;
+  EvalWs w;
+  const size_t need = eval_ws_layout(rows, classes, n_slices, ws, &w);
+  if (!ws || !aligned_to(ws, 256) || ws_bytes < need) return SYNK_ERR_WORKSPACE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const int chunks = (int)eval_chunks(rows, n_slices);
+  const int64_t n_counts = (int64_t)n_slices * classes;
+  int zb = (int)((n_counts + kEBlock - 1) / kEBlock);
+  if (zb > kNumCU * 8) zb = kNumCU * 8;
+  hipLaunchKernelGGL(zero_i32_kernel, dim3(zb), dim3(kEBlock), 0, s, w.slice_counts, n_counts);
+  SYNK_LAUNCH_CHECK();
+  const dim3 grid(chunks, n_slices);
+  if (classes % 4 == 0 && aligned_to(logits, 16))
+    hipLaunchKernelGGL((eval_stage1_kernel<true>), grid, dim3(kEBlock), 0, s, logits, labels, rows,
+                       (int)classes, n_slices, chunks, w, argmax);
+  else
+    hipLaunchKernelGGL((eval_stage1_kernel<false>), grid, dim3(kEBlock), 0, s, logits, labels, rows,
+                       (int)classes, n_slices, chunks, w, argmax);
+  SYNK_LAUNCH_CHECK();
+  int b2 = (int)((classes + kEBlock - 1) / kEBlock);
+  hipLaunchKernelGGL(eval_stage2_kernel, dim3(b2), dim3(kEBlock), 0, s, w, n_slices, chunks,
+                     (int)classes, ce_sum, class_counts, max_logit, min_logit, n_correct);
+  SYNK_LAUNCH_CHECK();
+  return SYNK_OK;
+}

@@ -1,0 +1,34 @@
+// Version, status strings and the host-side split rule.
+#include "common.h"
+
+extern "C" int synk_version(void) { return SYNK_VERSION; }
+
+extern "C" const char* synk_status_string(int status) {
+  switch (status) {
+    case SYNK_OK: return "ok";
+    case SYNK_ERR_NULL: return "a required pointer is NULL";
+    case SYNK_ERR_SHAPE: return "a size or count is out of range or inconsistent";
+    case SYNK_ERR_DTYPE: return "element type not supported by this call";
+    case SYNK_ERR_OP: return "reduce op unknown or not defined for the element type";
+    case SYNK_ERR_ALIGN: return "a device pointer is not aligned as documented";
+    case SYNK_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SYNK_ERR_INDEX: return "an index was out of range";
+    case SYNK_ERR_HIP: return "a HIP runtime call failed";
+    case SYNK_ERR_UNSUPPORTED: return "request outside what is implemented";
+    default: return "unknown status";
+  }
+}
+
+// Sec. 3.2 step 1 / Sec. 5.1: contiguous, as equal as possible, remainder to
+// the first shares.
+extern "C" int synk_split(int64_t count, int parts, int64_t* start) {
+  if (!start) return SYNK_ERR_NULL;
+  if (count < 0 || parts <= 0) return SYNK_ERR_SHAPE;
+  for (int i = 0; i < parts; ++i) {
+    int64_t s, n;
+    synk::share(count, parts, i, &s, &n);
+    start[i] = s;
+  }
+  start[parts] = count;
+  return SYNK_OK;
+}

@@ -1,0 +1,162 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header
+declares, and rejects bad arguments on the host before any HIP call."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import split as osplit
+from paper_1710_04162_amd import binding as synk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000        # a non-NULL, 16-byte aligned value never dereferenced by the checks
+lib = synk.lib
+
+
+def test_every_declared_symbol_is_exported():
+    text = open(os.path.join(ROOT, "include", "synk.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(synk_[a-z0-9_]+)\s*\(", text))
+    assert {"synk_gather_rows", "synk_sliced_grad", "synk_reduce_buffers", "synk_sgd_update",
+            "synk_reduce_sgd_update", "synk_sliced_eval"} <= names
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+    assert synk.synk_version() == 100
+    assert synk.synk_status_string(0) == "ok" and "NULL" in synk.synk_status_string(-1)
+
+
+@pytest.mark.parametrize("count,parts", [(0, 3), (7, 3), (256, 2), (1024, 8), (5, 8), (100, 7)])
+def test_split_rule_matches_oracle(count, parts):
+    got = synk.synk_split(count, parts)
+    ref = [a for a, _ in osplit.share_bounds(count, parts)] + [count]
+    assert got == ref
+
+
+def test_split_rejects_bad_arguments():
+    out = (ctypes.c_int64 * 4)()
+    assert lib.synk_split(5, 0, out) == -2
+    assert lib.synk_split(-1, 2, out) == -2
+    assert lib.synk_split(5, 2, None) == -1
+
+
+def _tbl(*vals):
+    return (ctypes.c_void_p * len(vals))(*vals)
+
+
+def test_reduce_buffers_argument_checks():
+    f = lib.synk_reduce_buffers
+    two = _tbl(FAKE, FAKE)
+    assert f(None, 2, 8, 2, 0, None, None, FAKE, None) == -1
+    assert f(two, 2, 8, 2, 0, None, None, None, None) == -1
+    assert f(two, 0, 8, 2, 0, None, None, FAKE, None) == -2
+    assert f(two, 65, 8, 2, 0, None, None, FAKE, None) == -2
+    assert f(two, 2, -1, 2, 0, None, None, FAKE, None) == -2
+    assert f(two, 2, 8, 0, 0, None, None, FAKE, None) == -3          # U8 not supported
+    assert f(two, 2, 8, 2, 9, None, None, FAKE, None) == -4
+    assert f(two, 2, 8, 1, 1, None, None, FAKE, None) == -4          # MEAN on I32
+    w = (ctypes.c_float * 2)(0.5, 0.5)
+    assert f(two, 2, 8, 2, 0, w, None, FAKE, None) == -4             # weights only with MEAN
+    assert f(two, 2, 8, 2, 5, None, None, FAKE, None) == -1          # CONCAT needs lens
+    assert f(_tbl(FAKE, FAKE + 2), 2, 8, 2, 0, None, None, FAKE, None) == -5
+    assert f(_tbl(FAKE, None), 2, 8, 2, 0, None, None, FAKE, None) == -1
+    assert f(two, 2, 0, 2, 0, None, None, FAKE, None) == 0           # empty: no-op, no launch
+
+
+def test_update_argument_checks():
+    f = lib.synk_sgd_update
+    assert f(None, FAKE, FAKE, 8, 0.1, 0.9, 0.0, None, None) == -1
+    assert f(FAKE, FAKE, FAKE, -1, 0.1, 0.9, 0.0, None, None) == -2
+    assert f(FAKE + 4, FAKE, FAKE, 8, 0.1, 0.9, 0.0, None, None) == -5
+    assert f(FAKE, FAKE, FAKE, 0, 0.1, 0.9, 0.0, None, None) == 0
+    h = lib.synk_reduce_sgd_update
+    two = _tbl(FAKE, FAKE)
+    assert h(two, 2, 8, None, FAKE, None, 0.1, 0.9, 0.0, None, None, None, None) == -1
+    assert h(two, 0, 8, None, FAKE, FAKE, 0.1, 0.9, 0.0, None, None, None, None) == -2
+    assert h(two, 2, 8, None, FAKE, FAKE, 0.1, 0.9, 0.0, None, FAKE, None, None) == -1   # loss pair
+    assert h(_tbl(FAKE, FAKE + 8), 2, 8, None, FAKE, FAKE, 0.1, 0.9, 0.0, None, None, None, None) == -5
+    assert h(two, 2, 0, None, FAKE, FAKE, 0.1, 0.9, 0.0, None, None, None, None) == 0
+    assert lib.synk_cast_bf16(None, FAKE, 4, None) == -1
+    assert lib.synk_cast_bf16(FAKE, FAKE + 1, 4, None) == -5
+
+
+def test_gather_argument_checks():
+    f = lib.synk_gather_rows
+    d2 = _tbl(FAKE, FAKE)
+
+    def call(data=FAKE, n_rows=10, row_elems=8, src=2, idx=FAKE, n_idx=4, dst=d2, nw=2, dd=2, lut=None,
+             ch=0, labels=None, dl=None, flags=0, ws=None, wsb=0):
+        return f(data, n_rows, row_elems, src, idx, n_idx, dst, nw, dd, lut, ch, labels, dl, flags, ws,
+                 wsb, None)
+
+    assert call(data=None) == -1 and call(idx=None) == -1 and call(dst=None) == -1
+    assert call(labels=FAKE) == -1                       # labels without dst_labels
+    assert call(row_elems=0) == -2 and call(n_idx=-1) == -2 and call(nw=0) == -2 and call(nw=65) == -2
+    assert call(src=7) == -3 and call(src=1, dd=2) == -3          # I32 -> F32 is not a listed pair
+    assert call(src=0, dd=2) == -1                       # U8 -> F32 needs the table
+    assert call(src=0, dd=2, lut=FAKE, ch=3) == -2       # 8 % 3 != 0
+    assert call(src=0, dd=2, lut=FAKE, ch=17) == -2
+    assert call(flags=1) == -6                           # flag without workspace
+    assert call(dst=_tbl(FAKE, None)) == -1              # non-empty share without a buffer
+    assert call(dst=_tbl(FAKE, FAKE + 2)) == -5
+    assert lib.synk_build_norm_lut(None, None, 3, FAKE, None) == -1
+    m = (ctypes.c_float * 3)(1, 2, 3)
+    z = (ctypes.c_float * 3)(1, 0, 3)
+    assert lib.synk_build_norm_lut(m, z, 3, FAKE, None) == -2      # std == 0
+    assert lib.synk_build_norm_lut(m, m, 17, FAKE, None) == -2
+    assert lib.synk_poll_error(None, None) == -1
+
+
+def test_sliced_grad_argument_checks_and_workspace():
+    dims = [20, 16, 10]
+    assert synk.synk_mlp_param_count(dims) == 20 * 16 + 16 + 16 * 10 + 10
+    assert synk.synk_mlp_param_count([3072, 1024, 1024, 10]) == 4206602
+    b32 = synk.synk_sliced_grad_workspace_bytes(dims, synk.SYNK_F32, [5, 0, 7])
+    b16 = synk.synk_sliced_grad_workspace_bytes(dims, synk.SYNK_BF16, [5, 0, 7])
+    assert b32 > b16 > 0 and b32 % 256 == 0
+    with pytest.raises(synk.SynkError) as e:
+        synk.synk_sliced_grad_workspace_bytes(dims, synk.SYNK_F32, [0, 0])
+    assert e.value.status == -2
+    with pytest.raises(synk.SynkError):
+        synk.synk_sliced_grad_workspace_bytes([20, 0, 10], synk.SYNK_F32, [4])
+    with pytest.raises(synk.SynkError) as e:
+        synk.synk_sliced_grad_workspace_bytes(dims, synk.SYNK_U8, [4])
+    assert e.value.status == -3
+
+    f = lib.synk_sliced_grad
+    d = synk._desc(dims, synk.SYNK_F32)
+    rows = (ctypes.c_int64 * 2)(4, 4)
+    t2 = _tbl(FAKE, FAKE)
+
+    def call(desc=d, params=FAKE, lp=None, x=t2, y=t2, r=rows, nw=2, ns=2, op=1, grad=t2, loss=FAKE,
+             ws=FAKE, wsb=1 << 30):
+        return f(ctypes.byref(desc), params, lp, x, y, r, nw, ns, op, grad, loss, ws, wsb, None)
+
+    assert call(params=None) == -1 and call(x=None) == -1 and call(loss=None) == -1
+    assert call(ns=0) == -2 and call(nw=0) == -2
+    assert call(op=2) == -4
+    assert call(desc=synk._desc(dims, synk.SYNK_BF16)) == -1          # bf16 needs params_lp
+    assert call(ws=None) == -6 and call(wsb=16) == -6 and call(ws=FAKE + 16) == -6
+    assert call(grad=_tbl(FAKE, FAKE + 2)) == -5
+    assert call(x=_tbl(FAKE, None)) == -1
+
+
+def test_sliced_eval_argument_checks_and_workspace():
+    assert synk.synk_sliced_eval_workspace_bytes(65536, 1000, 64) >= 64 * 1000 * 4
+    for bad in [(0, 10, 1), (10, 0, 1), (10, 5000, 1), (10, 10, 0)]:
+        with pytest.raises(synk.SynkError) as e:
+            synk.synk_sliced_eval_workspace_bytes(*bad)
+        assert e.value.status == -2
+    f = lib.synk_sliced_eval
+    assert f(None, FAKE, 8, 4, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 20, None) == -1
+    assert f(FAKE, FAKE, 8, 4, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, None) == -6
+    assert f(FAKE, FAKE, 8, 4, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 8, None) == -6
+    assert f(FAKE + 1, FAKE, 8, 4, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 20, None) == -5
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    t = torch.zeros(8)
+    with pytest.raises(ValueError):
+        synk.synk_sgd_update(t, t, t, 0.1, 0.9)

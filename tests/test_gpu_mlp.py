@@ -1,0 +1,227 @@
+"""GPU parity of the sliced gradient function and of the whole synchronous-SGD
+step (gather -> sliced grad -> reduce -> momentum update) against the CPU
+oracle, through the C ABI.
+
+fp32 cases are held to 1e-4, bf16-input cases to 2e-2, both as per-tensor
+max|got-ref|/max|ref|.  For bf16 the reference is the oracle with its values
+rounded to bfloat16 at the same points as the kernels (the distance of that
+reference to the all-float64 one is a property of bf16 inputs, checked on the
+CPU).  A hidden pre-activation that is zero up to accumulation rounding has two
+valid relu derivatives; for the column of such a unit either is accepted."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from helpers import TOL_BF16, TOL_F32, rel_err, rel_err_either_tie, tie_columns
+from oracle import gather as ogather, mlp as omlp, split as osplit, update as oupdate
+
+pytestmark = pytest.mark.gpu
+
+TIE_EPS = {"f32": 2e-6, "bf16": 1e-4}
+
+
+@pytest.fixture(scope="module")
+def synk():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1710_04162_amd import binding
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+class Step:
+    """Device state of one training setup; every compute step is a libsynk call."""
+
+    def __init__(self, synk, cfg):
+        self.s, self.cfg = synk, cfg
+        self.dims = cfg["dims"]
+        self.bf16 = cfg["compute"] == "bf16"
+        self.cd = synk.SYNK_BF16 if self.bf16 else synk.SYNK_F32
+        self.P = synk.synk_mlp_param_count(self.dims)
+        self.data, self.labels = dev(cfg["data"]), dev(cfg["labels"])
+        self.p = dev(cfg["theta"])
+        self.v = torch.zeros(self.P, device="cuda")
+        self.p_lp = torch.zeros(self.P, dtype=torch.bfloat16, device="cuda") if self.bf16 else None
+        if self.bf16:
+            synk.synk_cast_bf16(self.p, self.p_lp)
+
+    def gather(self, idx, n_workers):
+        B = len(idx)
+        self.rows = osplit.share_sizes(B, n_workers)
+        xdt = torch.bfloat16 if self.bf16 else torch.float32
+        self.x = [torch.zeros((n, self.dims[0]), dtype=xdt, device="cuda") for n in self.rows]
+        self.y = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in self.rows]
+        self.s.synk_gather_rows(self.data, dev(idx), self.x, labels=self.labels, dst_labels=self.y)
+
+    def sliced_grad(self, n_slices, op):
+        n = len(self.rows)
+        self.grad = [torch.full((self.P,), 123.0, device="cuda") for _ in range(n)]
+        self.loss = torch.full((n,), -1.0, device="cuda")
+        ws = torch.empty(self.s.synk_sliced_grad_workspace_bytes(self.dims, self.cd, self.rows),
+                         dtype=torch.uint8, device="cuda")
+        self.s.synk_sliced_grad(self.dims, self.cd, self.p, self.p_lp, self.x, self.y, self.rows, n_slices,
+                                self.s.OP[op], self.grad, self.loss, ws)
+        torch.cuda.synchronize()
+        return [g.cpu().numpy() for g in self.grad], self.loss.cpu().numpy()
+
+    def update(self):
+        c = self.cfg
+        self.loss_out = torch.zeros(1, device="cuda")
+        self.s.synk_reduce_sgd_update(self.grad, self.p, self.v, c["lr"], c["momentum"], c["weight_decay"],
+                                      p_lp=self.p_lp, loss_in=self.loss, loss_out=self.loss_out)
+        torch.cuda.synchronize()
+
+
+def small_cfg(dims, n_data, compute, seed):
+    rng = np.random.default_rng(seed)
+    return dict(dims=list(dims), compute=compute,
+                data=rng.standard_normal((n_data, dims[0])).astype(np.float32),
+                labels=rng.integers(0, dims[-1], n_data).astype(np.int32),
+                theta=workloads.mlp_init(dims, rng) + (rng.standard_normal(workloads.mlp_param_count(dims)) * 0.05).astype(np.float32),
+                lr=0.01, momentum=0.9, weight_decay=0.0)
+
+
+def worker_refs(cfg, idx, n_workers, bf16):
+    """Per worker: oracle gradient of the unsliced call on the share (what
+    mean-aggregated slices must equal), the other-relu-derivative variant, the
+    columns to skip and the loss."""
+    eps = TIE_EPS["bf16" if bf16 else "f32"]
+    out = []
+    for (a, b) in osplit.share_bounds(len(idx), n_workers):
+        X = ogather.gather_rows(cfg["data"], idx[a:b]); y = ogather.gather_rows(cfg["labels"], idx[a:b])
+        tr = []
+        l, g = omlp.function(cfg["theta"], cfg["dims"], X, y, bf16_points=bf16, trace=tr)
+        _, ga = omlp.function(cfg["theta"], cfg["dims"], X, y, bf16_points=bf16, tie_eps=eps, flip_ties=True)
+        skip, n_ties = tie_columns(tr, eps)
+        out.append(dict(loss=l, grad=g, alt=ga, skip=skip, ties=n_ties))
+    return out
+
+
+@pytest.mark.parametrize("dims,B,N,S,op", [
+    ([20, 16, 10], 12, 3, 2, "mean"),
+    ([20, 16, 10], 13, 3, 3, "mean"),     # ragged shares and ragged slices
+    ([20, 16, 10], 13, 3, 3, "sum"),
+    ([20, 16, 10], 2, 3, 2, "mean"),      # a worker with no rows, slices with no rows
+    ([13, 7, 5], 9, 2, 2, "mean"),        # nothing 16-byte aligned: element-wise loads
+    ([40, 72, 24, 8], 70, 2, 4, "mean"),  # two hidden layers, several 64-wide tiles, ragged tails
+    ([33, 10], 17, 2, 2, "sum"),          # no hidden layer
+])
+def test_sliced_grad_fp32_matches_sliced_oracle(synk, dims, B, N, S, op):
+    cfg = small_cfg(dims, 64, "f32", sum(dims) + B)
+    idx = np.random.default_rng(B).integers(0, 64, B).astype(np.int32)
+    st = Step(synk, cfg)
+    st.gather(idx, N)
+    grads, losses = st.sliced_grad(S, op)
+    ref = omlp.sliced(cfg["theta"], dims, cfg["data"], cfg["labels"], idx, N, S, op)
+    assert sum(r["ties"] for r in worker_refs(cfg, idx, N, False)) == 0    # nothing sits on a relu kink
+    for w in range(N):
+        if st.rows[w] == 0:
+            assert np.all(grads[w] == 0.0) and losses[w] == 0.0
+            continue
+        assert rel_err(grads[w], ref["worker_grads"][w]) < TOL_F32, w
+        assert abs(losses[w] - ref["worker_losses"][w]) < TOL_F32 * abs(ref["worker_losses"][w])
+
+
+@pytest.mark.parametrize("dims,B,N,S", [
+    ([64, 48, 32, 10], 50, 3, 2),
+    ([256, 136, 10], 300, 2, 4),      # several tiles in every direction, ragged
+])
+def test_sliced_grad_bf16_small(synk, dims, B, N, S):
+    cfg = small_cfg(dims, 400, "bf16", sum(dims))
+    idx = np.random.default_rng(B).integers(0, 400, B).astype(np.int32)
+    st = Step(synk, cfg)
+    st.gather(idx, N)
+    grads, losses = st.sliced_grad(S, "mean")
+    for w, r in enumerate(worker_refs(cfg, idx, N, True)):
+        e = rel_err_either_tie(grads[w], r["grad"], r["alt"], dims, r["skip"])
+        assert e < TOL_BF16, (w, e)
+        assert abs(losses[w] - r["loss"]) < TOL_BF16 * abs(r["loss"])
+
+
+def test_slice_count_does_not_change_mean_aggregated_result(synk):
+    cfg = small_cfg([40, 32, 10], 100, "f32", 1)
+    idx = np.random.default_rng(2).integers(0, 100, 48).astype(np.int32)
+    st = Step(synk, cfg)
+    st.gather(idx, 2)
+    g1, l1 = st.sliced_grad(1, "mean")
+    g5, l5 = st.sliced_grad(5, "mean")
+    for w in range(2):
+        assert rel_err(g5[w], g1[w]) < 1e-6 and abs(l5[w] - l1[w]) < 1e-6 * abs(l1[w])
+
+
+def full_step_check(synk, cfg, tol, bf16):
+    dims, idx, N, S = cfg["dims"], cfg["idx"], cfg["n_workers"], cfg["n_slices"]
+    st = Step(synk, cfg)
+    st.gather(idx, N)
+    grads, losses = st.sliced_grad(S, "mean")
+    refs = worker_refs(cfg, idx, N, bf16)
+    worst = 0.0
+    for w, r in enumerate(refs):
+        e = rel_err_either_tie(grads[w], r["grad"], r["alt"], dims, r["skip"])
+        worst = max(worst, e)
+        assert e < tol, ("worker grad", w, e)
+        assert abs(losses[w] - r["loss"]) < tol * abs(r["loss"])
+    st.update()
+    v0 = np.zeros_like(cfg["theta"])
+    rp, rv, rG, rl = oupdate.reduce_and_update(cfg["theta"], v0, [r["grad"] for r in refs], cfg["lr"],
+                                               cfg["momentum"], cfg["weight_decay"], None, [r["loss"] for r in refs])
+    ap, av, _, _ = oupdate.reduce_and_update(cfg["theta"], v0, [r["alt"] for r in refs], cfg["lr"],
+                                             cfg["momentum"], cfg["weight_decay"])
+    skip = {}
+    for r in refs:
+        for k, cols in r["skip"].items():
+            skip.setdefault(k, set()).update(cols)
+    assert rel_err_either_tie(st.p.cpu().numpy(), rp, ap, dims, skip) < tol
+    # a tie in one worker moves only that worker's share of v: the bound is per tensor as before
+    assert rel_err_either_tie(st.v.cpu().numpy(), rv, av, dims, skip) < tol
+    assert abs(st.loss_out.item() - rl) < tol * abs(rl)
+    if bf16:
+        want = ogather.round_to_bf16(st.p.cpu().numpy())
+        assert np.array_equal(st.p_lp.float().cpu().numpy().view(np.uint32), want.view(np.uint32))
+    return worst, sum(r["ties"] for r in refs)
+
+
+def test_full_step_config1_fp32(synk):
+    cfg = workloads.config1()
+    worst, ties = full_step_check(synk, cfg, TOL_F32, False)
+    print("config1 worst worker-gradient error %.2e, near-zero pre-activations %d" % (worst, ties))
+
+
+def test_full_step_config2_bf16_reduced(synk):
+    cfg = workloads.config2(n_data=2000, batch=96, dims=(512, 256, 128, 10), n_workers=4, n_slices=3)
+    worst, ties = full_step_check(synk, cfg, TOL_BF16, True)
+    print("config2 (reduced) worst error %.2e, ties %d" % (worst, ties))
+
+
+def test_full_step_config2_bf16_full_size(synk):
+    cfg = workloads.config2(n_data=8192)       # full model, batch, workers and slices; fewer dataset rows
+    worst, ties = full_step_check(synk, cfg, TOL_BF16, True)
+    print("config2 worst worker-gradient error %.2e, near-zero pre-activations %d" % (worst, ties))
+
+
+def test_two_steps_feed_the_updated_parameters_forward(synk):
+    cfg = workloads.config1(n_data=1024, batch=128)
+    st = Step(synk, cfg)
+    theta, v = cfg["theta"].astype(np.float64), np.zeros(len(cfg["theta"]))
+    rng = np.random.default_rng(3)
+    for step in range(2):
+        idx = rng.permutation(1024)[:128].astype(np.int32)
+        st.gather(idx, 2)
+        st.sliced_grad(4, "mean")
+        st.update()
+        r = omlp.sliced(theta, cfg["dims"], cfg["data"], cfg["labels"], idx, 2, 4)
+        theta, v, _, _ = oupdate.reduce_and_update(theta, v, r["worker_grads"], 0.01, 0.9)
+    assert rel_err(st.p.cpu().numpy(), theta) < TOL_F32
+    assert rel_err(st.v.cpu().numpy(), v) < 10 * TOL_F32   # second-step v carries first-step rounding of p
+
+
+def test_sliced_grad_is_bit_reproducible(synk):
+    cfg = workloads.config2(n_data=1000, batch=128, dims=(256, 128, 64, 10), n_workers=4, n_slices=2)
+    st = Step(synk, cfg)
+    st.gather(cfg["idx"], 4)
+    g1, l1 = st.sliced_grad(2, "mean")
+    g2, l2 = st.sliced_grad(2, "mean")
+    assert all(np.array_equal(a, b) for a, b in zip(g1, g2)) and np.array_equal(l1, l2)

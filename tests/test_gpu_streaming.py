@@ -1,0 +1,271 @@
+"""GPU parity of the data-movement and streaming kernels (gather, reduce,
+update, six-output evaluation) against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from helpers import TOL_F32, rel_err
+from oracle import evalops, gather as ogather, reduce as oreduce, split as osplit, update as oupdate
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def synk():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1710_04162_amd import binding
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def share_sizes(n, parts):
+    return osplit.share_sizes(n, parts)
+
+
+# ------------------------------------------------------------------ gather
+@pytest.mark.parametrize("n_data,row,batch,n_workers,dtype", [
+    (300, 784, 256, 2, np.float32),      # config-1 rows (16-byte path)
+    (64, 3072, 100, 8, np.float32),      # config-2 rows, ragged shares (100 = 8*12+4)
+    (50, 7, 33, 4, np.float32),          # 28-byte rows: 4-byte path
+    (40, 13, 9, 16, np.uint8),           # odd byte rows, more workers than some shares
+    (20, 5000, 8, 3, np.int32),          # several chunks per row
+    (10, 16, 0, 2, np.float32),          # empty index list
+])
+def test_gather_copy_bit_exact(synk, n_data, row, batch, n_workers, dtype):
+    rng = np.random.default_rng(n_data * 7 + row)
+    data = (rng.standard_normal((n_data, row)) * 100).astype(dtype)
+    labels = rng.integers(0, 1000, n_data).astype(np.int32)
+    idx = rng.integers(0, n_data, batch).astype(np.int32)        # duplicates allowed
+    sizes = share_sizes(batch, n_workers)
+    tdt = torch.from_numpy(np.zeros(1, dtype)).dtype
+    dst = [torch.full((max(n, 1), row), 77, dtype=tdt, device="cuda")[:n] for n in sizes]
+    dl = [torch.full((max(n, 1),), -5, dtype=torch.int32, device="cuda")[:n] for n in sizes]
+    synk.synk_gather_rows(dev(data), dev(idx), dst, labels=dev(labels), dst_labels=dl)
+    torch.cuda.synchronize()
+    ref = ogather.gather_shares(data, idx, n_workers)
+    refl = ogather.gather_shares(labels, idx, n_workers)
+    for w in range(n_workers):
+        assert np.array_equal(dst[w].cpu().numpy(), ref[w]), w
+        assert np.array_equal(dl[w].cpu().numpy(), refl[w]), w
+
+
+def test_gather_identity_and_permutation(synk):
+    rng = np.random.default_rng(5)
+    data = rng.standard_normal((128, 96)).astype(np.float32)
+    out = [torch.empty((128, 96), device="cuda")]
+    synk.synk_gather_rows(dev(data), dev(np.arange(128, dtype=np.int32)), out)
+    assert np.array_equal(out[0].cpu().numpy(), data)
+    perm = rng.permutation(128).astype(np.int32)
+    synk.synk_gather_rows(dev(data), dev(perm), out)
+    assert np.array_equal(out[0].cpu().numpy(), data[perm])
+
+
+@pytest.mark.parametrize("row,n_workers", [(3072, 8), (10, 3)])
+def test_gather_to_bf16_bit_exact(synk, row, n_workers):
+    rng = np.random.default_rng(row)
+    data = rng.random((77, row), dtype=np.float32)
+    data[0, :4] = [1.00390625, 1.01171875, 0.0, 3.0e38]      # ties to even, both directions
+    idx = rng.integers(0, 77, 50).astype(np.int32)
+    idx[0] = 0
+    sizes = share_sizes(50, n_workers)
+    dst = [torch.zeros((n, row), dtype=torch.bfloat16, device="cuda") for n in sizes]
+    synk.synk_gather_rows(dev(data), dev(idx), dst)
+    ref = [ogather.round_to_bf16(r) for r in ogather.gather_shares(data, idx, n_workers)]
+    for w in range(n_workers):
+        got = dst[w].float().cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), ref[w].view(np.uint32)), w
+
+
+@pytest.mark.parametrize("chw,batch,n_workers", [((3, 224, 224), 16, 8), ((3, 5, 7), 10, 4), ((1, 8, 8), 5, 2)])
+def test_gather_u8_normalise_bit_exact(synk, chw, batch, n_workers):
+    c = workloads.config4(n_data=24, batch=batch, chw=chw, n_workers=n_workers)
+    lut = torch.empty(chw[0] * 256, device="cuda")
+    synk.synk_build_norm_lut(c["mean"], c["std"], lut)
+    sizes = share_sizes(batch, n_workers)
+    dst = [torch.zeros((n,) + chw, device="cuda") for n in sizes]
+    dl = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in sizes]
+    synk.synk_gather_rows(dev(c["data"]), dev(c["idx"]), dst, lut=lut, channels=chw[0],
+                          labels=dev(c["labels"]), dst_labels=dl)
+    raw = ogather.gather_shares(c["data"], c["idx"], n_workers)
+    refl = ogather.gather_shares(c["labels"], c["idx"], n_workers)
+    for w in range(n_workers):
+        ref = ogather.normalise_u8(raw[w], c["mean"], c["std"])
+        assert np.array_equal(dst[w].cpu().numpy().view(np.uint32), ref.view(np.uint32)), w
+        assert np.array_equal(dl[w].cpu().numpy(), refl[w])
+
+
+def test_gather_out_of_range_index_is_skipped_and_reported(synk):
+    data = np.arange(40, dtype=np.float32).reshape(10, 4)
+    idx = np.array([3, 10, -1, 9], dtype=np.int32)
+    dst = [torch.full((4, 4), -1.0, device="cuda")]
+    ws = torch.zeros(synk.synk_gather_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    synk.synk_gather_rows(dev(data), dev(idx), dst, flags=synk.SYNK_FLAG_CHECK_INDEX, ws=ws)
+    assert synk.synk_poll_error(ws) == -7
+    got = dst[0].cpu().numpy()
+    assert np.array_equal(got[0], data[3]) and np.array_equal(got[3], data[9])
+    assert np.all(got[1:3] == -1.0)
+    synk.synk_gather_rows(dev(data), dev(np.array([1, 2], np.int32)), dst, flags=synk.SYNK_FLAG_CHECK_INDEX, ws=ws)
+    assert synk.synk_poll_error(ws) == 0
+
+
+# ------------------------------------------------------------------ reduce
+@pytest.mark.parametrize("n,length", [(1, 5), (2, 1024), (3, 1027), (8, 4099), (5, 3)])
+@pytest.mark.parametrize("op", ["sum", "mean", "max", "min", "prod"])
+def test_reduce_float_ops(synk, n, length, op):
+    rng = np.random.default_rng(n * 100 + length)
+    bufs = [rng.uniform(0.5, 2.0, length).astype(np.float32) * rng.choice([-1, 1], length).astype(np.float32)
+            for _ in range(n)]
+    out = torch.empty(length, device="cuda")
+    synk.synk_reduce_buffers([dev(b) for b in bufs], synk.OP[op], out)
+    ref = oreduce.reduce_buffers(bufs, op)
+    got = out.cpu().numpy()
+    if op in ("max", "min"):
+        assert np.array_equal(got, ref.astype(np.float32))
+    else:
+        assert rel_err(got, ref) < TOL_F32
+
+
+def test_reduce_weighted_mean_unaligned_and_bit_exact_cases(synk):
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(1001).astype(np.float32)
+    for n in (1, 2, 4, 8):      # the average of N equal buffers is the buffer, bit for bit
+        out = torch.empty(1001, device="cuda")
+        synk.synk_reduce_buffers([dev(x) for _ in range(n)], synk.SYNK_MEAN, out)
+        assert np.array_equal(out.cpu().numpy(), x)
+    out = torch.empty(1001, device="cuda")
+    synk.synk_reduce_buffers([dev(x), dev(-x)], synk.SYNK_SUM, out)
+    assert np.all(out.cpu().numpy() == 0.0)
+    # buffers that are only 4-byte aligned take the scalar path
+    big = [dev(np.r_[np.float32(0), rng.standard_normal(515).astype(np.float32)]) for _ in range(3)]
+    views = [b[1:] for b in big]
+    w = [0.2, 0.3, 0.5]
+    out = torch.empty(516, device="cuda")[1:]
+    synk.synk_reduce_buffers(views, synk.SYNK_MEAN, out, weights=w)
+    ref = oreduce.reduce_buffers([v.cpu().numpy() for v in views], "mean", w)
+    assert rel_err(out.cpu().numpy(), ref) < TOL_F32
+
+
+@pytest.mark.parametrize("op", ["sum", "max", "min", "prod"])
+def test_reduce_int_ops_exact(synk, op):
+    rng = np.random.default_rng(4)
+    hi = 6 if op == "prod" else 100000
+    bufs = [rng.integers(-hi, hi, 1003).astype(np.int32) for _ in range(5)]
+    out = torch.empty(1003, dtype=torch.int32, device="cuda")
+    synk.synk_reduce_buffers([dev(b) for b in bufs], synk.OP[op], out)
+    assert np.array_equal(out.cpu().numpy().astype(np.int64), oreduce.reduce_buffers(bufs, op))
+
+
+def test_reduce_concat(synk):
+    rng = np.random.default_rng(6)
+    for dt, tdt in ((np.float32, torch.float32), (np.int32, torch.int32)):
+        bufs = [(rng.standard_normal(n) * 1000).astype(dt) for n in (5, 0, 1300, 1)]
+        out = torch.zeros(1306, dtype=tdt, device="cuda")
+        synk.synk_reduce_buffers([dev(b) if b.size else torch.empty(0, dtype=tdt, device="cuda") for b in bufs],
+                                 synk.SYNK_CONCAT, out)
+        assert np.array_equal(out.cpu().numpy(), oreduce.reduce_buffers(bufs, "concat"))
+
+
+# ------------------------------------------------------------------ update
+@pytest.mark.parametrize("length", [1, 4, 1027, 203530])
+def test_sgd_update(synk, length):
+    rng = np.random.default_rng(length)
+    p = (rng.standard_normal(length) * 0.05).astype(np.float32)
+    v = (rng.standard_normal(length) * 0.01).astype(np.float32)
+    g = (rng.standard_normal(length) * 1e-3).astype(np.float32)
+    dp, dv, lp = dev(p), dev(v), torch.zeros(length, dtype=torch.bfloat16, device="cuda")
+    synk.synk_sgd_update(dp, dv, dev(g), 0.1, 0.9, 1e-4, p_lp=lp)
+    rp, rv = oupdate.sgd_momentum(p, v, g, 0.1, 0.9, 1e-4)
+    assert rel_err(dp.cpu().numpy(), rp) < TOL_F32 and rel_err(dv.cpu().numpy(), rv) < TOL_F32
+    # the bf16 copy is the nearest-even rounding of the fp32 value the kernel wrote
+    want = ogather.round_to_bf16(dp.cpu().numpy())
+    assert np.array_equal(lp.float().cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+@pytest.mark.parametrize("n,length", [(1, 1000), (2, 203530), (3, 1025), (8, 70001), (16, 513)])
+def test_reduce_sgd_update_matches_oracle_and_unfused_calls(synk, n, length):
+    c = workloads.config3(n_params=length, n_workers=n)
+    grads = [dev(g) for g in c["grads"]]
+    p1, v1 = dev(c["p"]), dev(c["v"])
+    loss_out = torch.zeros(1, device="cuda")
+    synk.synk_reduce_sgd_update(grads, p1, v1, c["lr"], c["momentum"], c["weight_decay"],
+                                loss_in=dev(c["losses"]), loss_out=loss_out)
+    rp, rv, rG, rl = oupdate.reduce_and_update(c["p"], c["v"], c["grads"], c["lr"], c["momentum"],
+                                               c["weight_decay"], None, c["losses"])
+    assert rel_err(p1.cpu().numpy(), rp) < TOL_F32
+    assert rel_err(v1.cpu().numpy(), rv) < TOL_F32
+    assert abs(loss_out.item() - rl) < TOL_F32 * abs(rl)
+    # same thing through the two separate entry points
+    G = torch.empty(length, device="cuda")
+    synk.synk_reduce_buffers(grads, synk.SYNK_MEAN, G)
+    assert rel_err(G.cpu().numpy(), rG) < TOL_F32
+    p2, v2 = dev(c["p"]), dev(c["v"])
+    synk.synk_sgd_update(p2, v2, G, c["lr"], c["momentum"], c["weight_decay"])
+    assert rel_err(p2.cpu().numpy(), rp) < TOL_F32 and rel_err(v2.cpu().numpy(), rv) < TOL_F32
+
+
+def test_reduce_sgd_update_weights_and_closed_form(synk):
+    rng = np.random.default_rng(8)
+    g = [rng.standard_normal(333).astype(np.float32) for _ in range(3)]
+    p = rng.standard_normal(333).astype(np.float32)
+    w = [0.5, 0.25, 0.25]
+    dp, dv = dev(p), dev(np.zeros(333, np.float32))
+    synk.synk_reduce_sgd_update([dev(x) for x in g], dp, dv, 0.05, 0.0, 0.0, weights=w)
+    G = 0.5 * g[0].astype(np.float64) + 0.25 * g[1] + 0.25 * g[2]
+    assert rel_err(dp.cpu().numpy(), p - 0.05 * G) < TOL_F32       # zero momentum: p - lr*G
+
+
+# -------------------------------------------------------------- sliced eval
+def run_eval(synk, logits, labels, n_slices):
+    rows, classes = logits.shape
+    ws = torch.empty(synk.synk_sliced_eval_workspace_bytes(rows, classes, n_slices), dtype=torch.uint8, device="cuda")
+    o = dict(ce_sum=torch.zeros(1, device="cuda"), counts=torch.full((classes,), -1, dtype=torch.int32, device="cuda"),
+             max_logit=torch.zeros(1, device="cuda"), min_logit=torch.zeros(1, device="cuda"),
+             n_correct=torch.zeros(1, dtype=torch.int32, device="cuda"),
+             argmax=torch.full((rows,), -1, dtype=torch.int32, device="cuda"))
+    synk.synk_sliced_eval(dev(logits), dev(labels), n_slices, o["ce_sum"], o["counts"], o["max_logit"],
+                          o["min_logit"], o["n_correct"], o["argmax"], ws)
+    return {k: v.cpu().numpy() for k, v in o.items()}
+
+
+def check_eval(got, ref):
+    for k in ("counts", "n_correct", "argmax"):
+        assert np.array_equal(got[k].astype(np.int64), ref[k]), k
+    assert got["max_logit"][0] == np.float32(ref["max_logit"][0])
+    assert got["min_logit"][0] == np.float32(ref["min_logit"][0])
+    assert abs(got["ce_sum"][0] - ref["ce_sum"][0]) < TOL_F32 * abs(ref["ce_sum"][0])
+
+
+@pytest.mark.parametrize("rows,classes,n_slices", [
+    (2048, 1000, 64),    # config-5 row shape, 32 rows a slice
+    (1000, 1000, 7),     # ragged slices, ragged chunks
+    (130, 37, 3),        # class count not a multiple of 4: scalar path
+    (5, 10, 8),          # more slices than rows
+    (300, 4096, 2),      # widest rows
+    (64, 1, 1),          # a single class
+])
+def test_sliced_eval_matches_oracle(synk, rows, classes, n_slices):
+    c = workloads.config5(rows=rows, classes=classes, n_slices=n_slices)
+    got = run_eval(synk, c["logits"], c["labels"], n_slices)
+    check_eval(got, evalops.sliced(c["logits"], c["labels"], n_slices))
+
+
+def test_sliced_eval_ties_take_the_lowest_class(synk):
+    rng = np.random.default_rng(9)
+    logits = (rng.standard_normal((96, 200)) * 2).astype(np.float32)
+    for i in range(96):        # plant equal maxima in different lanes / vector slots
+        a, b = rng.choice(200, 2, replace=False)
+        logits[i, a] = logits[i, b] = 50.0
+    labels = rng.integers(0, 200, 96).astype(np.int32)
+    got = run_eval(synk, logits, labels, 5)
+    check_eval(got, evalops.sliced(logits, labels, 5))
+
+
+def test_streaming_kernels_are_reproducible(synk):
+    c = workloads.config5(rows=4096, classes=1000, n_slices=16)
+    a = run_eval(synk, c["logits"], c["labels"], 16)
+    b = run_eval(synk, c["logits"], c["labels"], 16)
+    assert all(np.array_equal(a[k], b[k]) for k in a)
