@@ -181,7 +181,7 @@ extern "C" int synk_gather_rows(const void* data, int64_t n_rows, int64_t row_el
                                 int dst_dtype, const float* lut, int channels,
                                 const int32_t* labels, int32_t* const* dst_labels, uint32_t flags,
                                 void* ws, size_t ws_bytes, void* stream) {
-  if (!data || !idx || !dst) return SYNK_ERR_NULL;
+  if (!data || !dst || (!idx && n_idx > 0)) return SYNK_ERR_NULL;
   if (labels && !dst_labels) return SYNK_ERR_NULL;
   if (n_rows < 0 || row_elems <= 0 || n_idx < 0) return SYNK_ERR_SHAPE;
   if (n_workers < 1 || n_workers > SYNK_MAX_WORKERS) return SYNK_ERR_SHAPE;
