@@ -1,0 +1,323 @@
+#!/usr/bin/env python3
+"""Throughput of the data-parallel hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+
+A step is one pass of the whole path over one batch of synthetic input that is
+already resident in HBM: index gather + scatter over workers -> sliced gradient
+function -> worker reduce fused with the momentum update (config 2, the
+default, and config 1); or the single stage a configuration isolates (3: reduce
++ update of ResNet-50-sized gradients, 4: normalising image gather, 5:
+six-output sliced evaluation).  Prints ONE JSON line.
+
+`roofline` is for the dominant kernel of the step: algorithmic bytes per launch
+divided by that kernel's mean duration, measured here with events recorded on
+the launch stream around every launch of it inside the timed region.
+`cpu_baseline` is the NumPy float64 oracle timed on this machine's host cores on a
+bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def host_threads():
+    try:
+        from threadpoolctl import threadpool_info
+        n = [i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"]
+        return max(n) if n else 1
+    except Exception:
+        return 1
+
+
+class Timer:
+    """Events around every launch of the dominant kernel (on torch's current
+    stream, which is the stream the library launches on)."""
+
+    def __init__(self, torch):
+        self.torch, self.pairs, self.on = torch, [], False
+
+    def bracket(self, fn):
+        if not self.on:
+            return fn()
+        a = self.torch.cuda.Event(enable_timing=True)
+        b = self.torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        self.pairs.append((a, b))
+
+    def mean_ms(self):
+        return sum(a.elapsed_time(b) for a, b in self.pairs) / max(len(self.pairs), 1)
+
+
+# ------------------------------------------------------------------ workloads
+class MlpStep:
+    """Configs 1 and 2: the whole synchronous-SGD step."""
+
+    def __init__(self, torch, synk, cfg_no):
+        import numpy as np
+        import workloads
+        from oracle import split as osplit           # host-side share sizes for buffer allocation only
+        self.torch, self.s, self.np = torch, synk, np
+        if cfg_no == 1:
+            c = workloads.config1()
+            c["idx_sets"] = [np.random.default_rng(i).permutation(4096)[:256].astype(np.int32) for i in range(8)]
+        else:
+            c = workloads.config2(n_index_sets=8)
+        self.c = c
+        self.dims, self.N, self.S = c["dims"], c["n_workers"], c["n_slices"]
+        self.bf16 = c["compute"] == "bf16"
+        self.cd = synk.SYNK_BF16 if self.bf16 else synk.SYNK_F32
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        self.data, self.labels = up(c["data"]), up(c["labels"])
+        self.idx = [up(i) for i in c["idx_sets"]]
+        self.B = len(c["idx_sets"][0])
+        self.P = synk.synk_mlp_param_count(self.dims)
+        self.p, self.v = up(c["theta"]), torch.zeros(self.P, device="cuda")
+        self.p_lp = torch.zeros(self.P, dtype=torch.bfloat16, device="cuda") if self.bf16 else None
+        if self.bf16:
+            synk.synk_cast_bf16(self.p, self.p_lp)
+        self.rows = osplit.share_sizes(self.B, self.N)
+        xdt = torch.bfloat16 if self.bf16 else torch.float32
+        self.x = [torch.zeros((n, self.dims[0]), dtype=xdt, device="cuda") for n in self.rows]
+        self.y = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in self.rows]
+        self.grad = [torch.zeros(self.P, device="cuda") for _ in self.rows]
+        self.loss = torch.zeros(self.N, device="cuda")
+        self.loss_out = torch.zeros(1, device="cuda")
+        self.ws = torch.empty(synk.synk_sliced_grad_workspace_bytes(self.dims, self.cd, self.rows),
+                              dtype=torch.uint8, device="cuda")
+        self.units, self.unit = self.B, "samples/s"
+        self.dtype = "bf16" if self.bf16 else "f32"
+        self.workload = ("config 2: wide MLP 3072-1024-1024-10 step, batch 1024, 8 worker shares x 4 slices, "
+                         "bf16 GEMM inputs / fp32 accumulate" if cfg_no == 2 else
+                         "config 1: tiny MLP 784-256-10 step, batch 256, 2 worker shares x 4 slices, fp32")
+        # dominant kernel: the fused N-way reduce + momentum update.  Per parameter it reads N
+        # gradients, reads and writes p and v (fp32) and, with bf16 compute, writes the bf16 copy.
+        self.dom_name = "reduce_sgd_kernel"
+        self.dom_bytes = self.P * (4 * self.N + 16 + (2 if self.bf16 else 0))
+
+    def step(self, i, timer):
+        s, c = self.s, self.c
+        s.synk_gather_rows(self.data, self.idx[i % len(self.idx)], self.x, labels=self.labels, dst_labels=self.y)
+        s.synk_sliced_grad(self.dims, self.cd, self.p, self.p_lp, self.x, self.y, self.rows, self.S,
+                           s.SYNK_MEAN, self.grad, self.loss, self.ws)
+        timer.bracket(lambda: s.synk_reduce_sgd_update(self.grad, self.p, self.v, c["lr"], c["momentum"],
+                                                       c["weight_decay"], p_lp=self.p_lp, loss_in=self.loss,
+                                                       loss_out=self.loss_out))
+
+    def cpu_baseline(self):
+        from oracle import mlp as omlp, update as oupdate
+        c, np = self.c, self.np
+        theta, v = c["theta"].astype(np.float64), np.zeros(self.P)
+        best = 1e30
+        for rep in range(3):
+            t0 = time.perf_counter()
+            loss, g = omlp.full(theta, self.dims, c["data"], c["labels"], c["idx_sets"][rep])
+            oupdate.sgd_momentum(theta, v, g, c["lr"], c["momentum"], c["weight_decay"])
+            best = min(best, time.perf_counter() - t0)
+        return self.B / best, "3 whole steps (full-batch oracle: gather, fwd/bwd, update), best of 3"
+
+
+class ReduceStep:
+    """Config 3: N-way average of ResNet-50-sized gradients fused with momentum SGD."""
+
+    def __init__(self, torch, synk):
+        import numpy as np
+        import workloads
+        self.torch, self.s, self.np = torch, synk, np
+        c = workloads.config3()
+        self.c = c
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        self.P, self.N = c["n_params"], c["n_workers"]
+        # 3 rotating gradient sets (2.4 GB) so that the 256 MB last-level cache cannot serve the reads
+        self.grads = [[up(g) for g in c["grads"]]]
+        for k in range(2):
+            self.grads.append([g.roll(k + 1) for g in self.grads[0]])
+        self.p, self.v = up(c["p"]), up(c["v"])
+        self.loss_in, self.loss_out = up(c["losses"]), torch.zeros(1, device="cuda")
+        self.units, self.unit = self.P, "params/s"
+        self.dtype = "f32"
+        self.workload = ("config 3: average of 8 ResNet-50-sized fp32 gradient buffers (25,557,032 params, 161 "
+                         "tensors) fused with momentum SGD (lr .1, m .9, wd 1e-4) and the scalar-loss mean")
+        self.dom_name = "reduce_sgd_kernel"
+        self.dom_bytes = self.P * (4 * self.N + 16)
+
+    def step(self, i, timer):
+        c = self.c
+        timer.bracket(lambda: self.s.synk_reduce_sgd_update(
+            self.grads[i % 3], self.p, self.v, c["lr"], c["momentum"], c["weight_decay"],
+            loss_in=self.loss_in, loss_out=self.loss_out))
+
+    def cpu_baseline(self):
+        from oracle import update as oupdate
+        c = self.c
+        best = 1e30
+        for _ in range(3):
+            t0 = time.perf_counter()
+            oupdate.reduce_and_update(c["p"], c["v"], c["grads"], c["lr"], c["momentum"], c["weight_decay"],
+                                      None, c["losses"])
+            best = min(best, time.perf_counter() - t0)
+        return self.P / best, "3 whole steps at full size, best of 3"
+
+
+class GatherStep:
+    """Config 4: uint8 image gather + per-channel normalise to fp32, 8 worker shares."""
+
+    def __init__(self, torch, synk):
+        import numpy as np
+        import workloads
+        from oracle import split as osplit
+        self.torch, self.s, self.np = torch, synk, np
+        small = workloads.config4(n_data=8, batch=8)             # mean/std recipe
+        self.mean, self.std = small["mean"], small["std"]
+        self.n_data, self.B, self.N, self.chw = 50000, 256, 8, (3, 224, 224)
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(workloads.SEED_BASE + 4)
+        row = 3 * 224 * 224
+        self.data = torch.empty((self.n_data, row), dtype=torch.uint8, device="cuda")
+        for a in range(0, self.n_data, 5000):                    # 7.5 GB, filled on the device in pieces
+            self.data[a:a + 5000] = torch.randint(0, 256, (5000, row), dtype=torch.uint8, device="cuda",
+                                                  generator=gen)
+        rng = workloads.rng_for(4, salt=1)
+        self.labels = torch.from_numpy(rng.integers(0, 1000, self.n_data).astype(np.int32)).cuda()
+        self.idx = [torch.from_numpy(rng.integers(0, self.n_data, self.B).astype(np.int32)).cuda()
+                    for _ in range(64)]                          # fresh indexes every step
+        self.lut = torch.empty(3 * 256, device="cuda")
+        synk.synk_build_norm_lut(self.mean, self.std, self.lut)
+        rows = osplit.share_sizes(self.B, self.N)
+        self.dst = [torch.zeros((n, row), device="cuda") for n in rows]
+        self.dl = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in rows]
+        self.units, self.unit = self.B, "images/s"
+        self.dtype = "u8"
+        self.workload = ("config 4: gather 256 of 50000 uint8 3x224x224 images by random index, normalise to "
+                         "fp32 NCHW, 8 worker shares of 32, with labels")
+        self.dom_name = "gather_u8_lut_kernel"
+        self.dom_bytes = self.B * (row + 4 * row + 8)
+
+    def step(self, i, timer):
+        timer.bracket(lambda: self.s.synk_gather_rows(self.data, self.idx[i % 64], self.dst, lut=self.lut,
+                                                      channels=3, labels=self.labels, dst_labels=self.dl))
+
+    def cpu_baseline(self):
+        from oracle import gather as og
+        np = self.np
+        rng = np.random.default_rng(0)
+        data = rng.integers(0, 256, (512,) + self.chw, dtype=np.uint8)     # 77 MB stand-in dataset
+        idx = rng.integers(0, 512, self.B)
+        best = 1e30
+        for _ in range(3):
+            t0 = time.perf_counter()
+            for part in og.gather_shares(data, idx, self.N):
+                og.normalise_u8(part, self.mean, self.std)
+            best = min(best, time.perf_counter() - t0)
+        return self.B / best, "3 whole batches of 256 from a 512-image host dataset, best of 3"
+
+
+class EvalStep:
+    """Config 5: six-output evaluation over 64 slices with aggregation."""
+
+    def __init__(self, torch, synk):
+        import numpy as np
+        import workloads
+        self.torch, self.s, self.np = torch, synk, np
+        self.rows, self.C, self.S = 65536, 1000, 64
+        self.host = workloads.config5()
+        # 4 rotating input sets (1.05 GB) against the 256 MB last-level cache
+        self.logits = [torch.from_numpy(self.host["logits"]).cuda()]
+        for k in range(3):
+            self.logits.append(self.logits[0].roll(k + 1, dims=0).contiguous())
+        self.labels = torch.from_numpy(self.host["labels"]).cuda()
+        z = lambda n, dt: torch.zeros(n, dtype=dt, device="cuda")
+        self.out = (z(1, torch.float32), z(self.C, torch.int32), z(1, torch.float32), z(1, torch.float32),
+                    z(1, torch.int32), z(self.rows, torch.int32))
+        self.ws = torch.empty(synk.synk_sliced_eval_workspace_bytes(self.rows, self.C, self.S),
+                              dtype=torch.uint8, device="cuda")
+        self.units, self.unit = self.rows, "rows/s"
+        self.dtype = "f32"
+        self.workload = ("config 5: 65536 rows of 1000-class fp32 logits, 64 slices, outputs CE sum, class "
+                         "counts, max, min, top-1 correct, argmax, aggregated over slices")
+        self.dom_name = "eval_stage1_kernel"
+        self.dom_bytes = self.rows * (4 * self.C + 8)
+        self._timer = None
+
+    def step(self, i, timer):
+        # the dominant kernel is one of the three this call launches; the bracket covers the call and
+        # the rocprofv3 summary under profiles/ separates the kernels
+        timer.bracket(lambda: self.s.synk_sliced_eval(self.logits[i % 4], self.labels, self.S, *self.out, self.ws))
+
+    def cpu_baseline(self):
+        from oracle import evalops
+        n = 4096
+        t0 = time.perf_counter()
+        evalops.sliced(self.host["logits"][:n], self.host["labels"][:n], 4)
+        return n / (time.perf_counter() - t0), "4096 of the 65536 rows, 4 slices (the argmax loop is pure Python)"
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    from paper_1710_04162_amd import binding as synk
+    torch.cuda.set_device(0)
+
+    wl = {1: lambda: MlpStep(torch, synk, 1), 2: lambda: MlpStep(torch, synk, 2),
+          3: lambda: ReduceStep(torch, synk), 4: lambda: GatherStep(torch, synk),
+          5: lambda: EvalStep(torch, synk)}[a.config]()
+    steps = a.steps if a.steps is not None else {1: 2000, 2: 1000, 3: 300, 4: 1000, 5: 1000}[a.config]
+    warmup = a.warmup if a.warmup is not None else 20
+
+    timer = Timer(torch)
+    for i in range(warmup):
+        wl.step(i, timer)
+    torch.cuda.synchronize()
+    timer.on = True
+    t0 = time.perf_counter()
+    for i in range(steps):
+        wl.step(i, timer)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    dom_ms = timer.mean_ms()
+    achieved = wl.dom_bytes / (dom_ms * 1e-3) / 1e9
+    out = {
+        "metric": "samples/sec for gather+sliced grad+reduce+SGD step; HBM GB/s and MFMA % of peak",
+        "value": wl.units * steps / dt, "unit": wl.unit, "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.workload, "units_per_step": wl.units},
+        "roofline": {"bound": "hbm", "kernel": wl.dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": wl.dom_bytes, "ms_per_launch": dom_ms},
+    }
+    if not a.no_cpu_baseline:
+        v, sample = wl.cpu_baseline()
+        out["cpu_baseline"] = {"value": v, "unit": wl.unit, "cores": host_threads(), "kind": "oracle",
+                               "sample": sample}
+        out["context"] = "paper: 7.5x ResNet-50 speedup on 8x P100 (DGX-1) over 1 GPU; other hardware, not a target"
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
