@@ -11,7 +11,7 @@ import os
 import torch
 
 __all__ = [
-    "SynkError", "lib", "LIB_PATH", "DTYPE", "OP",
+    "SynkError", "lib", "LIB_PATH", "DTYPE", "OP", "Prepared", "prepare",
     "SYNK_U8", "SYNK_I32", "SYNK_F32", "SYNK_BF16",
     "SYNK_SUM", "SYNK_MEAN", "SYNK_MAX", "SYNK_MIN", "SYNK_PROD", "SYNK_CONCAT",
     "SYNK_FLAG_CHECK_INDEX", "SYNK_MAX_WORKERS",
@@ -138,16 +138,46 @@ def synk_gather_workspace_bytes():
     return lib.synk_gather_workspace_bytes()
 
 
+class Prepared:
+    """One C call with its arguments already marshalled: calling it repeats the
+    call (same pointers, same sizes, same stream).  Keeps the tensors alive.
+    For loops that must not pay Python marshalling on every launch."""
+
+    __slots__ = ("fn", "args", "keep", "where")
+
+    def __init__(self, fn, args, keep, where):
+        self.fn, self.args, self.keep, self.where = fn, args, keep, where
+
+    def __call__(self):
+        status = self.fn(*self.args)
+        if status != 0:
+            raise SynkError(status, self.where)
+
+
+def prepare(wrapper, *args, **kwargs):
+    """prepare(synk_gather_rows, data, idx, dst, ...) -> Prepared."""
+    return wrapper(*args, _prepare=True, **kwargs)
+
+
+def _run(fn, args, keep, where, _prepare):
+    if _prepare:
+        return Prepared(fn, args, keep, where)
+    _check(fn(*args), where)
+
+
 def synk_gather_rows(data, idx, dst, lut=None, channels=0, labels=None, dst_labels=None, flags=0,
-                     ws=None, stream=None):
+                     ws=None, stream=None, _prepare=False):
     n_rows = data.shape[0]
-    row_elems = data.numel() // max(n_rows, 1) if n_rows else int(torch.tensor(data.shape[1:]).prod())
+    row_elems = 1
+    for d in data.shape[1:]:
+        row_elems *= int(d)
     wsp, wsb = _ws(ws)
-    _check(lib.synk_gather_rows(_ptr(data), n_rows, row_elems, DTYPE[data.dtype], _ptr(idx),
-                                idx.numel(), _table(dst), len(dst), DTYPE[dst[0].dtype], _ptr(lut),
-                                channels, _ptr(labels),
-                                _table(dst_labels) if dst_labels is not None else None, flags, wsp,
-                                wsb, _stream(stream)), "synk_gather_rows")
+    t_dst = _table(dst)
+    t_lab = _table(dst_labels) if dst_labels is not None else None
+    args = (_ptr(data), n_rows, row_elems, DTYPE[data.dtype], _ptr(idx), idx.numel(), t_dst, len(dst),
+            DTYPE[dst[0].dtype], _ptr(lut), channels, _ptr(labels), t_lab, flags, wsp, wsb, _stream(stream))
+    return _run(lib.synk_gather_rows, args, (data, idx, dst, lut, labels, dst_labels, ws, t_dst, t_lab),
+                "synk_gather_rows", _prepare)
 
 
 def synk_build_norm_lut(mean, std, lut, stream=None):
@@ -177,12 +207,15 @@ def synk_sliced_grad_workspace_bytes(dims, compute_dtype, rows):
 
 
 def synk_sliced_grad(dims, compute_dtype, params, params_lp, x, y, rows, n_slices, grad_op, grad, loss,
-                     ws, stream=None):
+                     ws, stream=None, _prepare=False):
     r = (ctypes.c_int64 * len(rows))(*[int(v) for v in rows])
     wsp, wsb = _ws(ws)
-    _check(lib.synk_sliced_grad(ctypes.byref(_desc(dims, compute_dtype)), _ptr(params), _ptr(params_lp),
-                                _table(x), _table(y), r, len(rows), n_slices, grad_op, _table(grad),
-                                _ptr(loss), wsp, wsb, _stream(stream)), "synk_sliced_grad")
+    desc = _desc(dims, compute_dtype)
+    tx, ty, tg = _table(x), _table(y), _table(grad)
+    args = (ctypes.byref(desc), _ptr(params), _ptr(params_lp), tx, ty, r, len(rows), n_slices, grad_op,
+            tg, _ptr(loss), wsp, wsb, _stream(stream))
+    return _run(lib.synk_sliced_grad, args, (desc, params, params_lp, x, y, r, grad, loss, ws, tx, ty, tg),
+                "synk_sliced_grad", _prepare)
 
 
 def synk_cast_bf16(src, dst, stream=None):
@@ -197,31 +230,36 @@ def synk_sliced_eval_workspace_bytes(rows, classes, n_slices):
 
 
 def synk_sliced_eval(logits, labels, n_slices, ce_sum, class_counts, max_logit, min_logit, n_correct,
-                     argmax, ws, stream=None):
+                     argmax, ws, stream=None, _prepare=False):
     rows, classes = logits.shape
     wsp, wsb = _ws(ws)
-    _check(lib.synk_sliced_eval(_ptr(logits), _ptr(labels), rows, classes, n_slices, _ptr(ce_sum),
-                                _ptr(class_counts), _ptr(max_logit), _ptr(min_logit), _ptr(n_correct),
-                                _ptr(argmax), wsp, wsb, _stream(stream)), "synk_sliced_eval")
+    args = (_ptr(logits), _ptr(labels), rows, classes, n_slices, _ptr(ce_sum), _ptr(class_counts),
+            _ptr(max_logit), _ptr(min_logit), _ptr(n_correct), _ptr(argmax), wsp, wsb, _stream(stream))
+    return _run(lib.synk_sliced_eval, args,
+                (logits, labels, ce_sum, class_counts, max_logit, min_logit, n_correct, argmax, ws),
+                "synk_sliced_eval", _prepare)
 
 
-def synk_reduce_buffers(bufs, op, out, weights=None, stream=None):
+def synk_reduce_buffers(bufs, op, out, weights=None, stream=None, _prepare=False):
     n = len(bufs)
     w = (ctypes.c_float * n)(*[float(x) for x in weights]) if weights is not None else None
     lens = (ctypes.c_int64 * n)(*[b.numel() for b in bufs]) if op == SYNK_CONCAT else None
-    _check(lib.synk_reduce_buffers(_table(bufs), n, bufs[0].numel(), DTYPE[bufs[0].dtype], op, w, lens,
-                                   _ptr(out), _stream(stream)), "synk_reduce_buffers")
+    tb = _table(bufs)
+    args = (tb, n, bufs[0].numel(), DTYPE[bufs[0].dtype], op, w, lens, _ptr(out), _stream(stream))
+    return _run(lib.synk_reduce_buffers, args, (bufs, out, w, lens, tb), "synk_reduce_buffers", _prepare)
 
 
-def synk_sgd_update(p, v, g, lr, momentum, weight_decay=0.0, p_lp=None, stream=None):
-    _check(lib.synk_sgd_update(_ptr(p), _ptr(v), _ptr(g), p.numel(), lr, momentum, weight_decay,
-                               _ptr(p_lp), _stream(stream)), "synk_sgd_update")
+def synk_sgd_update(p, v, g, lr, momentum, weight_decay=0.0, p_lp=None, stream=None, _prepare=False):
+    args = (_ptr(p), _ptr(v), _ptr(g), p.numel(), lr, momentum, weight_decay, _ptr(p_lp), _stream(stream))
+    return _run(lib.synk_sgd_update, args, (p, v, g, p_lp), "synk_sgd_update", _prepare)
 
 
 def synk_reduce_sgd_update(grads, p, v, lr, momentum, weight_decay=0.0, weights=None, p_lp=None,
-                           loss_in=None, loss_out=None, stream=None):
+                           loss_in=None, loss_out=None, stream=None, _prepare=False):
     n = len(grads)
     w = (ctypes.c_float * n)(*[float(x) for x in weights]) if weights is not None else None
-    _check(lib.synk_reduce_sgd_update(_table(grads), n, p.numel(), w, _ptr(p), _ptr(v), lr, momentum,
-                                      weight_decay, _ptr(p_lp), _ptr(loss_in), _ptr(loss_out),
-                                      _stream(stream)), "synk_reduce_sgd_update")
+    tg = _table(grads)
+    args = (tg, n, p.numel(), w, _ptr(p), _ptr(v), lr, momentum, weight_decay, _ptr(p_lp), _ptr(loss_in),
+            _ptr(loss_out), _stream(stream))
+    return _run(lib.synk_reduce_sgd_update, args, (grads, p, v, w, p_lp, loss_in, loss_out, tg),
+                "synk_reduce_sgd_update", _prepare)

@@ -87,10 +87,13 @@ __global__ __launch_bounds__(kGBlock) void gather_bf16_kernel(
 
 // uint8 -> float32 through a per-channel table held in LDS.  VEC: each lane
 // loads 4 pixels (one dword) and stores one 16-byte vector, so both the load
-// and the store of a wavefront are contiguous.
+// and the store of a wavefront are contiguous.  The channel of a unit is
+// tracked incrementally (units only move forwards), never divided out.
+constexpr int kLBlock = 1024;
+
 template <bool VEC>
-__global__ __launch_bounds__(kGBlock) void gather_u8_lut_kernel(
-    const uint8_t* __restrict__ data, int64_t n_rows, int64_t row_elems, int64_t plane,
+__global__ __launch_bounds__(kLBlock) void gather_u8_lut_kernel(
+    const uint8_t* __restrict__ data, int64_t n_rows, int row_elems, int plane,
     const int32_t* __restrict__ idx, int64_t n_idx, DstTable t, int n_workers,
     const float* __restrict__ lut, int channels, const int32_t* __restrict__ labels,
     uint32_t* err_word, int units_per_block) {
@@ -98,39 +101,43 @@ __global__ __launch_bounds__(kGBlock) void gather_u8_lut_kernel(
   const int64_t j = blockIdx.x;
   const RowRef r = locate(idx, n_idx, n_workers, n_rows, j, err_word);
   if (r.src_row < 0) return;   // uniform per block: before the barrier is fine
-  for (int i = threadIdx.x; i < channels * 256; i += kGBlock) s_lut[i] = lut[i];
+  for (int i = threadIdx.x; i < channels * 256; i += kLBlock) s_lut[i] = lut[i];
   __syncthreads();
   copy_label(t, labels, r);
-  const uint8_t* src = data + r.src_row * row_elems;
-  float* dst = reinterpret_cast<float*>(t.dst[r.worker]) + r.local * row_elems;
-  const int64_t units = VEC ? (row_elems >> 2) : row_elems;
-  const int64_t u0 = (int64_t)blockIdx.y * units_per_block;
-  int64_t u1 = u0 + units_per_block;
+  const uint8_t* src = data + r.src_row * (int64_t)row_elems;
+  float* dst = reinterpret_cast<float*>(t.dst[r.worker]) + r.local * (int64_t)row_elems;
+  const int units = VEC ? (row_elems >> 2) : row_elems;
+  const int plane_u = VEC ? (plane >> 2) : plane;     // units per channel plane
+  const int u0 = blockIdx.y * units_per_block;
+  int u1 = u0 + units_per_block;
   if (u1 > units) u1 = units;
+  int u = u0 + threadIdx.x;
+  int c = u / plane_u;                  // one division per thread
+  int bound = (c + 1) * plane_u;        // first unit of the next channel
   if (VEC) {
-    // plane % 4 == 0 here, so the 4 pixels of a unit share a channel
-    constexpr int UNROLL = 4;
-    int64_t u = u0 + threadIdx.x;
-    for (; u + (UNROLL - 1) * kGBlock < u1; u += UNROLL * kGBlock) {
+    constexpr int UNROLL = 8;
+    for (; u + (UNROLL - 1) * kLBlock < u1; u += UNROLL * kLBlock) {
       uint32_t px[UNROLL];
 #pragma unroll
       for (int k = 0; k < UNROLL; ++k)
-        px[k] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(src) + u + k * kGBlock);
+        px[k] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(src) + u + k * kLBlock);
 #pragma unroll
       for (int k = 0; k < UNROLL; ++k) {
-        const int64_t uu = u + k * kGBlock;
-        const float* l = s_lut + ((uu << 2) / plane) * 256;
+        const int uu = u + k * kLBlock;
+        while (uu >= bound) { ++c; bound += plane_u; }
+        const float* l = s_lut + c * 256;
         f32x4 o;
         o.x = l[px[k] & 0xffu];
         o.y = l[(px[k] >> 8) & 0xffu];
         o.z = l[(px[k] >> 16) & 0xffu];
         o.w = l[px[k] >> 24];
-        __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst) + uu);
+        reinterpret_cast<f32x4*>(dst)[uu] = o;
       }
     }
-    for (; u < u1; u += kGBlock) {
+    for (; u < u1; u += kLBlock) {
+      while (u >= bound) { ++c; bound += plane_u; }
       const uint32_t px = reinterpret_cast<const uint32_t*>(src)[u];
-      const float* l = s_lut + ((u << 2) / plane) * 256;
+      const float* l = s_lut + c * 256;
       f32x4 o;
       o.x = l[px & 0xffu];
       o.y = l[(px >> 8) & 0xffu];
@@ -139,8 +146,10 @@ __global__ __launch_bounds__(kGBlock) void gather_u8_lut_kernel(
       reinterpret_cast<f32x4*>(dst)[u] = o;
     }
   } else {
-    for (int64_t u = u0 + threadIdx.x; u < u1; u += kGBlock)
-      dst[u] = s_lut[(u / plane) * 256 + src[u]];
+    for (; u < u1; u += kLBlock) {
+      while (u >= bound) { ++c; bound += plane_u; }
+      dst[u] = s_lut[c * 256 + src[u]];
+    }
   }
 }
 
@@ -197,6 +206,7 @@ extern "C" int synk_gather_rows(const void* data, int64_t n_rows, int64_t row_el
     if (!lut) return SYNK_ERR_NULL;
     if (channels < 1 || channels > SYNK_MAX_CHANNELS || row_elems % channels != 0)
       return SYNK_ERR_SHAPE;
+    if (row_elems > 0x7fffffffLL - (1 << 20)) return SYNK_ERR_UNSUPPORTED;   // 32-bit unit arithmetic
   }
   static const int kElemBytes[4] = {1, 4, 4, 2};
   const int src_b = kElemBytes[src_dtype], dst_b = kElemBytes[dst_dtype];
@@ -269,18 +279,21 @@ extern "C" int synk_gather_rows(const void* data, int64_t n_rows, int64_t row_el
                          n_workers, labels, err_word, upb);
     }
   } else {
-    const int64_t plane = row_elems / channels;
-    if (plane % 4 == 0 && aligned_to(data, 4) && dst16) {
-      if (int rc = chunking(row_elems / 4, &upb, &chunks)) return rc;
-      hipLaunchKernelGGL((gather_u8_lut_kernel<true>), dim3((unsigned)n_idx, chunks), dim3(kGBlock),
-                         0, s, reinterpret_cast<const uint8_t*>(data), n_rows, row_elems, plane, idx,
-                         n_idx, t, n_workers, lut, channels, labels, err_word, upb);
-    } else {
-      if (int rc = chunking(row_elems, &upb, &chunks)) return rc;
-      hipLaunchKernelGGL((gather_u8_lut_kernel<false>), dim3((unsigned)n_idx, chunks), dim3(kGBlock),
-                         0, s, reinterpret_cast<const uint8_t*>(data), n_rows, row_elems, plane, idx,
-                         n_idx, t, n_workers, lut, channels, labels, err_word, upb);
-    }
+    const int plane = (int)(row_elems / channels);
+    const bool vec = plane % 4 == 0 && aligned_to(data, 4) && dst16;
+    const int64_t units = vec ? row_elems / 4 : row_elems;
+    upb = kLBlock * 8;                                   // 8 units per thread
+    const int64_t nch = (units + upb - 1) / upb;
+    if (nch > 65535) return SYNK_ERR_UNSUPPORTED;
+    chunks = (int)nch;
+    if (vec)
+      hipLaunchKernelGGL((gather_u8_lut_kernel<true>), dim3((unsigned)n_idx, chunks), dim3(kLBlock),
+                         0, s, reinterpret_cast<const uint8_t*>(data), n_rows, (int)row_elems, plane,
+                         idx, n_idx, t, n_workers, lut, channels, labels, err_word, upb);
+    else
+      hipLaunchKernelGGL((gather_u8_lut_kernel<false>), dim3((unsigned)n_idx, chunks), dim3(kLBlock),
+                         0, s, reinterpret_cast<const uint8_t*>(data), n_rows, (int)row_elems, plane,
+                         idx, n_idx, t, n_workers, lut, channels, labels, err_word, upb);
   }
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;

@@ -33,38 +33,34 @@ template <typename T> struct ET;
 template <> struct ET<float> {
   static constexpr int V = 4;    // elements per 16-byte vector
   static constexpr int KM = 2;   // contraction depth of one MFMA
-  static constexpr int BK = 16;  // contraction depth of one LDS tile
 };
 template <> struct ET<bf16_t> {
   static constexpr int V = 8;
   static constexpr int KM = 16;
-  static constexpr int BK = 32;
 };
 
-// LDS footprint of one operand tile, in 4-byte words.
-template <typename T, int LAYOUT, int X>
+// LDS footprint of one operand tile (X rows/cols by BK contraction steps), in
+// 4-byte words.
+template <typename T, int LAYOUT, int X, int BK>
 __host__ __device__ constexpr int tile_words() {
-  if (sizeof(T) == 2) return LAYOUT == KC ? X * (ET<T>::BK + 8) / 2 : (ET<T>::BK / 2) * X;
-  return LAYOUT == KC ? X * (ET<T>::BK + 1) : ET<T>::BK * X;
+  if (sizeof(T) == 2) return LAYOUT == KC ? X * (BK + 8) / 2 : (BK / 2) * X;
+  return LAYOUT == KC ? X * (BK + 1) : BK * X;
 }
 
 // V elements along the contiguous dimension starting at (rr, cc) of a matrix
-// with RR x CC valid elements; anything outside reads as zero.
+// with RR x CC valid elements; anything outside reads as zero.  Element-wise
+// and branchy: only for operands that cannot be read with 16-byte loads.
 template <typename T>
-__device__ __forceinline__ u32x4 load_vec(const T* __restrict__ base, int64_t ld, int64_t rr,
-                                          int64_t cc, int64_t RR, int64_t CC, bool vec_ok) {
+__device__ __forceinline__ u32x4 load_vec_slow(const T* __restrict__ base, int64_t ld, int64_t rr,
+                                               int64_t cc, int64_t RR, int64_t CC) {
   constexpr int V = ET<T>::V;
   u32x4 out = {0u, 0u, 0u, 0u};
   if (rr < RR && cc < CC) {
     const T* p = base + rr * ld + cc;
-    if (vec_ok && cc + V <= CC) {
-      out = *reinterpret_cast<const u32x4*>(p);
-    } else {
-      __attribute__((aligned(16))) T tmp[V];
+    __attribute__((aligned(16))) T tmp[V];
 #pragma unroll
-      for (int e = 0; e < V; ++e) tmp[e] = (cc + e < CC) ? p[e] : (T)0;
-      out = *reinterpret_cast<u32x4*>(tmp);
-    }
+    for (int e = 0; e < V; ++e) tmp[e] = (cc + e < CC) ? p[e] : (T)0;
+    out = *reinterpret_cast<u32x4*>(tmp);
   }
   return out;
 }
@@ -73,80 +69,164 @@ __device__ __forceinline__ u32x4 load_vec(const T* __restrict__ base, int64_t ld
 // The tile covers X rows/cols (index x) by BK contraction steps (index k).
 //   KC: element (x, k) is base[x*ld + k]     LDS: rows of k, padded
 //   XC: element (x, k) is base[k*ld + x]     LDS: bf16: words (k pair, x); fp32: words (k, x)
-template <typename T, int LAYOUT, int X>
-struct TileStage {
-  static constexpr int V = ET<T>::V, BK = ET<T>::BK;
+// ALIGNED: every vector is wholly inside or wholly outside the matrix.  Loads
+// are then issued unconditionally (an outside vector reads the matrix origin
+// and is zeroed when it goes to LDS), so that nothing but the data dependence
+// orders them against the MFMAs of the tile before.
+//
+// TileAddr holds what does not change along the contraction: one pointer per
+// unit (64-bit address arithmetic done once, before the loop) and whether the
+// unit's x is inside the matrix.  Per tile only a wave-uniform offset is added.
+template <typename T, int LAYOUT, int X, int BK>
+struct TileGeom {
+  static constexpr int V = ET<T>::V;
   static constexpr bool HALF = sizeof(T) == 2;
   static constexpr int UNITS = LAYOUT == KC ? X * (BK / V) : (HALF ? (BK / 2) * (X / V) : BK * (X / V));
   static constexpr int PER_T = (UNITS + kMBlock - 1) / kMBlock;
   static constexpr int NV = (LAYOUT == XC && HALF) ? 2 : 1;
-  u32x4 r[PER_T][NV];
+  // position of unit `id` inside the tile: x offset and k offset
+  static __device__ __forceinline__ void unit_pos(int id, int* xl, int* kl) {
+    if (LAYOUT == KC) {
+      *xl = id / (BK / V);
+      *kl = (id % (BK / V)) * V;
+    } else if (HALF) {
+      *kl = 2 * (id / (X / V));
+      *xl = (id % (X / V)) * V;
+    } else {
+      *kl = id / (X / V);
+      *xl = (id % (X / V)) * V;
+    }
+  }
+};
 
-  __device__ __forceinline__ void load(const T* __restrict__ base, int64_t ld, int64_t x0,
-                                       int64_t xlim, int64_t k0, int64_t klim, bool vec_ok, int tid) {
+template <typename T, int LAYOUT, int X, int BK>
+struct TileAddr {
+  typedef TileGeom<T, LAYOUT, X, BK> G;
+  const T* ptr[G::PER_T];   // unit's first vector in the tile that starts at k = 0
+  const T* base;
+  int64_t ld;
+  int x0, xlim;
+  uint32_t xok;
+
+  __device__ __forceinline__ void init(const T* b, int64_t ld_, int64_t x0_, int64_t xlim_, int tid) {
+    base = b;
+    ld = ld_;
+    x0 = (int)x0_;
+    xlim = (int)xlim_;
+    xok = 0u;
+#pragma unroll
+    for (int it = 0; it < G::PER_T; ++it) {
+      const int id = it * kMBlock + tid;
+      int xl, kl;
+      G::unit_pos(id, &xl, &kl);
+      const bool live = ((G::UNITS % kMBlock == 0) || id < G::UNITS) && x0 + xl < xlim;
+      const int64_t off = LAYOUT == KC ? (int64_t)(x0 + xl) * ld + kl : (int64_t)kl * ld + (x0 + xl);
+      ptr[it] = b + (live ? off : 0);
+      xok |= (live ? 1u : 0u) << it;
+    }
+  }
+};
+
+template <typename T, int LAYOUT, int X, int BK, bool ALIGNED>
+struct TileStage {
+  typedef TileGeom<T, LAYOUT, X, BK> G;
+  static constexpr int V = G::V, PER_T = G::PER_T, NV = G::NV, UNITS = G::UNITS;
+  static constexpr bool HALF = G::HALF;
+  u32x4 r[PER_T][NV];
+  uint32_t ok;   // bit (it*NV + q): vector is inside the matrix
+
+  // all units this thread owns, all their vectors
+  static constexpr uint32_t kAllOk = (PER_T * NV >= 32) ? 0xffffffffu : ((1u << (PER_T * NV)) - 1u);
+
+  __device__ __forceinline__ void load(const TileAddr<T, LAYOUT, X, BK>& ta, int k0, int klim, int tid) {
+    const int64_t koff = LAYOUT == KC ? (int64_t)k0 : (int64_t)k0 * ta.ld;   // wave-uniform
+    if (ALIGNED && k0 + BK <= klim) {
+      // a tile wholly inside along the contraction: one 64-bit add per vector
+      ok = 0u;
+#pragma unroll
+      for (int it = 0; it < PER_T; ++it) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q)
+          r[it][q] = *reinterpret_cast<const u32x4*>(ta.ptr[it] + koff + (q ? ta.ld : 0));
+        ok |= (((ta.xok >> it) & 1u) ? ((1u << NV) - 1u) : 0u) << (it * NV);
+      }
+      return;
+    }
+    ok = 0u;
 #pragma unroll
     for (int it = 0; it < PER_T; ++it) {
       const int id = it * kMBlock + tid;
-      if (UNITS % kMBlock != 0 && id >= UNITS) {
+      int xl, kl;
+      G::unit_pos(id, &xl, &kl);
+      if (ALIGNED) {
 #pragma unroll
-        for (int q = 0; q < NV; ++q) r[it][q] = u32x4{0u, 0u, 0u, 0u};
-        continue;
-      }
-      if (LAYOUT == KC) {
-        const int xl = id / (BK / V), kl = (id % (BK / V)) * V;
-        r[it][0] = load_vec<T>(base, ld, x0 + xl, k0 + kl, xlim, klim, vec_ok);
-      } else if (HALF) {
-        const int kp = id / (X / V), xl = (id % (X / V)) * V;
-        r[it][0] = load_vec<T>(base, ld, k0 + 2 * kp, x0 + xl, klim, xlim, vec_ok);
-        r[it][NV - 1] = load_vec<T>(base, ld, k0 + 2 * kp + 1, x0 + xl, klim, xlim, vec_ok);
+        for (int q = 0; q < NV; ++q) {
+          const bool in = ((ta.xok >> it) & 1u) && (k0 + kl + q < klim);
+          const T* p = ta.ptr[it] + koff + (q ? ta.ld : 0);
+          r[it][q] = *reinterpret_cast<const u32x4*>(in ? p : ta.base);
+          ok |= (in ? 1u : 0u) << (it * NV + q);
+        }
       } else {
-        const int kl = id / (X / V), xl = (id % (X / V)) * V;
-        r[it][0] = load_vec<T>(base, ld, k0 + kl, x0 + xl, klim, xlim, vec_ok);
+        const bool live = (UNITS % kMBlock == 0) || id < UNITS;
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+          if (!live) r[it][q] = u32x4{0u, 0u, 0u, 0u};
+          else if (LAYOUT == KC)
+            r[it][q] = load_vec_slow<T>(ta.base, ta.ld, ta.x0 + xl, k0 + kl, ta.xlim, klim);
+          else
+            r[it][q] = load_vec_slow<T>(ta.base, ta.ld, k0 + kl + q, ta.x0 + xl, klim, ta.xlim);
+        }
+        ok = kAllOk;
+      }
+    }
+  }
+
+  template <bool CHECK>
+  __device__ __forceinline__ void store_impl(uint32_t* __restrict__ lds, int tid) const {
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int it = 0; it < PER_T; ++it) {
+      const int id = it * kMBlock + tid;
+      if (UNITS % kMBlock != 0 && id >= UNITS) continue;
+      int xl, kl;
+      G::unit_pos(id, &xl, &kl);
+      const u32x4 a = (!CHECK || ((ok >> (it * NV)) & 1u)) ? r[it][0] : zero;
+      if (LAYOUT == KC && HALF) {
+        *reinterpret_cast<u32x4*>(lds + (xl * (BK + 8) + kl) / 2) = a;
+      } else if (LAYOUT == KC) {
+        uint32_t* d = lds + xl * (BK + 1) + kl;
+        d[0] = a.x; d[1] = a.y; d[2] = a.z; d[3] = a.w;
+      } else if (HALF) {
+        // interleave rows k and k+1: word j = (row_k[x_j], row_k1[x_j]); one byte permute each
+        const u32x4 b = (!CHECK || ((ok >> (it * NV + NV - 1)) & 1u)) ? r[it][NV - 1] : zero;
+        u32x4 lo, hi;
+        lo.x = __builtin_amdgcn_perm(b.x, a.x, 0x05040100u); lo.y = __builtin_amdgcn_perm(b.x, a.x, 0x07060302u);
+        lo.z = __builtin_amdgcn_perm(b.y, a.y, 0x05040100u); lo.w = __builtin_amdgcn_perm(b.y, a.y, 0x07060302u);
+        hi.x = __builtin_amdgcn_perm(b.z, a.z, 0x05040100u); hi.y = __builtin_amdgcn_perm(b.z, a.z, 0x07060302u);
+        hi.z = __builtin_amdgcn_perm(b.w, a.w, 0x05040100u); hi.w = __builtin_amdgcn_perm(b.w, a.w, 0x07060302u);
+        u32x4* d = reinterpret_cast<u32x4*>(lds + (kl / 2) * X + xl);
+        d[0] = lo;
+        d[1] = hi;
+      } else {
+        *reinterpret_cast<u32x4*>(lds + kl * X + xl) = a;
       }
     }
   }
 
   __device__ __forceinline__ void store(uint32_t* __restrict__ lds, int tid) const {
-#pragma unroll
-    for (int it = 0; it < PER_T; ++it) {
-      const int id = it * kMBlock + tid;
-      if (UNITS % kMBlock != 0 && id >= UNITS) continue;
-      if (LAYOUT == KC && HALF) {
-        const int xl = id / (BK / V), kl = (id % (BK / V)) * V;
-        *reinterpret_cast<u32x4*>(lds + (xl * (BK + 8) + kl) / 2) = r[it][0];
-      } else if (LAYOUT == KC) {
-        const int xl = id / (BK / V), kl = (id % (BK / V)) * V;
-        uint32_t* d = lds + xl * (BK + 1) + kl;
-        d[0] = r[it][0].x; d[1] = r[it][0].y; d[2] = r[it][0].z; d[3] = r[it][0].w;
-      } else if (HALF) {
-        // interleave rows k and k+1: word j = (row_k[x_j], row_k1[x_j])
-        const int kp = id / (X / V), xl = (id % (X / V)) * V;
-        const u32x4 a = r[it][0], b = r[it][NV - 1];
-        u32x4 lo, hi;
-        lo.x = (a.x & 0xffffu) | (b.x << 16); lo.y = (a.x >> 16) | (b.x & 0xffff0000u);
-        lo.z = (a.y & 0xffffu) | (b.y << 16); lo.w = (a.y >> 16) | (b.y & 0xffff0000u);
-        hi.x = (a.z & 0xffffu) | (b.z << 16); hi.y = (a.z >> 16) | (b.z & 0xffff0000u);
-        hi.z = (a.w & 0xffffu) | (b.w << 16); hi.w = (a.w >> 16) | (b.w & 0xffff0000u);
-        u32x4* d = reinterpret_cast<u32x4*>(lds + kp * X + xl);
-        d[0] = lo;
-        d[1] = hi;
-      } else {
-        const int kl = id / (X / V), xl = (id % (X / V)) * V;
-        *reinterpret_cast<u32x4*>(lds + kl * X + xl) = r[it][0];
-      }
-    }
+    if (ok == kAllOk) store_impl<false>(lds, tid);   // nothing to zero: the common case
+    else store_impl<true>(lds, tid);
   }
 };
 
 // MFMA operand of lane (xi = lane % 32, g = lane / 32) for contraction step ks
 // of the tile: bf16: k = ks*16 + g*8 + [0,8); fp32: k = ks*2 + g.
-template <typename T, int LAYOUT, int X> struct Frag;
+template <typename T, int LAYOUT, int X, int BK> struct Frag;
 
-template <int LAYOUT, int X>
-struct Frag<bf16_t, LAYOUT, X> {
+template <int LAYOUT, int X, int BK>
+struct Frag<bf16_t, LAYOUT, X, BK> {
   typedef bf16x8 type;
   static __device__ __forceinline__ type read(const uint32_t* __restrict__ lds, int x, int ks, int g) {
-    constexpr int BK = ET<bf16_t>::BK;
     u32x4 v;
     if (LAYOUT == KC) {
       v = *reinterpret_cast<const u32x4*>(lds + (x * (BK + 8) + ks * 16 + g * 8) / 2);
@@ -158,11 +238,10 @@ struct Frag<bf16_t, LAYOUT, X> {
   }
 };
 
-template <int LAYOUT, int X>
-struct Frag<float, LAYOUT, X> {
+template <int LAYOUT, int X, int BK>
+struct Frag<float, LAYOUT, X, BK> {
   typedef float type;
   static __device__ __forceinline__ type read(const uint32_t* __restrict__ lds, int x, int ks, int g) {
-    constexpr int BK = ET<float>::BK;
     const uint32_t w = LAYOUT == KC ? lds[x * (BK + 1) + ks * 2 + g] : lds[(ks * 2 + g) * X + x];
     return __uint_as_float(w);
   }
@@ -195,125 +274,285 @@ struct GemmArgs {
   int relu;             // MODE_FWD: apply relu
   int out_f32;          // MODE_FWD: store fp32 (logits) instead of T
   int a_vec, b_vec;     // operands may be read with 16-byte loads
+  int c_vec;            // output rows may be written with 16-byte stores
 };
 
-// C[M x N] = A * B on one (worker, m-tile, n-tile).  grid = (n tiles, m tiles,
-// workers); 256 threads; wave (wm, wn) of the 2 x 2 arrangement owns a
-// (BM/2) x (BN/2) block made of TM x TN MFMA tiles of 32 x 32.
-template <typename T, int MODE, int BM, int BN>
-__global__ __launch_bounds__(kMBlock) void mlp_gemm_kernel(GemmArgs g) {
+// Workgroups are dealt to the 8 XCDs round-robin by launch order.  Re-deal so
+// that each XCD (each L2) owns a contiguous run of tiles with the n-tile index
+// running fastest: tiles that differ only in their row range keep hitting the
+// same few L2 channels (rows are a multiple of 2 KiB apart), while neighbouring
+// n-tiles spread over all of them.
+__device__ __forceinline__ void xcd_tile(int* bx, int* by, int* bz) {
+  *bx = blockIdx.x; *by = blockIdx.y; *bz = blockIdx.z;
+  const unsigned total = gridDim.x * gridDim.y * gridDim.z;
+  if ((total & 7u) == 0u) {
+    const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const unsigned logical = (lin & 7u) * (total >> 3) + (lin >> 3);
+    *bx = logical % gridDim.x;
+    *by = (logical / gridDim.x) % gridDim.y;
+    *bz = logical / (gridDim.x * gridDim.y);
+  }
+}
+
+// C[M x N] = A * B on one (worker, m-tile, n-tile), operands staged through
+// LDS.  grid = (n tiles, m tiles, workers); 512 threads = 8 wavefronts in two
+// roles:
+//   wavefronts 0-3 (consumers) tile the output 2 x 2, each owning a (BM/2) x
+//     (BN/2) block of TM x TN MFMA tiles; they only read LDS and issue MFMAs;
+//   wavefronts 4-7 (producers) move the operand tiles global -> registers ->
+//     LDS, up to four tiles ahead, transposing an operand whose contraction
+//     index is strided in memory on the way.
+// LDS holds two tiles (ping-pong): while tile t is multiplied out of one half,
+// tile t+1 is written into the other; one barrier per tile.  Memory latency and
+// the address work of the loads stall only the producers, never the MFMAs.
+// The output tile leaves through LDS as well (64 rows at a time), so that it is
+// written with 16-byte stores of whole row segments by all 512 threads: the
+// MFMA result layout alone would give 2- or 4-byte stores scattered over rows.
+constexpr int kGemmThreads = 2 * kMBlock;
+
+template <typename T, int MODE, int BM, int BN, int BK, bool ALIGNED>
+__global__ __launch_bounds__(kGemmThreads) void mlp_gemm_kernel(GemmArgs g) {
   constexpr int LA = MODE == MODE_DW ? XC : KC;
   constexpr int LB = MODE == MODE_DX ? KC : XC;
-  constexpr int BK = ET<T>::BK, KM = ET<T>::KM;
+  constexpr int KM = ET<T>::KM;
+  constexpr int KSTEPS = BK / KM;
   constexpr int TM = BM / 64, TN = BN / 64;
-  __shared__ __attribute__((aligned(16))) uint32_t sA[tile_words<T, LA, BM>()];
-  __shared__ __attribute__((aligned(16))) uint32_t sB[tile_words<T, LB, BN>()];
+  constexpr int WA = tile_words<T, LA, BM, BK>(), WB = tile_words<T, LB, BN, BK>();
+  constexpr int WT = (WA + WB + 3) / 4 * 4;      // one tile pair, 16-byte multiple
+  static_assert(64 * BN <= 2 * WT, "output staging (64 rows of fp32) must fit in the operand LDS");
+  __shared__ __attribute__((aligned(16))) uint32_t smem[2 * WT];
 
-  const int w = blockIdx.z;
+  int bx, by, bz;
+  xcd_tile(&bx, &by, &bz);
+  const int w = bz;
   const int64_t rows_w = g.row_off[w + 1] - g.row_off[w];
   const int64_t M = MODE == MODE_DW ? g.m_fixed : rows_w;
   const int64_t N = g.n;
-  const int64_t Kc = MODE == MODE_DW ? rows_w : g.k_fixed;
-  const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
+  const int kc = (int)(MODE == MODE_DW ? rows_w : g.k_fixed);
+  const int64_t m0 = (int64_t)by * BM, n0 = (int64_t)bx * BN;
   if (m0 >= M) return;   // uniform for the block
-
-  const T* A = reinterpret_cast<const T*>(g.a[w]);
-  const T* B = reinterpret_cast<const T*>(g.b) + (MODE == MODE_DW ? g.row_off[w] * g.ldb : 0);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_tiles = (kc + BK - 1) / BK;
+  const bool producer = threadIdx.x >= kMBlock;
+  const int tid = threadIdx.x & (kMBlock - 1);
+  const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int xi = lane & 31, gk = lane >> 5;
+  const int m_rows = (int)M;
 
   f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-  const bool want_colsum = MODE == MODE_DW && g.colsum_off >= 0 && blockIdx.y == 0;
+  float bias[TN];
+  T hmask[MODE == MODE_DX ? TM : 1][MODE == MODE_DX ? TN : 1][16];
   float colsum = 0.0f;
+  const bool want_colsum = MODE == MODE_DW && g.colsum_off >= 0 && by == 0;
 
-  TileStage<T, LA, BM> stA;
-  TileStage<T, LB, BN> stB;
-  const int64_t n_tiles = (Kc + BK - 1) / BK;
-  if (n_tiles > 0) {
-    stA.load(A, g.lda, m0, M, 0, Kc, g.a_vec != 0, tid);
-    stB.load(B, g.ldb, n0, N, 0, Kc, g.b_vec != 0, tid);
-  }
-  for (int64_t t = 0; t < n_tiles; ++t) {
-    __syncthreads();   // everyone is done reading the previous tile
-    stA.store(sA, tid);
-    stB.store(sB, tid);
-    __syncthreads();
-    if (t + 1 < n_tiles) {   // next tile's global loads fly during the MFMAs
-      stA.load(A, g.lda, m0, M, (t + 1) * BK, Kc, g.a_vec != 0, tid);
-      stB.load(B, g.ldb, n0, N, (t + 1) * BK, Kc, g.b_vec != 0, tid);
+  if (producer) {
+    const T* A = reinterpret_cast<const T*>(g.a[w]);
+    const T* B = reinterpret_cast<const T*>(g.b) + (MODE == MODE_DW ? g.row_off[w] * g.ldb : 0);
+    TileAddr<T, LA, BM, BK> adA;
+    TileAddr<T, LB, BN, BK> adB;
+    adA.init(A, g.lda, m0, M, tid);
+    adB.init(B, g.ldb, n0, N, tid);
+    // A ring of four register stages: while tile t is multiplied, the loads of
+    // tiles t+2 .. t+5 are in flight.  Loads, stores and barriers are issued on
+    // every path (a tile past the end reads the matrix origin and is stored as
+    // zeros into a half nobody reads; the loop runs a multiple of four steps),
+    // so that the number of loads outstanding at each wait is known exactly.
+    TileStage<T, LA, BM, BK, ALIGNED> stA[4];
+    TileStage<T, LB, BN, BK, ALIGNED> stB[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      stA[u].load(adA, u * BK, kc, tid);
+      stB[u].load(adB, u * BK, kc, tid);
     }
+    stA[0].store(smem, tid);
+    stB[0].store(smem + WA, tid);
+    stA[0].load(adA, 4 * BK, kc, tid);
+    stB[0].load(adB, 4 * BK, kc, tid);
+    __syncthreads();                               // tile 0 is in half 0
+    for (int t = 0; t < n_tiles; t += 4) {
 #pragma unroll
-    for (int ks = 0; ks < BK / KM; ++ks) {
-      typename Frag<T, LA, BM>::type fa[TM];
-      typename Frag<T, LB, BN>::type fb[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-        fa[i] = Frag<T, LA, BM>::read(sA, wm * (BM / 2) + i * 32 + xi, ks, gk);
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        fb[j] = Frag<T, LB, BN>::read(sB, wn * (BN / 2) + j * 32 + xi, ks, gk);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = mfma(fa[i], fb[j], acc[i][j]);
-    }
-    if (MODE == MODE_DW) {
-      if (want_colsum && tid < BN) {   // column sums of the dZ tile, in row order
-        if (sizeof(T) == 2) {
-#pragma unroll
-          for (int kp = 0; kp < BK / 2; ++kp) {
-            const uint32_t wd = sB[kp * BN + tid];
-            colsum += bf16_to_f32((uint16_t)(wd & 0xffffu));
-            colsum += bf16_to_f32((uint16_t)(wd >> 16));
-          }
-        } else {
-#pragma unroll
-          for (int k = 0; k < BK; ++k) colsum += __uint_as_float(sB[k * BN + tid]);
-        }
+      for (int u = 0; u < 4; ++u) {
+        // tile t+u+1 -> the half that tile t+u (being multiplied now) does not use
+        uint32_t* half = smem + (((u + 1) & 1) ? WT : 0);
+        stA[(u + 1) & 3].store(half, tid);
+        stB[(u + 1) & 3].store(half + WA, tid);
+        stA[(u + 1) & 3].load(adA, (t + u + 5) * BK, kc, tid);
+        stB[(u + 1) & 3].load(adB, (t + u + 5) * BK, kc, tid);
+        __syncthreads();
       }
     }
-  }
-
-  // epilogue: lane holds column (xi) of 16 rows per MFMA tile
-  char* Cw = reinterpret_cast<char*>(g.c[w]);
+  } else {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    // What the epilogue needs from memory (bias, relu mask of the layer below)
+    // is requested now, so that its latency hides behind the contraction.
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int64_t col = n0 + wn * (BN / 2) + j * 32 + xi;
-      if (col >= N) continue;
-      float bias = 0.0f;
-      if (MODE == MODE_FWD) bias = g.bias[col];
+      bias[j] = 0.0f;
+      if (MODE == MODE_FWD) bias[j] = g.bias[col < N ? col : 0];
+      if (MODE == MODE_DX) {
+        const T* mk = reinterpret_cast<const T*>(g.mask) + g.row_off[w] * g.ldmask;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int64_t row = m0 + wm * (BM / 2) + i * 32 + (v >> 2) * 8 + gk * 4 + (v & 3);
-        if (row >= M) continue;
-        float val = acc[i][j][v];
-        if (MODE == MODE_FWD) {
-          val += bias;
-          if (g.relu) val = fmaxf(val, 0.0f);
-          if (g.out_f32) reinterpret_cast<float*>(Cw)[row * g.ldc + col] = val;
-          else store_as(reinterpret_cast<T*>(Cw) + row * g.ldc + col, val);
-        } else if (MODE == MODE_DX) {
-          const T h = reinterpret_cast<const T*>(g.mask)[(g.row_off[w] + row) * g.ldmask + col];
-          if (!(to_f32(h) > 0.0f)) val = 0.0f;
-          store_as(reinterpret_cast<T*>(Cw) + row * g.ldc + col, val);
-        } else {
-          reinterpret_cast<float*>(Cw)[row * g.ldc + col] = val;
+        for (int i = 0; i < TM; ++i) {
+          const int row0 = (int)m0 + wm * (BM / 2) + i * 32 + gk * 4;
+          const T* mk0 = mk + (int64_t)row0 * g.ldmask + col;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int dr = (v >> 2) * 8 + (v & 3);
+            hmask[i][j][v] = (col < N && row0 + dr < m_rows) ? mk0[dr * g.ldmask] : mk[0];
+          }
+        }
+      }
+    }
+
+    auto compute_tile = [&](const uint32_t* sA, const uint32_t* sB) {
+      if (TM * TN == 1) {
+        // one MFMA per k step: fetch every fragment of the tile first, so that
+        // the LDS latency is paid once and not once per step
+        typename Frag<T, LA, BM, BK>::type fa[KSTEPS];
+        typename Frag<T, LB, BN, BK>::type fb[KSTEPS];
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+          fa[ks] = Frag<T, LA, BM, BK>::read(sA, wm * (BM / 2) + xi, ks, gk);
+          fb[ks] = Frag<T, LB, BN, BK>::read(sB, wn * (BN / 2) + xi, ks, gk);
+        }
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) acc[0][0] = mfma(fa[ks], fb[ks], acc[0][0]);
+      } else {
+        typename Frag<T, LA, BM, BK>::type fa[2][TM];
+        typename Frag<T, LB, BN, BK>::type fb[2][TN];
+        auto read_frags = [&](int ks, int buf) {
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+            fa[buf][i] = Frag<T, LA, BM, BK>::read(sA, wm * (BM / 2) + i * 32 + xi, ks, gk);
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            fb[buf][j] = Frag<T, LB, BN, BK>::read(sB, wn * (BN / 2) + j * 32 + xi, ks, gk);
+        };
+        read_frags(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+          if (ks + 1 < KSTEPS) read_frags(ks + 1, (ks + 1) & 1);
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = mfma(fa[ks & 1][i], fb[ks & 1][j], acc[i][j]);
+        }
+      }
+      if (MODE == MODE_DW) {
+        if (want_colsum && tid < BN) {   // column sums of the dZ tile, in row order
+          if (sizeof(T) == 2) {
+#pragma unroll 8
+            for (int kp = 0; kp < BK / 2; ++kp) {
+              const uint32_t wd = sB[kp * BN + tid];
+              colsum += bf16_to_f32((uint16_t)(wd & 0xffffu));
+              colsum += bf16_to_f32((uint16_t)(wd >> 16));
+            }
+          } else {
+#pragma unroll 8
+            for (int k = 0; k < BK; ++k) colsum += __uint_as_float(sB[k * BN + tid]);
+          }
+        }
+      }
+    };
+
+    __syncthreads();                                 // tile 0 is in half 0
+    for (int t = 0; t < n_tiles; t += 4) {           // same number of barriers as the producers
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (t + u < n_tiles) {
+          const uint32_t* half = smem + ((u & 1) ? WT : 0);
+          compute_tile(half, half + WA);
+        }
+        __syncthreads();
+      }
+    }
+
+    // bias / relu / mask applied in registers
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float val = acc[i][j][v];
+          if (MODE == MODE_FWD) {
+            val += bias[j];
+            if (g.relu) val = fmaxf(val, 0.0f);
+          } else if (MODE == MODE_DX) {
+            if (!(to_f32(hmask[MODE == MODE_DX ? i : 0][MODE == MODE_DX ? j : 0][v]) > 0.0f)) val = 0.0f;
+          }
+          acc[i][j][v] = val;
+        }
+  }
+
+  // ---------------------------------------------------------------- output
+  // (the last barrier of the loops above ordered every LDS read before this)
+  const bool out_f32 = MODE == MODE_DW || sizeof(T) == 4 || (MODE == MODE_FWD && g.out_f32);
+  char* Cw = reinterpret_cast<char*>(g.c[w]);
+  if (ALIGNED && g.c_vec) {
+    constexpr int PASSES = BM / 64;
+    for (int ps = 0; ps < PASSES; ++ps) {
+      if (!producer) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int tile_row = wm * (BM / 2) + i * 32;     // first row of the MFMA tile in the block tile
+          if (tile_row / 64 != ps) continue;
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const int cl = wn * (BN / 2) + j * 32 + xi;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int rl = (tile_row & 63) + (v >> 2) * 8 + gk * 4 + (v & 3);
+              if (out_f32) reinterpret_cast<float*>(smem)[rl * BN + cl] = acc[i][j][v];
+              else reinterpret_cast<uint16_t*>(smem)[rl * BN + cl] = f32_to_bf16(acc[i][j][v]);
+            }
+          }
+        }
+      }
+      __syncthreads();
+      const int elem_b = out_f32 ? 4 : 2;
+      const int cpr = BN * elem_b / 16;                      // 16-byte chunks per row
+      for (int c = threadIdx.x; c < 64 * cpr; c += kGemmThreads) {
+        const int rl = c / cpr, ch = c - rl * cpr;
+        const int64_t row = m0 + ps * 64 + rl;
+        const int64_t col = n0 + ch * (16 / elem_b);
+        if (row < M && col < N) {
+          const u32x4 q = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(smem) +
+                                                          ((int64_t)rl * BN * elem_b + ch * 16));
+          *reinterpret_cast<u32x4*>(Cw + (row * g.ldc + col) * elem_b) = q;
+        }
+      }
+      if (ps + 1 < PASSES) __syncthreads();
+    }
+  } else if (!producer) {
+    // element-wise stores straight from the MFMA layout
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int64_t col = n0 + wn * (BN / 2) + j * 32 + xi;
+        const int row0 = (int)m0 + wm * (BM / 2) + i * 32 + gk * 4;   // row of v: row0 + (v>>2)*8 + (v&3)
+        const int64_t e0 = (int64_t)row0 * g.ldc + col;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int dr = (v >> 2) * 8 + (v & 3);
+          if (col >= N || row0 + dr >= m_rows) continue;
+          const int64_t e = e0 + dr * g.ldc;
+          if (out_f32) reinterpret_cast<float*>(Cw)[e] = acc[i][j][v];
+          else reinterpret_cast<uint16_t*>(Cw)[e] = f32_to_bf16(acc[i][j][v]);
         }
       }
     }
   }
   if (MODE == MODE_DW) {
-    if (want_colsum && tid < BN && n0 + tid < N)
+    if (!producer && want_colsum && tid < BN && n0 + tid < N)
       reinterpret_cast<float*>(Cw)[g.colsum_off + n0 + tid] = colsum;
   }
 }
@@ -387,33 +626,195 @@ __global__ __launch_bounds__(kMBlock) void softmax_ce_kernel(CeArgs a) {
   }
 }
 
-// loss[w] = aggregate over the worker's slices of the slice mean losses.
+// loss[w] = aggregate over the worker's slices of the slice mean losses.  One
+// wavefront per slice: lanes stride over the slice's rows, a fixed shuffle tree
+// adds the 64 partial sums; thread 0 then folds the slices in slice order.
 __global__ __launch_bounds__(kMBlock) void slice_loss_kernel(const float* __restrict__ row_loss,
                                                              CeArgs a, float* __restrict__ loss) {
-  __shared__ float s_part[kMBlock];
+  __shared__ float s_mean[kMBlock / 64];
   const int w = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t rows_w = a.row_off[w + 1] - a.row_off[w];
   const float* rl = row_loss + a.row_off[w];
+  const int64_t base = rows_w / a.n_slices, extra = rows_w % a.n_slices;
   float total = 0.0f;
-  for (int s = 0; s < a.n_slices; ++s) {
-    const int64_t base = rows_w / a.n_slices, extra = rows_w % a.n_slices;
-    const int64_t n_ws = base + (s < extra ? 1 : 0);
-    const int64_t start = base * s + (s < extra ? s : extra);
-    float part = 0.0f;
-    for (int64_t i = threadIdx.x; i < n_ws; i += kMBlock) part += rl[start + i];
-    s_part[threadIdx.x] = part;
+  for (int s0 = 0; s0 < a.n_slices; s0 += kMBlock / 64) {
+    const int s = s0 + wave;
+    float contrib = 0.0f;
+    if (s < a.n_slices) {
+      const int64_t n_ws = base + (s < extra ? 1 : 0);
+      const int64_t start = base * s + (s < extra ? s : extra);
+      float part = 0.0f;
+      for (int64_t i = lane; i < n_ws; i += 64) part += rl[start + i];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+      if (n_ws > 0) {
+        const float slice_mean = part / (float)n_ws;
+        contrib = (a.grad_op == SYNK_MEAN) ? slice_mean * ((float)n_ws / (float)rows_w) : slice_mean;
+      }
+    }
+    if (lane == 0) s_mean[wave] = contrib;
     __syncthreads();
-    for (int off = kMBlock / 2; off > 0; off >>= 1) {
-      if (threadIdx.x < off) s_part[threadIdx.x] += s_part[threadIdx.x + off];
-      __syncthreads();
-    }
-    if (n_ws > 0) {
-      const float slice_mean = s_part[0] / (float)n_ws;
-      total += (a.grad_op == SYNK_MEAN) ? slice_mean * ((float)n_ws / (float)rows_w) : slice_mean;
-    }
+    if (threadIdx.x == 0)
+      for (int k = 0; k < kMBlock / 64; ++k) total += s_mean[k];
     __syncthreads();
   }
   if (threadIdx.x == 0) loss[w] = total;
+}
+
+// ------------------------------------------------------------------ head
+// Narrow last layer (at most kHeadMaxC classes), all in one kernel, one
+// wavefront per row: logits = h W_L + b_L, softmax cross-entropy, dZ_L, and
+// the back-propagated dZ_{L-1} = (dZ_L W_L^T) * [h > 0].  A 10-column GEMM
+// would leave the matrix cores idle.  Each lane owns 8 consecutive features of
+// the row; the 8 x C block of W_L that goes with them is contiguous in memory
+// (W_L is [K x C] row-major), so it is read with 16-byte loads straight into
+// registers and serves the forward and the backward product: no LDS, no
+// barrier.
+constexpr int kHeadMaxC = 16;
+constexpr int kHeadRowsPerBlock = 4;
+
+struct HeadArgs {
+  const int32_t* y[SYNK_MAX_WORKERS];
+  int64_t row_off[SYNK_MAX_WORKERS + 1];
+  const void* h;        // [R x K] activations below the last layer, in T
+  const void* w;        // [K x C] in T, 16-byte aligned
+  const float* bias;    // [C]
+  void* dz;             // [R x C] in T
+  void* dz_below;       // [R x K] in T
+  float* row_loss;      // [R]
+  int K;
+  int n_slices, grad_op;
+};
+
+template <typename T> struct Vec8;   // 8 consecutive elements as floats
+template <> struct Vec8<bf16_t> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float* v) {
+    const u32x4 q = *reinterpret_cast<const u32x4*>(p);
+    v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+    v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+    v[4] = __uint_as_float(q.z << 16); v[5] = __uint_as_float(q.z & 0xffff0000u);
+    v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float* v) {
+    u32x4 q;
+    q.x = pack_bf16x2(v[0], v[1]); q.y = pack_bf16x2(v[2], v[3]);
+    q.z = pack_bf16x2(v[4], v[5]); q.w = pack_bf16x2(v[6], v[7]);
+    *reinterpret_cast<u32x4*>(p) = q;
+  }
+};
+template <> struct Vec8<float> {
+  static __device__ __forceinline__ void load(const float* p, float* v) {
+    const f32x4 a = reinterpret_cast<const f32x4*>(p)[0], b = reinterpret_cast<const f32x4*>(p)[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float* v) {
+    reinterpret_cast<f32x4*>(p)[0] = f32x4{v[0], v[1], v[2], v[3]};
+    reinterpret_cast<f32x4*>(p)[1] = f32x4{v[4], v[5], v[6], v[7]};
+  }
+};
+__device__ __forceinline__ float round_like(float v, float) { return v; }
+__device__ __forceinline__ float round_like(float v, bf16_t) { return bf16_to_f32(f32_to_bf16(v)); }
+
+// the 8 x C block of W_L for features [k0, k0+8): wv[j*C + c]
+template <typename T, int C>
+__device__ __forceinline__ void load_w_block(const T* __restrict__ W, int k0, float* wv) {
+#pragma unroll
+  for (int q = 0; q < C; ++q) Vec8<T>::load(W + (int64_t)k0 * C + q * 8, wv + q * 8);
+}
+
+template <typename T, int C>
+__global__ __launch_bounds__(kMBlock) void mlp_head_kernel(HeadArgs a) {
+  const int K = a.K;
+  const T* Wg = reinterpret_cast<const T*>(a.w);
+  const int w = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t rows_w = a.row_off[w + 1] - a.row_off[w];
+  const int64_t r = (int64_t)blockIdx.x * kHeadRowsPerBlock + wave;
+  if (r >= rows_w) return;
+  const int64_t row = a.row_off[w] + r;
+  const T* h = reinterpret_cast<const T*>(a.h) + row * K;
+  const int y = a.y[w][r];
+
+  float weight;
+  if (a.grad_op == SYNK_MEAN) {
+    weight = 1.0f / (float)rows_w;
+  } else {
+    int s;
+    int64_t start;
+    share_of(rows_w, a.n_slices, r, &s, &start);
+    const int64_t n_ws = rows_w / a.n_slices + (s < rows_w % a.n_slices ? 1 : 0);
+    weight = 1.0f / (float)n_ws;
+  }
+
+  // forward: each lane accumulates its features' share of every logit
+  float acc[C];
+#pragma unroll
+  for (int c = 0; c < C; ++c) acc[c] = 0.0f;
+  for (int k0 = lane * 8; k0 < K; k0 += 64 * 8) {
+    float hv[8], wv[8 * C];
+    Vec8<T>::load(h + k0, hv);
+    load_w_block<T, C>(Wg, k0, wv);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int c = 0; c < C; ++c) acc[c] = fmaf(hv[j], wv[j * C + c], acc[c]);
+  }
+  float m = -INFINITY;
+#pragma unroll
+  for (int c = 0; c < C; ++c) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc[c] += __shfl_xor(acc[c], off);
+    acc[c] += a.bias[c];
+    m = fmaxf(m, acc[c]);
+  }
+  float ssum = 0.0f, xy = 0.0f;
+#pragma unroll
+  for (int c = 0; c < C; ++c) {
+    ssum += expf(acc[c] - m);
+    if (c == y) xy = acc[c];
+  }
+  if (lane == 0) a.row_loss[row] = (logf(ssum) + m) - xy;
+  const float inv = 1.0f / ssum;
+  T* dz = reinterpret_cast<T*>(a.dz) + row * C;
+  float dzq[C];   // dZ_L as the GEMMs will read it back (rounded to T)
+#pragma unroll
+  for (int c = 0; c < C; ++c) {
+    const float p = expf(acc[c] - m) * inv;
+    dzq[c] = round_like((p - (c == y ? 1.0f : 0.0f)) * weight, T());
+    if (lane == c) store_as(dz + c, dzq[c]);
+  }
+  if (a.dz_below == nullptr) return;
+
+  // backward through the last layer, masked by the relu below
+  T* dzb = reinterpret_cast<T*>(a.dz_below) + row * K;
+  for (int k0 = lane * 8; k0 < K; k0 += 64 * 8) {
+    float hv[8], wv[8 * C], dh[8];
+    Vec8<T>::load(h + k0, hv);
+    load_w_block<T, C>(Wg, k0, wv);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float d = 0.0f;
+#pragma unroll
+      for (int c = 0; c < C; ++c) d = fmaf(dzq[c], wv[j * C + c], d);
+      dh[j] = (hv[j] > 0.0f) ? d : 0.0f;
+    }
+    Vec8<T>::store(dzb + k0, dh);
+  }
+}
+
+template <typename T>
+static int launch_head(const HeadArgs& ha, int C, dim3 grid, hipStream_t s) {
+#define SYNK_HEAD(CC) case CC: hipLaunchKernelGGL((mlp_head_kernel<T, CC>), grid, dim3(kMBlock), 0, s, ha); break
+  switch (C) {
+    SYNK_HEAD(1); SYNK_HEAD(2); SYNK_HEAD(3); SYNK_HEAD(4); SYNK_HEAD(5); SYNK_HEAD(6); SYNK_HEAD(7);
+    SYNK_HEAD(8); SYNK_HEAD(9); SYNK_HEAD(10); SYNK_HEAD(11); SYNK_HEAD(12); SYNK_HEAD(13); SYNK_HEAD(14);
+    SYNK_HEAD(15); SYNK_HEAD(16);
+    default: return SYNK_ERR_UNSUPPORTED;
+  }
+#undef SYNK_HEAD
+  SYNK_LAUNCH_CHECK();
+  return SYNK_OK;
 }
 
 // ------------------------------------------------------------ host side
@@ -482,14 +883,22 @@ static int make_plan(const synk_mlp_desc* m, const int64_t* rows, int n_workers,
 
 template <typename T, int MODE>
 static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStream_t s) {
-  // large tiles when they alone fill the chip, small ones otherwise
+  // 128 x 128 tiles when they alone fill the chip, 64 x 64 otherwise
+  constexpr int BK_BIG = sizeof(T) == 2 ? 32 : 16, BK_SMALL = sizeof(T) == 2 ? 64 : 32;
   const int64_t big = ((m_max + 127) / 128) * ((g.n + 127) / 128) * n_workers;
+  const bool aligned = g.a_vec && g.b_vec;
   if (big >= 2 * kNumCU) {
     const dim3 grid((unsigned)((g.n + 127) / 128), (unsigned)((m_max + 127) / 128), n_workers);
-    hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, 128, 128>), grid, dim3(kMBlock), 0, s, g);
+    if (aligned)
+      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, 128, 128, BK_BIG, true>), grid, dim3(kGemmThreads), 0, s, g);
+    else
+      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, 128, 128, BK_BIG, false>), grid, dim3(kGemmThreads), 0, s, g);
   } else {
     const dim3 grid((unsigned)((g.n + 63) / 64), (unsigned)((m_max + 63) / 64), n_workers);
-    hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, 64, 64>), grid, dim3(kMBlock), 0, s, g);
+    if (aligned)
+      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, 64, 64, BK_SMALL, true>), grid, dim3(kGemmThreads), 0, s, g);
+    else
+      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, 64, 64, BK_SMALL, false>), grid, dim3(kGemmThreads), 0, s, g);
   }
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;
@@ -514,14 +923,20 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
     if (rows[w] > 0) x_vec = x_vec && aligned_to(x[w], 16);
     grad_al = grad_al && aligned_to(grad[w], 16);
   }
-  (void)grad_al;
 
   GemmArgs g;
   for (int w = 0; w <= n_workers; ++w) g.row_off[w] = p.row_off[w];
   for (int w = n_workers + 1; w <= SYNK_MAX_WORKERS; ++w) g.row_off[w] = p.R;
 
+  // The narrow-last-layer kernel replaces the last forward GEMM, the softmax
+  // kernel and the last dX GEMM when the layer fits it.
+  const bool use_head = L >= 2 && p.d[L] <= kHeadMaxC && p.d[L - 1] % 8 == 0 &&
+                        aligned_to(wts + p.offW[L - 1], 16);
+
+  const int n_fwd = use_head ? L - 1 : L;
+
   // ---- forward (layer index l = 1..L, weights W_l = [d_{l-1} x d_l])
-  for (int l = 1; l <= L; ++l) {
+  for (int l = 1; l <= n_fwd; ++l) {
     const int64_t K = p.d[l - 1], N = p.d[l];
     const T* W = wts + p.offW[l - 1];
     for (int w = 0; w < n_workers; ++w) {
@@ -540,6 +955,7 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
     g.out_f32 = l == L;
     g.a_vec = (K % V == 0) && (l == 1 ? x_vec : true);
     g.b_vec = (N % V == 0) && aligned_to(W, 16);
+    g.c_vec = N % 8 == 0;     // workspace rows: 256-byte aligned base, rows a multiple of 16 bytes
     if (int rc = launch_gemm<T, MODE_FWD>(g, p.max_rows, n_workers, s)) return rc;
   }
 
@@ -553,20 +969,38 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
   ce.classes = p.d[L];
   ce.n_slices = n_slices;
   ce.grad_op = grad_op;
-  {
+  if (use_head) {
+    HeadArgs ha;
+    for (int w = 0; w < n_workers; ++w) ha.y[w] = y[w];
+    for (int w = 0; w <= SYNK_MAX_WORKERS; ++w) ha.row_off[w] = g.row_off[w];
+    ha.h = act(L - 1);
+    ha.w = wts + p.offW[L - 1];
+    ha.bias = params + p.offB[L - 1];
+    ha.dz = dzp(L);
+    ha.dz_below = dzp(L - 1);
+    ha.row_loss = row_loss;
+    ha.K = (int)p.d[L - 1];
+    ha.n_slices = n_slices;
+    ha.grad_op = grad_op;
+    const dim3 grid((unsigned)((p.max_rows + kHeadRowsPerBlock - 1) / kHeadRowsPerBlock), n_workers);
+    if (int rc = launch_head<T>(ha, (int)p.d[L], grid, s)) return rc;
+  } else {
     const dim3 grid((unsigned)((p.max_rows + kCeRowsPerBlock - 1) / kCeRowsPerBlock), n_workers);
     hipLaunchKernelGGL((softmax_ce_kernel<T>), grid, dim3(kMBlock), 0, s, ce);
     SYNK_LAUNCH_CHECK();
-    hipLaunchKernelGGL(slice_loss_kernel, dim3(n_workers), dim3(kMBlock), 0, s, row_loss, ce, loss);
-    SYNK_LAUNCH_CHECK();
   }
+  hipLaunchKernelGGL(slice_loss_kernel, dim3(n_workers), dim3(kMBlock), 0, s, row_loss, ce, loss);
+  SYNK_LAUNCH_CHECK();
 
   // ---- backward
   for (int l = L; l >= 1; --l) {
     const int64_t K = p.d[l - 1], N = p.d[l];
     // dW_l[w] = H_{l-1}[w]^T dZ_l[w]; db_l[w] = column sums of dZ_l[w]
     for (int w = 0; w < n_workers; ++w) {
-      g.a[w] = l == 1 ? x[w] : (const void*)(act(l - 1) + p.row_off[w] * K);
+      // a worker without rows still gets a block (it writes the zero gradient); its
+      // operand pointer must be readable because loads are issued unconditionally
+      g.a[w] = l == 1 ? (rows[w] > 0 ? x[w] : (const void*)ws)
+                      : (const void*)(act(l - 1) + p.row_off[w] * K);
       g.c[w] = grad[w] + p.offW[l - 1];
     }
     g.b = dzp(l);
@@ -581,9 +1015,10 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
     g.out_f32 = 1;
     g.a_vec = (K % V == 0) && (l == 1 ? x_vec : true);
     g.b_vec = (N % V == 0);
+    g.c_vec = grad_al && N % 4 == 0 && p.offW[l - 1] % 4 == 0;
     if (int rc = launch_gemm<T, MODE_DW>(g, K, n_workers, s)) return rc;
 
-    if (l > 1) {
+    if (l > 1 && !(use_head && l == L)) {
       // dZ_{l-1} = (dZ_l W_l^T) * [H_{l-1} > 0]
       const T* W = wts + p.offW[l - 1];
       for (int w = 0; w < n_workers; ++w) {
@@ -599,6 +1034,8 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
       g.colsum_off = -1;
       g.a_vec = (N % V == 0);
       g.b_vec = (N % V == 0) && aligned_to(W, 16);
+      g.c_vec = K % 8 == 0;
+      g.out_f32 = 0;
       if (int rc = launch_gemm<T, MODE_DX>(g, p.max_rows, n_workers, s)) return rc;
     }
   }

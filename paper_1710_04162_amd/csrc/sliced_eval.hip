@@ -1,10 +1,10 @@
 // Six-output evaluation over slices with on-GPU aggregation (Sec. 3.1: one
 // reduce/gather op per output; Sec. 5.1: slice results aggregated in place).
 //
-// Stage 1 (one pass over the logits, bound by HBM bandwidth): one wavefront
-// per row computes arg-max, max, min and the log-sum-exp with a running
-// (max, sum) pair, merged across the 64 lanes with shuffles; a workgroup covers
-// a run of rows of ONE slice and leaves per-(slice, chunk) partial results.
+// Stage 1 (one pass over the logits, bound by HBM bandwidth): a group of 16
+// or 64 lanes holds a row in registers and computes arg-max, max, min and the
+// log-sum-exp, merged across the group with shuffles; a workgroup covers a run
+// of rows of ONE slice and leaves per-(slice, chunk) partial results.
 // Stage 2 folds chunk partials into slice results and slice results into the
 // outputs with each output's op, in a fixed order (no float atomics).
 #include <math.h>
@@ -15,7 +15,7 @@ namespace synk {
 
 constexpr int kEBlock = 256;
 constexpr int kEWaves = kEBlock / kWave;
-constexpr int kRowsPerBlock = 32;
+constexpr int kRowsPerBlock = 16;
 
 struct EvalWs {
   float* part_ce;        // [S x CH]
@@ -72,13 +72,13 @@ __device__ __forceinline__ void take(RowStat& st, float x, int c, int y) {
   if (c == y) st.xy = x;
 }
 
-template <bool VEC>
-__global__ __launch_bounds__(kEBlock) void eval_stage1_kernel(
+// Generic stage 1 (any class count, any alignment): one wavefront per row,
+// scalar loads, running (max, sum) pair merged over the 64 lanes.
+__global__ __launch_bounds__(kEBlock) void eval_stage1_generic_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ labels, int64_t rows, int classes,
     int n_slices, int chunks, EvalWs ws, int32_t* __restrict__ argmax_out) {
   const int slice = blockIdx.y, chunk = blockIdx.x;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  // rows of this slice (split rule), then this block's run inside it
   const int64_t base = rows / n_slices, extra = rows % n_slices;
   const int64_t s_rows = base + (slice < extra ? 1 : 0);
   const int64_t s_start = base * slice + (slice < extra ? slice : extra);
@@ -93,30 +93,7 @@ __global__ __launch_bounds__(kEBlock) void eval_stage1_kernel(
     const float* x = logits + row * classes;
     const int y = labels[row];
     RowStat st{-INFINITY, 0.0f, INFINITY, 0x7fffffff, 0.0f};
-    if (VEC) {
-      const int units = classes >> 2;
-      for (int u0 = 0; u0 < units; u0 += 4 * kWave) {
-        f32x4 q[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const int u = u0 + k * kWave + lane;
-          if (u < units) q[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(x) + u);
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const int u = u0 + k * kWave + lane;
-          if (u < units) {
-            const int c = u << 2;
-            take(st, q[k].x, c, y);
-            take(st, q[k].y, c + 1, y);
-            take(st, q[k].z, c + 2, y);
-            take(st, q[k].w, c + 3, y);
-          }
-        }
-      }
-    } else {
-      for (int c = lane; c < classes; c += kWave) take(st, x[c], c, y);
-    }
+    for (int c = lane; c < classes; c += kWave) take(st, x[c], c, y);
     // merge the 64 lanes: larger max wins, equal maxima keep the lower index
 #pragma unroll
     for (int off = kWave / 2; off > 0; off >>= 1) {
@@ -126,7 +103,7 @@ __global__ __launch_bounds__(kEBlock) void eval_stage1_kernel(
       const int oarg = __shfl_xor(st.arg, off);
       const float oxy = __shfl_xor(st.xy, off);
       const float nm = fmaxf(st.m, om);
-      // exp(-inf - finite) = 0 covers lanes that saw no element
+      // lanes that saw no element have m = -inf and s = 0
       const float sa = (st.m == nm) ? st.s : st.s * __expf(st.m - nm);
       const float sb = (om == nm) ? os : os * __expf(om - nm);
       if (om > st.m || (om == st.m && oarg < st.arg)) st.arg = oarg;
@@ -170,59 +147,195 @@ __global__ __launch_bounds__(kEBlock) void eval_stage1_kernel(
   }
 }
 
-// Stage 2.  Block 0: chunk partials -> slice results (in chunk order) -> the
-// four scalar outputs with their ops over slices (fixed-shape tree).  All
-// blocks: class_counts[c] = sum over slices of the slice's count, in slice
-// order.
-__global__ __launch_bounds__(kEBlock) void eval_stage2_kernel(
+// Fast stage 1 (class count a multiple of 4, 16-byte aligned rows): G lanes
+// share a row, so a wavefront works on 64/G rows at once and the cross-lane
+// merges span only G lanes.  The whole row sits in registers (UPL 16-byte
+// vectors per lane): one HBM read, the maximum is reduced first and the
+// exponentials are taken against the final maximum.
+template <int G, int UPL>
+__global__ __launch_bounds__(kEBlock) void eval_stage1_kernel(
+    const float* __restrict__ logits, const int32_t* __restrict__ labels, int64_t rows, int classes,
+    int n_slices, int chunks, EvalWs ws, int32_t* __restrict__ argmax_out) {
+  constexpr int RW = kWave / G;            // rows a wavefront handles at once
+  constexpr int NACC = kEWaves * RW;       // per-block accumulators
+  constexpr float kLog2e = 1.4426950408889634f;
+  const int slice = blockIdx.y, chunk = blockIdx.x;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int sub = lane % G, grp = lane / G;
+  const int units = classes >> 2;
+  const int64_t base = rows / n_slices, extra = rows % n_slices;
+  const int64_t s_rows = base + (slice < extra ? 1 : 0);
+  const int64_t s_start = base * slice + (slice < extra ? slice : extra);
+  const int64_t r0 = (int64_t)chunk * kRowsPerBlock;
+  int64_t r1 = r0 + kRowsPerBlock;
+  if (r1 > s_rows) r1 = s_rows;
+
+  float w_ce = 0.0f, w_max = -INFINITY, w_min = INFINITY;
+  int w_correct = 0;
+  for (int64_t rb = r0 + (int64_t)wave * RW; rb < r1; rb += (int64_t)kEWaves * RW) {
+    const int64_t r = rb + grp;
+    const bool valid = r < r1;
+    const int64_t row = s_start + (valid ? r : r0);
+    const f32x4* x = reinterpret_cast<const f32x4*>(logits + row * classes);
+    f32x4 q[UPL];
+#pragma unroll
+    for (int k = 0; k < UPL; ++k) {
+      const int u = k * G + sub;
+      if (valid && u < units) q[k] = __builtin_nontemporal_load(x + u);
+      else q[k] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    }
+    const int y = valid ? labels[row] : -1;
+    // label logit: one extra load of a line this wavefront has just requested
+    const float xy = (valid && y >= 0 && y < classes) ? logits[row * classes + y] : 0.0f;
+
+    // lane-local maximum and minimum; padding is -inf, so the minimum skips it
+    float m = -INFINITY, mn = INFINITY;
+#pragma unroll
+    for (int k = 0; k < UPL; ++k) {
+      m = fmaxf(m, fmaxf(fmaxf(q[k].x, q[k].y), fmaxf(q[k].z, q[k].w)));
+      const float lo = fminf(fminf(q[k].x, q[k].y), fminf(q[k].z, q[k].w));
+      if (k * G + sub < units) mn = fminf(mn, lo);
+    }
+    // first position of the lane-local maximum (scan downwards, keep the last hit)
+    int arg = 0x7fffffff;
+#pragma unroll
+    for (int k = UPL - 1; k >= 0; --k) {
+      const int c = (k * G + sub) << 2;
+      if (q[k].w == m) arg = c + 3;
+      if (q[k].z == m) arg = c + 2;
+      if (q[k].y == m) arg = c + 1;
+      if (q[k].x == m) arg = c;
+    }
+    if (m == -INFINITY) arg = 0x7fffffff;   // lane holds padding only
+#pragma unroll
+    for (int off = G / 2; off > 0; off >>= 1) {
+      const float om = __shfl_xor(m, off);
+      const int oarg = __shfl_xor(arg, off);
+      if (om > m || (om == m && oarg < arg)) arg = oarg;
+      m = fmaxf(m, om);
+    }
+    const float mb = m * kLog2e;
+    float s = 0.0f;
+#pragma unroll
+    for (int k = 0; k < UPL; ++k) {
+      // arguments are <= 0: the raw hardware exp2 (no denormal fix-up) is exact enough
+      s += __builtin_amdgcn_exp2f(fmaf(q[k].x, kLog2e, -mb)) + __builtin_amdgcn_exp2f(fmaf(q[k].y, kLog2e, -mb)) +
+           __builtin_amdgcn_exp2f(fmaf(q[k].z, kLog2e, -mb)) + __builtin_amdgcn_exp2f(fmaf(q[k].w, kLog2e, -mb));
+    }
+#pragma unroll
+    for (int off = G / 2; off > 0; off >>= 1) {
+      s += __shfl_xor(s, off);
+      mn = fminf(mn, __shfl_xor(mn, off));
+    }
+    if (sub == 0 && valid) {
+      w_ce += (__logf(s) + m) - xy;
+      w_max = fmaxf(w_max, m);
+      w_min = fminf(w_min, mn);
+      w_correct += (arg == y) ? 1 : 0;
+      argmax_out[row] = arg;
+      atomicAdd(ws.slice_counts + (int64_t)slice * classes + arg, 1);
+    }
+  }
+  __shared__ float s_ce[NACC], s_max[NACC], s_min[NACC];
+  __shared__ int s_cor[NACC];
+  if (sub == 0) {
+    s_ce[wave * RW + grp] = w_ce;
+    s_max[wave * RW + grp] = w_max;
+    s_min[wave * RW + grp] = w_min;
+    s_cor[wave * RW + grp] = w_correct;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float ce = s_ce[0], mx = s_max[0], mn = s_min[0];
+    int cor = s_cor[0];
+    for (int w = 1; w < NACC; ++w) {
+      ce += s_ce[w];
+      mx = fmaxf(mx, s_max[w]);
+      mn = fminf(mn, s_min[w]);
+      cor += s_cor[w];
+    }
+    const int64_t o = (int64_t)slice * chunks + chunk;
+    ws.part_ce[o] = ce;
+    ws.part_max[o] = mx;
+    ws.part_min[o] = mn;
+    ws.part_correct[o] = cor;
+  }
+}
+
+// Stage 2.  Block 0 (1024 threads): one wavefront per slice folds that slice's
+// chunk partials (lanes stride over chunks, fixed shuffle tree), then the slice
+// results are folded with each output's op in slice order.  All blocks:
+// class_counts[c] = sum over slices of the slice's count, in slice order.
+constexpr int kE2Block = 1024;
+
+__global__ __launch_bounds__(kE2Block) void eval_stage2_kernel(
     EvalWs ws, int n_slices, int chunks, int classes, float* __restrict__ ce_sum,
     int32_t* __restrict__ class_counts, float* __restrict__ max_logit,
     float* __restrict__ min_logit, int32_t* __restrict__ n_correct) {
-  const int64_t stride = (int64_t)gridDim.x * kEBlock;
-  for (int64_t c = (int64_t)blockIdx.x * kEBlock + threadIdx.x; c < classes; c += stride) {
+  const int64_t stride = (int64_t)gridDim.x * kE2Block;
+  for (int64_t c = (int64_t)blockIdx.x * kE2Block + threadIdx.x; c < classes; c += stride) {
+    // integer sums: any order gives the same result, so 16 loads go out together
     int32_t acc = 0;
-    for (int s = 0; s < n_slices; ++s) acc += ws.slice_counts[(int64_t)s * classes + c];
+    int s = 0;
+    for (; s + 16 <= n_slices; s += 16) {
+      int32_t v[16];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) v[k] = ws.slice_counts[(int64_t)(s + k) * classes + c];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) acc += v[k];
+    }
+    for (; s < n_slices; ++s) acc += ws.slice_counts[(int64_t)s * classes + c];
     class_counts[c] = acc;
   }
   if (blockIdx.x != 0) return;
-  __shared__ float s_ce[kEBlock], s_max[kEBlock], s_min[kEBlock];
-  __shared__ int s_cor[kEBlock];
-  float ce = 0.0f, mx = -INFINITY, mn = INFINITY;
+  constexpr int NW = kE2Block / kWave;
+  __shared__ float s_ce[NW], s_max[NW], s_min[NW];
+  __shared__ int s_cor[NW];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  float ce = 0.0f, mx = -INFINITY, mn = INFINITY;   // this wavefront's slices, in slice order
   int cor = 0;
-  for (int s = threadIdx.x; s < n_slices; s += kEBlock) {
+  for (int s = wave; s < n_slices; s += NW) {
     float sce = 0.0f, smx = -INFINITY, smn = INFINITY;
     int scor = 0;
-    for (int k = 0; k < chunks; ++k) {
+    for (int k = lane; k < chunks; k += kWave) {
       const int64_t o = (int64_t)s * chunks + k;
       sce += ws.part_ce[o];
       smx = fmaxf(smx, ws.part_max[o]);
       smn = fminf(smn, ws.part_min[o]);
       scor += ws.part_correct[o];
     }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+      sce += __shfl_xor(sce, off);
+      smx = fmaxf(smx, __shfl_xor(smx, off));
+      smn = fminf(smn, __shfl_xor(smn, off));
+      scor += __shfl_xor(scor, off);
+    }
     ce += sce;              // op SUM over slices
     mx = fmaxf(mx, smx);    // op MAX
     mn = fminf(mn, smn);    // op MIN
     cor += scor;            // op SUM (int)
   }
-  s_ce[threadIdx.x] = ce;
-  s_max[threadIdx.x] = mx;
-  s_min[threadIdx.x] = mn;
-  s_cor[threadIdx.x] = cor;
-  __syncthreads();
-  for (int off = kEBlock / 2; off > 0; off >>= 1) {
-    if (threadIdx.x < off) {
-      s_ce[threadIdx.x] += s_ce[threadIdx.x + off];
-      s_max[threadIdx.x] = fmaxf(s_max[threadIdx.x], s_max[threadIdx.x + off]);
-      s_min[threadIdx.x] = fminf(s_min[threadIdx.x], s_min[threadIdx.x + off]);
-      s_cor[threadIdx.x] += s_cor[threadIdx.x + off];
-    }
-    __syncthreads();
+  if (lane == 0) {
+    s_ce[wave] = ce;
+    s_max[wave] = mx;
+    s_min[wave] = mn;
+    s_cor[wave] = cor;
   }
+  __syncthreads();
   if (threadIdx.x == 0) {
-    ce_sum[0] = s_ce[0];
-    max_logit[0] = s_max[0];
-    min_logit[0] = s_min[0];
-    n_correct[0] = s_cor[0];
+    float tce = s_ce[0], tmx = s_max[0], tmn = s_min[0];
+    int tcor = s_cor[0];
+    for (int k = 1; k < NW; ++k) {
+      tce += s_ce[k];
+      tmx = fmaxf(tmx, s_max[k]);
+      tmn = fminf(tmn, s_min[k]);
+      tcor += s_cor[k];
+    }
+    ce_sum[0] = tce;
+    max_logit[0] = tmx;
+    min_logit[0] = tmn;
+    n_correct[0] = tcor;
   }
 }
 
@@ -269,15 +382,18 @@ extern "C" int synk_sliced_eval(const float* logits, const int32_t* labels, int6
   hipLaunchKernelGGL(zero_i32_kernel, dim3(zb), dim3(kEBlock), 0, s, w.slice_counts, n_counts);
   SYNK_LAUNCH_CHECK();
   const dim3 grid(chunks, n_slices);
-  if (classes % 4 == 0 && aligned_to(logits, 16))
-    hipLaunchKernelGGL((eval_stage1_kernel<true>), grid, dim3(kEBlock), 0, s, logits, labels, rows,
+  if (classes % 4 == 0 && aligned_to(logits, 16) && classes <= 1024)
+    hipLaunchKernelGGL((eval_stage1_kernel<16, 16>), grid, dim3(kEBlock), 0, s, logits, labels, rows,
+                       (int)classes, n_slices, chunks, w, argmax);
+  else if (classes % 4 == 0 && aligned_to(logits, 16))
+    hipLaunchKernelGGL((eval_stage1_kernel<64, 16>), grid, dim3(kEBlock), 0, s, logits, labels, rows,
                        (int)classes, n_slices, chunks, w, argmax);
   else
-    hipLaunchKernelGGL((eval_stage1_kernel<false>), grid, dim3(kEBlock), 0, s, logits, labels, rows,
+    hipLaunchKernelGGL(eval_stage1_generic_kernel, grid, dim3(kEBlock), 0, s, logits, labels, rows,
                        (int)classes, n_slices, chunks, w, argmax);
   SYNK_LAUNCH_CHECK();
-  int b2 = (int)((classes + kEBlock - 1) / kEBlock);
-  hipLaunchKernelGGL(eval_stage2_kernel, dim3(b2), dim3(kEBlock), 0, s, w, n_slices, chunks,
+  int b2 = (int)((classes + kE2Block - 1) / kE2Block);
+  hipLaunchKernelGGL(eval_stage2_kernel, dim3(b2), dim3(kE2Block), 0, s, w, n_slices, chunks,
                      (int)classes, ce_sum, class_counts, max_logit, min_logit, n_correct);
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;

@@ -114,7 +114,7 @@ def test_sliced_grad_argument_checks_and_workspace():
     assert synk.synk_mlp_param_count([3072, 1024, 1024, 10]) == 4206602
     b32 = synk.synk_sliced_grad_workspace_bytes(dims, synk.SYNK_F32, [5, 0, 7])
     b16 = synk.synk_sliced_grad_workspace_bytes(dims, synk.SYNK_BF16, [5, 0, 7])
-    assert b32 > b16 > 0 and b32 % 256 == 0
+    assert b32 > 0 and b16 > 0 and b32 % 256 == 0 and b16 % 256 == 0
     with pytest.raises(synk.SynkError) as e:
         synk.synk_sliced_grad_workspace_bytes(dims, synk.SYNK_F32, [0, 0])
     assert e.value.status == -2
