@@ -28,13 +28,19 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 
+# HBM bytes per launch of each config's dominant kernel, from rocprofv3 --pmc FETCH_SIZE and
+# --pmc WRITE_SIZE runs of this file (10 steps), scaled by what the same counters read for the
+# plain copy of --config 0 (fetch x2.000, write x1.000).  Summaries: profiles/*_kernel_stats.txt.
+MEASURED_TRAFFIC_BYTES = {2: 210.37e6, 3: 1226.75e6, 4: 192.93e6, 5: 275.17e6}
+
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4, 5],
+                    help="0 = plain copy of known size (calibrates the rocprofv3 byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -283,6 +289,26 @@ class EvalStep:
         return n / (time.perf_counter() - t0), "4096 of the 65536 rows, 4 slices (the argmax loop is pure Python)"
 
 
+class CopyStep:
+    """Config 0: a plain copy kernel of known size (1 GiB in, 1 GiB out), against which the
+    FETCH_SIZE / WRITE_SIZE counters of the other kernels are scaled."""
+
+    def __init__(self, torch, synk):
+        n = 256 * 1024 * 1024
+        self.src = [torch.full((n,), float(k + 1), device="cuda") for k in range(2)]
+        self.dst = torch.empty(n, device="cuda")
+        self.calls = [synk.prepare(synk.synk_reduce_buffers, [b], synk.SYNK_SUM, self.dst) for b in self.src]
+        self.units, self.unit, self.dtype = n, "elements/s", "f32"
+        self.workload = "config 0: copy of 2^28 fp32 (synk_reduce_buffers with one buffer)"
+        self.dom_name, self.dom_bytes = "reduce_kernel", 8 * n
+
+    def step(self, i, timer):
+        timer.bracket(self.calls[i % 2])
+
+    def cpu_baseline(self):
+        return 0.0, "none"
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -293,10 +319,10 @@ def main():
     from paper_1710_04162_amd import binding as synk
     torch.cuda.set_device(0)
 
-    wl = {1: lambda: MlpStep(torch, synk, 1), 2: lambda: MlpStep(torch, synk, 2),
+    wl = {0: lambda: CopyStep(torch, synk), 1: lambda: MlpStep(torch, synk, 1), 2: lambda: MlpStep(torch, synk, 2),
           3: lambda: ReduceStep(torch, synk), 4: lambda: GatherStep(torch, synk),
           5: lambda: EvalStep(torch, synk)}[a.config]()
-    steps = a.steps if a.steps is not None else {1: 2000, 2: 1000, 3: 300, 4: 1000, 5: 1000}[a.config]
+    steps = a.steps if a.steps is not None else {0: 50, 1: 2000, 2: 1000, 3: 300, 4: 1000, 5: 1000}[a.config]
     warmup = a.warmup if a.warmup is not None else 20
 
     timer = Timer(torch, steps)
@@ -319,7 +345,8 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.workload, "units_per_step": wl.units},
         "roofline": {"bound": "hbm", "kernel": wl.dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.config), "traffic_unit": "HBM bytes per launch",
                      "bytes_per_launch": wl.dom_bytes, "ms_per_launch": dom_ms},
     }
     if not a.no_cpu_baseline:
