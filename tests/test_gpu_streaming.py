@@ -272,3 +272,68 @@ def test_streaming_kernels_are_reproducible(synk):
     a = run_eval(synk, c["logits"], c["labels"], 16)
     b = run_eval(synk, c["logits"], c["labels"], 16)
     assert all(np.array_equal(a[k], b[k]) for k in a)
+
+
+# ----------------------------------------------- full sizes, as bench.py launches them
+def test_config3_full_size_reduce_and_update(synk):
+    c = workloads.config3()                                   # 8 x 25,557,032 fp32, 161 tensors
+    assert c["n_params"] == 25557032 and len(c["offsets"]) == 162
+    grads = [dev(g) for g in c["grads"]]
+    p, v = dev(c["p"]), dev(c["v"])
+    loss_out = torch.zeros(1, device="cuda")
+    synk.synk_reduce_sgd_update(grads, p, v, c["lr"], c["momentum"], c["weight_decay"],
+                                loss_in=dev(c["losses"]), loss_out=loss_out)
+    rp, rv, _, rl = oupdate.reduce_and_update(c["p"], c["v"], c["grads"], c["lr"], c["momentum"],
+                                              c["weight_decay"], None, c["losses"])
+    gp, gv = p.cpu().numpy(), v.cpu().numpy()
+    for t in range(161):                                      # per tensor, as the tolerance is defined
+        a, b = int(c["offsets"][t]), int(c["offsets"][t + 1])
+        assert rel_err(gp[a:b], rp[a:b]) < TOL_F32 and rel_err(gv[a:b], rv[a:b]) < TOL_F32, t
+    assert abs(loss_out.item() - rl) < TOL_F32 * abs(rl)
+
+
+def test_config4_full_size_gather_sampled_against_oracle(synk):
+    n_data, batch, n_workers, chw = 50000, 256, 8, (3, 224, 224)
+    row = chw[0] * chw[1] * chw[2]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(workloads.SEED_BASE + 4)
+    data = torch.empty((n_data, row), dtype=torch.uint8, device="cuda")          # 7.5 GB on the device
+    for a in range(0, n_data, 5000):
+        data[a:a + 5000] = torch.randint(0, 256, (5000, row), dtype=torch.uint8, device="cuda", generator=gen)
+    small = workloads.config4(n_data=8, batch=8)
+    rng = workloads.rng_for(4, salt=1)
+    labels = rng.integers(0, 1000, n_data).astype(np.int32)
+    idx = rng.integers(0, n_data, batch).astype(np.int32)
+    idx[:3] = [0, n_data - 1, idx[5]]                                            # ends and a duplicate
+    lut = torch.empty(3 * 256, device="cuda")
+    synk.synk_build_norm_lut(small["mean"], small["std"], lut)
+    sizes = share_sizes(batch, n_workers)
+    dst = [torch.zeros((n, row), device="cuda") for n in sizes]
+    dl = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in sizes]
+    synk.synk_gather_rows(data, dev(idx), dst, lut=lut, channels=3, labels=dev(labels), dst_labels=dl)
+    # the oracle sees exactly the rows the batch names (fetched from the device dataset)
+    src_rows = data[torch.from_numpy(idx.astype(np.int64)).cuda()].cpu().numpy().reshape((batch,) + chw)
+    ref = ogather.normalise_u8(src_rows, small["mean"], small["std"]).reshape(batch, row)
+    got = torch.cat(dst).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    assert np.array_equal(torch.cat(dl).cpu().numpy(), labels[idx])
+
+
+def test_config5_full_size_properties_and_sampled_rows(synk):
+    import scipy.special
+    c = workloads.config5()                                   # 65536 x 1000, 64 slices
+    logits, labels = c["logits"], c["labels"]
+    got = run_eval(synk, logits, labels, 64)
+    # rows the oracle computes one by one
+    sample = np.random.default_rng(0).choice(65536, 256, replace=False)
+    ref = evalops.function(logits[sample], labels[sample])
+    assert np.array_equal(got["argmax"][sample].astype(np.int64), ref["argmax"])
+    # properties that hold at any size (each equivalence is pinned on the CPU for the oracle)
+    am = got["argmax"].astype(np.int64)
+    assert np.array_equal(am, np.argmax(logits, axis=1))
+    assert np.array_equal(got["counts"].astype(np.int64), np.bincount(am, minlength=1000))
+    assert got["counts"].sum() == 65536
+    assert got["n_correct"][0] == int((am == labels).sum())
+    assert got["max_logit"][0] == logits.max() and got["min_logit"][0] == logits.min()
+    ce = (scipy.special.logsumexp(logits.astype(np.float64), axis=1) - logits[np.arange(65536), labels]).sum()
+    assert abs(got["ce_sum"][0] - ce) < TOL_F32 * abs(ce)
