@@ -271,7 +271,9 @@ class EvalStep:
         self.dtype = "f32"
         self.workload = ("config 5: 65536 rows of 1000-class fp32 logits, 64 slices, outputs CE sum, class "
                          "counts, max, min, top-1 correct, argmax, aggregated over slices")
-        self.dom_name = "eval_stage1_kernel"
+        # one call = three kernels (zero the per-slice counts, stage 1, stage 2); the bracket covers the
+        # call, so the fraction below is the whole call's; profiles/ has the per-kernel split
+        self.dom_name = "synk_sliced_eval (zero_i32_kernel + eval_stage1_kernel + eval_stage2_kernel)"
         self.dom_bytes = self.rows * (4 * self.C + 8)
         self.calls = [synk.prepare(synk.synk_sliced_eval, lg, self.labels, self.S, *self.out, self.ws)
                       for lg in self.logits]
@@ -336,6 +338,8 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
+    # Raw event time: it includes the launch gap in front of the kernel (a few microseconds more than
+    # the kernel-only duration rocprofv3 reports), so the fraction below errs on the low side.
     dom_ms = timer.mean_ms()
     achieved = wl.dom_bytes / (dom_ms * 1e-3) / 1e9
     out = {

@@ -56,19 +56,21 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 }
 
 // Device-side form of the split rule: which share holds point j, and where
-// that share starts.
-__device__ __forceinline__ void share_of(int64_t count, int parts, int64_t j, int* which,
+// that share starts.  Counts handled on the device fit 31 bits (grid and row
+// limits), so the divisions are 32-bit.
+__device__ __forceinline__ void share_of(int64_t count64, int parts, int64_t j64, int* which,
                                          int64_t* start) {
-  const int64_t base = count / parts, extra = count % parts;
-  const int64_t big = extra * (base + 1);
+  const uint32_t count = (uint32_t)count64, j = (uint32_t)j64, n = (uint32_t)parts;
+  const uint32_t base = count / n, extra = count % n;
+  const uint32_t big = extra * (base + 1);
   if (j < big) {
-    const int64_t w = j / (base + 1);
+    const uint32_t w = j / (base + 1);
     *which = (int)w;
-    *start = w * (base + 1);
+    *start = (int64_t)(w * (base + 1));
   } else {
-    const int64_t w = extra + (base > 0 ? (j - big) / base : 0);
+    const uint32_t w = extra + (base > 0 ? (j - big) / base : 0);
     *which = (int)w;
-    *start = big + (w - extra) * base;
+    *start = (int64_t)(big + (w - extra) * base);
   }
 }
 
