@@ -115,7 +115,7 @@ __global__ __launch_bounds__(kLBlock) void gather_u8_lut_kernel(
   int c = u / plane_u;                  // one division per thread
   int bound = (c + 1) * plane_u;        // first unit of the next channel
   if (VEC) {
-    constexpr int UNROLL = 8;
+    constexpr int UNROLL = 4;
     for (; u + (UNROLL - 1) * kLBlock < u1; u += UNROLL * kLBlock) {
       uint32_t px[UNROLL];
 #pragma unroll
@@ -282,7 +282,7 @@ extern "C" int synk_gather_rows(const void* data, int64_t n_rows, int64_t row_el
     const int plane = (int)(row_elems / channels);
     const bool vec = plane % 4 == 0 && aligned_to(data, 4) && dst16;
     const int64_t units = vec ? row_elems / 4 : row_elems;
-    upb = kLBlock * 8;                                   // 8 units per thread
+    upb = kLBlock * 4;                                   // 4 units per thread: one unrolled batch
     const int64_t nch = (units + upb - 1) / upb;
     if (nch > 65535) return SYNK_ERR_UNSUPPORTED;
     chunks = (int)nch;
