@@ -17,6 +17,8 @@
 // contraction index is strided in memory is transposed on its way into LDS.
 #include <math.h>
 
+#include <type_traits>
+
 #include "common.h"
 
 namespace synk {
@@ -107,6 +109,12 @@ struct TileAddr {
   int64_t ld;
   int x0, xlim;
   uint32_t xok;
+  // Fast path (tile wholly inside the matrix): address = wave-uniform tile
+  // origin (scalar registers) + a 32-bit per-thread byte offset that never
+  // changes, so a load costs no vector address arithmetic at all.
+  const char* origin;       // element (x0, k = 0)
+  uint32_t off[G::PER_T];   // bytes from the tile origin to the unit's first vector
+  bool interior;            // x0 + X <= xlim: every unit is inside along x
 
   __device__ __forceinline__ void init(const T* b, int64_t ld_, int64_t x0_, int64_t xlim_, int tid) {
     base = b;
@@ -114,15 +122,20 @@ struct TileAddr {
     x0 = (int)x0_;
     xlim = (int)xlim_;
     xok = 0u;
+    interior = x0_ + X <= xlim_;
+    origin = reinterpret_cast<const char*>(b + (LAYOUT == KC ? x0_ * ld_ : x0_));
 #pragma unroll
     for (int it = 0; it < G::PER_T; ++it) {
       const int id = it * kMBlock + tid;
       int xl, kl;
       G::unit_pos(id, &xl, &kl);
-      const bool live = ((G::UNITS % kMBlock == 0) || id < G::UNITS) && x0 + xl < xlim;
-      const int64_t off = LAYOUT == KC ? (int64_t)(x0 + xl) * ld + kl : (int64_t)kl * ld + (x0 + xl);
-      ptr[it] = b + (live ? off : 0);
+      const bool unit = (G::UNITS % kMBlock == 0) || id < G::UNITS;
+      const bool live = unit && x0 + xl < xlim;
+      const int64_t off64 = LAYOUT == KC ? (int64_t)(x0 + xl) * ld + kl : (int64_t)kl * ld + (x0 + xl);
+      ptr[it] = b + (live ? off64 : 0);
       xok |= (live ? 1u : 0u) << it;
+      const int64_t rel = LAYOUT == KC ? (int64_t)xl * ld + kl : (int64_t)kl * ld + xl;
+      off[it] = unit ? (uint32_t)(rel * (int64_t)sizeof(T)) : 0u;
     }
   }
 };
@@ -134,11 +147,32 @@ struct TileStage {
   static constexpr bool HALF = G::HALF;
   u32x4 r[PER_T][NV];
   uint32_t ok;   // bit (it*NV + q): vector is inside the matrix
+  bool whole;    // wave-uniform: loaded by load_whole(), nothing to zero
 
   // all units this thread owns, all their vectors
   static constexpr uint32_t kAllOk = (PER_T * NV >= 32) ? 0xffffffffu : ((1u << (PER_T * NV)) - 1u);
 
+  // A tile wholly inside the matrix (ALIGNED, ta.interior, k0 + BK <= klim).
+  __device__ __forceinline__ void load_whole(const TileAddr<T, LAYOUT, X, BK>& ta, int k0) {
+    const int64_t ldb = ta.ld * (int64_t)sizeof(T);
+    load_at(ta, ta.origin + (LAYOUT == KC ? (int64_t)k0 * (int64_t)sizeof(T) : (int64_t)k0 * ldb));
+  }
+  // tb: the tile's origin (wave-uniform); offmask 0 sends every lane to tb itself
+  __device__ __forceinline__ void load_at(const TileAddr<T, LAYOUT, X, BK>& ta, const char* tb,
+                                          uint32_t offmask = 0xffffffffu) {
+    const int64_t ldb = offmask ? ta.ld * (int64_t)sizeof(T) : 0;
+#pragma unroll
+    for (int it = 0; it < PER_T; ++it) {
+#pragma unroll
+      for (int q = 0; q < NV; ++q)
+        r[it][q] = *reinterpret_cast<const u32x4*>(tb + (q ? ldb : 0) + (ta.off[it] & offmask));
+    }
+    ok = kAllOk;
+    whole = true;
+  }
+
   __device__ __forceinline__ void load(const TileAddr<T, LAYOUT, X, BK>& ta, int k0, int klim, int tid) {
+    whole = false;
     const int64_t koff = LAYOUT == KC ? (int64_t)k0 : (int64_t)k0 * ta.ld;   // wave-uniform
     if (ALIGNED && k0 + BK <= klim) {
       // a tile wholly inside along the contraction: one 64-bit add per vector
@@ -214,7 +248,7 @@ struct TileStage {
   }
 
   __device__ __forceinline__ void store(uint32_t* __restrict__ lds, int tid) const {
-    if (ok == kAllOk) store_impl<false>(lds, tid);   // nothing to zero: the common case
+    if (whole) store_impl<false>(lds, tid);   // nothing to zero: the common case (a scalar branch)
     else store_impl<true>(lds, tid);
   }
 };
@@ -302,16 +336,20 @@ __device__ __forceinline__ void xcd_tile(int* bx, int* by, int* bz) {
 //   wavefronts 4-7 (producers) move the operand tiles global -> registers ->
 //     LDS, up to four tiles ahead, transposing an operand whose contraction
 //     index is strided in memory on the way.
-// LDS holds two tiles (ping-pong): while tile t is multiplied out of one half,
-// tile t+1 is written into the other; one barrier per tile.  Memory latency and
-// the address work of the loads stall only the producers, never the MFMAs.
+// LDS holds two tiles (ping-pong), one barrier per tile: between barriers t+1
+// and t+2 the producers write tile t+2 while the consumers multiply tile t
+// out of registers and fetch the fragments of tile t+1, so LDS reads, LDS
+// writes and MFMAs of three different tiles overlap.  A half is rewritten
+// only after the barrier that follows its last read, and a barrier waits for
+// the LDS reads issued before it.  Memory latency and the address work of the
+// loads stall only the producers, never the MFMAs.
 // The output tile leaves through LDS as well (64 rows at a time), so that it is
 // written with 16-byte stores of whole row segments by all 512 threads: the
 // MFMA result layout alone would give 2- or 4-byte stores scattered over rows.
 constexpr int kGemmThreads = 2 * kMBlock;
 
 template <typename T, int MODE, int BM, int BN, int BK, bool ALIGNED>
-__global__ __launch_bounds__(kGemmThreads) void mlp_gemm_kernel(GemmArgs g) {
+__global__ __launch_bounds__(kGemmThreads, 2) void mlp_gemm_kernel(GemmArgs g) {
   constexpr int LA = MODE == MODE_DW ? XC : KC;
   constexpr int LB = MODE == MODE_DX ? KC : XC;
   constexpr int KM = ET<T>::KM;
@@ -354,30 +392,65 @@ __global__ __launch_bounds__(kGemmThreads) void mlp_gemm_kernel(GemmArgs g) {
     adB.init(B, g.ldb, n0, N, tid);
     // A ring of four register stages: while tile t is multiplied, the loads of
     // tiles t+2 .. t+5 are in flight.  Loads, stores and barriers are issued on
-    // every path (a tile past the end reads the matrix origin and is stored as
-    // zeros into a half nobody reads; the loop runs a multiple of four steps),
-    // so that the number of loads outstanding at each wait is known exactly.
+    // every path (the loop runs a multiple of four steps), so that the number
+    // of loads outstanding at each wait is known exactly.
     TileStage<T, LA, BM, BK, ALIGNED> stA[4];
     TileStage<T, LB, BN, BK, ALIGNED> stB[4];
+    const int n_whole = kc / BK;                     // tiles wholly inside along the contraction
+    const bool fastA = ALIGNED && adA.interior, fastB = ALIGNED && adB.interior;
+    auto load_tile = [&](auto& sa, auto& sb, int j) {
+      // (a tile past the end has every vector masked and lands in a half nobody reads)
+      if (fastA && j < n_whole) sa.load_whole(adA, j * BK);
+      else sa.load(adA, j * BK, kc, tid);
+      if (fastB && j < n_whole) sb.load_whole(adB, j * BK);
+      else sb.load(adB, j * BK, kc, tid);
+    };
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      stA[u].load(adA, u * BK, kc, tid);
-      stB[u].load(adB, u * BK, kc, tid);
-    }
+    for (int u = 0; u < 4; ++u) load_tile(stA[u], stB[u], u);
     stA[0].store(smem, tid);
     stB[0].store(smem + WA, tid);
-    stA[0].load(adA, 4 * BK, kc, tid);
-    stB[0].load(adB, 4 * BK, kc, tid);
-    __syncthreads();                               // tile 0 is in half 0
-    for (int t = 0; t < n_tiles; t += 4) {
+    load_tile(stA[0], stB[0], 4);
+    __syncthreads();                               // tile 0 is in slot 0
+    int t = 0;
+    if (fastA && fastB) {
+      // Steady state: every tile stored (t+1 .. t+4) or loaded (t+5 .. t+8) in
+      // the round is wholly inside both operands, or past the end (then what is
+      // stored goes to a half nobody reads).  Straight-line code: four loads,
+      // the LDS stores and one barrier per tile, with the two tile origins
+      // advanced in scalar registers until they reach the last whole tile.
+      const int64_t stepA = (LA == KC ? (int64_t)BK : (int64_t)BK * g.lda) * (int64_t)sizeof(T);
+      const int64_t stepB = (LB == KC ? (int64_t)BK : (int64_t)BK * g.ldb) * (int64_t)sizeof(T);
+      const char* nextA = adA.origin + 5 * stepA;     // used only while tile 5, 6, ... exist
+      const char* nextB = adB.origin + 5 * stepB;
+      // TAIL: some tile loaded in the round is past the end; every lane then
+      // reads the first vector of the operand's first tile (one cache line).
+      auto fast_round = [&](int t0, auto tail) {
+        constexpr bool TAIL = decltype(tail)::value;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          uint32_t* half = smem + ((u + 1) & 1) * WT;
+          stA[(u + 1) & 3].template store_impl<false>(half, tid);
+          stB[(u + 1) & 3].template store_impl<false>(half + WA, tid);
+          const bool in = !TAIL || t0 + u + 5 < n_whole;
+          stA[(u + 1) & 3].load_at(adA, in ? nextA : adA.origin, in ? 0xffffffffu : 0u);
+          stB[(u + 1) & 3].load_at(adB, in ? nextB : adB.origin, in ? 0xffffffffu : 0u);
+          nextA += in ? stepA : 0;
+          nextB += in ? stepB : 0;
+          __syncthreads();
+        }
+      };
+      for (; t + 8 < n_whole; t += 4) fast_round(t, std::false_type());
+      if (n_whole == n_tiles)                        // no partial tile: the tail rounds are fast too
+        for (; t < n_tiles; t += 4) fast_round(t, std::true_type());
+    }
+    for (; t < n_tiles; t += 4) {
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        // tile t+u+1 -> the half that tile t+u (being multiplied now) does not use
-        uint32_t* half = smem + (((u + 1) & 1) ? WT : 0);
+        // tile t+u+1 -> the half that tile t+u (read before the last barrier) does not use
+        uint32_t* half = smem + ((u + 1) & 1) * WT;
         stA[(u + 1) & 3].store(half, tid);
         stB[(u + 1) & 3].store(half + WA, tid);
-        stA[(u + 1) & 3].load(adA, (t + u + 5) * BK, kc, tid);
-        stB[(u + 1) & 3].load(adB, (t + u + 5) * BK, kc, tid);
+        load_tile(stA[(u + 1) & 3], stB[(u + 1) & 3], t + u + 5);
         __syncthreads();
       }
     }
@@ -411,40 +484,33 @@ __global__ __launch_bounds__(kGemmThreads) void mlp_gemm_kernel(GemmArgs g) {
       }
     }
 
-    auto compute_tile = [&](const uint32_t* sA, const uint32_t* sB) {
-      if (TM * TN == 1) {
-        // one MFMA per k step: fetch every fragment of the tile first, so that
-        // the LDS latency is paid once and not once per step
-        typename Frag<T, LA, BM, BK>::type fa[KSTEPS];
-        typename Frag<T, LB, BN, BK>::type fb[KSTEPS];
+    // A wavefront that owns one MFMA tile (WHOLE) asks for every fragment of an
+    // operand tile at once, one tile ahead: the LDS reads of tile t+1 are in
+    // flight while tile t is multiplied out of registers, and the LDS latency
+    // is paid once per tile.  A wavefront that owns several MFMA tiles reads
+    // the fragments of k-step s+1 while step s is multiplied, inside the tile.
+    constexpr bool WHOLE = TM * TN == 1;
+    constexpr int FK = WHOLE ? KSTEPS : 1;
+    static_assert(WHOLE || KSTEPS % 2 == 0, "fragment parity must not depend on the tile");
+    typename Frag<T, LA, BM, BK>::type fa[2][FK][TM];
+    typename Frag<T, LB, BN, BK>::type fb[2][FK][TN];
+    auto read_frags = [&](const uint32_t* sA, const uint32_t* sB, int ks, auto& da, auto& db) {
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-          fa[ks] = Frag<T, LA, BM, BK>::read(sA, wm * (BM / 2) + xi, ks, gk);
-          fb[ks] = Frag<T, LB, BN, BK>::read(sB, wn * (BN / 2) + xi, ks, gk);
-        }
+      for (int i = 0; i < TM; ++i) da[i] = Frag<T, LA, BM, BK>::read(sA, wm * (BM / 2) + i * 32 + xi, ks, gk);
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) acc[0][0] = mfma(fa[ks], fb[ks], acc[0][0]);
-      } else {
-        typename Frag<T, LA, BM, BK>::type fa[2][TM];
-        typename Frag<T, LB, BN, BK>::type fb[2][TN];
-        auto read_frags = [&](int ks, int buf) {
+      for (int j = 0; j < TN; ++j) db[j] = Frag<T, LB, BN, BK>::read(sB, wn * (BN / 2) + j * 32 + xi, ks, gk);
+    };
+    auto read_tile = [&](const uint32_t* sA, const uint32_t* sB, int buf) {
 #pragma unroll
-          for (int i = 0; i < TM; ++i)
-            fa[buf][i] = Frag<T, LA, BM, BK>::read(sA, wm * (BM / 2) + i * 32 + xi, ks, gk);
+      for (int ks = 0; ks < FK; ++ks) read_frags(sA, sB, ks, fa[buf][ks], fb[buf][ks]);
+    };
+    auto mfma_step = [&](int buf, int ks) {
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
-            fb[buf][j] = Frag<T, LB, BN, BK>::read(sB, wn * (BN / 2) + j * 32 + xi, ks, gk);
-        };
-        read_frags(0, 0);
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-          if (ks + 1 < KSTEPS) read_frags(ks + 1, (ks + 1) & 1);
-#pragma unroll
-          for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) acc[i][j] = mfma(fa[ks & 1][i], fb[ks & 1][j], acc[i][j]);
-        }
-      }
+        for (int j = 0; j < TN; ++j) acc[i][j] = mfma(fa[buf][ks][i], fb[buf][ks][j], acc[i][j]);
+    };
+    auto column_sums = [&](const uint32_t* sB) {
       if (MODE == MODE_DW) {
         if (want_colsum && tid < BN) {   // column sums of the dZ tile, in row order
           if (sizeof(T) == 2) {
@@ -463,16 +529,45 @@ __global__ __launch_bounds__(kGemmThreads) void mlp_gemm_kernel(GemmArgs g) {
     };
 
     __syncthreads();                                 // tile 0 is in half 0
-    for (int t = 0; t < n_tiles; t += 4) {           // same number of barriers as the producers
+    if (WHOLE) {
+      read_tile(smem, smem + WA, 0);
+      column_sums(smem + WA);
+    }
+    // One round of the loop; ALL: tiles t .. t+4 exist (no tests in the round).
+    auto round = [&](int t, auto all) {
+      constexpr bool ALL = decltype(all)::value;
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        if (t + u < n_tiles) {
-          const uint32_t* half = smem + ((u & 1) ? WT : 0);
-          compute_tile(half, half + WA);
+        const uint32_t* cur = smem + (u & 1) * WT;
+        const uint32_t* nxt = smem + ((u + 1) & 1) * WT;
+        const bool live = ALL || t + u < n_tiles, more = ALL || t + u + 1 < n_tiles;
+        if (WHOLE) {
+          __syncthreads();                           // tile t+u+1 is in its half
+          if (more) {
+            read_tile(nxt, nxt + WA, (u + 1) & 1);
+            column_sums(nxt + WA);
+          }
+          if (live) {
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) mfma_step(u & 1, ks);
+          }
+        } else {
+          if (live) {
+            column_sums(cur + WA);
+            read_frags(cur, cur + WA, 0, fa[0][0], fb[0][0]);
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+              if (ks + 1 < KSTEPS) read_frags(cur, cur + WA, ks + 1, fa[(ks + 1) & 1][0], fb[(ks + 1) & 1][0]);
+              mfma_step(ks & 1, 0);
+            }
+          }
+          __syncthreads();                           // tile t+u+1 is in its half
         }
-        __syncthreads();
       }
-    }
+    };
+    int t = 0;
+    for (; t + 5 <= n_tiles; t += 4) round(t, std::true_type());
+    for (; t < n_tiles; t += 4) round(t, std::false_type());   // same number of barriers as the producers
 
     // bias / relu / mask applied in registers
 #pragma unroll
@@ -493,7 +588,7 @@ __global__ __launch_bounds__(kGemmThreads) void mlp_gemm_kernel(GemmArgs g) {
   }
 
   // ---------------------------------------------------------------- output
-  // (the last barrier of the loops above ordered every LDS read before this)
+  __syncthreads();   // every LDS read of the contraction is over before the output is staged
   const bool out_f32 = MODE == MODE_DW || sizeof(T) == 4 || (MODE == MODE_FWD && g.out_f32);
   char* Cw = reinterpret_cast<char*>(g.c[w]);
   if (ALIGNED && g.c_vec) {
