@@ -19,8 +19,9 @@ the definition of what each step of the path computes:
               Sec. 3.2 step 3.
   reduce      Sec. 3.1 "Build Functions" (a reduce/gather op per output),
               Sec. 3.3 step 2 (all-reduce of the flat gradient).
-  update      Sec. 3.3 step 3 (momentum update applied with the combined
-              gradient on the flat parameter array).
+  update      Sec. 3.3 step 3 (the update rule applied with the combined
+              gradient on the flat parameter array: momentum, Nesterov
+              momentum, RMSProp, Adam).
   evalops     a six-output evaluation function, each output with its own
               reduce op, aggregated over slices (Sec. 3.1, Sec. 5.1).
   brute       pure-Python-loop twins used only to pin the NumPy code at tiny
@@ -28,7 +29,8 @@ the definition of what each step of the path computes:
 
 Pins (tests/test_oracle_*.py): finite differences, closed forms, brute-force
 loops, library routines (np.array_split, np.take, scipy logsumexp,
-torch.optim.SGD on CPU, torch.bfloat16 casts) and the paper's defining
+torch.optim.SGD / RMSprop / Adam on CPU where the formulas coincide,
+hand-worked single elements where they do not, torch.bfloat16 casts) and the paper's defining
 invariant (Sec. 1.1): aggregating independent calls over any subdivision of
 the data equals the one full-batch call.
 

@@ -66,3 +66,20 @@ def momentum_closed_form(p0, g, lr, m, k):
     p_k = p0 - lr * g * sum_{j=1..k} (1 - m^j) / (1 - m)."""
     s = sum((1.0 - m ** j) / (1.0 - m) for j in range(1, k + 1))
     return p0 - lr * g * s
+
+
+def adam_first_step(p0, g, lr, beta2, eps):
+    """Adam's first update from zero moments, element by element: the bias
+    corrections cancel beta1 entirely and leave
+    p1 = p0 - lr * g / (|g| + eps / sqrt(1 - beta2))."""
+    return [float(a) - lr * float(b) / (abs(float(b)) + eps / math.sqrt(1.0 - beta2)) for a, b in zip(p0, g)]
+
+
+def rmsprop_constant_gradient(p0, g, lr, rho, eps, k):
+    """RMSProp after k steps with a constant gradient and a zero accumulator:
+    a_j = (1 - rho^j) g^2, so p_k = p0 - lr * g * sum_j 1 / sqrt((1 - rho^j) g^2 + eps)."""
+    out = []
+    for a, b in zip(p0, g):
+        a, b = float(a), float(b)
+        out.append(a - lr * b * sum(1.0 / math.sqrt((1.0 - rho ** j) * b * b + eps) for j in range(1, k + 1)))
+    return out

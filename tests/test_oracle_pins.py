@@ -295,6 +295,91 @@ def test_sgd_trajectory_matches_torch_optim():
         assert np.allclose(p, t.detach().numpy(), atol=1e-13)
 
 
+def test_nesterov_trajectory_matches_torch_optim_and_differs_from_momentum():
+    rng = np.random.default_rng(151)
+    p0 = rng.standard_normal(64)
+    grads = [rng.standard_normal(64) for _ in range(6)]
+    t = torch.nn.Parameter(torch.tensor(p0))
+    opt = torch.optim.SGD([t], lr=0.05, momentum=0.9, nesterov=True, weight_decay=1e-2)
+    p, v = p0.copy(), np.zeros(64)
+    pm, vm = p0.copy(), np.zeros(64)
+    for g in grads:
+        t.grad = torch.tensor(g)
+        opt.step()
+        p, v = update.nesterov_momentum(p, v, g, 0.05, 0.9, 1e-2)
+        pm, vm = update.sgd_momentum(pm, vm, g, 0.05, 0.9, 1e-2)
+        assert np.allclose(p, t.detach().numpy(), atol=1e-13)
+    assert np.abs(p - pm).max() > 1e-3            # the look-ahead term is not a no-op
+    # with zero momentum both rules are plain SGD
+    a, _ = update.nesterov_momentum(p0, np.zeros(64), grads[0], 0.1, 0.0)
+    assert np.allclose(a, p0 - 0.1 * grads[0], atol=1e-16)
+
+
+def test_rmsprop_against_torch_closed_form_and_hand_numbers():
+    rng = np.random.default_rng(152)
+    p0 = rng.standard_normal(48)
+    grads = [rng.standard_normal(48) for _ in range(5)]
+    # eps = 0: eps inside or outside the square root makes no difference -> torch's routine applies
+    t = torch.nn.Parameter(torch.tensor(p0))
+    opt = torch.optim.RMSprop([t], lr=0.01, alpha=0.9, eps=0.0, weight_decay=1e-2)
+    p, a = p0.copy(), np.zeros(48)
+    for g in grads:
+        t.grad = torch.tensor(g)
+        opt.step()
+        p, a = update.rmsprop(p, a, g, 0.01, 0.9, 0.0, 1e-2)
+        assert np.allclose(p, t.detach().numpy(), atol=1e-12)
+    # eps > 0 (inside the root): constant gradient, closed form
+    g = rng.standard_normal(48)
+    pk, ak = p0.copy(), np.zeros(48)
+    for k in range(1, 7):
+        pk, ak = update.rmsprop(pk, ak, g, 0.02, 0.9, 1e-6)
+        assert np.allclose(pk, brute.rmsprop_constant_gradient(p0, g, 0.02, 0.9, 1e-6, k), atol=1e-13)
+    # one element by hand: a = 0.1 * 4 = 0.4 ; p = 1 - 0.5 * 2 / sqrt(0.4 + 0.09) = 1 - 1/0.7
+    p1, a1 = update.rmsprop([1.0], [0.0], [2.0], 0.5, 0.9, 0.09)
+    assert a1[0] == pytest.approx(0.4, abs=1e-15) and p1[0] == pytest.approx(1.0 - 1.0 / 0.7, abs=1e-14)
+
+
+def test_adam_against_torch_first_step_closed_form_and_hand_numbers():
+    rng = np.random.default_rng(153)
+    p0 = rng.standard_normal(48)
+    grads = [rng.standard_normal(48) for _ in range(6)]
+    # eps = 0: the two published placements of eps coincide -> torch's routine applies
+    t = torch.nn.Parameter(torch.tensor(p0))
+    opt = torch.optim.Adam([t], lr=0.01, betas=(0.9, 0.999), eps=0.0, weight_decay=1e-2)
+    p, m, v = p0.copy(), np.zeros(48), np.zeros(48)
+    for k, g in enumerate(grads, 1):
+        t.grad = torch.tensor(g)
+        opt.step()
+        p, m, v = update.adam(p, m, v, g, 0.01, 0.9, 0.999, 0.0, k, 1e-2)
+        assert np.allclose(p, t.detach().numpy(), atol=1e-12)
+    # eps > 0: the first step from zero moments has a closed form without beta1
+    p1, m1, v1 = update.adam(p0, np.zeros(48), np.zeros(48), grads[0], 0.01, 0.9, 0.999, 1e-8, 1)
+    assert np.allclose(p1, brute.adam_first_step(p0, grads[0], 0.01, 0.999, 1e-8), atol=1e-14)
+    p1b, _, _ = update.adam(p0, np.zeros(48), np.zeros(48), grads[0], 0.01, 0.5, 0.999, 1e-8, 1)
+    assert np.allclose(p1, p1b, atol=1e-14)
+    # second step, one element, by hand: g = 1 then g = 3, b1 = .5, b2 = .75, lr = 1, eps = 0.5
+    #   t=1: m = .5, v = .25 ; t=2: m = .25 + 1.5 = 1.75, v = .1875 + 2.25 = 2.4375
+    #   a_2 = sqrt(1 - .5625) / (1 - .25) = sqrt(.4375) / .75
+    q, m_, v_ = update.adam([0.0], [0.0], [0.0], [1.0], 1.0, 0.5, 0.75, 0.5, 1)
+    q, m_, v_ = update.adam(q, m_, v_, [3.0], 1.0, 0.5, 0.75, 0.5, 2)
+    first = -(np.sqrt(0.25) / 0.5) * 0.5 / (np.sqrt(0.25) + 0.5)
+    second = -(np.sqrt(0.4375) / 0.75) * 1.75 / (np.sqrt(2.4375) + 0.5)
+    assert m_[0] == pytest.approx(1.75, abs=1e-15) and v_[0] == pytest.approx(2.4375, abs=1e-15)
+    assert q[0] == pytest.approx(first + second, abs=1e-14)
+
+
+def test_apply_rule_dispatch_matches_the_rule_functions():
+    rng = np.random.default_rng(154)
+    p = rng.standard_normal(16); s1 = rng.standard_normal(16) * 0.1; s2 = rng.random(16); g = rng.standard_normal(16)
+    h = dict(lr=0.01, momentum=0.9, rho=0.9, beta1=0.9, beta2=0.999, eps=1e-6, t=3, weight_decay=1e-3)
+    assert np.array_equal(update.apply_rule("momentum", p, s1, None, g, h)[0], update.sgd_momentum(p, s1, g, 0.01, 0.9, 1e-3)[0])
+    assert np.array_equal(update.apply_rule("nesterov", p, s1, None, g, h)[0], update.nesterov_momentum(p, s1, g, 0.01, 0.9, 1e-3)[0])
+    assert np.array_equal(update.apply_rule("rmsprop", p, s2, None, g, h)[1], update.rmsprop(p, s2, g, 0.01, 0.9, 1e-6, 1e-3)[1])
+    assert np.array_equal(update.apply_rule("adam", p, s1, s2, g, h)[0], update.adam(p, s1, s2, g, 0.01, 0.9, 0.999, 1e-6, 3, 1e-3)[0])
+    with pytest.raises(ValueError):
+        update.apply_rule("adagrad", p, s1, s2, g, h)
+
+
 def test_whole_step_independent_of_worker_count():
     # App. A: averaging over workers "preserves the algorithm" for plain SGD.
     dims = [6, 8, 3]
