@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4, 5],
                     help="0 = plain copy of known size (calibrates the rocprofv3 byte counters)")
+    ap.add_argument("--rule", default="momentum", choices=["momentum", "nesterov", "rmsprop", "adam"],
+                    help="config 3 only: the update rule fused with the N-way average (Sec. 3.3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -151,14 +153,18 @@ class MlpStep:
 
 
 class ReduceStep:
-    """Config 3: N-way average of ResNet-50-sized gradients fused with momentum SGD."""
+    """Config 3: N-way average of ResNet-50-sized gradients fused with the update rule."""
 
-    def __init__(self, torch, synk):
+    HYPER = dict(nesterov=dict(lr=0.1, momentum=0.9, weight_decay=1e-4),
+                 rmsprop=dict(lr=0.01, rho=0.9, eps=1e-6, weight_decay=1e-4),
+                 adam=dict(lr=0.001, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=1e-4))
+
+    def __init__(self, torch, synk, rule="momentum"):
         import numpy as np
         import workloads
         self.torch, self.s, self.np = torch, synk, np
         c = workloads.config3()
-        self.c = c
+        self.c, self.rule = c, rule
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
         self.P, self.N = c["n_params"], c["n_workers"]
         # 3 rotating gradient sets (2.4 GB) so that the 256 MB last-level cache cannot serve the reads
@@ -169,26 +175,42 @@ class ReduceStep:
         self.loss_in, self.loss_out = up(c["losses"]), torch.zeros(1, device="cuda")
         self.units, self.unit = self.P, "params/s"
         self.dtype = "f32"
-        self.workload = ("config 3: average of 8 ResNet-50-sized fp32 gradient buffers (25,557,032 params, 161 "
-                         "tensors) fused with momentum SGD (lr .1, m .9, wd 1e-4) and the scalar-loss mean")
-        self.dom_name = "reduce_sgd_kernel"
-        self.dom_bytes = self.P * (4 * self.N + 16)
-
-        self.calls = [synk.prepare(synk.synk_reduce_sgd_update, gs, self.p, self.v, c["lr"], c["momentum"],
-                                   c["weight_decay"], loss_in=self.loss_in, loss_out=self.loss_out)
-                      for gs in self.grads]
+        n_state = 2 if rule == "adam" else 1
+        self.dom_bytes = self.P * (4 * self.N + 8 + 8 * n_state)
+        if rule == "momentum":
+            self.workload = ("config 3: average of 8 ResNet-50-sized fp32 gradient buffers (25,557,032 params, 161 "
+                             "tensors) fused with momentum SGD (lr .1, m .9, wd 1e-4) and the scalar-loss mean")
+            self.dom_name = "reduce_sgd_kernel"
+            self.calls = [synk.prepare(synk.synk_reduce_sgd_update, gs, self.p, self.v, c["lr"], c["momentum"],
+                                       c["weight_decay"], loss_in=self.loss_in, loss_out=self.loss_out)
+                          for gs in self.grads]
+        else:
+            h = self.HYPER[rule]
+            self.workload = ("config 3 shape with the %s rule: average of 8 ResNet-50-sized fp32 gradient buffers "
+                             "(25,557,032 params) fused with the update (%s) and the scalar-loss mean" %
+                             (rule, ", ".join("%s %g" % kv for kv in h.items())))
+            self.dom_name = "reduce_update_kernel"
+            self.s2 = torch.zeros_like(self.v) if rule == "adam" else None
+            # the step number only enters the host-side bias correction of Adam; a fixed one times the same work
+            self.calls = [synk.prepare(synk.synk_reduce_update, rule, gs, self.p, self.v, self.s2, step=1000,
+                                       loss_in=self.loss_in, loss_out=self.loss_out, **h)
+                          for gs in self.grads]
 
     def step(self, i, timer):
         timer.bracket(self.calls[i % 3])
 
     def cpu_baseline(self):
-        from oracle import update as oupdate
+        from oracle import reduce as oreduce, update as oupdate
         c = self.c
         best = 1e30
         for _ in range(3):
             t0 = time.perf_counter()
-            oupdate.reduce_and_update(c["p"], c["v"], c["grads"], c["lr"], c["momentum"], c["weight_decay"],
-                                      None, c["losses"])
+            if self.rule == "momentum":
+                oupdate.reduce_and_update(c["p"], c["v"], c["grads"], c["lr"], c["momentum"], c["weight_decay"],
+                                          None, c["losses"])
+            else:
+                G = oreduce.reduce_buffers(list(c["grads"]), "mean")
+                oupdate.apply_rule(self.rule, c["p"], c["v"], c["v"], G, dict(self.HYPER[self.rule], t=1000))
             best = min(best, time.perf_counter() - t0)
         return self.P / best, "3 whole steps at full size, best of 3"
 
@@ -322,7 +344,7 @@ def main():
     torch.cuda.set_device(0)
 
     wl = {0: lambda: CopyStep(torch, synk), 1: lambda: MlpStep(torch, synk, 1), 2: lambda: MlpStep(torch, synk, 2),
-          3: lambda: ReduceStep(torch, synk), 4: lambda: GatherStep(torch, synk),
+          3: lambda: ReduceStep(torch, synk, a.rule), 4: lambda: GatherStep(torch, synk),
           5: lambda: EvalStep(torch, synk)}[a.config]()
     steps = a.steps if a.steps is not None else {0: 50, 1: 2000, 2: 1000, 3: 300, 4: 1000, 5: 1000}[a.config]
     warmup = a.warmup if a.warmup is not None else 20
@@ -350,7 +372,7 @@ def main():
         "config": {"workload": wl.workload, "units_per_step": wl.units},
         "roofline": {"bound": "hbm", "kernel": wl.dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.config), "traffic_unit": "HBM bytes per launch",
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if a.rule == "momentum" else None, "traffic_unit": "HBM bytes per launch",
                      "bytes_per_launch": wl.dom_bytes, "ms_per_launch": dom_ms},
     }
     if not a.no_cpu_baseline:

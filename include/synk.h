@@ -17,6 +17,8 @@
  *                           3, Sec. 3.3 step 2)
  *   synk_sgd_update         momentum update on the flat array (Sec. 3.3 step 3)
  *   synk_reduce_sgd_update  the last two fused into one pass over memory
+ *   synk_reduce_update      the same pass with the other update rules of
+ *                           Sec. 3.3 (Nesterov momentum, RMSProp, Adam)
  *
  * Conventions common to every call
  * --------------------------------
@@ -264,6 +266,41 @@ int synk_sgd_update(float* p, float* v, const float* g, int64_t len,
 int synk_reduce_sgd_update(const float* const* grads, int n, int64_t len, const float* weights,
                            float* p, float* v, float lr, float momentum, float weight_decay,
                            void* p_lp, const float* loss_in, float* loss_out, void* stream);
+
+/* The other update rules the paper lists for its synchronous-SGD helpers
+ * (Sec. 3.3: momentum, Nesterov momentum, RMSProp, Adam), fused with the
+ * N-buffer average exactly like synk_reduce_sgd_update.  The paper gives no
+ * formulas; these are the published forms, with g = G[i] + weight_decay*p[i]:
+ *   SYNK_RULE_MOMENTUM  s1 = momentum*s1 - lr*g;  p += s1
+ *   SYNK_RULE_NESTEROV  s1 = momentum*s1 - lr*g;  p += momentum*s1 - lr*g
+ *   SYNK_RULE_RMSPROP   s1 = rho*s1 + (1-rho)*g*g;  p -= lr*g / sqrt(s1 + eps)
+ *   SYNK_RULE_ADAM      s1 = beta1*s1 + (1-beta1)*g;  s2 = beta2*s2 + (1-beta2)*g*g;
+ *                       p -= lr*sqrt(1-beta2^step)/(1-beta1^step) * s1 / (sqrt(s2) + eps)
+ * u: host; `step` is the number of this update (1 for the first; ADAM only).
+ * p, s1, s2: device float[len], updated in place, 16-byte aligned; s2 is
+ * required for ADAM and ignored otherwise.  grads, weights, p_lp, loss_in,
+ * loss_out as in synk_reduce_sgd_update.  All arithmetic in fp32; the ADAM
+ * step size is formed on the host in double and rounded once.
+ * Errors: NULL -> ERR_NULL; unknown rule -> ERR_OP; n or len out of range,
+ * ADAM with step < 1 or a beta outside [0,1) -> ERR_SHAPE; alignment ->
+ * ERR_ALIGN. */
+#define SYNK_RULE_MOMENTUM 0
+#define SYNK_RULE_NESTEROV 1
+#define SYNK_RULE_RMSPROP 2
+#define SYNK_RULE_ADAM 3
+typedef struct {
+  int rule;
+  float lr;
+  float momentum;     /* MOMENTUM, NESTEROV */
+  float rho;          /* RMSPROP */
+  float beta1, beta2; /* ADAM */
+  float eps;          /* RMSPROP, ADAM */
+  float weight_decay;
+  int64_t step;       /* ADAM: 1, 2, ... */
+} synk_update_desc;
+int synk_reduce_update(const synk_update_desc* u, const float* const* grads, int n, int64_t len,
+                       const float* weights, float* p, float* s1, float* s2, void* p_lp,
+                       const float* loss_in, float* loss_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -19,7 +19,7 @@ __all__ = [
     "synk_gather_rows", "synk_build_norm_lut", "synk_poll_error", "synk_mlp_param_count",
     "synk_sliced_grad_workspace_bytes", "synk_sliced_grad", "synk_cast_bf16",
     "synk_sliced_eval_workspace_bytes", "synk_sliced_eval", "synk_reduce_buffers",
-    "synk_sgd_update", "synk_reduce_sgd_update",
+    "synk_sgd_update", "synk_reduce_sgd_update", "synk_reduce_update",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsynk.so")
@@ -48,6 +48,16 @@ class MlpDesc(ctypes.Structure):
     _fields_ = [("n_layers", _int), ("dims", _pi64), ("compute_dtype", _int)]
 
 
+class UpdateDesc(ctypes.Structure):
+    _fields_ = [("rule", _int), ("lr", _f32), ("momentum", _f32), ("rho", _f32), ("beta1", _f32),
+                ("beta2", _f32), ("eps", _f32), ("weight_decay", _f32), ("step", _i64)]
+
+
+SYNK_RULE_MOMENTUM, SYNK_RULE_NESTEROV, SYNK_RULE_RMSPROP, SYNK_RULE_ADAM = 0, 1, 2, 3
+RULE = dict(momentum=SYNK_RULE_MOMENTUM, nesterov=SYNK_RULE_NESTEROV, rmsprop=SYNK_RULE_RMSPROP,
+            adam=SYNK_RULE_ADAM)
+
+
 lib.synk_version.restype = _int
 lib.synk_status_string.restype = ctypes.c_char_p
 lib.synk_status_string.argtypes = [_int]
@@ -70,6 +80,9 @@ lib.synk_reduce_buffers.argtypes = [_pp, _int, _i64, _int, _int, _pf32, _pi64, _
 lib.synk_sgd_update.argtypes = [_vp, _vp, _vp, _i64, _f32, _f32, _f32, _vp, _vp]
 lib.synk_reduce_sgd_update.argtypes = [_pp, _int, _i64, _pf32, _vp, _vp, _f32, _f32, _f32, _vp, _vp,
                                        _vp, _vp]
+lib.synk_reduce_update.argtypes = [ctypes.POINTER(UpdateDesc), _pp, _int, _i64, _pf32, _vp, _vp, _vp, _vp,
+                                   _vp, _vp, _vp]
+lib.synk_reduce_update.restype = _int
 for _n in ("synk_split", "synk_gather_rows", "synk_build_norm_lut", "synk_poll_error",
            "synk_mlp_param_count", "synk_sliced_grad_workspace_bytes", "synk_sliced_grad",
            "synk_cast_bf16", "synk_sliced_eval_workspace_bytes", "synk_sliced_eval",
@@ -263,3 +276,19 @@ def synk_reduce_sgd_update(grads, p, v, lr, momentum, weight_decay=0.0, weights=
             _ptr(loss_out), _stream(stream))
     return _run(lib.synk_reduce_sgd_update, args, (grads, p, v, w, p_lp, loss_in, loss_out, tg),
                 "synk_reduce_sgd_update", _prepare)
+
+
+def synk_reduce_update(rule, grads, p, s1, s2=None, lr=0.0, momentum=0.0, rho=0.0, beta1=0.0, beta2=0.0,
+                       eps=0.0, weight_decay=0.0, step=1, weights=None, p_lp=None, loss_in=None,
+                       loss_out=None, stream=None, _prepare=False):
+    """rule: one of SYNK_RULE_* (or its name).  A prepared call keeps `step` as given:
+    prepare one call per step value for ADAM."""
+    n = len(grads)
+    u = UpdateDesc(RULE[rule] if isinstance(rule, str) else int(rule), lr, momentum, rho, beta1, beta2, eps,
+                   weight_decay, int(step))
+    w = (ctypes.c_float * n)(*[float(x) for x in weights]) if weights is not None else None
+    tg = _table(grads)
+    args = (ctypes.byref(u), tg, n, p.numel(), w, _ptr(p), _ptr(s1), _ptr(s2), _ptr(p_lp), _ptr(loss_in),
+            _ptr(loss_out), _stream(stream))
+    return _run(lib.synk_reduce_update, args, (u, grads, p, s1, s2, w, p_lp, loss_in, loss_out, tg),
+                "synk_reduce_update", _prepare)

@@ -2,6 +2,8 @@
 // step 3) and the two fused.  All three are streaming kernels bound by HBM
 // bandwidth: 16-byte loads/stores, every input element read exactly once,
 // grid-stride loops sized to keep every CU busy with many loads in flight.
+#include <math.h>
+
 #include "common.h"
 
 namespace synk {
@@ -38,6 +40,108 @@ __device__ __forceinline__ void sgd_elem(float G, float& p, float& v, float lr, 
   const float g = G + wd * p;
   v = m * v - lr * g;
   p = p + v;
+}
+
+// The other update rules of Sec. 3.3 (published forms; g = G + wd * p):
+//   NESTEROV  v' = m v - lr g ;  p' = p + m v' - lr g
+//   RMSPROP   a' = rho a + (1 - rho) g^2 ;  p' = p - lr g / sqrt(a' + eps)
+//   ADAM      m' = b1 m + (1 - b1) g ;  v' = b2 v + (1 - b2) g^2 ;
+//             p' = p - a_t m' / (sqrt(v') + eps),  a_t = lr sqrt(1 - b2^t) / (1 - b1^t)
+// s1 is the velocity / the accumulator / the first moment, s2 the second moment.
+struct RuleParams {
+  float lr, m, wd;        // momentum rules: m = momentum; RMSPROP: m = rho; ADAM: m = beta1
+  float b2, eps, a_t;     // ADAM: beta2, eps, bias-corrected step; RMSPROP: eps
+};
+
+template <int RULE>
+__device__ __forceinline__ void rule_elem(float G, float& p, float& s1, float& s2, const RuleParams& h) {
+  const float g = G + h.wd * p;
+  if (RULE == SYNK_RULE_MOMENTUM) {
+    s1 = h.m * s1 - h.lr * g;
+    p = p + s1;
+  } else if (RULE == SYNK_RULE_NESTEROV) {
+    s1 = h.m * s1 - h.lr * g;
+    p = p + h.m * s1 - h.lr * g;
+  } else if (RULE == SYNK_RULE_RMSPROP) {
+    s1 = h.m * s1 + (1.0f - h.m) * g * g;
+    p = p - h.lr * g / sqrtf(s1 + h.eps);
+  } else {
+    s1 = h.m * s1 + (1.0f - h.m) * g;
+    s2 = h.b2 * s2 + (1.0f - h.b2) * g * g;
+    p = p - h.a_t * s1 / (sqrtf(s2) + h.eps);
+  }
+}
+
+// The fused reduce + update for any rule: the skeleton of reduce_sgd_kernel
+// with one more state stream for ADAM.
+template <int NS, int RULE>
+__global__ __launch_bounds__(kBlock) void reduce_update_kernel(BufTable t, int n_dyn, int64_t len,
+                                                               float* __restrict__ p,
+                                                               float* __restrict__ s1,
+                                                               float* __restrict__ s2, RuleParams h,
+                                                               uint16_t* __restrict__ p_lp,
+                                                               const float* __restrict__ loss_in,
+                                                               float* __restrict__ loss_out) {
+  constexpr bool TWO = RULE == SYNK_RULE_ADAM;
+  const int n = NS > 0 ? NS : n_dyn;
+  const int64_t n_vec = len >> 2;
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  f32x4* p4 = reinterpret_cast<f32x4*>(p);
+  f32x4* a4 = reinterpret_cast<f32x4*>(s1);
+  f32x4* b4 = reinterpret_cast<f32x4*>(s2);
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n_vec; i += stride) {
+    f32x4 acc;
+    if (NS > 0) {
+      f32x4 g[NS > 0 ? NS : 1];
+#pragma unroll
+      for (int w = 0; w < NS; ++w) g[w] = ld_stream(reinterpret_cast<const f32x4*>(t.p[w]) + i);
+      acc = t.w[0] * g[0];
+#pragma unroll
+      for (int w = 1; w < NS; ++w) acc = fma4(t.w[w], g[w], acc);
+    } else {
+      f32x4 g = ld_stream(reinterpret_cast<const f32x4*>(t.p[0]) + i);
+      acc = t.w[0] * g;
+      for (int w = 1; w < n; ++w) {
+        g = ld_stream(reinterpret_cast<const f32x4*>(t.p[w]) + i);
+        acc = fma4(t.w[w], g, acc);
+      }
+    }
+    f32x4 pp = p4[i], aa = a4[i], bb = TWO ? b4[i] : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    float x0 = pp.x, x1 = pp.y, x2 = pp.z, x3 = pp.w;
+    float a0 = aa.x, a1 = aa.y, a2 = aa.z, a3 = aa.w;
+    float b0 = bb.x, b1 = bb.y, b2 = bb.z, b3 = bb.w;
+    rule_elem<RULE>(acc.x, x0, a0, b0, h);
+    rule_elem<RULE>(acc.y, x1, a1, b1, h);
+    rule_elem<RULE>(acc.z, x2, a2, b2, h);
+    rule_elem<RULE>(acc.w, x3, a3, b3, h);
+    p4[i] = f32x4{x0, x1, x2, x3};
+    a4[i] = f32x4{a0, a1, a2, a3};
+    if (TWO) b4[i] = f32x4{b0, b1, b2, b3};
+    if (p_lp) {
+      u32x2 q;
+      q.x = pack_bf16x2(x0, x1);
+      q.y = pack_bf16x2(x2, x3);
+      reinterpret_cast<u32x2*>(p_lp)[i] = q;
+    }
+  }
+  if (blockIdx.x == 0) {
+    const int64_t e = (n_vec << 2) + threadIdx.x;
+    if (threadIdx.x < 4 && e < len) {
+      float acc = t.w[0] * reinterpret_cast<const float*>(t.p[0])[e];
+      for (int w = 1; w < n; ++w) acc = fmaf(t.w[w], reinterpret_cast<const float*>(t.p[w])[e], acc);
+      float pp = p[e], aa = s1[e], bb = TWO ? s2[e] : 0.0f;
+      rule_elem<RULE>(acc, pp, aa, bb, h);
+      p[e] = pp;
+      s1[e] = aa;
+      if (TWO) s2[e] = bb;
+      if (p_lp) p_lp[e] = f32_to_bf16(pp);
+    }
+    if (threadIdx.x == 0 && loss_out) {
+      float acc = t.w[0] * loss_in[0];
+      for (int w = 1; w < n; ++w) acc = fmaf(t.w[w], loss_in[w], acc);
+      loss_out[0] = acc;
+    }
+  }
 }
 
 // G = sum_w weight_w * grad_w ; (p, v) <- momentum update ; optional bf16 copy
@@ -334,6 +438,76 @@ extern "C" int synk_reduce_sgd_update(const float* const* grads, int n, int64_t 
   if (len == 0 && !loss_out) return SYNK_OK;
   return launch_reduce_sgd(t, n, len, p, v, lr, momentum, weight_decay, p_lp, loss_in, loss_out,
                            reinterpret_cast<hipStream_t>(stream));
+}
+
+template <int RULE>
+static int launch_reduce_update(const BufTable& t, int n, int64_t len, float* p, float* s1, float* s2,
+                                const RuleParams& h, void* p_lp, const float* loss_in,
+                                float* loss_out, hipStream_t s) {
+  const dim3 grid(stream_grid(len >> 2)), block(kBlock);
+  uint16_t* lp = reinterpret_cast<uint16_t*>(p_lp);
+#define SYNK_RU(NS)                                                                                \
+  hipLaunchKernelGGL((reduce_update_kernel<NS, RULE>), grid, block, 0, s, t, n, len, p, s1, s2, h, \
+                     lp, loss_in, loss_out)
+  switch (n) {
+    case 1: SYNK_RU(1); break;
+    case 2: SYNK_RU(2); break;
+    case 4: SYNK_RU(4); break;
+    case 8: SYNK_RU(8); break;
+    default: SYNK_RU(0); break;
+  }
+#undef SYNK_RU
+  SYNK_LAUNCH_CHECK();
+  return SYNK_OK;
+}
+
+extern "C" int synk_reduce_update(const synk_update_desc* u, const float* const* grads, int n,
+                                  int64_t len, const float* weights, float* p, float* s1, float* s2,
+                                  void* p_lp, const float* loss_in, float* loss_out, void* stream) {
+  if (!u || !grads || !p || !s1) return SYNK_ERR_NULL;
+  if (u->rule < SYNK_RULE_MOMENTUM || u->rule > SYNK_RULE_ADAM) return SYNK_ERR_OP;
+  if (u->rule == SYNK_RULE_ADAM && !s2) return SYNK_ERR_NULL;
+  if ((loss_in == nullptr) != (loss_out == nullptr)) return SYNK_ERR_NULL;
+  if (n < 1 || n > SYNK_MAX_WORKERS || len < 0) return SYNK_ERR_SHAPE;
+  if (u->rule == SYNK_RULE_ADAM &&
+      (u->step < 1 || !(u->beta1 >= 0.0f && u->beta1 < 1.0f) || !(u->beta2 >= 0.0f && u->beta2 < 1.0f)))
+    return SYNK_ERR_SHAPE;
+  if (!aligned_to(p, 16) || !aligned_to(s1, 16) || (s2 && !aligned_to(s2, 16)) ||
+      (p_lp && !aligned_to(p_lp, 8)))
+    return SYNK_ERR_ALIGN;
+  BufTable t;
+  for (int w = 0; w < n; ++w) {
+    if (!grads[w]) return SYNK_ERR_NULL;
+    if (!aligned_to(grads[w], 16)) return SYNK_ERR_ALIGN;
+    t.p[w] = grads[w];
+  }
+  fill_weights(t, n, weights);
+  if (len == 0 && !loss_out) return SYNK_OK;
+  RuleParams h;
+  h.lr = u->lr;
+  h.wd = u->weight_decay;
+  h.eps = u->eps;
+  h.b2 = u->beta2;
+  h.a_t = 0.0f;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  switch (u->rule) {
+    case SYNK_RULE_MOMENTUM:
+      h.m = u->momentum;
+      return launch_reduce_update<SYNK_RULE_MOMENTUM>(t, n, len, p, s1, s2, h, p_lp, loss_in, loss_out, s);
+    case SYNK_RULE_NESTEROV:
+      h.m = u->momentum;
+      return launch_reduce_update<SYNK_RULE_NESTEROV>(t, n, len, p, s1, s2, h, p_lp, loss_in, loss_out, s);
+    case SYNK_RULE_RMSPROP:
+      h.m = u->rho;
+      return launch_reduce_update<SYNK_RULE_RMSPROP>(t, n, len, p, s1, s2, h, p_lp, loss_in, loss_out, s);
+    default: {
+      h.m = u->beta1;
+      // the bias-corrected step size, once per call on the host in double precision
+      const double b1t = pow((double)u->beta1, (double)u->step), b2t = pow((double)u->beta2, (double)u->step);
+      h.a_t = (float)((double)u->lr * sqrt(1.0 - b2t) / (1.0 - b1t));
+      return launch_reduce_update<SYNK_RULE_ADAM>(t, n, len, p, s1, s2, h, p_lp, loss_in, loss_out, s);
+    }
+  }
 }
 
 extern "C" int synk_sgd_update(float* p, float* v, const float* g, int64_t len, float lr,

@@ -78,6 +78,30 @@ def test_update_argument_checks():
     assert h(_tbl(FAKE, FAKE + 8), 2, 8, None, FAKE, FAKE, 0.1, 0.9, 0.0, None, None, None, None) == -5
     assert h(two, 2, 0, None, FAKE, FAKE, 0.1, 0.9, 0.0, None, None, None, None) == 0
     assert lib.synk_cast_bf16(None, FAKE, 4, None) == -1
+
+
+def test_reduce_update_argument_checks():
+    f = lib.synk_reduce_update
+    two = _tbl(FAKE, FAKE)
+    D = synk.UpdateDesc
+    mom = D(synk.SYNK_RULE_MOMENTUM, 0.1, 0.9, 0, 0, 0, 0, 0, 1)
+    adam = D(synk.SYNK_RULE_ADAM, 0.1, 0, 0, 0.9, 0.999, 1e-8, 0, 1)
+    r = ctypes.byref
+    assert f(None, two, 2, 8, None, FAKE, FAKE, None, None, None, None, None) == -1
+    assert f(r(mom), two, 2, 8, None, FAKE, None, None, None, None, None, None) == -1      # s1 missing
+    assert f(r(adam), two, 2, 8, None, FAKE, FAKE, None, None, None, None, None) == -1     # ADAM needs s2
+    assert f(r(D(7, 0.1, 0, 0, 0, 0, 0, 0, 1)), two, 2, 8, None, FAKE, FAKE, None, None, None, None, None) == -4
+    assert f(r(D(-1, 0.1, 0, 0, 0, 0, 0, 0, 1)), two, 2, 8, None, FAKE, FAKE, None, None, None, None, None) == -4
+    assert f(r(mom), two, 65, 8, None, FAKE, FAKE, None, None, None, None, None) == -2
+    assert f(r(mom), two, 2, -3, None, FAKE, FAKE, None, None, None, None, None) == -2
+    bad_step = D(synk.SYNK_RULE_ADAM, 0.1, 0, 0, 0.9, 0.999, 1e-8, 0, 0)
+    assert f(r(bad_step), two, 2, 8, None, FAKE, FAKE, FAKE, None, None, None, None) == -2
+    bad_beta = D(synk.SYNK_RULE_ADAM, 0.1, 0, 0, 1.0, 0.999, 1e-8, 0, 1)
+    assert f(r(bad_beta), two, 2, 8, None, FAKE, FAKE, FAKE, None, None, None, None) == -2
+    assert f(r(adam), two, 2, 8, None, FAKE, FAKE, FAKE + 4, None, None, None, None) == -5
+    assert f(r(mom), _tbl(FAKE, FAKE + 8), 2, 8, None, FAKE, FAKE, None, None, None, None, None) == -5
+    assert f(r(mom), two, 2, 8, None, FAKE, FAKE, None, None, FAKE, None, None) == -1     # loss pair
+    assert f(r(adam), two, 2, 0, None, FAKE, FAKE, FAKE, None, None, None, None) == 0     # empty: no launch
     assert lib.synk_cast_bf16(FAKE, FAKE + 1, 4, None) == -5
 
 

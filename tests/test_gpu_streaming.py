@@ -221,6 +221,70 @@ def test_reduce_sgd_update_weights_and_closed_form(synk):
     assert rel_err(dp.cpu().numpy(), p - 0.05 * G) < TOL_F32       # zero momentum: p - lr*G
 
 
+RULE_HYPER = dict(
+    momentum=dict(lr=0.05, momentum=0.9, weight_decay=1e-4),
+    nesterov=dict(lr=0.05, momentum=0.9, weight_decay=1e-4),
+    rmsprop=dict(lr=0.01, rho=0.9, eps=1e-6, weight_decay=1e-4),
+    adam=dict(lr=0.001, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=1e-4),
+)
+
+
+@pytest.mark.parametrize("rule", ["momentum", "nesterov", "rmsprop", "adam"])
+@pytest.mark.parametrize("n,length", [(1, 1000), (3, 1027), (8, 70001), (16, 513)])
+def test_reduce_update_rules_match_oracle_over_several_steps(synk, rule, n, length):
+    """Sec. 3.3 steps 2-3 with each update rule: three consecutive updates (state carried on
+    the device) against the float64 oracle; gradients sized so that every state array moves."""
+    rng = np.random.default_rng(900 + n)
+    h = RULE_HYPER[rule]
+    p = rng.standard_normal(length).astype(np.float32)
+    s1 = np.zeros(length, np.float32)
+    s2 = np.zeros(length, np.float32)
+    dp, d1, d2 = dev(p), dev(s1), dev(s2)
+    lp = torch.zeros(length, dtype=torch.bfloat16, device="cuda")
+    rp, r1, r2 = p.astype(np.float64), s1.astype(np.float64), s2.astype(np.float64)
+    for step in (1, 2, 3):
+        grads = [(rng.standard_normal(length) * 0.1).astype(np.float32) for _ in range(n)]
+        losses = rng.random(n).astype(np.float32)
+        loss_out = torch.zeros(1, device="cuda")
+        synk.synk_reduce_update(rule, [dev(g) for g in grads], dp, d1, d2 if rule == "adam" else None,
+                                step=step, p_lp=lp, loss_in=dev(losses), loss_out=loss_out, **h)
+        G = oreduce.reduce_buffers(grads, "mean")
+        rp, r1, r2n = oupdate.apply_rule(rule, rp, r1, r2, G, dict(h, t=step))
+        if r2n is not None:
+            r2 = r2n
+        assert rel_err(dp.cpu().numpy(), rp) < TOL_F32, (rule, step)
+        assert rel_err(d1.cpu().numpy(), r1) < TOL_F32, (rule, step)
+        if rule == "adam":
+            assert rel_err(d2.cpu().numpy(), r2) < TOL_F32, (rule, step)
+        else:
+            assert not d2.any().item()                       # untouched
+        assert abs(loss_out.item() - float(np.mean(losses.astype(np.float64)))) < 1e-6
+        want = ogather.round_to_bf16(dp.cpu().numpy())
+        assert np.array_equal(lp.float().cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+def test_reduce_update_momentum_rule_equals_the_dedicated_entry_point(synk):
+    c = workloads.config3(n_params=40003, n_workers=8)
+    grads = [dev(g) for g in c["grads"]]
+    p1, v1, p2, v2 = dev(c["p"]), dev(c["v"]), dev(c["p"]), dev(c["v"])
+    synk.synk_reduce_sgd_update(grads, p1, v1, c["lr"], c["momentum"], c["weight_decay"])
+    synk.synk_reduce_update("momentum", grads, p2, v2, lr=c["lr"], momentum=c["momentum"],
+                            weight_decay=c["weight_decay"])
+    assert torch.equal(p1, p2) and torch.equal(v1, v2)      # same arithmetic, same order: bit-exact
+
+
+def test_reduce_update_adam_weights_and_first_step_closed_form(synk):
+    rng = np.random.default_rng(77)
+    g = [rng.standard_normal(515).astype(np.float32) for _ in range(2)]
+    p = rng.standard_normal(515).astype(np.float32)
+    dp, dm, dv = dev(p), dev(np.zeros(515, np.float32)), dev(np.zeros(515, np.float32))
+    synk.synk_reduce_update("adam", [dev(x) for x in g], dp, dm, dv, lr=0.01, beta1=0.9, beta2=0.999, eps=1e-8,
+                            step=1, weights=[0.75, 0.25])
+    G = 0.75 * g[0].astype(np.float64) + 0.25 * g[1]
+    want = p - 0.01 * G / (np.abs(G) + 1e-8 / np.sqrt(1 - 0.999))   # first step from zero moments
+    assert rel_err(dp.cpu().numpy(), want) < TOL_F32
+
+
 # -------------------------------------------------------------- sliced eval
 def run_eval(synk, logits, labels, n_slices):
     rows, classes = logits.shape
