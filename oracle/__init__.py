@@ -19,6 +19,8 @@ the definition of what each step of the path computes:
               Sec. 3.2 step 3.
   reduce      Sec. 3.1 "Build Functions" (a reduce/gather op per output),
               Sec. 3.3 step 2 (all-reduce of the flat gradient).
+  collectives Sec. 3.2 "Shared Variable Management" (broadcast, all-reduce,
+              all-gather over the N worker copies), App. A (parameter average).
   update      Sec. 3.3 step 3 (the update rule applied with the combined
               gradient on the flat parameter array: momentum, Nesterov
               momentum, RMSProp, Adam).

@@ -11,7 +11,7 @@ import pytest
 import scipy.special
 import torch
 
-from oracle import brute, evalops, gather, mlp, reduce as oreduce, split, update
+from oracle import brute, collectives, evalops, gather, mlp, reduce as oreduce, split, update
 
 
 # ----------------------------------------------------------------- split
@@ -267,6 +267,40 @@ def test_mean_of_equal_buffers_is_bit_exact_and_pairs_cancel():
     x64 = x.astype(np.float64)
     w = oreduce.reduce_buffers([x64, 3 * x64], "mean", weights=[0.25, 0.75])
     assert np.allclose(w, 2.5 * x64, rtol=1e-15)
+
+
+# ----------------------------------------------------------- collectives
+def test_collectives_against_library_routines_and_invariants():
+    rng = np.random.default_rng(131)
+    bufs = [rng.standard_normal(37) for _ in range(5)]
+    stack = np.stack(bufs)
+    for op, ref in (("sum", stack.sum(0)), ("max", stack.max(0)), ("min", stack.min(0)),
+                    ("prod", stack.prod(0)), ("mean", stack.mean(0))):
+        out = collectives.all_reduce(bufs, op)
+        assert len(out) == 5 and all(np.allclose(o, ref, rtol=1e-13, atol=1e-15) for o in out)
+        assert all(np.array_equal(o, out[0]) for o in out)          # every worker holds the same result
+    # the parameter average (App. A): identical copies are a fixed point, and averaging is idempotent
+    same = collectives.all_reduce([bufs[0]] * 4, "mean")
+    assert all(np.allclose(o, bufs[0], rtol=1e-15) for o in same)
+    once = collectives.all_reduce(bufs, "mean")
+    twice = collectives.all_reduce(once, "mean")
+    assert np.allclose(twice[0], once[0], rtol=1e-15)
+    # results are copies, not views of one array
+    once[0][0] = 123.0
+    assert once[1][0] != 123.0
+    ints = [rng.integers(-9, 9, 11).astype(np.int32) for _ in range(3)]
+    assert np.array_equal(collectives.all_reduce(ints, "sum")[2], np.stack(ints).sum(0))
+    with pytest.raises(ValueError):
+        collectives.all_reduce(bufs, "concat")
+    b = collectives.broadcast(bufs[2], 4)
+    assert len(b) == 4 and all(np.array_equal(x, bufs[2]) for x in b) and b[0] is not b[1]
+    ragged = [rng.standard_normal(k) for k in (3, 0, 7, 1)]
+    g = collectives.all_gather(ragged)
+    assert len(g) == 4 and all(np.array_equal(x, np.concatenate(ragged)) for x in g)
+    # gathering a scattered array returns the array (Sec. 6: scatter by first dimension)
+    whole = rng.standard_normal(23)
+    parts = np.array_split(whole, 4)
+    assert np.array_equal(collectives.all_gather(parts)[3], whole)
 
 
 # ---------------------------------------------------------------- update
