@@ -43,6 +43,8 @@ def parse():
                     help="0 = plain copy of known size (calibrates the rocprofv3 byte counters)")
     ap.add_argument("--rule", default="momentum", choices=["momentum", "nesterov", "rmsprop", "adam"],
                     help="config 3 only: the update rule fused with the N-way average (Sec. 3.3)")
+    ap.add_argument("--collective", default=None, choices=["all_reduce", "broadcast", "all_gather"],
+                    help="config 3 shape only: time one collective over the 8 worker copies instead (Sec. 3.2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -215,6 +217,57 @@ class ReduceStep:
         return self.P / best, "3 whole steps at full size, best of 3"
 
 
+class CollectiveStep:
+    """Config 3's shape (8 worker copies of a 25,557,032-element fp32 array) under one collective of Sec. 3.2."""
+
+    def __init__(self, torch, synk, which):
+        import numpy as np
+        import workloads
+        self.torch, self.s, self.np, self.which = torch, synk, np, which
+        c = workloads.config3()
+        self.c = c
+        self.P, self.N = c["n_params"], c["n_workers"]
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        self.bufs = [up(g) for g in c["grads"]]
+        self.units, self.unit, self.dtype = self.P, "params/s", "f32"
+        if which == "all_reduce":
+            # in place on 818 MB of buffers: values decay towards the mean, the traffic stays the same
+            self.call = synk.prepare(synk.synk_all_reduce, self.bufs, "mean")
+            self.dom_name, self.dom_bytes = "all_reduce_kernel", self.P * 4 * 2 * self.N
+            what = "all-reduce (mean: the parameter / gradient average), in place"
+        elif which == "broadcast":
+            self.src = up(c["p"])
+            self.call = synk.prepare(synk.synk_broadcast, self.src, self.bufs)
+            self.dom_name, self.dom_bytes = "broadcast_kernel", self.P * 4 * (1 + self.N)
+            what = "broadcast of one array to the 8 copies"
+        else:
+            from oracle import split as osplit
+            self.bounds = osplit.share_bounds(self.P, self.N)
+            self.srcs = [up(c["p"][a:b]) for a, b in self.bounds]
+            self.call = synk.prepare(synk.synk_all_gather, self.srcs, self.bufs)
+            self.dom_name, self.dom_bytes = "all_gather_kernel", self.P * 4 * (1 + self.N)
+            what = "all-gather of 8 equal shares into the 8 copies"
+        self.workload = "config 3 shape (8 x 25,557,032 fp32): " + what
+
+    def step(self, i, timer):
+        timer.bracket(self.call)
+
+    def cpu_baseline(self):
+        from oracle import collectives as ocoll
+        c = self.c
+        best = 1e30
+        for _ in range(3):
+            t0 = time.perf_counter()
+            if self.which == "all_reduce":
+                ocoll.all_reduce(list(c["grads"]), "mean")
+            elif self.which == "broadcast":
+                ocoll.broadcast(c["p"], self.N)
+            else:
+                ocoll.all_gather([c["p"][a:b] for a, b in self.bounds])
+            best = min(best, time.perf_counter() - t0)
+        return self.P / best, "3 whole calls at full size, best of 3"
+
+
 class GatherStep:
     """Config 4: uint8 image gather + per-channel normalise to fp32, 8 worker shares."""
 
@@ -344,7 +397,7 @@ def main():
     torch.cuda.set_device(0)
 
     wl = {0: lambda: CopyStep(torch, synk), 1: lambda: MlpStep(torch, synk, 1), 2: lambda: MlpStep(torch, synk, 2),
-          3: lambda: ReduceStep(torch, synk, a.rule), 4: lambda: GatherStep(torch, synk),
+          3: lambda: (CollectiveStep(torch, synk, a.collective) if a.collective else ReduceStep(torch, synk, a.rule)), 4: lambda: GatherStep(torch, synk),
           5: lambda: EvalStep(torch, synk)}[a.config]()
     steps = a.steps if a.steps is not None else {0: 50, 1: 2000, 2: 1000, 3: 300, 4: 1000, 5: 1000}[a.config]
     warmup = a.warmup if a.warmup is not None else 20
@@ -372,7 +425,7 @@ def main():
         "config": {"workload": wl.workload, "units_per_step": wl.units},
         "roofline": {"bound": "hbm", "kernel": wl.dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if a.rule == "momentum" else None, "traffic_unit": "HBM bytes per launch",
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (a.rule == "momentum" and not a.collective) else None, "traffic_unit": "HBM bytes per launch",
                      "bytes_per_launch": wl.dom_bytes, "ms_per_launch": dom_ms},
     }
     if not a.no_cpu_baseline:

@@ -15,6 +15,9 @@
  *                           each (Sec. 3.1), evaluated in slices (Sec. 5.1)
  *   synk_reduce_buffers     reduce/gather of N worker results (Sec. 3.2 step
  *                           3, Sec. 3.3 step 2)
+ *   synk_broadcast, synk_all_reduce, synk_all_gather
+ *                           the collectives over the N worker copies of a
+ *                           variable (Sec. 3.2), incl. the parameter average
  *   synk_sgd_update         momentum update on the flat array (Sec. 3.3 step 3)
  *   synk_reduce_sgd_update  the last two fused into one pass over memory
  *   synk_reduce_update      the same pass with the other update rules of
@@ -246,6 +249,35 @@ int synk_sliced_eval(const float* logits, const int32_t* labels, int64_t rows, i
  */
 int synk_reduce_buffers(const void* const* bufs, int n, int64_t len, int dtype, int op,
                         const float* weights, const int64_t* lens, void* out, void* stream);
+
+/* ------------------------------------------------------------- collectives
+ * The collectives over the N worker copies of a variable (Sec. 3.2 "Shared
+ * Variable Management": broadcast, all-reduce and the other MPI-like
+ * collectives; App. A: averaging the parameters over the workers).  Reduce-
+ * to-one and gather-to-one are synk_reduce_buffers.  Elements are 4 bytes
+ * (SYNK_F32 or SYNK_I32); pointer tables, lens and weights are host arrays
+ * read during the call, the buffers device memory, 4-byte aligned (16-byte
+ * alignment of every buffer selects the vector path).
+ *
+ * synk_broadcast: dsts[w][i] = src[i], i < len, for each of the n workers.
+ *   src must not overlap a destination (src == dsts[w] itself is allowed).
+ * synk_all_reduce: in place; every bufs[w][i] becomes the fold, in worker
+ *   order, of bufs[0..n)[i] under op (SUM, MEAN, MAX, MIN, PROD; MEAN takes
+ *   optional weights, default 1/n, and is the parameter / gradient average).
+ *   The n buffers must be distinct and must not overlap.
+ * synk_all_gather: every dsts[w] (length sum of lens) receives the
+ *   concatenation of srcs[0..n) in worker order; srcs[w] has lens[w] >= 0
+ *   elements.  A source may be the matching segment of its own destination.
+ * Errors: NULL -> ERR_NULL; n out of [1,SYNK_MAX_WORKERS], negative length,
+ * repeated buffer in all_reduce -> ERR_SHAPE; dtype -> ERR_DTYPE; op (CONCAT,
+ * MEAN on I32, weights without MEAN) -> ERR_OP; alignment -> ERR_ALIGN.  A
+ * call with nothing to move returns SYNK_OK without a launch.
+ */
+int synk_broadcast(const void* src, void* const* dsts, int n, int64_t len, int dtype, void* stream);
+int synk_all_reduce(void* const* bufs, int n, int64_t len, int dtype, int op, const float* weights,
+                    void* stream);
+int synk_all_gather(const void* const* srcs, const int64_t* lens, int n, int dtype, void* const* dsts,
+                    void* stream);
 
 /* ------------------------------------------------------------------ update
  * Momentum update with the combined gradient (Sec. 3.3 step 3; the paper

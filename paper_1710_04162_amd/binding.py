@@ -20,6 +20,7 @@ __all__ = [
     "synk_sliced_grad_workspace_bytes", "synk_sliced_grad", "synk_cast_bf16",
     "synk_sliced_eval_workspace_bytes", "synk_sliced_eval", "synk_reduce_buffers",
     "synk_sgd_update", "synk_reduce_sgd_update", "synk_reduce_update",
+    "synk_broadcast", "synk_all_reduce", "synk_all_gather",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsynk.so")
@@ -83,6 +84,11 @@ lib.synk_reduce_sgd_update.argtypes = [_pp, _int, _i64, _pf32, _vp, _vp, _f32, _
 lib.synk_reduce_update.argtypes = [ctypes.POINTER(UpdateDesc), _pp, _int, _i64, _pf32, _vp, _vp, _vp, _vp,
                                    _vp, _vp, _vp]
 lib.synk_reduce_update.restype = _int
+lib.synk_broadcast.argtypes = [_vp, _pp, _int, _i64, _int, _vp]
+lib.synk_all_reduce.argtypes = [_pp, _int, _i64, _int, _int, _pf32, _vp]
+lib.synk_all_gather.argtypes = [_pp, _pi64, _int, _int, _pp, _vp]
+for _n in ("synk_broadcast", "synk_all_reduce", "synk_all_gather"):
+    getattr(lib, _n).restype = _int
 for _n in ("synk_split", "synk_gather_rows", "synk_build_norm_lut", "synk_poll_error",
            "synk_mlp_param_count", "synk_sliced_grad_workspace_bytes", "synk_sliced_grad",
            "synk_cast_bf16", "synk_sliced_eval_workspace_bytes", "synk_sliced_eval",
@@ -292,3 +298,26 @@ def synk_reduce_update(rule, grads, p, s1, s2=None, lr=0.0, momentum=0.0, rho=0.
             _ptr(loss_out), _stream(stream))
     return _run(lib.synk_reduce_update, args, (u, grads, p, s1, s2, w, p_lp, loss_in, loss_out, tg),
                 "synk_reduce_update", _prepare)
+
+
+def synk_broadcast(src, dsts, stream=None, _prepare=False):
+    td = _table(dsts)
+    args = (_ptr(src), td, len(dsts), src.numel(), DTYPE[src.dtype], _stream(stream))
+    return _run(lib.synk_broadcast, args, (src, dsts, td), "synk_broadcast", _prepare)
+
+
+def synk_all_reduce(bufs, op, weights=None, stream=None, _prepare=False):
+    n = len(bufs)
+    w = (ctypes.c_float * n)(*[float(x) for x in weights]) if weights is not None else None
+    tb = _table(bufs)
+    args = (tb, n, bufs[0].numel(), DTYPE[bufs[0].dtype], OP[op] if isinstance(op, str) else int(op), w,
+            _stream(stream))
+    return _run(lib.synk_all_reduce, args, (bufs, tb, w), "synk_all_reduce", _prepare)
+
+
+def synk_all_gather(srcs, dsts, stream=None, _prepare=False):
+    n = len(srcs)
+    lens = (ctypes.c_int64 * n)(*[int(s.numel()) for s in srcs])
+    ts, td = _table(srcs), _table(dsts)
+    args = (ts, lens, n, DTYPE[srcs[0].dtype], td, _stream(stream))
+    return _run(lib.synk_all_gather, args, (srcs, dsts, lens, ts, td), "synk_all_gather", _prepare)

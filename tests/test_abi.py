@@ -184,3 +184,37 @@ def test_binding_refuses_host_tensors():
     t = torch.zeros(8)
     with pytest.raises(ValueError):
         synk.synk_sgd_update(t, t, t, 0.1, 0.9)
+
+
+def test_collectives_argument_checks():
+    two = _tbl(FAKE, FAKE + 64)
+    b = lib.synk_broadcast
+    assert b(None, two, 2, 8, 2, None) == -1
+    assert b(FAKE, None, 2, 8, 2, None) == -1
+    assert b(FAKE, _tbl(FAKE, None), 2, 8, 2, None) == -1
+    assert b(FAKE, two, 0, 8, 2, None) == -2
+    assert b(FAKE, two, 2, -1, 2, None) == -2
+    assert b(FAKE, two, 2, 8, 0, None) == -3
+    assert b(FAKE + 2, two, 2, 8, 2, None) == -5
+    assert b(FAKE, two, 2, 0, 2, None) == 0
+    ar = lib.synk_all_reduce
+    w = (ctypes.c_float * 2)(0.5, 0.5)
+    assert ar(None, 2, 8, 2, 0, None, None) == -1
+    assert ar(two, 65, 8, 2, 0, None, None) == -2
+    assert ar(_tbl(FAKE, FAKE), 2, 8, 2, 0, None, None) == -2          # the same buffer twice
+    assert ar(two, 2, 8, 3, 0, None, None) == -3
+    assert ar(two, 2, 8, 2, 5, None, None) == -4                       # CONCAT is all_gather
+    assert ar(two, 2, 8, 1, 1, None, None) == -4                       # MEAN on I32
+    assert ar(two, 2, 8, 2, 0, w, None) == -4                          # weights only with MEAN
+    assert ar(_tbl(FAKE, FAKE + 66), 2, 8, 2, 0, None, None) == -5
+    assert ar(two, 2, 0, 2, 1, w, None) == 0
+    ag = lib.synk_all_gather
+    lens = (ctypes.c_int64 * 2)(3, 5)
+    assert ag(None, lens, 2, 2, two, None) == -1
+    assert ag(two, None, 2, 2, two, None) == -1
+    assert ag(two, lens, 2, 2, None, None) == -1
+    assert ag(two, (ctypes.c_int64 * 2)(3, -1), 2, 2, two, None) == -2
+    assert ag(two, lens, 2, 0, two, None) == -3
+    assert ag(_tbl(FAKE, FAKE + 3), lens, 2, 2, two, None) == -5
+    assert ag(two, lens, 2, 2, _tbl(FAKE, None), None) == -1
+    assert ag(two, (ctypes.c_int64 * 2)(0, 0), 2, 2, two, None) == 0

@@ -6,7 +6,7 @@ import torch
 
 import workloads
 from helpers import TOL_F32, rel_err
-from oracle import evalops, gather as ogather, reduce as oreduce, split as osplit, update as oupdate
+from oracle import collectives as ocoll, evalops, gather as ogather, reduce as oreduce, split as osplit, update as oupdate
 
 pytestmark = pytest.mark.gpu
 
@@ -283,6 +283,98 @@ def test_reduce_update_adam_weights_and_first_step_closed_form(synk):
     G = 0.75 * g[0].astype(np.float64) + 0.25 * g[1]
     want = p - 0.01 * G / (np.abs(G) + 1e-8 / np.sqrt(1 - 0.999))   # first step from zero moments
     assert rel_err(dp.cpu().numpy(), want) < TOL_F32
+
+
+# ------------------------------------------------------------- collectives
+@pytest.mark.parametrize("n,length", [(1, 5), (2, 4099), (3, 1027), (8, 70001), (16, 513)])
+def test_broadcast_is_bit_exact(synk, n, length):
+    rng = np.random.default_rng(40 + n)
+    src = rng.standard_normal(length).astype(np.float32)
+    dsts = [torch.full((length,), -7.0, device="cuda") for _ in range(n)]
+    synk.synk_broadcast(dev(src), dsts)
+    for d, r in zip(dsts, ocoll.broadcast(src, n)):
+        assert np.array_equal(d.cpu().numpy().view(np.uint32), r.view(np.uint32))
+    isrc = rng.integers(-2**31, 2**31 - 1, length).astype(np.int32)
+    idst = [torch.zeros(length, dtype=torch.int32, device="cuda") for _ in range(n)]
+    synk.synk_broadcast(dev(isrc), idst)
+    assert all(np.array_equal(d.cpu().numpy(), isrc) for d in idst)
+
+
+def test_broadcast_unaligned_views(synk):
+    src = np.arange(1000, dtype=np.float32)
+    big = [torch.zeros(1003, device="cuda") for _ in range(3)]
+    dsts = [b[1 + k:1 + k + 1000] for k, b in enumerate(big)]        # 4-byte aligned only
+    synk.synk_broadcast(dev(src), dsts)
+    for k, b in enumerate(big):
+        got = b.cpu().numpy()
+        assert np.array_equal(got[1 + k:1001 + k], src) and got[:1 + k].sum() == 0 and got[1001 + k:].sum() == 0
+
+
+@pytest.mark.parametrize("op", ["sum", "mean", "max", "min", "prod"])
+@pytest.mark.parametrize("n,length", [(1, 7), (2, 4099), (3, 1027), (8, 70001), (16, 513)])
+def test_all_reduce_matches_oracle_on_every_worker(synk, op, n, length):
+    rng = np.random.default_rng(50 + n)
+    host = [((rng.random(length) * 1.5 + 0.5) * (1.0 if op == "prod" else rng.choice([-1.0, 1.0]))).astype(np.float32)
+            for _ in range(n)]
+    bufs = [dev(h) for h in host]
+    synk.synk_all_reduce(bufs, op)
+    ref = ocoll.all_reduce(host, op)
+    for b, r in zip(bufs, ref):
+        got = b.cpu().numpy()
+        if op in ("max", "min"):
+            assert np.array_equal(got, r.astype(np.float32))        # selections are exact
+        else:
+            assert rel_err(got, r) < TOL_F32
+    assert all(torch.equal(b, bufs[0]) for b in bufs)                 # identical bits on every worker
+
+
+def test_all_reduce_int32_exact_weights_and_parameter_average(synk):
+    rng = np.random.default_rng(61)
+    ints = [rng.integers(-1000, 1000, 3001).astype(np.int32) for _ in range(5)]
+    for op in ("sum", "max", "min"):
+        bufs = [dev(x) for x in ints]
+        synk.synk_all_reduce(bufs, op)
+        ref = ocoll.all_reduce(ints, op)
+        assert all(np.array_equal(b.cpu().numpy(), r.astype(np.int32)) for b, r in zip(bufs, ref))
+    host = [rng.standard_normal(2050).astype(np.float32) for _ in range(4)]
+    w = [0.4, 0.3, 0.2, 0.1]
+    bufs = [dev(h) for h in host]
+    synk.synk_all_reduce(bufs, "mean", weights=w)
+    assert rel_err(bufs[3].cpu().numpy(), ocoll.all_reduce(host, "mean", w)[3]) < TOL_F32
+    # App. A: averaging the parameter copies; a second average changes nothing (up to rounding)
+    params = [dev(h) for h in host]
+    synk.synk_all_reduce(params, "mean")
+    once = params[0].clone()
+    synk.synk_all_reduce(params, "mean")
+    assert rel_err(params[2].cpu().numpy(), once.cpu().numpy().astype(np.float64)) < 1e-6
+    # same numbers as reduce-to-one followed by broadcast
+    out = torch.empty(2050, device="cuda")
+    synk.synk_reduce_buffers([dev(h) for h in host], synk.SYNK_MEAN, out)
+    assert torch.equal(out, once)
+
+
+@pytest.mark.parametrize("lens", [[5], [3, 0, 7, 1], [1000, 1001, 999, 1000, 1000, 1000, 1000, 1000], [0, 0, 4]])
+def test_all_gather_is_bit_exact(synk, lens):
+    rng = np.random.default_rng(70 + len(lens))
+    host = [rng.standard_normal(k).astype(np.float32) for k in lens]
+    total = sum(lens)
+    dsts = [torch.full((total,), -3.0, device="cuda") for _ in lens]
+    synk.synk_all_gather([dev(h) for h in host], dsts)
+    for d, r in zip(dsts, ocoll.all_gather(host)):
+        assert np.array_equal(d.cpu().numpy().view(np.uint32), r.view(np.uint32))
+
+
+def test_all_gather_in_place_segments_and_scatter_roundtrip(synk):
+    # each worker's share is the matching segment of its own destination (Sec. 6: scatter by first dimension)
+    whole = np.random.default_rng(72).standard_normal(4101).astype(np.float32)
+    bounds = osplit.share_bounds(4101, 4)
+    dsts = [torch.zeros(4101, device="cuda") for _ in range(4)]
+    srcs = []
+    for w, (a, b) in enumerate(bounds):
+        dsts[w][a:b] = dev(whole[a:b])
+        srcs.append(dsts[w][a:b])
+    synk.synk_all_gather(srcs, dsts)
+    assert all(np.array_equal(d.cpu().numpy(), whole) for d in dsts)
 
 
 # -------------------------------------------------------------- sliced eval
