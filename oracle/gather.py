@@ -1,6 +1,9 @@
 """Input indexing (Sec. 5.2): the minibatch is data[idx] for a list of row
-indexes, duplicates allowed; worker w receives the rows named by its
-contiguous share of the list."""
+indexes, duplicates allowed, or for a slice start:stop:step; worker w receives
+the rows named by its contiguous share of the list.  For data that already
+lives on the workers (Sec. 5.2 last part, Sec. 4.3 "scatter": an array is
+divided over the workers by its first dimension), every worker indexes its own
+share with its own list, or all of them with the same one."""
 import numpy as np
 
 from . import split
@@ -20,6 +23,33 @@ def gather_rows(data, idx):
 def gather_shares(data, idx, n_workers):
     """List of per-worker arrays, in worker order."""
     return [gather_rows(data, idx[a:b]) for (a, b) in split.share_bounds(len(idx), n_workers)]
+
+
+def slice_indexes(start, stop, step):
+    """The index list a slice start:stop:step (step >= 1, 0 <= start <= stop)
+    stands for: start, start+step, ... below stop."""
+    if step < 1 or start < 0 or stop < start:
+        raise ValueError("slice out of the supported form")
+    out = []
+    j = start
+    while j < stop:
+        out.append(j)
+        j += step
+    return np.asarray(out, dtype=np.int64)
+
+
+def scatter(data, n_workers):
+    """Sec. 4.3: the array divided over the workers by its first dimension,
+    shares as equal as possible, in order."""
+    data = np.asarray(data)
+    return [data[a:b].copy() for (a, b) in split.share_bounds(data.shape[0], n_workers)]
+
+
+def gather_resident(shares, idx_lists):
+    """Every worker w excerpts rows idx_lists[w] from its own resident share."""
+    if len(shares) != len(idx_lists):
+        raise ValueError("one index list per worker")
+    return [gather_rows(s, i) for s, i in zip(shares, idx_lists)]
 
 
 def normalise_u8(rows_u8, mean, std):

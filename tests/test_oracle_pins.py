@@ -269,6 +269,36 @@ def test_mean_of_equal_buffers_is_bit_exact_and_pairs_cancel():
     assert np.allclose(w, 2.5 * x64, rtol=1e-15)
 
 
+def test_slice_indexes_scatter_and_resident_gather_against_python_and_numpy():
+    rng = np.random.default_rng(121)
+    data = rng.standard_normal((29, 5))
+    for start, stop, step in [(0, 29, 1), (3, 20, 4), (5, 5, 1), (0, 29, 30), (7, 28, 3)]:
+        ix = gather.slice_indexes(start, stop, step)
+        assert list(ix) == list(range(start, stop, step))
+        assert np.array_equal(gather.gather_rows(data, ix), data[start:stop:step])
+    for bad in [(0, 5, 0), (-1, 5, 1), (6, 5, 1)]:
+        with pytest.raises(ValueError):
+            gather.slice_indexes(*bad)
+    for n in (1, 3, 4, 8, 40):
+        sh = gather.scatter(data, n)
+        ref = np.array_split(data, n)
+        assert len(sh) == n and all(np.array_equal(a, b) for a, b in zip(sh, ref))
+        assert np.array_equal(np.concatenate(sh), data)
+        # scatter == indexing with the full slice, shares taken by the same split rule
+        via = gather.gather_shares(data, gather.slice_indexes(0, 29, 1), n)
+        assert all(np.array_equal(a, b) for a, b in zip(sh, via))
+    shares = gather.scatter(data, 3)
+    lists = [rng.integers(0, len(s), 6) for s in shares]
+    out = gather.gather_resident(shares, lists)
+    assert all(np.array_equal(o, np.take(s, i, axis=0)) for o, s, i in zip(out, shares, lists))
+    same = gather.gather_resident(shares, [np.array([1, 0, 1])] * 3)
+    assert all(np.array_equal(o, s[[1, 0, 1]]) for o, s in zip(same, shares))
+    with pytest.raises(IndexError):
+        gather.gather_resident(shares, [np.array([0]), np.array([len(shares[1])]), np.array([0])])
+    with pytest.raises(ValueError):
+        gather.gather_resident(shares, lists[:2])
+
+
 # ----------------------------------------------------------- collectives
 def test_collectives_against_library_routines_and_invariants():
     rng = np.random.default_rng(131)
