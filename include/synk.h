@@ -7,6 +7,10 @@
  *
  *   synk_gather_rows        input indexing (Sec. 5.2) + scatter of the index
  *                           list over workers (Sec. 3.2 step 1)
+ *   synk_gather_slice, synk_scatter_rows, synk_gather_resident
+ *                           the same with a slice for a list, the scatter of an
+ *                           array over the workers (Sec. 4.3), and indexing of
+ *                           shares that already live on the workers (Sec. 5.2)
  *   synk_sliced_grad        the gradient function run over every worker's
  *                           share in slices, slice results aggregated on the
  *                           GPU (Sec. 5.1), one flat gradient per worker
@@ -134,6 +138,44 @@ int synk_gather_rows(const void* data, int64_t n_rows, int64_t row_elems, int sr
                      const float* lut, int channels,
                      const int32_t* labels, int32_t* const* dst_labels,
                      uint32_t flags, void* ws, size_t ws_bytes, void* stream);
+
+/* The same gather with the index list given as a slice (Sec. 5.2: "indexes
+ * can make a slice or can be a list"): row j of the minibatch is
+ * data[start + j*step], j < ceil((stop-start)/step), step >= 1,
+ * 0 <= start <= stop <= n_rows; the list is split over the workers as above.
+ * Errors as synk_gather_rows; step < 1 -> ERR_SHAPE; start/stop outside the
+ * stated range -> ERR_INDEX (nothing is launched). */
+int synk_gather_slice(const void* data, int64_t n_rows, int64_t row_elems, int src_dtype,
+                      int64_t start, int64_t stop, int64_t step,
+                      void* const* dst, int n_workers, int dst_dtype,
+                      const float* lut, int channels,
+                      const int32_t* labels, int32_t* const* dst_labels, void* stream);
+
+/* The "scatter" collective (Sec. 4.3): an array is divided over the workers'
+ * memories by its first dimension, shares as equal as possible, in order:
+ * dst[w] receives rows [start_w, start_w + size_w) of data (split rule),
+ * bit-exact, and dst_labels[w] the matching labels when labels != NULL.
+ * Equals synk_gather_slice(0, n_rows, 1) with dst_dtype == dtype. */
+int synk_scatter_rows(const void* data, int64_t n_rows, int64_t row_elems, int dtype,
+                      void* const* dst, int n_workers,
+                      const int32_t* labels, int32_t* const* dst_labels, void* stream);
+
+/* Input indexing of data that already lives on the workers (Sec. 5.2: for
+ * inputs stored on the devices "the same or different indexes can be applied
+ * to each device"): worker w excerpts rows idx[w][0..n_idx[w]) of its own
+ * share shares[w] ([share_rows[w] x row_elems]) into dst[w], in list order.
+ * shares, share_rows, idx, n_idx, dst, labels, dst_labels: host arrays of
+ * n_workers entries (idx[w], shares[w], labels[w] device pointers; pass the
+ * same idx pointer n times to apply one list everywhere).  A worker with
+ * n_idx[w] == 0 is skipped and may have NULL pointers.  dtype pairs, lut,
+ * flags/ws and out-of-range handling as in synk_gather_rows; the error word
+ * collects over all workers.  One launch per worker with a non-empty list. */
+int synk_gather_resident(const void* const* shares, const int64_t* share_rows, int64_t row_elems,
+                         int src_dtype, const int32_t* const* idx, const int64_t* n_idx,
+                         void* const* dst, int n_workers, int dst_dtype,
+                         const float* lut, int channels,
+                         const int32_t* const* labels, int32_t* const* dst_labels,
+                         uint32_t flags, void* ws, size_t ws_bytes, void* stream);
 
 /* Builds on the device the table used by the U8->F32 gather:
  * lut[c*256 + x] = (float)(((double)x - (double)mean[c]) / (double)std[c]),

@@ -21,6 +21,7 @@ __all__ = [
     "synk_sliced_eval_workspace_bytes", "synk_sliced_eval", "synk_reduce_buffers",
     "synk_sgd_update", "synk_reduce_sgd_update", "synk_reduce_update",
     "synk_broadcast", "synk_all_reduce", "synk_all_gather",
+    "synk_gather_slice", "synk_scatter_rows", "synk_gather_resident",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsynk.so")
@@ -66,6 +67,13 @@ lib.synk_split.argtypes = [_i64, _int, _pi64]
 lib.synk_gather_workspace_bytes.restype = _sz
 lib.synk_gather_rows.argtypes = [_vp, _i64, _i64, _int, _vp, _i64, _pp, _int, _int, _vp, _int, _vp,
                                  _pp, ctypes.c_uint32, _vp, _sz, _vp]
+lib.synk_gather_slice.argtypes = [_vp, _i64, _i64, _int, _i64, _i64, _i64, _pp, _int, _int, _vp, _int, _vp, _pp,
+                                  _vp]
+lib.synk_scatter_rows.argtypes = [_vp, _i64, _i64, _int, _pp, _int, _vp, _pp, _vp]
+lib.synk_gather_resident.argtypes = [_pp, _pi64, _i64, _int, _pp, _pi64, _pp, _int, _int, _vp, _int, _pp, _pp,
+                                     ctypes.c_uint32, _vp, _sz, _vp]
+for _n in ("synk_gather_slice", "synk_scatter_rows", "synk_gather_resident"):
+    getattr(lib, _n).restype = _int
 lib.synk_build_norm_lut.argtypes = [_pf32, _pf32, _int, _vp, _vp]
 lib.synk_poll_error.argtypes = [_vp, _vp]
 lib.synk_mlp_param_count.argtypes = [ctypes.POINTER(MlpDesc), _pi64]
@@ -317,7 +325,52 @@ def synk_all_reduce(bufs, op, weights=None, stream=None, _prepare=False):
 
 def synk_all_gather(srcs, dsts, stream=None, _prepare=False):
     n = len(srcs)
+    if len(dsts) != n:
+        raise ValueError("synk_all_gather: one destination per worker")
     lens = (ctypes.c_int64 * n)(*[int(s.numel()) for s in srcs])
     ts, td = _table(srcs), _table(dsts)
     args = (ts, lens, n, DTYPE[srcs[0].dtype], td, _stream(stream))
     return _run(lib.synk_all_gather, args, (srcs, dsts, lens, ts, td), "synk_all_gather", _prepare)
+
+
+def _row_elems(data):
+    n = 1
+    for d in data.shape[1:]:
+        n *= int(d)
+    return n
+
+
+def synk_gather_slice(data, start, stop, step, dst, lut=None, channels=0, labels=None, dst_labels=None,
+                      stream=None, _prepare=False):
+    t_dst = _table(dst)
+    t_lab = _table(dst_labels) if dst_labels is not None else None
+    args = (_ptr(data), data.shape[0], _row_elems(data), DTYPE[data.dtype], int(start), int(stop), int(step),
+            t_dst, len(dst), DTYPE[dst[0].dtype], _ptr(lut), channels, _ptr(labels), t_lab, _stream(stream))
+    return _run(lib.synk_gather_slice, args, (data, dst, lut, labels, dst_labels, t_dst, t_lab),
+                "synk_gather_slice", _prepare)
+
+
+def synk_scatter_rows(data, dst, labels=None, dst_labels=None, stream=None, _prepare=False):
+    t_dst = _table(dst)
+    t_lab = _table(dst_labels) if dst_labels is not None else None
+    args = (_ptr(data), data.shape[0], _row_elems(data), DTYPE[data.dtype], t_dst, len(dst), _ptr(labels), t_lab,
+            _stream(stream))
+    return _run(lib.synk_scatter_rows, args, (data, dst, labels, dst_labels, t_dst, t_lab),
+                "synk_scatter_rows", _prepare)
+
+
+def synk_gather_resident(shares, idx, dst, lut=None, channels=0, labels=None, dst_labels=None, flags=0,
+                         ws=None, stream=None, _prepare=False):
+    """shares, idx, dst (and labels, dst_labels): one tensor per worker."""
+    n = len(shares)
+    rows = (ctypes.c_int64 * n)(*[int(s.shape[0]) for s in shares])
+    nidx = (ctypes.c_int64 * n)(*[int(i.numel()) for i in idx])
+    wsp, wsb = _ws(ws)
+    t_sh, t_ix, t_dst = _table(shares), _table(idx), _table(dst)
+    t_lab = _table(labels) if labels is not None else None
+    t_dl = _table(dst_labels) if dst_labels is not None else None
+    args = (t_sh, rows, _row_elems(shares[0]), DTYPE[shares[0].dtype], t_ix, nidx, t_dst, n, DTYPE[dst[0].dtype],
+            _ptr(lut), channels, t_lab, t_dl, flags, wsp, wsb, _stream(stream))
+    return _run(lib.synk_gather_resident, args,
+                (shares, idx, dst, lut, labels, dst_labels, ws, rows, nidx, t_sh, t_ix, t_dst, t_lab, t_dl),
+                "synk_gather_resident", _prepare)

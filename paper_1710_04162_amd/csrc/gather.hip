@@ -20,11 +20,16 @@ struct RowRef {
   int64_t local;     // row inside the worker's buffer
 };
 
-__device__ __forceinline__ RowRef locate(const int32_t* __restrict__ idx, int64_t n_idx,
-                                         int n_workers, int64_t n_rows, int64_t j,
-                                         uint32_t* err_word) {
+// Where batch row j comes from: a list entry, or start + j * step (slice form).
+struct IdxSrc {
+  const int32_t* idx;   // device int32[n_idx]; NULL = slice form
+  int64_t start, step;
+};
+
+__device__ __forceinline__ RowRef locate(const IdxSrc& ix, int64_t n_idx, int n_workers,
+                                         int64_t n_rows, int64_t j, uint32_t* err_word) {
   RowRef r;
-  const int64_t src = idx[j];
+  const int64_t src = ix.idx ? (int64_t)ix.idx[j] : ix.start + j * ix.step;
   int64_t start;
   share_of(n_idx, n_workers, j, &r.worker, &start);
   r.local = j - start;
@@ -41,7 +46,7 @@ __device__ __forceinline__ void copy_label(const DstTable& t, const int32_t* __r
 // Bit-exact copy in units of V (16, 4 or 1 bytes).  grid = (n_idx, chunks).
 template <typename V>
 __global__ __launch_bounds__(kGBlock) void gather_copy_kernel(
-    const V* __restrict__ data, int64_t n_rows, int64_t row_units, const int32_t* __restrict__ idx,
+    const V* __restrict__ data, int64_t n_rows, int64_t row_units, IdxSrc idx,
     int64_t n_idx, DstTable t, int n_workers, const int32_t* __restrict__ labels,
     uint32_t* err_word, int units_per_block) {
   const int64_t j = blockIdx.x;
@@ -60,7 +65,7 @@ __global__ __launch_bounds__(kGBlock) void gather_copy_kernel(
 template <bool VEC>
 __global__ __launch_bounds__(kGBlock) void gather_bf16_kernel(
     const float* __restrict__ data, int64_t n_rows, int64_t row_elems,
-    const int32_t* __restrict__ idx, int64_t n_idx, DstTable t, int n_workers,
+    IdxSrc idx, int64_t n_idx, DstTable t, int n_workers,
     const int32_t* __restrict__ labels, uint32_t* err_word, int units_per_block) {
   const int64_t j = blockIdx.x;
   const RowRef r = locate(idx, n_idx, n_workers, n_rows, j, err_word);
@@ -94,7 +99,7 @@ constexpr int kLBlock = 1024;
 template <bool VEC>
 __global__ __launch_bounds__(kLBlock) void gather_u8_lut_kernel(
     const uint8_t* __restrict__ data, int64_t n_rows, int row_elems, int plane,
-    const int32_t* __restrict__ idx, int64_t n_idx, DstTable t, int n_workers,
+    IdxSrc idx, int64_t n_idx, DstTable t, int n_workers,
     const float* __restrict__ lut, int channels, const int32_t* __restrict__ labels,
     uint32_t* err_word, int units_per_block) {
   __shared__ float s_lut[SYNK_MAX_CHANNELS * 256];
@@ -185,12 +190,14 @@ using namespace synk;
 
 extern "C" size_t synk_gather_workspace_bytes(void) { return 256; }
 
-extern "C" int synk_gather_rows(const void* data, int64_t n_rows, int64_t row_elems, int src_dtype,
-                                const int32_t* idx, int64_t n_idx, void* const* dst, int n_workers,
-                                int dst_dtype, const float* lut, int channels,
-                                const int32_t* labels, int32_t* const* dst_labels, uint32_t flags,
-                                void* ws, size_t ws_bytes, void* stream) {
-  if (!data || !dst || (!idx && n_idx > 0)) return SYNK_ERR_NULL;
+// The gather behind every entry point.  clear_err: reset the error word first
+// (a call made of several launches resets it once).
+static int gather_impl(const void* data, int64_t n_rows, int64_t row_elems, int src_dtype,
+                       IdxSrc idx, int64_t n_idx, void* const* dst, int n_workers,
+                       int dst_dtype, const float* lut, int channels,
+                       const int32_t* labels, int32_t* const* dst_labels, uint32_t flags,
+                       void* ws, size_t ws_bytes, void* stream, bool clear_err, bool check_only = false) {
+  if (!data || !dst) return SYNK_ERR_NULL;
   if (labels && !dst_labels) return SYNK_ERR_NULL;
   if (n_rows < 0 || row_elems <= 0 || n_idx < 0) return SYNK_ERR_SHAPE;
   if (n_workers < 1 || n_workers > SYNK_MAX_WORKERS) return SYNK_ERR_SHAPE;
@@ -228,8 +235,9 @@ extern "C" int synk_gather_rows(const void* data, int64_t n_rows, int64_t row_el
     t.dst[w] = dst[w];
     t.lab[w] = labels ? dst_labels[w] : nullptr;
   }
+  if (check_only) return SYNK_OK;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  if (err_word) {
+  if (err_word && clear_err) {
     hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, s, err_word);
     SYNK_LAUNCH_CHECK();
   }
@@ -296,6 +304,80 @@ extern "C" int synk_gather_rows(const void* data, int64_t n_rows, int64_t row_el
                          idx, n_idx, t, n_workers, lut, channels, labels, err_word, upb);
   }
   SYNK_LAUNCH_CHECK();
+  return SYNK_OK;
+}
+
+extern "C" int synk_gather_rows(const void* data, int64_t n_rows, int64_t row_elems, int src_dtype,
+                                const int32_t* idx, int64_t n_idx, void* const* dst, int n_workers,
+                                int dst_dtype, const float* lut, int channels,
+                                const int32_t* labels, int32_t* const* dst_labels, uint32_t flags,
+                                void* ws, size_t ws_bytes, void* stream) {
+  if (!idx && n_idx > 0) return SYNK_ERR_NULL;
+  return gather_impl(data, n_rows, row_elems, src_dtype, IdxSrc{idx, 0, 0}, n_idx, dst, n_workers, dst_dtype,
+                     lut, channels, labels, dst_labels, flags, ws, ws_bytes, stream, true);
+}
+
+extern "C" int synk_gather_slice(const void* data, int64_t n_rows, int64_t row_elems, int src_dtype,
+                                 int64_t start, int64_t stop, int64_t step, void* const* dst,
+                                 int n_workers, int dst_dtype, const float* lut, int channels,
+                                 const int32_t* labels, int32_t* const* dst_labels, void* stream) {
+  if (step < 1) return SYNK_ERR_SHAPE;
+  if (n_rows < 0) return SYNK_ERR_SHAPE;
+  if (start < 0 || stop < start || stop > n_rows) return SYNK_ERR_INDEX;
+  const int64_t n_idx = (stop - start + step - 1) / step;
+  return gather_impl(data, n_rows, row_elems, src_dtype, IdxSrc{nullptr, start, step}, n_idx, dst, n_workers,
+                     dst_dtype, lut, channels, labels, dst_labels, 0u, nullptr, 0, stream, false);
+}
+
+extern "C" int synk_scatter_rows(const void* data, int64_t n_rows, int64_t row_elems, int dtype,
+                                 void* const* dst, int n_workers, const int32_t* labels,
+                                 int32_t* const* dst_labels, void* stream) {
+  return synk_gather_slice(data, n_rows, row_elems, dtype, 0, n_rows, 1, dst, n_workers, dtype, nullptr, 0,
+                           labels, dst_labels, stream);
+}
+
+extern "C" int synk_gather_resident(const void* const* shares, const int64_t* share_rows, int64_t row_elems,
+                                    int src_dtype, const int32_t* const* idx, const int64_t* n_idx,
+                                    void* const* dst, int n_workers, int dst_dtype, const float* lut,
+                                    int channels, const int32_t* const* labels,
+                                    int32_t* const* dst_labels, uint32_t flags, void* ws,
+                                    size_t ws_bytes, void* stream) {
+  if (!shares || !share_rows || !idx || !n_idx || !dst) return SYNK_ERR_NULL;
+  if (labels && !dst_labels) return SYNK_ERR_NULL;
+  if (n_workers < 1 || n_workers > SYNK_MAX_WORKERS) return SYNK_ERR_SHAPE;
+  // every argument is checked before the first launch
+  for (int w = 0; w < n_workers; ++w) {
+    if (n_idx[w] < 0 || share_rows[w] < 0) return SYNK_ERR_SHAPE;
+    if (n_idx[w] > 0 && (!shares[w] || !idx[w] || !dst[w])) return SYNK_ERR_NULL;
+    if (n_idx[w] > 0 && labels && (!labels[w] || !dst_labels[w])) return SYNK_ERR_NULL;
+  }
+  if ((flags & SYNK_FLAG_CHECK_INDEX) &&
+      (!ws || ws_bytes < synk_gather_workspace_bytes() || !aligned_to(ws, 256)))
+    return SYNK_ERR_WORKSPACE;
+  for (int w = 0; w < n_workers; ++w) {          // every worker's arguments, before the first launch
+    if (n_idx[w] == 0) continue;
+    void* const d1[1] = {dst[w]};
+    int32_t* const l1[1] = {labels ? dst_labels[w] : nullptr};
+    if (int rc = gather_impl(shares[w], share_rows[w], row_elems, src_dtype, IdxSrc{idx[w], 0, 0}, n_idx[w], d1,
+                             1, dst_dtype, lut, channels, labels ? labels[w] : nullptr, l1, flags, ws,
+                             ws_bytes, stream, false, true))
+      return rc;
+  }
+  if (flags & SYNK_FLAG_CHECK_INDEX) {
+    hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, reinterpret_cast<hipStream_t>(stream),
+                       reinterpret_cast<uint32_t*>(ws));
+    SYNK_LAUNCH_CHECK();
+  }
+  // one worker at a time: its share, its list, its buffer (the error word collects over all of them)
+  for (int w = 0; w < n_workers; ++w) {
+    if (n_idx[w] == 0) continue;
+    void* const d1[1] = {dst[w]};
+    int32_t* const l1[1] = {labels ? dst_labels[w] : nullptr};
+    if (int rc = gather_impl(shares[w], share_rows[w], row_elems, src_dtype, IdxSrc{idx[w], 0, 0}, n_idx[w], d1,
+                             1, dst_dtype, lut, channels, labels ? labels[w] : nullptr, l1, flags, ws,
+                             ws_bytes, stream, false))
+      return rc;
+  }
   return SYNK_OK;
 }
 

@@ -218,3 +218,33 @@ def test_collectives_argument_checks():
     assert ag(_tbl(FAKE, FAKE + 3), lens, 2, 2, two, None) == -5
     assert ag(two, lens, 2, 2, _tbl(FAKE, None), None) == -1
     assert ag(two, (ctypes.c_int64 * 2)(0, 0), 2, 2, two, None) == 0
+
+
+def test_slice_scatter_and_resident_gather_argument_checks():
+    one = _tbl(FAKE)
+    gs = lib.synk_gather_slice
+    assert gs(FAKE, 10, 4, 2, 0, 10, 0, one, 1, 2, None, 0, None, None, None) == -2      # step < 1
+    assert gs(FAKE, 10, 4, 2, -1, 10, 1, one, 1, 2, None, 0, None, None, None) == -7
+    assert gs(FAKE, 10, 4, 2, 0, 11, 1, one, 1, 2, None, 0, None, None, None) == -7
+    assert gs(FAKE, 10, 4, 2, 6, 5, 1, one, 1, 2, None, 0, None, None, None) == -7
+    assert gs(None, 10, 4, 2, 0, 10, 1, one, 1, 2, None, 0, None, None, None) == -1
+    assert gs(FAKE, 10, 4, 2, 0, 10, 1, one, 0, 2, None, 0, None, None, None) == -2
+    assert gs(FAKE, 10, 4, 2, 0, 10, 1, one, 1, 0, None, 0, None, None, None) == -3      # F32 -> U8
+    assert gs(FAKE, 10, 4, 2, 5, 5, 1, one, 1, 2, None, 0, None, None, None) == 0        # empty slice
+    sc = lib.synk_scatter_rows
+    assert sc(None, 10, 4, 2, one, 1, None, None, None) == -1
+    assert sc(FAKE, 10, 4, 2, _tbl(None), 1, None, None, None) == -1
+    assert sc(FAKE, 10, 0, 2, one, 1, None, None, None) == -2
+    assert sc(FAKE, 0, 4, 2, one, 1, None, None, None) == 0
+    gr = lib.synk_gather_resident
+    rows = (ctypes.c_int64 * 2)(5, 5)
+    nidx = (ctypes.c_int64 * 2)(3, 3)
+    two = _tbl(FAKE, FAKE + 64)
+    assert gr(None, rows, 4, 2, two, nidx, two, 2, 2, None, 0, None, None, 0, None, 0, None) == -1
+    assert gr(two, rows, 4, 2, _tbl(FAKE, None), nidx, two, 2, 2, None, 0, None, None, 0, None, 0, None) == -1
+    assert gr(two, rows, 4, 2, two, (ctypes.c_int64 * 2)(3, -1), two, 2, 2, None, 0, None, None, 0, None, 0, None) == -2
+    assert gr(two, rows, 4, 2, two, nidx, two, 65, 2, None, 0, None, None, 0, None, 0, None) == -2
+    assert gr(two, rows, 4, 2, two, nidx, two, 2, 0, None, 0, None, None, 0, None, 0, None) == -3
+    assert gr(two, rows, 4, 2, two, nidx, two, 2, 2, None, 0, None, None, 1, None, 0, None) == -6   # flag, no ws
+    assert gr(two, rows, 4, 2, two, (ctypes.c_int64 * 2)(0, 0), _tbl(None, None), 2, 2, None, 0, None, None, 0,
+              None, 0, None) == 0

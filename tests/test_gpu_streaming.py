@@ -112,6 +112,101 @@ def test_gather_out_of_range_index_is_skipped_and_reported(synk):
     assert synk.synk_poll_error(ws) == 0
 
 
+@pytest.mark.parametrize("start,stop,step,n_workers", [(0, 200, 1, 4), (3, 197, 4, 3), (50, 50, 1, 2), (7, 200, 13, 8),
+                                                       (0, 200, 200, 2)])
+def test_gather_slice_matches_list_form_and_oracle(synk, start, stop, step, n_workers):
+    rng = np.random.default_rng(start + stop + step)
+    data = rng.standard_normal((200, 40)).astype(np.float32)
+    labels = rng.integers(0, 10, 200).astype(np.int32)
+    ix = ogather.slice_indexes(start, stop, step)
+    sizes = share_sizes(len(ix), n_workers)
+    mk = lambda: ([torch.full((max(n, 1), 40), 9.0, device="cuda")[:n] for n in sizes],
+                  [torch.full((max(n, 1),), -5, dtype=torch.int32, device="cuda")[:n] for n in sizes])
+    d1, l1 = mk()
+    synk.synk_gather_slice(dev(data), start, stop, step, d1, labels=dev(labels), dst_labels=l1)
+    ref = ogather.gather_shares(data, ix, n_workers)
+    refl = ogather.gather_shares(labels, ix, n_workers)
+    for w in range(n_workers):
+        assert np.array_equal(d1[w].cpu().numpy(), ref[w]) and np.array_equal(l1[w].cpu().numpy(), refl[w])
+    if len(ix):
+        d2, l2 = mk()
+        synk.synk_gather_rows(dev(data), dev(ix.astype(np.int32)), d2, labels=dev(labels), dst_labels=l2)
+        assert all(torch.equal(a, b) for a, b in zip(d1, d2)) and all(torch.equal(a, b) for a, b in zip(l1, l2))
+
+
+def test_gather_slice_to_bf16_and_u8_paths(synk):
+    rng = np.random.default_rng(31)
+    data = rng.random((64, 24), dtype=np.float32)
+    ix = ogather.slice_indexes(2, 60, 3)
+    sizes = share_sizes(len(ix), 4)
+    dst = [torch.zeros((n, 24), dtype=torch.bfloat16, device="cuda") for n in sizes]
+    synk.synk_gather_slice(dev(data), 2, 60, 3, dst)
+    for d, r in zip(dst, ogather.gather_shares(data, ix, 4)):
+        assert np.array_equal(d.float().cpu().numpy().view(np.uint32), ogather.round_to_bf16(r).view(np.uint32))
+    c = workloads.config4(n_data=24, batch=8, chw=(3, 8, 8), n_workers=2)
+    lut = torch.empty(3 * 256, device="cuda")
+    synk.synk_build_norm_lut(c["mean"], c["std"], lut)
+    ix = ogather.slice_indexes(1, 24, 2)
+    sizes = share_sizes(len(ix), 2)
+    dst = [torch.zeros((n, 3, 8, 8), device="cuda") for n in sizes]
+    synk.synk_gather_slice(dev(c["data"]), 1, 24, 2, dst, lut=lut, channels=3)
+    for d, r in zip(dst, ogather.gather_shares(c["data"], ix, 2)):
+        assert np.array_equal(d.cpu().numpy().view(np.uint32), ogather.normalise_u8(r, c["mean"], c["std"]).view(np.uint32))
+
+
+@pytest.mark.parametrize("n_rows,row,n_workers,dtype", [(1000, 48, 8, np.float32), (37, 7, 4, np.float32),
+                                                        (5, 16, 8, np.int32), (129, 13, 3, np.uint8)])
+def test_scatter_rows_is_the_split_of_the_first_dimension(synk, n_rows, row, n_workers, dtype):
+    rng = np.random.default_rng(n_rows)
+    data = (rng.standard_normal((n_rows, row)) * 50).astype(dtype)
+    labels = rng.integers(0, 10, n_rows).astype(np.int32)
+    sizes = share_sizes(n_rows, n_workers)
+    tdt = torch.from_numpy(np.zeros(1, dtype)).dtype
+    dst = [torch.full((max(n, 1), row), 3, dtype=tdt, device="cuda")[:n] for n in sizes]
+    dl = [torch.full((max(n, 1),), -1, dtype=torch.int32, device="cuda")[:n] for n in sizes]
+    synk.synk_scatter_rows(dev(data), dst, labels=dev(labels), dst_labels=dl)
+    for d, l, r, rl in zip(dst, dl, ogather.scatter(data, n_workers), ogather.scatter(labels, n_workers)):
+        assert np.array_equal(d.cpu().numpy(), r) and np.array_equal(l.cpu().numpy(), rl)
+    # gathering the shares back in worker order returns the array
+    if dtype == np.float32:
+        back = torch.zeros(n_rows * row, device="cuda")
+        synk.synk_reduce_buffers([d.reshape(-1) for d in dst], synk.SYNK_CONCAT, back)
+        assert np.array_equal(back.cpu().numpy().reshape(n_rows, row), data)
+
+
+def test_gather_resident_different_and_same_lists(synk):
+    rng = np.random.default_rng(88)
+    data = rng.standard_normal((103, 32)).astype(np.float32)
+    labels = rng.integers(0, 10, 103).astype(np.int32)
+    shares, lshares = ogather.scatter(data, 4), ogather.scatter(labels, 4)
+    dsh, dlsh = [dev(s) for s in shares], [dev(s) for s in lshares]
+    lists = [rng.integers(0, len(s), k).astype(np.int32) for s, k in zip(shares, (9, 0, 17, 4))]
+    dst = [torch.full((max(len(i), 1), 32), 5.0, device="cuda")[:len(i)] for i in lists]
+    dl = [torch.full((max(len(i), 1),), -2, dtype=torch.int32, device="cuda")[:len(i)] for i in lists]
+    synk.synk_gather_resident(dsh, [dev(i) for i in lists], dst, labels=dlsh, dst_labels=dl)
+    for d, l, r, rl in zip(dst, dl, ogather.gather_resident(shares, lists), ogather.gather_resident(lshares, lists)):
+        assert np.array_equal(d.cpu().numpy(), r) and np.array_equal(l.cpu().numpy(), rl)
+    # the same list on every worker, rounded to bf16 on the way
+    one = dev(np.array([2, 0, 2, 7], np.int32))
+    dst = [torch.zeros((4, 32), dtype=torch.bfloat16, device="cuda") for _ in range(4)]
+    synk.synk_gather_resident(dsh, [one] * 4, dst)
+    for d, r in zip(dst, ogather.gather_resident(shares, [np.array([2, 0, 2, 7])] * 4)):
+        assert np.array_equal(d.float().cpu().numpy().view(np.uint32), ogather.round_to_bf16(r).view(np.uint32))
+
+
+def test_gather_resident_reports_out_of_range_over_all_workers(synk):
+    shares = [dev(np.arange(12, dtype=np.float32).reshape(3, 4)), dev(np.arange(8, dtype=np.float32).reshape(2, 4))]
+    ws = torch.zeros(synk.synk_gather_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    dst = [torch.full((2, 4), -1.0, device="cuda") for _ in range(2)]
+    lists = [dev(np.array([0, 2], np.int32)), dev(np.array([1, 2], np.int32))]      # 2 is outside share 1
+    synk.synk_gather_resident(shares, lists, dst, flags=synk.SYNK_FLAG_CHECK_INDEX, ws=ws)
+    assert synk.synk_poll_error(ws) == -7
+    assert np.array_equal(dst[1].cpu().numpy()[0], [4, 5, 6, 7]) and np.all(dst[1].cpu().numpy()[1] == -1.0)
+    lists[1] = dev(np.array([1, 0], np.int32))
+    synk.synk_gather_resident(shares, lists, dst, flags=synk.SYNK_FLAG_CHECK_INDEX, ws=ws)
+    assert synk.synk_poll_error(ws) == 0
+
+
 # ------------------------------------------------------------------ reduce
 @pytest.mark.parametrize("n,length", [(1, 5), (2, 1024), (3, 1027), (8, 4099), (5, 3)])
 @pytest.mark.parametrize("op", ["sum", "mean", "max", "min", "prod"])
