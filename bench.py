@@ -45,6 +45,9 @@ def parse():
                     help="config 3 only: the update rule fused with the N-way average (Sec. 3.3)")
     ap.add_argument("--collective", default=None, choices=["all_reduce", "broadcast", "all_gather"],
                     help="config 3 shape only: time one collective over the 8 worker copies instead (Sec. 3.2)")
+    ap.add_argument("--indexing", default="list", choices=["list", "slice", "resident"],
+                    help="config 4 only: index list (default), slice-form indexes, or per-worker lists over "
+                         "shares resident on the workers (Sec. 5.2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -271,11 +274,11 @@ class CollectiveStep:
 class GatherStep:
     """Config 4: uint8 image gather + per-channel normalise to fp32, 8 worker shares."""
 
-    def __init__(self, torch, synk):
+    def __init__(self, torch, synk, indexing="list"):
         import numpy as np
         import workloads
         from oracle import split as osplit
-        self.torch, self.s, self.np = torch, synk, np
+        self.torch, self.s, self.np, self.indexing = torch, synk, np, indexing
         small = workloads.config4(n_data=8, batch=8)             # mean/std recipe
         self.mean, self.std = small["mean"], small["std"]
         self.n_data, self.B, self.N, self.chw = 50000, 256, 8, (3, 224, 224)
@@ -302,8 +305,28 @@ class GatherStep:
         self.dom_name = "gather_u8_lut_kernel"
         self.dom_bytes = self.B * (row + 4 * row + 8)
 
-        self.calls = [synk.prepare(synk.synk_gather_rows, self.data, ix, self.dst, lut=self.lut, channels=3,
-                                   labels=self.labels, dst_labels=self.dl) for ix in self.idx]
+        if indexing == "list":
+            self.calls = [synk.prepare(synk.synk_gather_rows, self.data, ix, self.dst, lut=self.lut, channels=3,
+                                       labels=self.labels, dst_labels=self.dl) for ix in self.idx]
+        elif indexing == "slice":
+            # 256 rows start, start+190, ...: a different start every step
+            self.workload = ("config 4 shape with slice-form indexes: rows start::190 (256 of 50000 uint8 3x224x224 "
+                             "images), normalise to fp32, 8 worker shares of 32, with labels")
+            self.calls = [synk.prepare(synk.synk_gather_slice, self.data, s0, s0 + 256 * 190, 190, self.dst,
+                                       lut=self.lut, channels=3, labels=self.labels, dst_labels=self.dl)
+                          for s0 in [(k * 37) % 1000 for k in range(64)]]
+        else:
+            # the dataset scattered by first dimension into 8 resident shares of 6250 images (views of one
+            # allocation); every worker excerpts 32 rows of its own share with its own list
+            self.workload = ("config 4 shape with resident shares: 8 workers x 32 own indexes into their 6250-image "
+                             "uint8 share, normalise to fp32, with labels")
+            bounds = osplit.share_bounds(self.n_data, self.N)
+            shares = [self.data[a:b] for a, b in bounds]
+            lshares = [self.labels[a:b] for a, b in bounds]
+            self.lists = [[torch.from_numpy(rng.integers(0, b - a, n).astype(np.int32)).cuda()
+                           for (a, b), n in zip(bounds, rows)] for _ in range(64)]
+            self.calls = [synk.prepare(synk.synk_gather_resident, shares, ls, self.dst, lut=self.lut, channels=3,
+                                       labels=lshares, dst_labels=self.dl) for ls in self.lists]
 
     def step(self, i, timer):
         timer.bracket(self.calls[i % 64])
@@ -397,7 +420,7 @@ def main():
     torch.cuda.set_device(0)
 
     wl = {0: lambda: CopyStep(torch, synk), 1: lambda: MlpStep(torch, synk, 1), 2: lambda: MlpStep(torch, synk, 2),
-          3: lambda: (CollectiveStep(torch, synk, a.collective) if a.collective else ReduceStep(torch, synk, a.rule)), 4: lambda: GatherStep(torch, synk),
+          3: lambda: (CollectiveStep(torch, synk, a.collective) if a.collective else ReduceStep(torch, synk, a.rule)), 4: lambda: GatherStep(torch, synk, a.indexing),
           5: lambda: EvalStep(torch, synk)}[a.config]()
     steps = a.steps if a.steps is not None else {0: 50, 1: 2000, 2: 1000, 3: 300, 4: 1000, 5: 1000}[a.config]
     warmup = a.warmup if a.warmup is not None else 20
@@ -425,7 +448,7 @@ def main():
         "config": {"workload": wl.workload, "units_per_step": wl.units},
         "roofline": {"bound": "hbm", "kernel": wl.dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (a.rule == "momentum" and not a.collective) else None, "traffic_unit": "HBM bytes per launch",
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (a.rule == "momentum" and not a.collective and a.indexing == "list") else None, "traffic_unit": "HBM bytes per launch",
                      "bytes_per_launch": wl.dom_bytes, "ms_per_launch": dom_ms},
     }
     if not a.no_cpu_baseline:

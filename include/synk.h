@@ -169,7 +169,8 @@ int synk_scatter_rows(const void* data, int64_t n_rows, int64_t row_elems, int d
  * same idx pointer n times to apply one list everywhere).  A worker with
  * n_idx[w] == 0 is skipped and may have NULL pointers.  dtype pairs, lut,
  * flags/ws and out-of-range handling as in synk_gather_rows; the error word
- * collects over all workers.  One launch per worker with a non-empty list. */
+ * collects over all workers.  One launch for all workers; a share holds
+ * fewer than 2^31 rows. */
 int synk_gather_resident(const void* const* shares, const int64_t* share_rows, int64_t row_elems,
                          int src_dtype, const int32_t* const* idx, const int64_t* n_idx,
                          void* const* dst, int n_workers, int dst_dtype,

@@ -18,6 +18,8 @@ struct RowRef {
   int64_t src_row;   // idx[j], or -1 when out of range
   int worker;
   int64_t local;     // row inside the worker's buffer
+  const void* base;  // the array the row is read from
+  const int32_t* labels;
 };
 
 // Where batch row j comes from: a list entry, or start + j * step (slice form).
@@ -26,34 +28,66 @@ struct IdxSrc {
   int64_t start, step;
 };
 
-__device__ __forceinline__ RowRef locate(const IdxSrc& ix, int64_t n_idx, int n_workers,
+// Resident shares: worker w indexes its own array with its own list; batch
+// row j belongs to the worker whose run [off[w], off[w+1]) of the concatenated
+// lists holds it.
+struct ResTable {
+  const void* data[SYNK_MAX_WORKERS];
+  const int32_t* idx[SYNK_MAX_WORKERS];
+  const int32_t* lab[SYNK_MAX_WORKERS];
+  int32_t n_rows[SYNK_MAX_WORKERS];
+  int32_t off[SYNK_MAX_WORKERS + 1];
+};
+template <bool RES>
+struct ResArg {};
+template <>
+struct ResArg<true> {
+  ResTable t;
+};
+
+template <bool RES>
+__device__ __forceinline__ RowRef locate(const IdxSrc& ix, const ResArg<RES>& ra, const void* data,
+                                         const int32_t* labels, int64_t n_idx, int n_workers,
                                          int64_t n_rows, int64_t j, uint32_t* err_word) {
   RowRef r;
-  const int64_t src = ix.idx ? (int64_t)ix.idx[j] : ix.start + j * ix.step;
-  int64_t start;
-  share_of(n_idx, n_workers, j, &r.worker, &start);
-  r.local = j - start;
+  int64_t src;
+  if constexpr (RES) {
+    int w = 0;
+    while (w + 1 < n_workers && j >= ra.t.off[w + 1]) ++w;   // block-uniform, at most 63 steps
+    r.worker = w;
+    r.local = j - ra.t.off[w];
+    src = ra.t.idx[w][r.local];
+    r.base = ra.t.data[w];
+    r.labels = ra.t.lab[w];
+    n_rows = ra.t.n_rows[w];
+  } else {
+    src = ix.idx ? (int64_t)ix.idx[j] : ix.start + j * ix.step;
+    int64_t start;
+    share_of(n_idx, n_workers, j, &r.worker, &start);
+    r.local = j - start;
+    r.base = data;
+    r.labels = labels;
+  }
   r.src_row = (src >= 0 && src < n_rows) ? src : -1;
   if (r.src_row < 0 && err_word && threadIdx.x == 0 && blockIdx.y == 0) atomicOr(err_word, 1u);
   return r;
 }
 
-__device__ __forceinline__ void copy_label(const DstTable& t, const int32_t* __restrict__ labels,
-                                           const RowRef& r) {
-  if (labels && blockIdx.y == 0 && threadIdx.x == 0) t.lab[r.worker][r.local] = labels[r.src_row];
+__device__ __forceinline__ void copy_label(const DstTable& t, const RowRef& r) {
+  if (r.labels && blockIdx.y == 0 && threadIdx.x == 0) t.lab[r.worker][r.local] = r.labels[r.src_row];
 }
 
 // Bit-exact copy in units of V (16, 4 or 1 bytes).  grid = (n_idx, chunks).
-template <typename V>
+template <bool RES, typename V>
 __global__ __launch_bounds__(kGBlock) void gather_copy_kernel(
-    const V* __restrict__ data, int64_t n_rows, int64_t row_units, IdxSrc idx,
+    const V* __restrict__ data, int64_t n_rows, int64_t row_units, IdxSrc idx, ResArg<RES> ra,
     int64_t n_idx, DstTable t, int n_workers, const int32_t* __restrict__ labels,
     uint32_t* err_word, int units_per_block) {
   const int64_t j = blockIdx.x;
-  const RowRef r = locate(idx, n_idx, n_workers, n_rows, j, err_word);
+  const RowRef r = locate<RES>(idx, ra, data, labels, n_idx, n_workers, n_rows, j, err_word);
   if (r.src_row < 0) return;
-  copy_label(t, labels, r);
-  const V* src = data + r.src_row * row_units;
+  copy_label(t, r);
+  const V* src = reinterpret_cast<const V*>(r.base) + r.src_row * row_units;
   V* dst = reinterpret_cast<V*>(t.dst[r.worker]) + r.local * row_units;
   const int64_t u0 = (int64_t)blockIdx.y * units_per_block;
   int64_t u1 = u0 + units_per_block;
@@ -62,16 +96,16 @@ __global__ __launch_bounds__(kGBlock) void gather_copy_kernel(
 }
 
 // float32 -> bfloat16 (nearest-even).  VEC: 4 floats in, 8 bytes out per lane.
-template <bool VEC>
+template <bool RES, bool VEC>
 __global__ __launch_bounds__(kGBlock) void gather_bf16_kernel(
     const float* __restrict__ data, int64_t n_rows, int64_t row_elems,
-    IdxSrc idx, int64_t n_idx, DstTable t, int n_workers,
+    IdxSrc idx, ResArg<RES> ra, int64_t n_idx, DstTable t, int n_workers,
     const int32_t* __restrict__ labels, uint32_t* err_word, int units_per_block) {
   const int64_t j = blockIdx.x;
-  const RowRef r = locate(idx, n_idx, n_workers, n_rows, j, err_word);
+  const RowRef r = locate<RES>(idx, ra, data, labels, n_idx, n_workers, n_rows, j, err_word);
   if (r.src_row < 0) return;
-  copy_label(t, labels, r);
-  const float* src = data + r.src_row * row_elems;
+  copy_label(t, r);
+  const float* src = reinterpret_cast<const float*>(r.base) + r.src_row * row_elems;
   uint16_t* dst = reinterpret_cast<uint16_t*>(t.dst[r.worker]) + r.local * row_elems;
   const int64_t units = VEC ? (row_elems >> 2) : row_elems;
   const int64_t u0 = (int64_t)blockIdx.y * units_per_block;
@@ -96,20 +130,20 @@ __global__ __launch_bounds__(kGBlock) void gather_bf16_kernel(
 // tracked incrementally (units only move forwards), never divided out.
 constexpr int kLBlock = 1024;
 
-template <bool VEC>
+template <bool RES, bool VEC>
 __global__ __launch_bounds__(kLBlock) void gather_u8_lut_kernel(
     const uint8_t* __restrict__ data, int64_t n_rows, int row_elems, int plane,
-    IdxSrc idx, int64_t n_idx, DstTable t, int n_workers,
+    IdxSrc idx, ResArg<RES> ra, int64_t n_idx, DstTable t, int n_workers,
     const float* __restrict__ lut, int channels, const int32_t* __restrict__ labels,
     uint32_t* err_word, int units_per_block) {
   __shared__ float s_lut[SYNK_MAX_CHANNELS * 256];
   const int64_t j = blockIdx.x;
-  const RowRef r = locate(idx, n_idx, n_workers, n_rows, j, err_word);
+  const RowRef r = locate<RES>(idx, ra, data, labels, n_idx, n_workers, n_rows, j, err_word);
   if (r.src_row < 0) return;   // uniform per block: before the barrier is fine
   for (int i = threadIdx.x; i < channels * 256; i += kLBlock) s_lut[i] = lut[i];
   __syncthreads();
-  copy_label(t, labels, r);
-  const uint8_t* src = data + r.src_row * (int64_t)row_elems;
+  copy_label(t, r);
+  const uint8_t* src = reinterpret_cast<const uint8_t*>(r.base) + r.src_row * (int64_t)row_elems;
   float* dst = reinterpret_cast<float*>(t.dst[r.worker]) + r.local * (int64_t)row_elems;
   const int units = VEC ? (row_elems >> 2) : row_elems;
   const int plane_u = VEC ? (plane >> 2) : plane;     // units per channel plane
@@ -190,14 +224,17 @@ using namespace synk;
 
 extern "C" size_t synk_gather_workspace_bytes(void) { return 256; }
 
-// The gather behind every entry point.  clear_err: reset the error word first
-// (a call made of several launches resets it once).
+// The gather behind every entry point.  res != NULL: resident shares (worker
+// w reads res->data[w] with res->idx[w]; counts[w] rows each, n_idx their sum;
+// data, n_rows, idx and labels are then unused).
 static int gather_impl(const void* data, int64_t n_rows, int64_t row_elems, int src_dtype,
                        IdxSrc idx, int64_t n_idx, void* const* dst, int n_workers,
                        int dst_dtype, const float* lut, int channels,
                        const int32_t* labels, int32_t* const* dst_labels, uint32_t flags,
-                       void* ws, size_t ws_bytes, void* stream, bool clear_err, bool check_only = false) {
-  if (!data || !dst) return SYNK_ERR_NULL;
+                       void* ws, size_t ws_bytes, void* stream, const ResTable* res = nullptr,
+                       const int64_t* counts = nullptr) {
+  if ((!res && !data) || !dst) return SYNK_ERR_NULL;
+  const bool want_labels = res ? (dst_labels != nullptr) : (labels != nullptr);
   if (labels && !dst_labels) return SYNK_ERR_NULL;
   if (n_rows < 0 || row_elems <= 0 || n_idx < 0) return SYNK_ERR_SHAPE;
   if (n_workers < 1 || n_workers > SYNK_MAX_WORKERS) return SYNK_ERR_SHAPE;
@@ -217,7 +254,14 @@ static int gather_impl(const void* data, int64_t n_rows, int64_t row_elems, int 
   }
   static const int kElemBytes[4] = {1, 4, 4, 2};
   const int src_b = kElemBytes[src_dtype], dst_b = kElemBytes[dst_dtype];
-  if (!aligned_to(data, src_b)) return SYNK_ERR_ALIGN;
+  // alignment that every array rows are read from has
+  auto src_aligned = [&](size_t a) {
+    if (!res) return aligned_to(data, a);
+    for (int w = 0; w < n_workers; ++w)
+      if (counts[w] > 0 && !aligned_to(res->data[w], a)) return false;
+    return true;
+  };
+  if (!src_aligned(src_b)) return SYNK_ERR_ALIGN;
   uint32_t* err_word = nullptr;
   if (flags & SYNK_FLAG_CHECK_INDEX) {
     if (!ws || ws_bytes < synk_gather_workspace_bytes() || !aligned_to(ws, 256))
@@ -225,83 +269,88 @@ static int gather_impl(const void* data, int64_t n_rows, int64_t row_elems, int 
     err_word = reinterpret_cast<uint32_t*>(ws);
   }
   DstTable t;
-  bool dst16 = true;
+  bool dst16 = true, dst8 = true, dst4 = true;
   for (int w = 0; w < n_workers; ++w) {
     int64_t s, n;
     share(n_idx, n_workers, w, &s, &n);
-    if (n > 0 && (!dst[w] || (labels && !dst_labels[w]))) return SYNK_ERR_NULL;
+    if (counts) n = counts[w];
+    if (n > 0 && (!dst[w] || (want_labels && !dst_labels[w]))) return SYNK_ERR_NULL;
     if (n > 0 && !aligned_to(dst[w], dst_b)) return SYNK_ERR_ALIGN;
-    if (n > 0) dst16 = dst16 && aligned_to(dst[w], 16);
+    if (n > 0) {
+      dst16 = dst16 && aligned_to(dst[w], 16);
+      dst8 = dst8 && aligned_to(dst[w], 8);
+      dst4 = dst4 && aligned_to(dst[w], 4);
+    }
     t.dst[w] = dst[w];
-    t.lab[w] = labels ? dst_labels[w] : nullptr;
+    t.lab[w] = want_labels ? dst_labels[w] : nullptr;
   }
-  if (check_only) return SYNK_OK;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  if (err_word && clear_err) {
+  if (err_word) {
     hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, s, err_word);
     SYNK_LAUNCH_CHECK();
   }
   if (n_idx == 0) return SYNK_OK;
 
+
   int upb, chunks;
+  const dim3 gb(kGBlock), lb(kLBlock);
   if (mode == COPY) {
     const int64_t row_bytes = row_elems * src_b;
-    if (row_bytes % 16 == 0 && aligned_to(data, 16) && dst16) {
-      if (int rc = chunking(row_bytes / 16, &upb, &chunks)) return rc;
-      hipLaunchKernelGGL((gather_copy_kernel<u32x4>), dim3((unsigned)n_idx, chunks), dim3(kGBlock), 0,
-                         s, reinterpret_cast<const u32x4*>(data), n_rows, row_bytes / 16, idx, n_idx,
-                         t, n_workers, labels, err_word, upb);
-    } else if (row_bytes % 4 == 0 && aligned_to(data, 4)) {
-      // every dst is at least element aligned; 4-byte rows keep dwords aligned
-      bool dst4 = true;
-      for (int w = 0; w < n_workers; ++w) dst4 = dst4 && aligned_to(t.dst[w], 4);
-      if (dst4) {
-        if (int rc = chunking(row_bytes / 4, &upb, &chunks)) return rc;
-        hipLaunchKernelGGL((gather_copy_kernel<uint32_t>), dim3((unsigned)n_idx, chunks),
-                           dim3(kGBlock), 0, s, reinterpret_cast<const uint32_t*>(data), n_rows,
-                           row_bytes / 4, idx, n_idx, t, n_workers, labels, err_word, upb);
-      } else {
-        if (int rc = chunking(row_bytes, &upb, &chunks)) return rc;
-        hipLaunchKernelGGL((gather_copy_kernel<uint8_t>), dim3((unsigned)n_idx, chunks),
-                           dim3(kGBlock), 0, s, reinterpret_cast<const uint8_t*>(data), n_rows,
-                           row_bytes, idx, n_idx, t, n_workers, labels, err_word, upb);
-      }
+    int unit = 1;
+    if (row_bytes % 16 == 0 && src_aligned(16) && dst16) unit = 16;
+    else if (row_bytes % 4 == 0 && src_aligned(4) && dst4) unit = 4;
+    const int64_t row_units = row_bytes / unit;
+    if (int rc = chunking(row_units, &upb, &chunks)) return rc;
+    const dim3 grid((unsigned)n_idx, chunks);
+#define SYNK_COPY(V, RES, RA)                                                                        \
+  hipLaunchKernelGGL((gather_copy_kernel<RES, V>), grid, gb, 0, s, reinterpret_cast<const V*>(data), \
+                     n_rows, row_units, idx, RA, n_idx, t, n_workers, labels, err_word, upb)
+    if (res) {
+      if (unit == 16) SYNK_COPY(u32x4, true, ResArg<true>{*res});
+      else if (unit == 4) SYNK_COPY(uint32_t, true, ResArg<true>{*res});
+      else SYNK_COPY(uint8_t, true, ResArg<true>{*res});
     } else {
-      if (int rc = chunking(row_bytes, &upb, &chunks)) return rc;
-      hipLaunchKernelGGL((gather_copy_kernel<uint8_t>), dim3((unsigned)n_idx, chunks), dim3(kGBlock),
-                         0, s, reinterpret_cast<const uint8_t*>(data), n_rows, row_bytes, idx, n_idx,
-                         t, n_workers, labels, err_word, upb);
+      if (unit == 16) SYNK_COPY(u32x4, false, ResArg<false>{});
+      else if (unit == 4) SYNK_COPY(uint32_t, false, ResArg<false>{});
+      else SYNK_COPY(uint8_t, false, ResArg<false>{});
     }
+#undef SYNK_COPY
   } else if (mode == TO_BF16) {
-    bool dst8 = true;
-    for (int w = 0; w < n_workers; ++w) dst8 = dst8 && aligned_to(t.dst[w], 8);
-    if (row_elems % 4 == 0 && aligned_to(data, 16) && dst8) {
-      if (int rc = chunking(row_elems / 4, &upb, &chunks)) return rc;
-      hipLaunchKernelGGL((gather_bf16_kernel<true>), dim3((unsigned)n_idx, chunks), dim3(kGBlock), 0,
-                         s, reinterpret_cast<const float*>(data), n_rows, row_elems, idx, n_idx, t,
-                         n_workers, labels, err_word, upb);
+    const bool vec = row_elems % 4 == 0 && src_aligned(16) && dst8;
+    if (int rc = chunking(vec ? row_elems / 4 : row_elems, &upb, &chunks)) return rc;
+    const dim3 grid((unsigned)n_idx, chunks);
+#define SYNK_BF(VEC, RES, RA)                                                                            \
+  hipLaunchKernelGGL((gather_bf16_kernel<RES, VEC>), grid, gb, 0, s, reinterpret_cast<const float*>(data), \
+                     n_rows, row_elems, idx, RA, n_idx, t, n_workers, labels, err_word, upb)
+    if (res) {
+      if (vec) SYNK_BF(true, true, ResArg<true>{*res});
+      else SYNK_BF(false, true, ResArg<true>{*res});
     } else {
-      if (int rc = chunking(row_elems, &upb, &chunks)) return rc;
-      hipLaunchKernelGGL((gather_bf16_kernel<false>), dim3((unsigned)n_idx, chunks), dim3(kGBlock), 0,
-                         s, reinterpret_cast<const float*>(data), n_rows, row_elems, idx, n_idx, t,
-                         n_workers, labels, err_word, upb);
+      if (vec) SYNK_BF(true, false, ResArg<false>{});
+      else SYNK_BF(false, false, ResArg<false>{});
     }
+#undef SYNK_BF
   } else {
     const int plane = (int)(row_elems / channels);
-    const bool vec = plane % 4 == 0 && aligned_to(data, 4) && dst16;
+    const bool vec = plane % 4 == 0 && src_aligned(4) && dst16;
     const int64_t units = vec ? row_elems / 4 : row_elems;
     upb = kLBlock * 4;                                   // 4 units per thread: one unrolled batch
     const int64_t nch = (units + upb - 1) / upb;
     if (nch > 65535) return SYNK_ERR_UNSUPPORTED;
     chunks = (int)nch;
-    if (vec)
-      hipLaunchKernelGGL((gather_u8_lut_kernel<true>), dim3((unsigned)n_idx, chunks), dim3(kLBlock),
-                         0, s, reinterpret_cast<const uint8_t*>(data), n_rows, (int)row_elems, plane,
-                         idx, n_idx, t, n_workers, lut, channels, labels, err_word, upb);
-    else
-      hipLaunchKernelGGL((gather_u8_lut_kernel<false>), dim3((unsigned)n_idx, chunks), dim3(kLBlock),
-                         0, s, reinterpret_cast<const uint8_t*>(data), n_rows, (int)row_elems, plane,
-                         idx, n_idx, t, n_workers, lut, channels, labels, err_word, upb);
+    const dim3 grid((unsigned)n_idx, chunks);
+#define SYNK_LUT(VEC, RES, RA)                                                                   \
+  hipLaunchKernelGGL((gather_u8_lut_kernel<RES, VEC>), grid, lb, 0, s,                           \
+                     reinterpret_cast<const uint8_t*>(data), n_rows, (int)row_elems, plane, idx, \
+                     RA, n_idx, t, n_workers, lut, channels, labels, err_word, upb)
+    if (res) {
+      if (vec) SYNK_LUT(true, true, ResArg<true>{*res});
+      else SYNK_LUT(false, true, ResArg<true>{*res});
+    } else {
+      if (vec) SYNK_LUT(true, false, ResArg<false>{});
+      else SYNK_LUT(false, false, ResArg<false>{});
+    }
+#undef SYNK_LUT
   }
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;
@@ -314,7 +363,7 @@ extern "C" int synk_gather_rows(const void* data, int64_t n_rows, int64_t row_el
                                 void* ws, size_t ws_bytes, void* stream) {
   if (!idx && n_idx > 0) return SYNK_ERR_NULL;
   return gather_impl(data, n_rows, row_elems, src_dtype, IdxSrc{idx, 0, 0}, n_idx, dst, n_workers, dst_dtype,
-                     lut, channels, labels, dst_labels, flags, ws, ws_bytes, stream, true);
+                     lut, channels, labels, dst_labels, flags, ws, ws_bytes, stream);
 }
 
 extern "C" int synk_gather_slice(const void* data, int64_t n_rows, int64_t row_elems, int src_dtype,
@@ -326,7 +375,7 @@ extern "C" int synk_gather_slice(const void* data, int64_t n_rows, int64_t row_e
   if (start < 0 || stop < start || stop > n_rows) return SYNK_ERR_INDEX;
   const int64_t n_idx = (stop - start + step - 1) / step;
   return gather_impl(data, n_rows, row_elems, src_dtype, IdxSrc{nullptr, start, step}, n_idx, dst, n_workers,
-                     dst_dtype, lut, channels, labels, dst_labels, 0u, nullptr, 0, stream, false);
+                     dst_dtype, lut, channels, labels, dst_labels, 0u, nullptr, 0, stream);
 }
 
 extern "C" int synk_scatter_rows(const void* data, int64_t n_rows, int64_t row_elems, int dtype,
@@ -345,40 +394,24 @@ extern "C" int synk_gather_resident(const void* const* shares, const int64_t* sh
   if (!shares || !share_rows || !idx || !n_idx || !dst) return SYNK_ERR_NULL;
   if (labels && !dst_labels) return SYNK_ERR_NULL;
   if (n_workers < 1 || n_workers > SYNK_MAX_WORKERS) return SYNK_ERR_SHAPE;
-  // every argument is checked before the first launch
+  ResTable rt;
+  int64_t total = 0;
   for (int w = 0; w < n_workers; ++w) {
-    if (n_idx[w] < 0 || share_rows[w] < 0) return SYNK_ERR_SHAPE;
-    if (n_idx[w] > 0 && (!shares[w] || !idx[w] || !dst[w])) return SYNK_ERR_NULL;
-    if (n_idx[w] > 0 && labels && (!labels[w] || !dst_labels[w])) return SYNK_ERR_NULL;
+    if (n_idx[w] < 0 || share_rows[w] < 0 || share_rows[w] > 0x7fffffffLL) return SYNK_ERR_SHAPE;
+    if (n_idx[w] > 0 && (!shares[w] || !idx[w])) return SYNK_ERR_NULL;
+    if (n_idx[w] > 0 && labels && !labels[w]) return SYNK_ERR_NULL;
+    rt.data[w] = shares[w];
+    rt.idx[w] = idx[w];
+    rt.lab[w] = labels ? labels[w] : nullptr;
+    rt.n_rows[w] = (int32_t)share_rows[w];
+    rt.off[w] = (int32_t)total;
+    total += n_idx[w];
+    if (total > 0x7fffffffLL) return SYNK_ERR_SHAPE;
   }
-  if ((flags & SYNK_FLAG_CHECK_INDEX) &&
-      (!ws || ws_bytes < synk_gather_workspace_bytes() || !aligned_to(ws, 256)))
-    return SYNK_ERR_WORKSPACE;
-  for (int w = 0; w < n_workers; ++w) {          // every worker's arguments, before the first launch
-    if (n_idx[w] == 0) continue;
-    void* const d1[1] = {dst[w]};
-    int32_t* const l1[1] = {labels ? dst_labels[w] : nullptr};
-    if (int rc = gather_impl(shares[w], share_rows[w], row_elems, src_dtype, IdxSrc{idx[w], 0, 0}, n_idx[w], d1,
-                             1, dst_dtype, lut, channels, labels ? labels[w] : nullptr, l1, flags, ws,
-                             ws_bytes, stream, false, true))
-      return rc;
-  }
-  if (flags & SYNK_FLAG_CHECK_INDEX) {
-    hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, reinterpret_cast<hipStream_t>(stream),
-                       reinterpret_cast<uint32_t*>(ws));
-    SYNK_LAUNCH_CHECK();
-  }
-  // one worker at a time: its share, its list, its buffer (the error word collects over all of them)
-  for (int w = 0; w < n_workers; ++w) {
-    if (n_idx[w] == 0) continue;
-    void* const d1[1] = {dst[w]};
-    int32_t* const l1[1] = {labels ? dst_labels[w] : nullptr};
-    if (int rc = gather_impl(shares[w], share_rows[w], row_elems, src_dtype, IdxSrc{idx[w], 0, 0}, n_idx[w], d1,
-                             1, dst_dtype, lut, channels, labels ? labels[w] : nullptr, l1, flags, ws,
-                             ws_bytes, stream, false))
-      return rc;
-  }
-  return SYNK_OK;
+  for (int w = n_workers; w <= SYNK_MAX_WORKERS; ++w) rt.off[w] = (int32_t)total;
+  return gather_impl(nullptr, 0, row_elems, src_dtype, IdxSrc{nullptr, 0, 0}, total, dst, n_workers, dst_dtype,
+                     lut, channels, nullptr, labels ? dst_labels : nullptr, flags, ws, ws_bytes, stream, &rt,
+                     n_idx);
 }
 
 extern "C" int synk_build_norm_lut(const float* mean, const float* std, int channels, float* lut,
