@@ -96,6 +96,16 @@ extern "C" {
 int synk_version(void);
 const char* synk_status_string(int status);
 
+/* For callers that time one kernel: the next launch, on this host thread, of
+ * a call's main kernel (the fused reduce+update kernels, the reduce and
+ * collective kernels, the uint8 gather, stage 1 of synk_sliced_eval) carries
+ * the two events (hipEvent_t created with timing enabled, passed as void*):
+ * start_event takes the dispatch's begin timestamp and stop_event its end
+ * timestamp, so hipEventElapsedTime between them is the kernel's duration
+ * without the gaps around it.  Other kernels leave the pair pending.  Both
+ * NULL cancels a pending pair; exactly one NULL -> ERR_NULL. */
+int synk_profile_next_launch(void* start_event, void* stop_event);
+
 /* Host-side helper: the split rule above.  Writes parts+1 offsets
  * (start[0] = 0, start[parts] = count) into `start` (host). */
 int synk_split(int64_t count, int parts, int64_t* start);

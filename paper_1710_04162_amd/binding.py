@@ -21,7 +21,7 @@ __all__ = [
     "synk_sliced_eval_workspace_bytes", "synk_sliced_eval", "synk_reduce_buffers",
     "synk_sgd_update", "synk_reduce_sgd_update", "synk_reduce_update",
     "synk_broadcast", "synk_all_reduce", "synk_all_gather",
-    "synk_gather_slice", "synk_scatter_rows", "synk_gather_resident",
+    "synk_gather_slice", "synk_scatter_rows", "synk_gather_resident", "synk_profile_next_launch",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsynk.so")
@@ -74,6 +74,8 @@ lib.synk_gather_resident.argtypes = [_pp, _pi64, _i64, _int, _pp, _pi64, _pp, _i
                                      ctypes.c_uint32, _vp, _sz, _vp]
 for _n in ("synk_gather_slice", "synk_scatter_rows", "synk_gather_resident"):
     getattr(lib, _n).restype = _int
+lib.synk_profile_next_launch.argtypes = [_vp, _vp]
+lib.synk_profile_next_launch.restype = _int
 lib.synk_build_norm_lut.argtypes = [_pf32, _pf32, _int, _vp, _vp]
 lib.synk_poll_error.argtypes = [_vp, _vp]
 lib.synk_mlp_param_count.argtypes = [ctypes.POINTER(MlpDesc), _pi64]
@@ -374,3 +376,11 @@ def synk_gather_resident(shares, idx, dst, lut=None, channels=0, labels=None, ds
     return _run(lib.synk_gather_resident, args,
                 (shares, idx, dst, lut, labels, dst_labels, ws, rows, nidx, t_sh, t_ix, t_dst, t_lab, t_dl),
                 "synk_gather_resident", _prepare)
+
+
+def synk_profile_next_launch(start, stop):
+    """start, stop: torch.cuda.Event(enable_timing=True) that have been recorded once (torch creates
+    the underlying hipEvent_t at the first record), or None, None to cancel."""
+    a = start.cuda_event if start is not None else None
+    b = stop.cuda_event if stop is not None else None
+    _check(lib.synk_profile_next_launch(a, b), "synk_profile_next_launch")

@@ -160,7 +160,7 @@ __global__ __launch_bounds__(kCBlock) void all_gather_kernel(GatherTable t, int 
 template <typename T, int OP, bool VEC>
 static int launch_all_reduce_n(const PtrTable& t, int n, int64_t len, hipStream_t s) {
   const dim3 grid(coll_grid(VEC ? (len >> 2) + 1 : len)), block(kCBlock);
-#define SYNK_AR(NS) hipLaunchKernelGGL((all_reduce_kernel<T, OP, NS, VEC>), grid, block, 0, s, t, n, len)
+#define SYNK_AR(NS) SYNK_LAUNCH_TIMED((all_reduce_kernel<T, OP, NS, VEC>), grid, block, 0, s, t, n, len)
   switch (n) {
     case 2: SYNK_AR(2); break;
     case 4: SYNK_AR(4); break;
@@ -211,9 +211,9 @@ extern "C" int synk_broadcast(const void* src, void* const* dsts, int n, int64_t
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   const uint32_t* sp = reinterpret_cast<const uint32_t*>(src);
   if (vec)
-    hipLaunchKernelGGL((broadcast_kernel<true>), dim3(coll_grid((len >> 2) + 1)), dim3(kCBlock), 0, s, sp, t, n, len);
+    SYNK_LAUNCH_TIMED((broadcast_kernel<true>), dim3(coll_grid((len >> 2) + 1)), dim3(kCBlock), 0, s, sp, t, n, len);
   else
-    hipLaunchKernelGGL((broadcast_kernel<false>), dim3(coll_grid(len)), dim3(kCBlock), 0, s, sp, t, n, len);
+    SYNK_LAUNCH_TIMED((broadcast_kernel<false>), dim3(coll_grid(len)), dim3(kCBlock), 0, s, sp, t, n, len);
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;
 }
@@ -271,8 +271,8 @@ extern "C" int synk_all_gather(const void* const* srcs, const int64_t* lens, int
   int gx = coll_grid(vec ? (longest >> 2) + 1 : longest);
   if (gx > 1024) gx = 1024;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  if (vec) hipLaunchKernelGGL((all_gather_kernel<true>), dim3(gx, n), dim3(kCBlock), 0, s, t, n);
-  else hipLaunchKernelGGL((all_gather_kernel<false>), dim3(gx, n), dim3(kCBlock), 0, s, t, n);
+  if (vec) SYNK_LAUNCH_TIMED((all_gather_kernel<true>), dim3(gx, n), dim3(kCBlock), 0, s, t, n);
+  else SYNK_LAUNCH_TIMED((all_gather_kernel<false>), dim3(gx, n), dim3(kCBlock), 0, s, t, n);
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;
 }

@@ -1,6 +1,7 @@
 // Internal helpers shared by the kernels of libsynk (not part of the C ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/synk.h"
@@ -14,6 +15,26 @@
 #define SYNK_LAUNCH_CHECK()                                   \
   do {                                                        \
     if (hipGetLastError() != hipSuccess) return SYNK_ERR_HIP; \
+  } while (0)
+
+namespace synk {
+
+// Events handed in by synk_profile_next_launch (consumed by the first launch
+// made through SYNK_LAUNCH_TIMED on this host thread).
+bool take_profile_events(hipEvent_t* start, hipEvent_t* stop);
+
+}  // namespace synk
+
+// Launch of a kernel that a caller may want timed on its own: with events
+// pending, they are attached to this very dispatch (start/stop timestamps of
+// the kernel, not of the gaps around it).
+#define SYNK_LAUNCH_TIMED(KERNEL, GRID, BLOCK, SHMEM, STREAM, ...)                                   \
+  do {                                                                                               \
+    hipEvent_t e0_, e1_;                                                                             \
+    if (synk::take_profile_events(&e0_, &e1_))                                                       \
+      hipExtLaunchKernelGGL(KERNEL, GRID, BLOCK, SHMEM, STREAM, e0_, e1_, 0, __VA_ARGS__);           \
+    else                                                                                             \
+      hipLaunchKernelGGL(KERNEL, GRID, BLOCK, SHMEM, STREAM, __VA_ARGS__);                           \
   } while (0)
 
 namespace synk {

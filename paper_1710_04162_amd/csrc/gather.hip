@@ -340,7 +340,7 @@ static int gather_impl(const void* data, int64_t n_rows, int64_t row_elems, int 
     chunks = (int)nch;
     const dim3 grid((unsigned)n_idx, chunks);
 #define SYNK_LUT(VEC, RES, RA)                                                                   \
-  hipLaunchKernelGGL((gather_u8_lut_kernel<RES, VEC>), grid, lb, 0, s,                           \
+  SYNK_LAUNCH_TIMED((gather_u8_lut_kernel<RES, VEC>), grid, lb, 0, s,                            \
                      reinterpret_cast<const uint8_t*>(data), n_rows, (int)row_elems, plane, idx, \
                      RA, n_idx, t, n_workers, lut, channels, labels, err_word, upb)
     if (res) {

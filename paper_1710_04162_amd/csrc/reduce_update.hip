@@ -319,10 +319,10 @@ template <typename T, int OP>
 static int launch_reduce(const BufTable& t, int n, int64_t len, void* out, bool vec,
                          hipStream_t s) {
   if (vec)
-    hipLaunchKernelGGL((reduce_kernel<T, OP>), dim3(stream_grid(len >> 2)), dim3(kBlock), 0, s, t, n,
+    SYNK_LAUNCH_TIMED((reduce_kernel<T, OP>), dim3(stream_grid(len >> 2)), dim3(kBlock), 0, s, t, n,
                        len, reinterpret_cast<T*>(out));
   else
-    hipLaunchKernelGGL((reduce_kernel_scalar<T, OP>), dim3(stream_grid(len)), dim3(kBlock), 0, s, t,
+    SYNK_LAUNCH_TIMED((reduce_kernel_scalar<T, OP>), dim3(stream_grid(len)), dim3(kBlock), 0, s, t,
                        n, len, reinterpret_cast<T*>(out));
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;
@@ -405,7 +405,7 @@ static int launch_reduce_sgd(const BufTable& t, int n, int64_t len, float* p, fl
   const dim3 grid(stream_grid(len >> 2)), block(kBlock);
   uint16_t* lp = reinterpret_cast<uint16_t*>(p_lp);
 #define SYNK_RS(NS)                                                                              \
-  hipLaunchKernelGGL((reduce_sgd_kernel<NS>), grid, block, 0, s, t, n, len, p, v, lr, m, wd, lp, \
+  SYNK_LAUNCH_TIMED((reduce_sgd_kernel<NS>), grid, block, 0, s, t, n, len, p, v, lr, m, wd, lp,  \
                      loss_in, loss_out)
   switch (n) {
     case 1: SYNK_RS(1); break;
@@ -447,7 +447,7 @@ static int launch_reduce_update(const BufTable& t, int n, int64_t len, float* p,
   const dim3 grid(stream_grid(len >> 2)), block(kBlock);
   uint16_t* lp = reinterpret_cast<uint16_t*>(p_lp);
 #define SYNK_RU(NS)                                                                                \
-  hipLaunchKernelGGL((reduce_update_kernel<NS, RULE>), grid, block, 0, s, t, n, len, p, s1, s2, h, \
+  SYNK_LAUNCH_TIMED((reduce_update_kernel<NS, RULE>), grid, block, 0, s, t, n, len, p, s1, s2, h,  \
                      lp, loss_in, loss_out)
   switch (n) {
     case 1: SYNK_RU(1); break;

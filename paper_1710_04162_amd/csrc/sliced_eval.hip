@@ -383,13 +383,13 @@ extern "C" int synk_sliced_eval(const float* logits, const int32_t* labels, int6
   SYNK_LAUNCH_CHECK();
   const dim3 grid(chunks, n_slices);
   if (classes % 4 == 0 && aligned_to(logits, 16) && classes <= 1024)
-    hipLaunchKernelGGL((eval_stage1_kernel<16, 16>), grid, dim3(kEBlock), 0, s, logits, labels, rows,
+    SYNK_LAUNCH_TIMED((eval_stage1_kernel<16, 16>), grid, dim3(kEBlock), 0, s, logits, labels, rows,
                        (int)classes, n_slices, chunks, w, argmax);
   else if (classes % 4 == 0 && aligned_to(logits, 16))
-    hipLaunchKernelGGL((eval_stage1_kernel<64, 16>), grid, dim3(kEBlock), 0, s, logits, labels, rows,
+    SYNK_LAUNCH_TIMED((eval_stage1_kernel<64, 16>), grid, dim3(kEBlock), 0, s, logits, labels, rows,
                        (int)classes, n_slices, chunks, w, argmax);
   else
-    hipLaunchKernelGGL(eval_stage1_generic_kernel, grid, dim3(kEBlock), 0, s, logits, labels, rows,
+    SYNK_LAUNCH_TIMED(eval_stage1_generic_kernel, grid, dim3(kEBlock), 0, s, logits, labels, rows,
                        (int)classes, n_slices, chunks, w, argmax);
   SYNK_LAUNCH_CHECK();
   int b2 = (int)((classes + kE2Block - 1) / kE2Block);

@@ -32,3 +32,23 @@ extern "C" int synk_split(int64_t count, int parts, int64_t* start) {
   start[parts] = count;
   return SYNK_OK;
 }
+
+// ---------------------------------------------------------------- profiling
+namespace synk {
+static thread_local hipEvent_t tl_start = nullptr, tl_stop = nullptr;
+
+bool take_profile_events(hipEvent_t* start, hipEvent_t* stop) {
+  if (!tl_start) return false;
+  *start = tl_start;
+  *stop = tl_stop;
+  tl_start = tl_stop = nullptr;
+  return true;
+}
+}  // namespace synk
+
+extern "C" int synk_profile_next_launch(void* start_event, void* stop_event) {
+  if ((start_event == nullptr) != (stop_event == nullptr)) return SYNK_ERR_NULL;
+  synk::tl_start = reinterpret_cast<hipEvent_t>(start_event);
+  synk::tl_stop = reinterpret_cast<hipEvent_t>(stop_event);
+  return SYNK_OK;
+}

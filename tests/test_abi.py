@@ -248,3 +248,10 @@ def test_slice_scatter_and_resident_gather_argument_checks():
     assert gr(two, rows, 4, 2, two, nidx, two, 2, 2, None, 0, None, None, 1, None, 0, None) == -6   # flag, no ws
     assert gr(two, rows, 4, 2, two, (ctypes.c_int64 * 2)(0, 0), _tbl(None, None), 2, 2, None, 0, None, None, 0,
               None, 0, None) == 0
+
+
+def test_profile_next_launch_argument_checks():
+    f = lib.synk_profile_next_launch
+    assert f(FAKE, None) == -1 and f(None, FAKE) == -1
+    assert f(FAKE, FAKE + 8) == 0
+    assert f(None, None) == 0          # cancels the pending pair: nothing is left for a later launch

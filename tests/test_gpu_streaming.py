@@ -380,6 +380,29 @@ def test_reduce_update_adam_weights_and_first_step_closed_form(synk):
     assert rel_err(dp.cpu().numpy(), want) < TOL_F32
 
 
+def test_profile_next_launch_times_the_kernel_itself(synk):
+    n = 1 << 22
+    grads = [torch.randn(n, device="cuda") for _ in range(4)]
+    p, v = torch.randn(n, device="cuda"), torch.zeros(n, device="cuda")
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(); b.record()                      # torch creates the events at the first record
+    torch.cuda.synchronize()
+    ref_p, ref_v = p.clone(), v.clone()
+    synk.synk_reduce_sgd_update(grads, ref_p, ref_v, 0.1, 0.9, 0.0)
+    synk.synk_profile_next_launch(a, b)
+    synk.synk_reduce_sgd_update(grads, p, v, 0.1, 0.9, 0.0)
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b)
+    # 4 M elements x 48 B = 100 MB: between 8 TB/s (12.6 us) and a very slow 0.2 TB/s
+    assert 0.010 < ms < 0.5, ms
+    assert torch.equal(p, ref_p) and torch.equal(v, ref_v)      # the timed launch computes the same
+    # the pair was consumed: the next call runs untimed and a cancelled pair leaves nothing pending
+    synk.synk_profile_next_launch(a, b)
+    synk.synk_profile_next_launch(None, None)
+    synk.synk_reduce_sgd_update(grads, p, v, 0.1, 0.9, 0.0)
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------- collectives
 @pytest.mark.parametrize("n,length", [(1, 5), (2, 4099), (3, 1027), (8, 70001), (16, 513)])
 def test_broadcast_is_bit_exact(synk, n, length):
