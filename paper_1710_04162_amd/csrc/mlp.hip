@@ -349,7 +349,7 @@ __device__ __forceinline__ void xcd_tile(int* bx, int* by, int* bz) {
 constexpr int kGemmThreads = 2 * kMBlock;
 
 template <typename T, int MODE, int BM, int BN, int BK, bool ALIGNED>
-__global__ __launch_bounds__(kGemmThreads, 2) void mlp_gemm_kernel(GemmArgs g) {
+__global__ __launch_bounds__(kGemmThreads, (BM == 128 && MODE != MODE_DX) ? 4 : 2) void mlp_gemm_kernel(GemmArgs g) {
   constexpr int LA = MODE == MODE_DW ? XC : KC;
   constexpr int LB = MODE == MODE_DX ? KC : XC;
   constexpr int KM = ET<T>::KM;
@@ -601,13 +601,19 @@ __global__ __launch_bounds__(kGemmThreads, 2) void mlp_gemm_kernel(GemmArgs g) {
           if (tile_row / 64 != ps) continue;
 #pragma unroll
           for (int j = 0; j < TN; ++j) {
-            const int cl = wn * (BN / 2) + j * 32 + xi;
+            // one base address per MFMA tile; the 16 results sit at compile-time offsets from it
+            const int base = ((tile_row & 63) + gk * 4) * BN + wn * (BN / 2) + j * 32 + xi;
+            if (out_f32) {
+              float* sp = reinterpret_cast<float*>(smem) + base;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int rl = (tile_row & 63) + (v >> 2) * 8 + gk * 4 + (v & 3);
-              if (out_f32) reinterpret_cast<float*>(smem)[rl * BN + cl] = acc[i][j][v];
-              else reinterpret_cast<uint16_t*>(smem)[rl * BN + cl] = f32_to_bf16(acc[i][j][v]);
+              for (int v = 0; v < 16; ++v) sp[((v >> 2) * 8 + (v & 3)) * BN] = acc[i][j][v];
+            } else {
+              uint16_t* sp = reinterpret_cast<uint16_t*>(smem) + base;
+#pragma unroll
+              for (int v = 0; v < 16; ++v) sp[((v >> 2) * 8 + (v & 3)) * BN] = f32_to_bf16(acc[i][j][v]);
             }
+            // keep the tiles apart in the schedule: interleaving them only lengthens live ranges
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
       }
