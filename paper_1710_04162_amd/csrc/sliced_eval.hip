@@ -15,7 +15,7 @@ namespace synk {
 
 constexpr int kEBlock = 256;
 constexpr int kEWaves = kEBlock / kWave;
-constexpr int kRowsPerBlock = 16;
+constexpr int kRowsPerBlock = 32;
 
 struct EvalWs {
   float* part_ce;        // [S x CH]
@@ -262,6 +262,151 @@ __global__ __launch_bounds__(kEBlock) void eval_stage1_kernel(
   }
 }
 
+// The same stage 1 as a two-deep software pipeline, for the regular case: every
+// slice has a multiple of kRowsPerBlock rows and the row needs all UPL vectors
+// of a lane group ((UPL-1)*G < classes/4 <= UPL*G).  A workgroup owns NSETS
+// sets of 16 rows; while set s is reduced out of registers, the loads of set
+// s+1 are in flight into a second register buffer.  Every load is issued
+// unconditionally (the last vector's address is clamped into the row, its
+// padding applied when it is used), so the number of loads outstanding at
+// each wait is known and a wait for set s never waits for set s+1.
+template <int G, int UPL, int NSETS>
+__global__ __launch_bounds__(kEBlock) void eval_stage1_pipe_kernel(
+    const float* __restrict__ logits, const int32_t* __restrict__ labels, int64_t rows, int classes,
+    int n_slices, int chunks, EvalWs ws, int32_t* __restrict__ argmax_out) {
+  constexpr int RW = kWave / G;            // rows a wavefront handles at once
+  constexpr int NACC = kEWaves * RW;       // rows of a set = per-block accumulators
+  static_assert(NSETS * NACC == kRowsPerBlock, "sets must tile the block's rows");
+  constexpr float kLog2e = 1.4426950408889634f;
+  const int slice = blockIdx.y, chunk = blockIdx.x;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int sub = lane % G, grp = lane / G;
+  const int units = classes >> 2;
+  const int64_t s_rows = rows / n_slices;                     // the same for every slice here
+  const int64_t first = s_rows * slice + (int64_t)chunk * kRowsPerBlock + wave * RW + grp;
+
+  const int u_last = (UPL - 1) * G + sub;                     // this lane's last vector
+  const bool last_in = u_last < units;
+  const int u_last_c = last_in ? u_last : units - 1;
+  const float pad_ub = last_in ? INFINITY : -INFINITY;
+
+  int y[NSETS];
+#pragma unroll
+  for (int s = 0; s < NSETS; ++s) y[s] = labels[first + s * NACC];
+
+  f32x4 q[2][UPL];
+  float xy[NSETS];
+  auto issue = [&](int s, int b) {
+    const int64_t row = first + s * NACC;
+    const f32x4* x = reinterpret_cast<const f32x4*>(logits + row * classes);
+#pragma unroll
+    for (int k = 0; k < UPL - 1; ++k) q[b][k] = __builtin_nontemporal_load(x + k * G + sub);
+    q[b][UPL - 1] = __builtin_nontemporal_load(x + u_last_c);
+  };
+
+  float w_ce = 0.0f, w_max = -INFINITY, w_min = INFINITY;
+  int w_correct = 0;
+  auto reduce_set = [&](int s, int b) {
+    const int64_t row = first + s * NACC;
+    float m = -INFINITY, mn = INFINITY;
+#pragma unroll
+    for (int k = 0; k < UPL - 1; ++k) {
+      m = fmaxf(m, fmaxf(fmaxf(q[b][k].x, q[b][k].y), fmaxf(q[b][k].z, q[b][k].w)));
+      mn = fminf(mn, fminf(fminf(q[b][k].x, q[b][k].y), fminf(q[b][k].z, q[b][k].w)));
+    }
+    {
+      // padding by arithmetic, not by a branch: the load above must stay unconditional
+      f32x4& v = q[b][UPL - 1];
+      const float lo = fminf(fminf(v.x, v.y), fminf(v.z, v.w));
+      mn = fminf(mn, fmaxf(lo, -pad_ub));                      // +inf where the lane holds padding
+      v = f32x4{fminf(v.x, pad_ub), fminf(v.y, pad_ub), fminf(v.z, pad_ub), fminf(v.w, pad_ub)};   // -inf there
+      m = fmaxf(m, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
+    }
+    // first position of the lane-local maximum (scan downwards, keep the last hit)
+    int arg = 0x7fffffff;
+#pragma unroll
+    for (int k = UPL - 1; k >= 0; --k) {
+      const int c = (k * G + sub) << 2;
+      if (q[b][k].w == m) arg = c + 3;
+      if (q[b][k].z == m) arg = c + 2;
+      if (q[b][k].y == m) arg = c + 1;
+      if (q[b][k].x == m) arg = c;
+    }
+#pragma unroll
+    for (int off = G / 2; off > 0; off >>= 1) {
+      const float om = __shfl_xor(m, off);
+      const int oarg = __shfl_xor(arg, off);
+      if (om > m || (om == m && oarg < arg)) arg = oarg;
+      m = fmaxf(m, om);
+    }
+    const float mb = m * kLog2e;
+    float sum = 0.0f;
+#pragma unroll
+    for (int k = 0; k < UPL; ++k) {
+      // arguments are <= 0: the raw hardware exp2 (no denormal fix-up) is exact enough
+      sum += __builtin_amdgcn_exp2f(fmaf(q[b][k].x, kLog2e, -mb)) + __builtin_amdgcn_exp2f(fmaf(q[b][k].y, kLog2e, -mb)) +
+             __builtin_amdgcn_exp2f(fmaf(q[b][k].z, kLog2e, -mb)) + __builtin_amdgcn_exp2f(fmaf(q[b][k].w, kLog2e, -mb));
+    }
+#pragma unroll
+    for (int off = G / 2; off > 0; off >>= 1) {
+      sum += __shfl_xor(sum, off);
+      mn = fminf(mn, __shfl_xor(mn, off));
+    }
+    if (sub == 0) {
+      const float label_logit = (y[s] >= 0 && y[s] < classes) ? xy[s] : 0.0f;
+      w_ce += (__logf(sum) + m) - label_logit;
+      w_max = fmaxf(w_max, m);
+      w_min = fminf(w_min, mn);
+      w_correct += (arg == y[s]) ? 1 : 0;
+      argmax_out[row] = arg;
+      atomicAdd(ws.slice_counts + (int64_t)slice * classes + arg, 1);
+    }
+  };
+
+  issue(0, 0);
+  __builtin_amdgcn_sched_barrier(0);
+  // the label logits of every set, asked for while the first set is still on its way: they
+  // hang on the label loads, and must not end up queued behind the loads of a later set
+#pragma unroll
+  for (int s = 0; s < NSETS; ++s) {
+    const int yc = (y[s] >= 0 && y[s] < classes) ? y[s] : 0;
+    xy[s] = logits[(first + s * NACC) * classes + yc];
+  }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int s = 0; s < NSETS; ++s) {
+    if (s + 1 < NSETS) issue(s + 1, (s + 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);     // keep the loads of later sets from drifting up here
+    reduce_set(s, s & 1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  __shared__ float s_ce[NACC], s_max[NACC], s_min[NACC];
+  __shared__ int s_cor[NACC];
+  if (sub == 0) {
+    s_ce[wave * RW + grp] = w_ce;
+    s_max[wave * RW + grp] = w_max;
+    s_min[wave * RW + grp] = w_min;
+    s_cor[wave * RW + grp] = w_correct;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float ce = s_ce[0], mx = s_max[0], mn = s_min[0];
+    int cor = s_cor[0];
+    for (int w = 1; w < NACC; ++w) {
+      ce += s_ce[w];
+      mx = fmaxf(mx, s_max[w]);
+      mn = fminf(mn, s_min[w]);
+      cor += s_cor[w];
+    }
+    const int64_t o = (int64_t)slice * chunks + chunk;
+    ws.part_ce[o] = ce;
+    ws.part_max[o] = mx;
+    ws.part_min[o] = mn;
+    ws.part_correct[o] = cor;
+  }
+}
+
 // Stage 2.  Block 0 (1024 threads): one wavefront per slice folds that slice's
 // chunk partials (lanes stride over chunks, fixed shuffle tree), then the slice
 // results are folded with each output's op in slice order.  All blocks:
@@ -382,7 +527,11 @@ extern "C" int synk_sliced_eval(const float* logits, const int32_t* labels, int6
   hipLaunchKernelGGL(zero_i32_kernel, dim3(zb), dim3(kEBlock), 0, s, w.slice_counts, n_counts);
   SYNK_LAUNCH_CHECK();
   const dim3 grid(chunks, n_slices);
-  if (classes % 4 == 0 && aligned_to(logits, 16) && classes <= 1024)
+  const bool regular = rows % ((int64_t)n_slices * kRowsPerBlock) == 0 && classes > 960 && classes <= 1024;
+  if (classes % 4 == 0 && aligned_to(logits, 16) && regular)
+    SYNK_LAUNCH_TIMED((eval_stage1_pipe_kernel<16, 16, kRowsPerBlock / 16>), grid, dim3(kEBlock), 0, s, logits,
+                      labels, rows, (int)classes, n_slices, chunks, w, argmax);
+  else if (classes % 4 == 0 && aligned_to(logits, 16) && classes <= 1024)
     SYNK_LAUNCH_TIMED((eval_stage1_kernel<16, 16>), grid, dim3(kEBlock), 0, s, logits, labels, rows,
                        (int)classes, n_slices, chunks, w, argmax);
   else if (classes % 4 == 0 && aligned_to(logits, 16))

@@ -523,6 +523,11 @@ def check_eval(got, ref):
     (5, 10, 8),          # more slices than rows
     (300, 4096, 2),      # widest rows
     (64, 1, 1),          # a single class
+    (512, 1024, 4),      # pipelined path: full last vector
+    (768, 964, 3),       # pipelined path: one valid vector slot in the last lane group
+    (256, 1000, 8),      # pipelined path: one block a slice
+    (2080, 1000, 65),    # 32 rows a slice but 65 slices: still regular
+    (2048, 960, 64),     # just below the pipelined path's class range
 ])
 def test_sliced_eval_matches_oracle(synk, rows, classes, n_slices):
     c = workloads.config5(rows=rows, classes=classes, n_slices=n_slices)
@@ -539,6 +544,19 @@ def test_sliced_eval_ties_take_the_lowest_class(synk):
     labels = rng.integers(0, 200, 96).astype(np.int32)
     got = run_eval(synk, logits, labels, 5)
     check_eval(got, evalops.sliced(logits, labels, 5))
+
+
+def test_sliced_eval_pipelined_path_ties_and_bad_labels(synk):
+    rng = np.random.default_rng(19)
+    logits = (rng.standard_normal((128, 1000)) * 2).astype(np.float32)
+    for i in range(128):       # equal maxima in different lane groups / vector slots, also in the last vector
+        a, b = rng.choice(1000, 2, replace=False)
+        if i % 4 == 0:
+            b = 996 + (i // 4) % 4
+        logits[i, a] = logits[i, b] = 60.0
+    labels = rng.integers(0, 1000, 128).astype(np.int32)
+    got = run_eval(synk, logits, labels, 2)
+    check_eval(got, evalops.sliced(logits, labels, 2))
 
 
 def test_streaming_kernels_are_reproducible(synk):
