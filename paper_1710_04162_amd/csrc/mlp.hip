@@ -348,7 +348,7 @@ __device__ __forceinline__ void xcd_tile(int* bx, int* by, int* bz) {
 // MFMA result layout alone would give 2- or 4-byte stores scattered over rows.
 constexpr int kGemmThreads = 2 * kMBlock;
 
-template <typename T, int MODE, int BM, int BN, int BK, bool ALIGNED>
+template <typename T, int MODE, int BM, int BN, int BK, bool AL_A, bool AL_B>
 __global__ __launch_bounds__(kGemmThreads, (BM == 128 && MODE != MODE_DX) ? 4 : 2) void mlp_gemm_kernel(GemmArgs g) {
   constexpr int LA = MODE == MODE_DW ? XC : KC;
   constexpr int LB = MODE == MODE_DX ? KC : XC;
@@ -394,10 +394,10 @@ __global__ __launch_bounds__(kGemmThreads, (BM == 128 && MODE != MODE_DX) ? 4 : 
     // tiles t+2 .. t+5 are in flight.  Loads, stores and barriers are issued on
     // every path (the loop runs a multiple of four steps), so that the number
     // of loads outstanding at each wait is known exactly.
-    TileStage<T, LA, BM, BK, ALIGNED> stA[4];
-    TileStage<T, LB, BN, BK, ALIGNED> stB[4];
+    TileStage<T, LA, BM, BK, AL_A> stA[4];
+    TileStage<T, LB, BN, BK, AL_B> stB[4];
     const int n_whole = kc / BK;                     // tiles wholly inside along the contraction
-    const bool fastA = ALIGNED && adA.interior, fastB = ALIGNED && adB.interior;
+    const bool fastA = AL_A && adA.interior, fastB = AL_B && adB.interior;
     auto load_tile = [&](auto& sa, auto& sb, int j) {
       // (a tile past the end has every vector masked and lands in a half nobody reads)
       if (fastA && j < n_whole) sa.load_whole(adA, j * BK);
@@ -591,7 +591,7 @@ __global__ __launch_bounds__(kGemmThreads, (BM == 128 && MODE != MODE_DX) ? 4 : 
   __syncthreads();   // every LDS read of the contraction is over before the output is staged
   const bool out_f32 = MODE == MODE_DW || sizeof(T) == 4 || (MODE == MODE_FWD && g.out_f32);
   char* Cw = reinterpret_cast<char*>(g.c[w]);
-  if (ALIGNED && g.c_vec) {
+  if (g.c_vec) {
     constexpr int PASSES = BM / 64;
     for (int ps = 0; ps < PASSES; ++ps) {
       if (!producer) {
@@ -987,20 +987,25 @@ static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStrea
   // 128 x 128 tiles when they alone fill the chip, 64 x 64 otherwise
   constexpr int BK_BIG = sizeof(T) == 2 ? 32 : 16, BK_SMALL = sizeof(T) == 2 ? 64 : 32;
   const int64_t big = ((m_max + 127) / 128) * ((g.n + 127) / 128) * n_workers;
-  const bool aligned = g.a_vec && g.b_vec;
+  // vector loads per operand: both, only A (e.g. a narrow last layer's dZ as B), or neither
+  const int al = (g.a_vec && g.b_vec) ? 2 : (g.a_vec ? 1 : 0);
+#define SYNK_GEMM(BM_, BN_, BK_)                                                                              \
+  do {                                                                                                       \
+    if (al == 2)                                                                                             \
+      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, BM_, BN_, BK_, true, true>), grid, dim3(kGemmThreads), 0, s, g);  \
+    else if (al == 1)                                                                                        \
+      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, BM_, BN_, BK_, true, false>), grid, dim3(kGemmThreads), 0, s, g); \
+    else                                                                                                     \
+      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, BM_, BN_, BK_, false, false>), grid, dim3(kGemmThreads), 0, s, g);\
+  } while (0)
   if (big >= 2 * kNumCU) {
     const dim3 grid((unsigned)((g.n + 127) / 128), (unsigned)((m_max + 127) / 128), n_workers);
-    if (aligned)
-      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, 128, 128, BK_BIG, true>), grid, dim3(kGemmThreads), 0, s, g);
-    else
-      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, 128, 128, BK_BIG, false>), grid, dim3(kGemmThreads), 0, s, g);
+    SYNK_GEMM(128, 128, BK_BIG);
   } else {
     const dim3 grid((unsigned)((g.n + 63) / 64), (unsigned)((m_max + 63) / 64), n_workers);
-    if (aligned)
-      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, 64, 64, BK_SMALL, true>), grid, dim3(kGemmThreads), 0, s, g);
-    else
-      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, 64, 64, BK_SMALL, false>), grid, dim3(kGemmThreads), 0, s, g);
+    SYNK_GEMM(64, 64, BK_SMALL);
   }
+#undef SYNK_GEMM
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;
 }
