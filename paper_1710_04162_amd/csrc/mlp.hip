@@ -293,6 +293,43 @@ __device__ __forceinline__ float to_f32(bf16_t x) { return bf16_to_f32(x); }
 __device__ __forceinline__ void store_as(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_as(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 
+// loss[w] = aggregate over the worker's slices of the slice mean losses.  One
+// wavefront per slice: lanes stride over the slice's rows, a fixed shuffle tree
+// adds the 64 partial sums; thread 0 then folds the slices in slice order.
+// Called by a whole workgroup of NW wavefronts; s_mean: NW floats of LDS.
+template <int NW>
+__device__ __forceinline__ void slice_loss_worker(const float* __restrict__ row_loss,
+                                                  const int64_t* row_off, int n_slices, int grad_op,
+                                                  int w, float* __restrict__ loss, float* s_mean) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t rows_w = row_off[w + 1] - row_off[w];
+  const float* rl = row_loss + row_off[w];
+  const int64_t base = rows_w / n_slices, extra = rows_w % n_slices;
+  float total = 0.0f;
+  for (int s0 = 0; s0 < n_slices; s0 += NW) {
+    const int s = s0 + wave;
+    float contrib = 0.0f;
+    if (s < n_slices) {
+      const int64_t n_ws = base + (s < extra ? 1 : 0);
+      const int64_t start = base * s + (s < extra ? s : extra);
+      float part = 0.0f;
+      for (int64_t i = lane; i < n_ws; i += 64) part += rl[start + i];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+      if (n_ws > 0) {
+        const float slice_mean = part / (float)n_ws;
+        contrib = (grad_op == SYNK_MEAN) ? slice_mean * ((float)n_ws / (float)rows_w) : slice_mean;
+      }
+    }
+    if (lane == 0) s_mean[wave] = contrib;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      for (int k = 0; k < NW; ++k) total += s_mean[k];   // slice order: s0, s0+1, ...
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) loss[w] = total;
+}
+
 struct GemmArgs {
   const void* a[SYNK_MAX_WORKERS];   // A operand base per worker
   void* c[SYNK_MAX_WORKERS];         // output base per worker
@@ -309,6 +346,12 @@ struct GemmArgs {
   int out_f32;          // MODE_FWD: store fp32 (logits) instead of T
   int a_vec, b_vec;     // operands may be read with 16-byte loads
   int c_vec;            // output rows may be written with 16-byte stores
+  // MODE_DW only: the workgroups of grid slice z == task_z do no GEMM; the first
+  // of them turns the row losses of the kernel before into the workers' slice-
+  // aggregated losses (a launch saved).  task_z < 0: no such slice.
+  int task_z, task_workers, task_slices, task_op;
+  const float* task_row_loss;
+  float* task_loss;
 };
 
 // Workgroups are dealt to the 8 XCDs round-robin by launch order.  Re-deal so
@@ -362,6 +405,15 @@ __global__ __launch_bounds__(kGemmThreads, (BM == 128 && MODE != MODE_DX) ? 4 : 
 
   int bx, by, bz;
   xcd_tile(&bx, &by, &bz);
+  if (MODE == MODE_DW && g.task_z >= 0 && bz == g.task_z) {   // uniform for the block
+    if (bx == 0 && by == 0) {
+      __shared__ float s_mean[kGemmThreads / 64];
+      for (int ww = 0; ww < g.task_workers; ++ww)
+        slice_loss_worker<kGemmThreads / 64>(g.task_row_loss, g.row_off, g.task_slices, g.task_op, ww, g.task_loss,
+                                             s_mean);
+    }
+    return;
+  }
   const int w = bz;
   const int64_t rows_w = g.row_off[w + 1] - g.row_off[w];
   const int64_t M = MODE == MODE_DW ? g.m_fixed : rows_w;
@@ -727,42 +779,6 @@ __global__ __launch_bounds__(kMBlock) void softmax_ce_kernel(CeArgs a) {
   }
 }
 
-// loss[w] = aggregate over the worker's slices of the slice mean losses.  One
-// wavefront per slice: lanes stride over the slice's rows, a fixed shuffle tree
-// adds the 64 partial sums; thread 0 then folds the slices in slice order.
-__global__ __launch_bounds__(kMBlock) void slice_loss_kernel(const float* __restrict__ row_loss,
-                                                             CeArgs a, float* __restrict__ loss) {
-  __shared__ float s_mean[kMBlock / 64];
-  const int w = blockIdx.x;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t rows_w = a.row_off[w + 1] - a.row_off[w];
-  const float* rl = row_loss + a.row_off[w];
-  const int64_t base = rows_w / a.n_slices, extra = rows_w % a.n_slices;
-  float total = 0.0f;
-  for (int s0 = 0; s0 < a.n_slices; s0 += kMBlock / 64) {
-    const int s = s0 + wave;
-    float contrib = 0.0f;
-    if (s < a.n_slices) {
-      const int64_t n_ws = base + (s < extra ? 1 : 0);
-      const int64_t start = base * s + (s < extra ? s : extra);
-      float part = 0.0f;
-      for (int64_t i = lane; i < n_ws; i += 64) part += rl[start + i];
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
-      if (n_ws > 0) {
-        const float slice_mean = part / (float)n_ws;
-        contrib = (a.grad_op == SYNK_MEAN) ? slice_mean * ((float)n_ws / (float)rows_w) : slice_mean;
-      }
-    }
-    if (lane == 0) s_mean[wave] = contrib;
-    __syncthreads();
-    if (threadIdx.x == 0)
-      for (int k = 0; k < kMBlock / 64; ++k) total += s_mean[k];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) loss[w] = total;
-}
-
 // ------------------------------------------------------------------ head
 // Narrow last layer (at most kHeadMaxC classes), all in one kernel, one
 // wavefront per row: logits = h W_L + b_L, softmax cross-entropy, dZ_L, and
@@ -1031,6 +1047,10 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
   }
 
   GemmArgs g;
+  g.task_z = -1;
+  g.task_workers = g.task_slices = g.task_op = 0;
+  g.task_row_loss = nullptr;
+  g.task_loss = nullptr;
   for (int w = 0; w <= n_workers; ++w) g.row_off[w] = p.row_off[w];
   for (int w = n_workers + 1; w <= SYNK_MAX_WORKERS; ++w) g.row_off[w] = p.R;
 
@@ -1095,8 +1115,6 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
     hipLaunchKernelGGL((softmax_ce_kernel<T>), grid, dim3(kMBlock), 0, s, ce);
     SYNK_LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(slice_loss_kernel, dim3(n_workers), dim3(kMBlock), 0, s, row_loss, ce, loss);
-  SYNK_LAUNCH_CHECK();
 
   // ---- backward
   for (int l = L; l >= 1; --l) {
@@ -1122,7 +1140,16 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
     g.a_vec = (K % V == 0) && (l == 1 ? x_vec : true);
     g.b_vec = (N % V == 0);
     g.c_vec = grad_al && N % 4 == 0 && p.offW[l - 1] % 4 == 0;
-    if (int rc = launch_gemm<T, MODE_DW>(g, K, n_workers, s)) return rc;
+    // the first kernel after the row losses exist also aggregates them over slices (one more grid slice)
+    const bool with_loss = l == L;
+    g.task_z = with_loss ? n_workers : -1;
+    g.task_workers = n_workers;
+    g.task_slices = n_slices;
+    g.task_op = grad_op;
+    g.task_row_loss = row_loss;
+    g.task_loss = loss;
+    if (int rc = launch_gemm<T, MODE_DW>(g, K, n_workers + (with_loss ? 1 : 0), s)) return rc;
+    g.task_z = -1;
 
     if (l > 1 && !(use_head && l == L)) {
       // dZ_{l-1} = (dZ_l W_l^T) * [H_{l-1} > 0]
