@@ -710,6 +710,210 @@ __global__ __launch_bounds__(kGemmThreads, (BM == 128 && MODE != MODE_DX) ? 4 : 
   }
 }
 
+// ------------------------------------------------------- persistent dW
+// dW_l[w] = H_{l-1}[w]^T dZ_l[w] when a worker has few rows: the contraction is
+// then a handful of k-tiles and a workgroup per output tile spends its life in
+// the first loads and in the write-out.  Here a workgroup walks a list of
+// output tiles and the producers' tile stream runs straight across tile
+// boundaries: while the consumers write tile i out (through a staging area of
+// its own in LDS, as whole 512-byte row segments: 32-byte pieces straight from
+// the accumulators measured slower), the operand tiles of tile i+1 are already
+// on their way.
+// Preconditions (checked on the host): both operands and the output take
+// 16-byte accesses, the output is a whole number of 128 x 128 tiles, and every
+// worker's row count is a multiple of four k-tiles (zero rows allowed).
+template <typename T>
+__global__ __launch_bounds__(kGemmThreads, 4) void mlp_dw_persistent_kernel(GemmArgs g, int tiles_m,
+                                                                            int tiles_n, int n_workers) {
+  constexpr int BM = 128, BN = 128, BK = sizeof(T) == 2 ? 32 : 16;
+  constexpr int KM = ET<T>::KM;
+  constexpr int KSTEPS = BK / KM;
+  constexpr int TM = 2, TN = 2;
+  constexpr int WA = tile_words<T, XC, BM, BK>(), WB = tile_words<T, XC, BN, BK>();
+  constexpr int WT = (WA + WB + 3) / 4 * 4;
+  __shared__ __attribute__((aligned(16))) uint32_t smem[2 * WT + 64 * BN];
+  float* stage = reinterpret_cast<float*>(smem + 2 * WT);       // 64 rows of the fp32 output tile
+
+  const bool producer = threadIdx.x >= kMBlock;
+  const int tid = threadIdx.x & (kMBlock - 1);
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int xi = lane & 31, gk = lane >> 5;
+  const int tiles_w = tiles_m * tiles_n;
+  const int total = tiles_w * n_workers;
+  const int64_t lda = g.lda, ldb = g.ldb;
+
+  // j-th tile of this workgroup.  Workgroups are dealt to the 8 XCDs round-robin;
+  // each XCD (each L2) gets a contiguous run of tiles with the n-tile running fastest.
+  auto tile_of = [&](int j, int* w, int* m0, int* n0) -> bool {
+    int lin;
+    if ((total & 7) == 0 && (gridDim.x & 7) == 0) {
+      const int per = total >> 3, idx = (int)(blockIdx.x >> 3) + j * (int)(gridDim.x >> 3);
+      if (idx >= per) return false;
+      lin = (int)(blockIdx.x & 7) * per + idx;
+    } else {
+      lin = (int)blockIdx.x + j * (int)gridDim.x;
+      if (lin >= total) return false;
+    }
+    *w = lin / tiles_w;
+    const int r = lin - *w * tiles_w;
+    *m0 = (r / tiles_n) * BM;
+    *n0 = (r % tiles_n) * BN;
+    return true;
+  };
+  auto k_tiles = [&](int w) { return (int)((g.row_off[w + 1] - g.row_off[w]) / BK); };
+
+  if (producer) {
+    // per-thread byte offsets inside a tile do not depend on the tile
+    TileAddr<T, XC, BM, BK> adA;
+    TileAddr<T, XC, BN, BK> adB;
+    adA.init(reinterpret_cast<const T*>(g.a[0]), lda, 0, BM, tid);
+    adB.init(reinterpret_cast<const T*>(g.b), ldb, 0, BN, tid);
+    const int64_t stepA = (int64_t)BK * lda * (int64_t)sizeof(T), stepB = (int64_t)BK * ldb * (int64_t)sizeof(T);
+    // load cursor: the next k-tile of the stream (tiles without rows contribute none)
+    int lj = -1, lk = 0, lnk = 0;
+    const char* la = reinterpret_cast<const char*>(g.a[0]);
+    const char* lb = reinterpret_cast<const char*>(g.b);
+    bool lvalid = true;
+    auto next_tile = [&]() {
+      while (lvalid) {
+        ++lj;
+        int w, m0, n0;
+        if (!tile_of(lj, &w, &m0, &n0)) { lvalid = false; break; }
+        lnk = k_tiles(w);
+        if (lnk == 0) continue;
+        lk = 0;
+        la = reinterpret_cast<const char*>(reinterpret_cast<const T*>(g.a[w]) + m0);
+        lb = reinterpret_cast<const char*>(reinterpret_cast<const T*>(g.b) + g.row_off[w] * ldb + n0);
+        break;
+      }
+    };
+    next_tile();
+    TileStage<T, XC, BM, BK, true> stA[4];
+    TileStage<T, XC, BN, BK, true> stB[4];
+    auto load_next = [&](auto& sa, auto& sb) {
+      // past the end of the stream every lane reads the first vector of the first operand (one line)
+      sa.load_at(adA, lvalid ? la : reinterpret_cast<const char*>(g.a[0]), lvalid ? 0xffffffffu : 0u);
+      sb.load_at(adB, lvalid ? lb : reinterpret_cast<const char*>(g.b), lvalid ? 0xffffffffu : 0u);
+      if (lvalid) {
+        la += stepA;
+        lb += stepB;
+        if (++lk == lnk) next_tile();
+      }
+    };
+#pragma unroll
+    for (int u = 0; u < 4; ++u) load_next(stA[u], stB[u]);
+    stA[0].template store_impl<false>(smem, tid);
+    stB[0].template store_impl<false>(smem + WA, tid);
+    load_next(stA[0], stB[0]);
+    __syncthreads();                               // stream step 0 is in half 0
+    for (int j = 0;; ++j) {
+      int w, m0, n0;
+      if (!tile_of(j, &w, &m0, &n0)) break;
+      const int nk = k_tiles(w);
+      for (int k = 0; k < nk; k += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          uint32_t* half = smem + ((u + 1) & 1) * WT;
+          stA[(u + 1) & 3].template store_impl<false>(half, tid);
+          stB[(u + 1) & 3].template store_impl<false>(half + WA, tid);
+          load_next(stA[(u + 1) & 3], stB[(u + 1) & 3]);
+          __syncthreads();
+        }
+      }
+      // the consumers write the tile out: four barriers of theirs to keep step with
+      __syncthreads();
+      __syncthreads();
+      __syncthreads();
+      __syncthreads();
+    }
+  } else {
+    __syncthreads();                               // stream step 0 is in half 0
+    for (int j = 0;; ++j) {
+      int w, m0, n0;
+      if (!tile_of(j, &w, &m0, &n0)) break;
+      const int nk = k_tiles(w);
+      f32x16 acc[TM][TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jj = 0; jj < TN; ++jj)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.0f;
+      float colsum = 0.0f;
+      const bool want_colsum = g.colsum_off >= 0 && m0 == 0;
+      for (int k = 0; k < nk; k += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const uint32_t* sA = smem + (u & 1) * WT;
+          const uint32_t* sB = sA + WA;
+          if (want_colsum && tid < BN) {   // column sums of the dZ tile, in row order
+            if (sizeof(T) == 2) {
+#pragma unroll 8
+              for (int kp = 0; kp < BK / 2; ++kp) {
+                const uint32_t wd = sB[kp * BN + tid];
+                colsum += bf16_to_f32((uint16_t)(wd & 0xffffu));
+                colsum += bf16_to_f32((uint16_t)(wd >> 16));
+              }
+            } else {
+#pragma unroll 8
+              for (int kk = 0; kk < BK; ++kk) colsum += __uint_as_float(sB[kk * BN + tid]);
+            }
+          }
+          typename Frag<T, XC, BM, BK>::type fa[2][TM];
+          typename Frag<T, XC, BN, BK>::type fb[2][TN];
+#pragma unroll
+          for (int i = 0; i < TM; ++i) fa[0][i] = Frag<T, XC, BM, BK>::read(sA, wm * 64 + i * 32 + xi, 0, gk);
+#pragma unroll
+          for (int jj = 0; jj < TN; ++jj) fb[0][jj] = Frag<T, XC, BN, BK>::read(sB, wn * 64 + jj * 32 + xi, 0, gk);
+#pragma unroll
+          for (int ks = 0; ks < KSTEPS; ++ks) {
+            if (ks + 1 < KSTEPS) {
+#pragma unroll
+              for (int i = 0; i < TM; ++i)
+                fa[(ks + 1) & 1][i] = Frag<T, XC, BM, BK>::read(sA, wm * 64 + i * 32 + xi, ks + 1, gk);
+#pragma unroll
+              for (int jj = 0; jj < TN; ++jj)
+                fb[(ks + 1) & 1][jj] = Frag<T, XC, BN, BK>::read(sB, wn * 64 + jj * 32 + xi, ks + 1, gk);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+              for (int jj = 0; jj < TN; ++jj) acc[i][jj] = mfma(fa[ks & 1][i], fb[ks & 1][jj], acc[i][jj]);
+          }
+          __syncthreads();
+        }
+      }
+      // write-out, 64 rows at a time through the staging area (the producers keep
+      // filling the operand halves meanwhile)
+      float* Cw = reinterpret_cast<float*>(g.c[w]);
+#pragma unroll
+      for (int ps = 0; ps < 2; ++ps) {
+        if (wm == ps) {
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int jj = 0; jj < TN; ++jj) {
+              float* sp = stage + (i * 32 + gk * 4) * BN + wn * 64 + jj * 32 + xi;
+#pragma unroll
+              for (int v = 0; v < 16; ++v) sp[((v >> 2) * 8 + (v & 3)) * BN] = acc[i][jj][v];
+              __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        __syncthreads();
+        constexpr int CPR = BN * 4 / 16;                       // 16-byte chunks per row
+        for (int c = tid; c < 64 * CPR; c += kMBlock) {
+          const int rl = c / CPR, ch = c - rl * CPR;
+          const f32x4 q = *reinterpret_cast<const f32x4*>(stage + rl * BN + ch * 4);
+          *reinterpret_cast<f32x4*>(Cw + (int64_t)(m0 + ps * 64 + rl) * g.ldc + n0 + ch * 4) = q;
+        }
+        __syncthreads();
+      }
+      if (want_colsum && tid < BN) Cw[g.colsum_off + n0 + tid] = colsum;
+    }
+  }
+}
+
 // ---------------------------------------------------------------- softmax CE
 struct CeArgs {
   const int32_t* y[SYNK_MAX_WORKERS];
@@ -1014,6 +1218,25 @@ static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStrea
     else                                                                                                     \
       hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, BM_, BN_, BK_, false, false>), grid, dim3(kGemmThreads), 0, s, g);\
   } while (0)
+  if (MODE == MODE_DW && big >= 2 * kNumCU && al == 2 && g.c_vec && g.task_z < 0 && m_max % 128 == 0 &&
+      g.n % 128 == 0) {
+    // few rows per worker: the persistent kernel, if every worker's rows are whole rounds of k-tiles
+    bool rounds = true;
+    int64_t most = 0;
+    for (int w = 0; w < n_workers; ++w) {
+      const int64_t r = g.row_off[w + 1] - g.row_off[w];
+      rounds = rounds && r % (4 * BK_BIG) == 0;
+      if (r > most) most = r;
+    }
+    if (rounds && most <= 16 * BK_BIG) {
+      int64_t blocks = big < 2 * kNumCU ? big : 2 * kNumCU;
+      if (big % 8 == 0) blocks = blocks / 8 * 8;
+      hipLaunchKernelGGL((mlp_dw_persistent_kernel<T>), dim3((unsigned)blocks), dim3(kGemmThreads), 0, s, g,
+                         (int)(m_max / 128), (int)(g.n / 128), n_workers);
+      SYNK_LAUNCH_CHECK();
+      return SYNK_OK;
+    }
+  }
   if (big >= 2 * kNumCU) {
     const dim3 grid((unsigned)((g.n + 127) / 128), (unsigned)((m_max + 127) / 128), n_workers);
     SYNK_GEMM(128, 128, BK_BIG);

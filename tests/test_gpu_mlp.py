@@ -169,6 +169,44 @@ def test_large_tile_paths(synk, compute, dims, rows_per_worker, N):
         assert abs(losses[w] - r["loss"]) < tol * abs(r["loss"])
 
 
+@pytest.mark.parametrize("compute,rows", [
+    ("bf16", [128, 0, 256, 128, 128, 0, 256, 128]),     # whole rounds of four 32-row k-tiles, two empty workers
+    ("f32", [64, 192, 0, 64, 128, 64, 64, 64]),         # fp32: rounds of four 16-row k-tiles
+    ("bf16", [128, 96, 128, 128, 128, 128, 128, 128]),  # one worker breaks the rounds: the per-tile kernel runs
+])
+def test_weight_gradient_with_unequal_worker_rows(synk, compute, rows):
+    """dW of the 1024 x 1024 layer has 512 large tiles: the tile-walking kernel when every worker's
+    row count allows it, with workers of different sizes (and none) in one launch."""
+    bf16 = compute == "bf16"
+    dims = [128, 1024, 1024, 10]
+    B = sum(rows)
+    cfg = small_cfg(dims, B, compute, 11)
+    cfg["data"] = np.abs(cfg["data"])
+    st = Step(synk, cfg)
+    xdt = torch.bfloat16 if bf16 else torch.float32
+    bounds = np.concatenate([[0], np.cumsum(rows)])
+    st.rows = list(rows)
+    st.x = [dev(cfg["data"][a:b]).to(xdt) if b > a else torch.zeros((0, dims[0]), dtype=xdt, device="cuda")
+            for a, b in zip(bounds[:-1], bounds[1:])]
+    st.y = [dev(cfg["labels"][a:b]) if b > a else torch.zeros(0, dtype=torch.int32, device="cuda")
+            for a, b in zip(bounds[:-1], bounds[1:])]
+    grads, losses = st.sliced_grad(2, "mean")
+    eps = TIE_EPS[compute]
+    tol = TOL_BF16 if bf16 else TOL_F32
+    for w, (a, b) in enumerate(zip(bounds[:-1], bounds[1:])):
+        if b == a:
+            assert not grads[w].any()                 # a worker without rows contributes the zero gradient
+            continue
+        X, y = cfg["data"][a:b], cfg["labels"][a:b]
+        tr = []
+        l, gref = omlp.function(cfg["theta"], dims, X, y, bf16_points=bf16, trace=tr)
+        _, galt = omlp.function(cfg["theta"], dims, X, y, bf16_points=bf16, tie_eps=eps, flip_ties=True)
+        skip, _ = tie_columns(tr, eps)
+        e = rel_err_either_tie(grads[w], gref, galt, dims, skip)
+        assert e < tol, (w, e)
+        assert abs(losses[w] - l) < tol * abs(l)
+
+
 def test_slice_count_does_not_change_mean_aggregated_result(synk):
     cfg = small_cfg([40, 32, 10], 100, "f32", 1)
     idx = np.random.default_rng(2).integers(0, 100, 48).astype(np.int32)
