@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--indexing", default="list", choices=["list", "slice", "resident"],
                     help="config 4 only: index list (default), slice-form indexes, or per-worker lists over "
                          "shares resident on the workers (Sec. 5.2)")
+    ap.add_argument("--batch", type=int, default=None,
+                    help="configs 1 and 2 only: minibatch size, to time worker shares that do not divide evenly "
+                         "(default: the configuration's own, 256 / 1024)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -93,7 +96,7 @@ class Timer:
 class MlpStep:
     """Configs 1 and 2: the whole synchronous-SGD step."""
 
-    def __init__(self, torch, synk, cfg_no):
+    def __init__(self, torch, synk, cfg_no, batch=None):
         import numpy as np
         import workloads
         from oracle import split as osplit           # host-side share sizes for buffer allocation only
@@ -103,6 +106,10 @@ class MlpStep:
             c["idx_sets"] = [np.random.default_rng(i).permutation(4096)[:256].astype(np.int32) for i in range(8)]
         else:
             c = workloads.config2(n_index_sets=8)
+        if batch is not None:
+            if not 1 <= batch <= len(c["idx_sets"][0]):
+                raise SystemExit("--batch must be in [1, %d] for this configuration" % len(c["idx_sets"][0]))
+            c["idx_sets"] = [ix[:batch] for ix in c["idx_sets"]]
         self.c = c
         self.dims, self.N, self.S = c["dims"], c["n_workers"], c["n_slices"]
         self.bf16 = c["compute"] == "bf16"
@@ -127,9 +134,11 @@ class MlpStep:
                               dtype=torch.uint8, device="cuda")
         self.units, self.unit = self.B, "samples/s"
         self.dtype = "bf16" if self.bf16 else "f32"
-        self.workload = ("config 2: wide MLP 3072-1024-1024-10 step, batch 1024, 8 worker shares x 4 slices, "
-                         "bf16 GEMM inputs / fp32 accumulate" if cfg_no == 2 else
-                         "config 1: tiny MLP 784-256-10 step, batch 256, 2 worker shares x 4 slices, fp32")
+        self.workload = ("config 2: wide MLP 3072-1024-1024-10 step, batch %d, 8 worker shares x 4 slices, "
+                         "bf16 GEMM inputs / fp32 accumulate" % self.B if cfg_no == 2 else
+                         "config 1: tiny MLP 784-256-10 step, batch %d, 2 worker shares x 4 slices, fp32" % self.B)
+        if batch is not None:
+            self.workload += " (worker shares %s)" % "/".join(str(r) for r in sorted(set(self.rows), reverse=True))
         # dominant kernel: the fused N-way reduce + momentum update.  Per parameter it reads N
         # gradients, reads and writes p and v (fp32) and, with bf16 compute, writes the bf16 copy.
         self.dom_name = "reduce_sgd_kernel"
@@ -424,7 +433,7 @@ def main():
     from paper_1710_04162_amd import binding as synk
     torch.cuda.set_device(0)
 
-    wl = {0: lambda: CopyStep(torch, synk), 1: lambda: MlpStep(torch, synk, 1), 2: lambda: MlpStep(torch, synk, 2),
+    wl = {0: lambda: CopyStep(torch, synk), 1: lambda: MlpStep(torch, synk, 1, a.batch), 2: lambda: MlpStep(torch, synk, 2, a.batch),
           3: lambda: (CollectiveStep(torch, synk, a.collective) if a.collective else ReduceStep(torch, synk, a.rule)), 4: lambda: GatherStep(torch, synk, a.indexing),
           5: lambda: EvalStep(torch, synk)}[a.config]()
     steps = a.steps if a.steps is not None else {0: 50, 1: 2000, 2: 1000, 3: 300, 4: 1000, 5: 1000}[a.config]
@@ -453,7 +462,7 @@ def main():
         "config": {"workload": wl.workload, "units_per_step": wl.units},
         "roofline": {"bound": "hbm", "kernel": wl.dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (a.rule == "momentum" and not a.collective and a.indexing == "list") else None, "traffic_unit": "HBM bytes per launch",
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (a.rule == "momentum" and not a.collective and a.indexing == "list" and a.batch is None) else None, "traffic_unit": "HBM bytes per launch",
                      "bytes_per_launch": wl.dom_bytes, "ms_per_launch": dom_ms},
     }
     if not a.no_cpu_baseline:
