@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kCBlock) void all_reduce_kernel(PtrTable t, int n_d
     if (NS > 0) {
       V g[NS > 0 ? NS : 1];
 #pragma unroll
-      for (int w = 0; w < NS; ++w) g[w] = reinterpret_cast<const V*>(t.p[w])[i];
+      for (int w = 0; w < NS; ++w) g[w] = __builtin_nontemporal_load(reinterpret_cast<const V*>(t.p[w]) + i);
       acc = g[0];
       if (OP == SYNK_MEAN) {
         acc.x = (T)(t.w[0] * (float)acc.x); acc.y = (T)(t.w[0] * (float)acc.y);
