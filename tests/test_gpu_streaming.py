@@ -584,6 +584,46 @@ def test_config3_full_size_reduce_and_update(synk):
     assert abs(loss_out.item() - rl) < TOL_F32 * abs(rl)
 
 
+@pytest.mark.parametrize("rule", ["nesterov", "rmsprop", "adam"])
+def test_config3_full_size_other_update_rules(synk, rule):
+    c = workloads.config3()
+    h = RULE_HYPER[rule]
+    grads = [dev(g) for g in c["grads"]]
+    p = dev(c["p"])
+    s1 = torch.full_like(p, 1e-4) if rule != "nesterov" else dev(c["v"])
+    s2 = torch.full_like(p, 2e-6)
+    r1, r2 = s1.cpu().numpy().astype(np.float64), s2.cpu().numpy().astype(np.float64)
+    synk.synk_reduce_update(rule, grads, p, s1, s2 if rule == "adam" else None, step=7, **h)
+    G = oreduce.reduce_buffers(list(c["grads"]), "mean")
+    rp, q1, q2 = oupdate.apply_rule(rule, c["p"], r1, r2, G, dict(h, t=7))
+    gp, g1, g2 = p.cpu().numpy(), s1.cpu().numpy(), s2.cpu().numpy()
+    for t in range(0, 161, 8):                                # every 8th tensor, per tensor
+        a, b = int(c["offsets"][t]), int(c["offsets"][t + 1])
+        assert rel_err(gp[a:b], rp[a:b]) < TOL_F32 and rel_err(g1[a:b], q1[a:b]) < TOL_F32, (rule, t)
+        if rule == "adam":
+            assert rel_err(g2[a:b], q2[a:b]) < TOL_F32, t
+
+
+def test_config3_full_size_collectives(synk):
+    c = workloads.config3()
+    n, P = c["n_workers"], c["n_params"]
+    bufs = [dev(g) for g in c["grads"]]
+    synk.synk_all_reduce(bufs, "mean")
+    ref = oreduce.reduce_buffers(list(c["grads"]), "mean")
+    got = bufs[5].cpu().numpy()
+    for t in range(0, 161, 8):
+        a, b = int(c["offsets"][t]), int(c["offsets"][t + 1])
+        assert rel_err(got[a:b], ref[a:b]) < TOL_F32, t
+    assert all(torch.equal(b, bufs[0]) for b in bufs[1:])
+    src = dev(c["p"])
+    synk.synk_broadcast(src, bufs)
+    assert all(torch.equal(b, src) for b in bufs)
+    bounds = osplit.share_bounds(P, n)                         # shares of 3,194,629: not a multiple of 4
+    synk.synk_all_gather([dev(c["v"][a:b] + np.float32(w)) for w, (a, b) in enumerate(bounds)], bufs)
+    want = np.concatenate([c["v"][a:b] + np.float32(w) for w, (a, b) in enumerate(bounds)])
+    assert np.array_equal(bufs[3].cpu().numpy(), want) and all(torch.equal(b, bufs[0]) for b in bufs[1:])
+
+
 def test_config4_full_size_gather_sampled_against_oracle(synk):
     n_data, batch, n_workers, chw = 50000, 256, 8, (3, 224, 224)
     row = chw[0] * chw[1] * chw[2]
