@@ -359,40 +359,30 @@ struct GemmArgs {
 // running fastest: tiles that differ only in their row range keep hitting the
 // same few L2 channels (rows are a multiple of 2 KiB apart), while neighbouring
 // n-tiles spread over all of them.
-__device__ __forceinline__ void xcd_tile(int* bx, int* by, int* bz) {
-  *bx = blockIdx.x; *by = blockIdx.y; *bz = blockIdx.z;
-  const unsigned total = gridDim.x * gridDim.y * gridDim.z;
-  if ((total & 7u) == 0u) {
-    const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-    const unsigned logical = (lin & 7u) * (total >> 3) + (lin >> 3);
-    *bx = logical % gridDim.x;
-    *by = (logical / gridDim.x) % gridDim.y;
-    *bz = logical / (gridDim.x * gridDim.y);
-  }
+// (lin: the workgroup's launch-order index in a gx x gy x gz grid whose first
+// workgroup sits on XCD 0; a kernel that holds several grids passes each one's
+// own index and extent.)
+__device__ __forceinline__ void xcd_tile(unsigned lin, unsigned gx, unsigned gy, unsigned gz, int* bx,
+                                         int* by, int* bz) {
+  const unsigned total = gx * gy * gz;
+  const unsigned logical = (total & 7u) == 0u ? (lin & 7u) * (total >> 3) + (lin >> 3) : lin;
+  *bx = logical % gx;
+  *by = (logical / gx) % gy;
+  *bz = logical / (gx * gy);
 }
-
-// C[M x N] = A * B on one (worker, m-tile, n-tile), operands staged through
-// LDS.  grid = (n tiles, m tiles, workers); 512 threads = 8 wavefronts in two
-// roles:
-//   wavefronts 0-3 (consumers) tile the output 2 x 2, each owning a (BM/2) x
-//     (BN/2) block of TM x TN MFMA tiles; they only read LDS and issue MFMAs;
-//   wavefronts 4-7 (producers) move the operand tiles global -> registers ->
-//     LDS, up to four tiles ahead, transposing an operand whose contraction
-//     index is strided in memory on the way.
-// LDS holds two tiles (ping-pong), one barrier per tile: between barriers t+1
-// and t+2 the producers write tile t+2 while the consumers multiply tile t
-// out of registers and fetch the fragments of tile t+1, so LDS reads, LDS
-// writes and MFMAs of three different tiles overlap.  A half is rewritten
-// only after the barrier that follows its last read, and a barrier waits for
-// the LDS reads issued before it.  Memory latency and the address work of the
-// loads stall only the producers, never the MFMAs.
-// The output tile leaves through LDS as well (64 rows at a time), so that it is
-// written with 16-byte stores of whole row segments by all 512 threads: the
-// MFMA result layout alone would give 2- or 4-byte stores scattered over rows.
 constexpr int kGemmThreads = 2 * kMBlock;
 
+// LDS words one workgroup of the kernel below needs (two operand tile pairs).
+template <typename T, int MODE, int BM, int BN, int BK>
+__host__ __device__ constexpr int gemm_lds_words() {
+  return 2 * ((tile_words<T, MODE == MODE_DW ? XC : KC, BM, BK>() + tile_words<T, MODE == MODE_DX ? KC : XC, BN, BK>() + 3) / 4 * 4);
+}
+
+// The body of the kernel as a function of the workgroup's place (lin) in a
+// gx x gy x gz grid and of its LDS, so that one launch can hold several grids.
 template <typename T, int MODE, int BM, int BN, int BK, bool AL_A, bool AL_B>
-__global__ __launch_bounds__(kGemmThreads, (BM == 128 && MODE != MODE_DX) ? 4 : 2) void mlp_gemm_kernel(GemmArgs g) {
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, unsigned lin, unsigned gx, unsigned gy, unsigned gz,
+                                          uint32_t* __restrict__ smem) {
   constexpr int LA = MODE == MODE_DW ? XC : KC;
   constexpr int LB = MODE == MODE_DX ? KC : XC;
   constexpr int KM = ET<T>::KM;
@@ -400,11 +390,11 @@ __global__ __launch_bounds__(kGemmThreads, (BM == 128 && MODE != MODE_DX) ? 4 : 
   constexpr int TM = BM / 64, TN = BN / 64;
   constexpr int WA = tile_words<T, LA, BM, BK>(), WB = tile_words<T, LB, BN, BK>();
   constexpr int WT = (WA + WB + 3) / 4 * 4;      // one tile pair, 16-byte multiple
+  static_assert(2 * WT == gemm_lds_words<T, MODE, BM, BN, BK>(), "LDS size helper out of step");
   static_assert(64 * BN <= 2 * WT, "output staging (64 rows of fp32) must fit in the operand LDS");
-  __shared__ __attribute__((aligned(16))) uint32_t smem[2 * WT];
 
   int bx, by, bz;
-  xcd_tile(&bx, &by, &bz);
+  xcd_tile(lin, gx, gy, gz, &bx, &by, &bz);
   if (MODE == MODE_DW && g.task_z >= 0 && bz == g.task_z) {   // uniform for the block
     if (bx == 0 && by == 0) {
       __shared__ float s_mean[kGemmThreads / 64];
@@ -710,6 +700,13 @@ __global__ __launch_bounds__(kGemmThreads, (BM == 128 && MODE != MODE_DX) ? 4 : 
   }
 }
 
+template <typename T, int MODE, int BM, int BN, int BK, bool AL_A, bool AL_B>
+__global__ __launch_bounds__(kGemmThreads, (BM == 128 && MODE != MODE_DX) ? 4 : 2) void mlp_gemm_kernel(GemmArgs g) {
+  __shared__ __attribute__((aligned(16))) uint32_t smem[gemm_lds_words<T, MODE, BM, BN, BK>()];
+  gemm_tile<T, MODE, BM, BN, BK, AL_A, AL_B>(g, blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z),
+                                             gridDim.x, gridDim.y, gridDim.z, smem);
+}
+
 // ------------------------------------------------------- persistent dW
 // dW_l[w] = H_{l-1}[w]^T dZ_l[w] when a worker has few rows: the contraction is
 // then a handful of k-tiles and a workgroup per output tile spends its life in
@@ -723,15 +720,22 @@ __global__ __launch_bounds__(kGemmThreads, (BM == 128 && MODE != MODE_DX) ? 4 : 
 // 16-byte accesses, the output is a whole number of 128 x 128 tiles, and every
 // worker's row count is a multiple of four k-tiles (zero rows allowed).
 template <typename T>
-__global__ __launch_bounds__(kGemmThreads, 4) void mlp_dw_persistent_kernel(GemmArgs g, int tiles_m,
-                                                                            int tiles_n, int n_workers) {
+__host__ __device__ constexpr int dw_persistent_lds_words() {
+  constexpr int BK = sizeof(T) == 2 ? 32 : 16;
+  return 2 * ((tile_words<T, XC, 128, BK>() + tile_words<T, XC, 128, BK>() + 3) / 4 * 4) + 64 * 128;
+}
+
+// vblock of vgrid: this workgroup's place among the workgroups that share the tile list
+template <typename T>
+__device__ __forceinline__ void dw_persistent_body(const GemmArgs& g, int tiles_m, int tiles_n, int n_workers,
+                                                   unsigned vblock, unsigned vgrid, uint32_t* __restrict__ smem) {
   constexpr int BM = 128, BN = 128, BK = sizeof(T) == 2 ? 32 : 16;
   constexpr int KM = ET<T>::KM;
   constexpr int KSTEPS = BK / KM;
   constexpr int TM = 2, TN = 2;
   constexpr int WA = tile_words<T, XC, BM, BK>(), WB = tile_words<T, XC, BN, BK>();
   constexpr int WT = (WA + WB + 3) / 4 * 4;
-  __shared__ __attribute__((aligned(16))) uint32_t smem[2 * WT + 64 * BN];
+  static_assert(2 * WT + 64 * BN == dw_persistent_lds_words<T>(), "LDS size helper out of step");
   float* stage = reinterpret_cast<float*>(smem + 2 * WT);       // 64 rows of the fp32 output tile
 
   const bool producer = threadIdx.x >= kMBlock;
@@ -747,12 +751,12 @@ __global__ __launch_bounds__(kGemmThreads, 4) void mlp_dw_persistent_kernel(Gemm
   // each XCD (each L2) gets a contiguous run of tiles with the n-tile running fastest.
   auto tile_of = [&](int j, int* w, int* m0, int* n0) -> bool {
     int lin;
-    if ((total & 7) == 0 && (gridDim.x & 7) == 0) {
-      const int per = total >> 3, idx = (int)(blockIdx.x >> 3) + j * (int)(gridDim.x >> 3);
+    if ((total & 7) == 0 && (vgrid & 7u) == 0u) {
+      const int per = total >> 3, idx = (int)(vblock >> 3) + j * (int)(vgrid >> 3);
       if (idx >= per) return false;
-      lin = (int)(blockIdx.x & 7) * per + idx;
+      lin = (int)(vblock & 7u) * per + idx;
     } else {
-      lin = (int)blockIdx.x + j * (int)gridDim.x;
+      lin = (int)vblock + j * (int)vgrid;
       if (lin >= total) return false;
     }
     *w = lin / tiles_w;
@@ -912,6 +916,13 @@ __global__ __launch_bounds__(kGemmThreads, 4) void mlp_dw_persistent_kernel(Gemm
       if (want_colsum && tid < BN) Cw[g.colsum_off + n0 + tid] = colsum;
     }
   }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kGemmThreads, 4) void mlp_dw_persistent_kernel(GemmArgs g, int tiles_m,
+                                                                            int tiles_n, int n_workers) {
+  __shared__ __attribute__((aligned(16))) uint32_t smem[dw_persistent_lds_words<T>()];
+  dw_persistent_body<T>(g, tiles_m, tiles_n, n_workers, blockIdx.x, gridDim.x, smem);
 }
 
 // ---------------------------------------------------------------- softmax CE
