@@ -925,6 +925,51 @@ __global__ __launch_bounds__(kGemmThreads, 4) void mlp_dw_persistent_kernel(Gemm
   dw_persistent_body<T>(g, tiles_m, tiles_n, n_workers, blockIdx.x, gridDim.x, smem);
 }
 
+// ------------------------------------------------------- backward group
+// After the last-layer kernel both dZ_L and dZ_{L-1} exist, so dW_L, dW_{L-1}
+// and dZ_{L-2} = (dZ_{L-1} W_{L-1}^T) * [H_{L-2} > 0] do not depend on one
+// another: one launch holds the three grids (every kernel boundary costs a few
+// microseconds of dispatch and drain, and none of the three fills the chip
+// alone).  Each grid starts at a multiple of eight workgroups so that its
+// workgroups keep their XCD phase.
+struct GroupArgs {
+  GemmArgs dwp;   // dW_{L-1}: the tile-walking kernel
+  GemmArgs dx;    // dZ_{L-2}: 64 x 64 tiles
+  GemmArgs dwl;   // dW_L (+ the slice losses): 64 x 64 tiles
+  unsigned n_dwp, n_dx, n_dwl;          // workgroups of each grid (n_dwp and n_dx multiples of 8)
+  unsigned dx_gx, dx_gy, dx_gz, dwl_gx, dwl_gy, dwl_gz;
+  int tiles_m, tiles_n, n_workers;
+};
+
+template <typename T>
+__host__ __device__ constexpr int group_lds_words() {
+  constexpr int BKS = sizeof(T) == 2 ? 64 : 32;
+  int m = dw_persistent_lds_words<T>();
+  if (gemm_lds_words<T, MODE_DX, 64, 64, BKS>() > m) m = gemm_lds_words<T, MODE_DX, 64, 64, BKS>();
+  if (gemm_lds_words<T, MODE_DW, 64, 64, BKS>() > m) m = gemm_lds_words<T, MODE_DW, 64, 64, BKS>();
+  return m;
+}
+
+template <typename T, bool AL_B_LAST>
+__global__ __launch_bounds__(kGemmThreads, 4) void mlp_backward_group_kernel(GroupArgs ga) {
+  constexpr int BKS = sizeof(T) == 2 ? 64 : 32;
+  __shared__ __attribute__((aligned(16))) uint32_t smem[group_lds_words<T>()];
+  unsigned b = blockIdx.x;
+  if (b < ga.n_dwp) {
+    dw_persistent_body<T>(ga.dwp, ga.tiles_m, ga.tiles_n, ga.n_workers, b, ga.n_dwp, smem);
+    return;
+  }
+  b -= ga.n_dwp;
+  if (b < ga.n_dx) {
+    if (b < ga.dx_gx * ga.dx_gy * ga.dx_gz)
+      gemm_tile<T, MODE_DX, 64, 64, BKS, true, true>(ga.dx, b, ga.dx_gx, ga.dx_gy, ga.dx_gz, smem);
+    return;
+  }
+  b -= ga.n_dx;
+  if (b < ga.dwl_gx * ga.dwl_gy * ga.dwl_gz)
+    gemm_tile<T, MODE_DW, 64, 64, BKS, true, AL_B_LAST>(ga.dwl, b, ga.dwl_gx, ga.dwl_gy, ga.dwl_gz, smem);
+}
+
 // ---------------------------------------------------------------- softmax CE
 struct CeArgs {
   const int32_t* y[SYNK_MAX_WORKERS];
@@ -1213,13 +1258,45 @@ static int make_plan(const synk_mlp_desc* m, const int64_t* rows, int n_workers,
   return SYNK_OK;
 }
 
+template <typename T>
+struct GemmTiling {
+  static constexpr int BK_BIG = sizeof(T) == 2 ? 32 : 16, BK_SMALL = sizeof(T) == 2 ? 64 : 32;
+};
+
+// 128 x 128 tiles when they alone fill the chip, 64 x 64 otherwise
+static inline int64_t big_tiles(const GemmArgs& g, int64_t m_max, int grid_z) {
+  return ((m_max + 127) / 128) * ((g.n + 127) / 128) * grid_z;
+}
+
+// vector loads per operand: both (2), only A (1: e.g. a narrow last layer's dZ as B), or neither (0)
+static inline int gemm_alignment(const GemmArgs& g) { return (g.a_vec && g.b_vec) ? 2 : (g.a_vec ? 1 : 0); }
+
+// The tile-walking weight-gradient kernel applies: few rows per worker, in whole rounds of k-tiles.
+template <typename T>
+static bool dw_persistent_ok(const GemmArgs& g, int64_t m_max, int n_workers) {
+  constexpr int BK = GemmTiling<T>::BK_BIG;
+  if (!(big_tiles(g, m_max, n_workers) >= 2 * kNumCU && gemm_alignment(g) == 2 && g.c_vec && g.task_z < 0 &&
+        m_max % 128 == 0 && g.n % 128 == 0))
+    return false;
+  for (int w = 0; w < n_workers; ++w) {
+    const int64_t r = g.row_off[w + 1] - g.row_off[w];
+    if (r % (4 * BK) != 0 || r > 16 * BK) return false;
+  }
+  return true;
+}
+
+static inline unsigned dw_persistent_blocks(const GemmArgs& g, int64_t m_max, int n_workers) {
+  const int64_t big = big_tiles(g, m_max, n_workers);
+  int64_t blocks = big < 2 * kNumCU ? big : 2 * kNumCU;
+  if (big % 8 == 0) blocks = blocks / 8 * 8;
+  return (unsigned)blocks;
+}
+
 template <typename T, int MODE>
 static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStream_t s) {
-  // 128 x 128 tiles when they alone fill the chip, 64 x 64 otherwise
-  constexpr int BK_BIG = sizeof(T) == 2 ? 32 : 16, BK_SMALL = sizeof(T) == 2 ? 64 : 32;
-  const int64_t big = ((m_max + 127) / 128) * ((g.n + 127) / 128) * n_workers;
-  // vector loads per operand: both, only A (e.g. a narrow last layer's dZ as B), or neither
-  const int al = (g.a_vec && g.b_vec) ? 2 : (g.a_vec ? 1 : 0);
+  constexpr int BK_BIG = GemmTiling<T>::BK_BIG, BK_SMALL = GemmTiling<T>::BK_SMALL;
+  const int64_t big = big_tiles(g, m_max, n_workers);
+  const int al = gemm_alignment(g);
 #define SYNK_GEMM(BM_, BN_, BK_)                                                                              \
   do {                                                                                                       \
     if (al == 2)                                                                                             \
@@ -1229,24 +1306,11 @@ static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStrea
     else                                                                                                     \
       hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, BM_, BN_, BK_, false, false>), grid, dim3(kGemmThreads), 0, s, g);\
   } while (0)
-  if (MODE == MODE_DW && big >= 2 * kNumCU && al == 2 && g.c_vec && g.task_z < 0 && m_max % 128 == 0 &&
-      g.n % 128 == 0) {
-    // few rows per worker: the persistent kernel, if every worker's rows are whole rounds of k-tiles
-    bool rounds = true;
-    int64_t most = 0;
-    for (int w = 0; w < n_workers; ++w) {
-      const int64_t r = g.row_off[w + 1] - g.row_off[w];
-      rounds = rounds && r % (4 * BK_BIG) == 0;
-      if (r > most) most = r;
-    }
-    if (rounds && most <= 16 * BK_BIG) {
-      int64_t blocks = big < 2 * kNumCU ? big : 2 * kNumCU;
-      if (big % 8 == 0) blocks = blocks / 8 * 8;
-      hipLaunchKernelGGL((mlp_dw_persistent_kernel<T>), dim3((unsigned)blocks), dim3(kGemmThreads), 0, s, g,
-                         (int)(m_max / 128), (int)(g.n / 128), n_workers);
-      SYNK_LAUNCH_CHECK();
-      return SYNK_OK;
-    }
+  if (MODE == MODE_DW && dw_persistent_ok<T>(g, m_max, n_workers)) {
+    hipLaunchKernelGGL((mlp_dw_persistent_kernel<T>), dim3(dw_persistent_blocks(g, m_max, n_workers)),
+                       dim3(kGemmThreads), 0, s, g, (int)(m_max / 128), (int)(g.n / 128), n_workers);
+    SYNK_LAUNCH_CHECK();
+    return SYNK_OK;
   }
   if (big >= 2 * kNumCU) {
     const dim3 grid((unsigned)((g.n + 127) / 128), (unsigned)((m_max + 127) / 128), n_workers);
@@ -1351,58 +1415,102 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
   }
 
   // ---- backward
-  for (int l = L; l >= 1; --l) {
+  // dW_l[w] = H_{l-1}[w]^T dZ_l[w]; db_l[w] = column sums of dZ_l[w]
+  auto fill_dw = [&](GemmArgs& q, int l, bool with_loss) {
     const int64_t K = p.d[l - 1], N = p.d[l];
-    // dW_l[w] = H_{l-1}[w]^T dZ_l[w]; db_l[w] = column sums of dZ_l[w]
     for (int w = 0; w < n_workers; ++w) {
       // a worker without rows still gets a block (it writes the zero gradient); its
       // operand pointer must be readable because loads are issued unconditionally
-      g.a[w] = l == 1 ? (rows[w] > 0 ? x[w] : (const void*)ws)
+      q.a[w] = l == 1 ? (rows[w] > 0 ? x[w] : (const void*)ws)
                       : (const void*)(act(l - 1) + p.row_off[w] * K);
-      g.c[w] = grad[w] + p.offW[l - 1];
+      q.c[w] = grad[w] + p.offW[l - 1];
     }
-    g.b = dzp(l);
-    g.mask = nullptr;
-    g.bias = nullptr;
-    g.m_fixed = K;
-    g.n = N;
-    g.k_fixed = 0;
-    g.lda = K; g.ldb = N; g.ldc = N; g.ldmask = 0;
-    g.colsum_off = p.offB[l - 1] - p.offW[l - 1];
-    g.relu = 0;
-    g.out_f32 = 1;
-    g.a_vec = (K % V == 0) && (l == 1 ? x_vec : true);
-    g.b_vec = (N % V == 0);
-    g.c_vec = grad_al && N % 4 == 0 && p.offW[l - 1] % 4 == 0;
+    q.b = dzp(l);
+    q.mask = nullptr;
+    q.bias = nullptr;
+    q.m_fixed = K;
+    q.n = N;
+    q.k_fixed = 0;
+    q.lda = K; q.ldb = N; q.ldc = N; q.ldmask = 0;
+    q.colsum_off = p.offB[l - 1] - p.offW[l - 1];
+    q.relu = 0;
+    q.out_f32 = 1;
+    q.a_vec = (K % V == 0) && (l == 1 ? x_vec : true);
+    q.b_vec = (N % V == 0);
+    q.c_vec = grad_al && N % 4 == 0 && p.offW[l - 1] % 4 == 0;
     // the first kernel after the row losses exist also aggregates them over slices (one more grid slice)
-    const bool with_loss = l == L;
-    g.task_z = with_loss ? n_workers : -1;
-    g.task_workers = n_workers;
-    g.task_slices = n_slices;
-    g.task_op = grad_op;
-    g.task_row_loss = row_loss;
-    g.task_loss = loss;
-    if (int rc = launch_gemm<T, MODE_DW>(g, K, n_workers + (with_loss ? 1 : 0), s)) return rc;
-    g.task_z = -1;
+    q.task_z = with_loss ? n_workers : -1;
+    q.task_workers = n_workers;
+    q.task_slices = n_slices;
+    q.task_op = grad_op;
+    q.task_row_loss = row_loss;
+    q.task_loss = loss;
+  };
+  // dZ_{l-1} = (dZ_l W_l^T) * [H_{l-1} > 0]
+  auto fill_dx = [&](GemmArgs& q, int l) {
+    const int64_t K = p.d[l - 1], N = p.d[l];
+    const T* W = wts + p.offW[l - 1];
+    for (int w = 0; w < n_workers; ++w) {
+      q.a[w] = dzp(l) + p.row_off[w] * N;
+      q.c[w] = dzp(l - 1) + p.row_off[w] * K;
+    }
+    q.b = W;
+    q.mask = act(l - 1);
+    q.bias = nullptr;
+    q.m_fixed = 0;
+    q.n = K;          // output columns = fan-in of layer l
+    q.k_fixed = N;    // contraction over the layer's outputs
+    q.lda = N; q.ldb = N; q.ldc = K; q.ldmask = K;
+    q.colsum_off = -1;
+    q.relu = 0;
+    q.a_vec = (N % V == 0);
+    q.b_vec = (N % V == 0) && aligned_to(W, 16);
+    q.c_vec = K % 8 == 0;
+    q.out_f32 = 0;
+    q.task_z = -1;
+  };
 
+  int l = L;
+  if (use_head && L >= 3) {
+    // dZ_L and dZ_{L-1} both exist: dW_L, dW_{L-1} and dZ_{L-2} in one launch when each takes the
+    // tiling the group kernel holds
+    GroupArgs ga;
+    ga.dwl = g; ga.dwp = g; ga.dx = g;
+    fill_dw(ga.dwl, L, true);
+    fill_dw(ga.dwp, L - 1, false);
+    fill_dx(ga.dx, L - 1);
+    const int al_last = gemm_alignment(ga.dwl);
+    const bool ok = al_last >= 1 && big_tiles(ga.dwl, p.d[L - 1], n_workers + 1) < 2 * kNumCU &&
+                    dw_persistent_ok<T>(ga.dwp, p.d[L - 2], n_workers) && gemm_alignment(ga.dx) == 2 &&
+                    big_tiles(ga.dx, p.max_rows, n_workers) < 2 * kNumCU;
+    if (ok) {
+      ga.n_dwp = dw_persistent_blocks(ga.dwp, p.d[L - 2], n_workers);
+      ga.tiles_m = (int)(p.d[L - 2] / 128);
+      ga.tiles_n = (int)(p.d[L - 1] / 128);
+      ga.n_workers = n_workers;
+      ga.dx_gx = (unsigned)((ga.dx.n + 63) / 64);
+      ga.dx_gy = (unsigned)((p.max_rows + 63) / 64);
+      ga.dx_gz = (unsigned)n_workers;
+      ga.n_dx = (ga.dx_gx * ga.dx_gy * ga.dx_gz + 7u) / 8u * 8u;
+      ga.dwl_gx = (unsigned)((ga.dwl.n + 63) / 64);
+      ga.dwl_gy = (unsigned)((p.d[L - 1] + 63) / 64);
+      ga.dwl_gz = (unsigned)(n_workers + 1);
+      ga.n_dwl = ga.dwl_gx * ga.dwl_gy * ga.dwl_gz;
+      const dim3 grid(ga.n_dwp + ga.n_dx + ga.n_dwl);
+      if (al_last == 2)
+        hipLaunchKernelGGL((mlp_backward_group_kernel<T, true>), grid, dim3(kGemmThreads), 0, s, ga);
+      else
+        hipLaunchKernelGGL((mlp_backward_group_kernel<T, false>), grid, dim3(kGemmThreads), 0, s, ga);
+      SYNK_LAUNCH_CHECK();
+      l = L - 2;
+    }
+  }
+  for (; l >= 1; --l) {
+    fill_dw(g, l, l == L);
+    if (int rc = launch_gemm<T, MODE_DW>(g, p.d[l - 1], n_workers + (l == L ? 1 : 0), s)) return rc;
+    g.task_z = -1;
     if (l > 1 && !(use_head && l == L)) {
-      // dZ_{l-1} = (dZ_l W_l^T) * [H_{l-1} > 0]
-      const T* W = wts + p.offW[l - 1];
-      for (int w = 0; w < n_workers; ++w) {
-        g.a[w] = dzp(l) + p.row_off[w] * N;
-        g.c[w] = dzp(l - 1) + p.row_off[w] * K;
-      }
-      g.b = W;
-      g.mask = act(l - 1);
-      g.m_fixed = 0;
-      g.n = K;          // output columns = fan-in of layer l
-      g.k_fixed = N;    // contraction over the layer's outputs
-      g.lda = N; g.ldb = N; g.ldc = K; g.ldmask = K;
-      g.colsum_off = -1;
-      g.a_vec = (N % V == 0);
-      g.b_vec = (N % V == 0) && aligned_to(W, 16);
-      g.c_vec = K % 8 == 0;
-      g.out_f32 = 0;
+      fill_dx(g, l);
       if (int rc = launch_gemm<T, MODE_DX>(g, p.max_rows, n_workers, s)) return rc;
     }
   }
