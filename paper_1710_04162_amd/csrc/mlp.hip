@@ -736,7 +736,7 @@ __device__ __forceinline__ void dw_persistent_body(const GemmArgs& g, int tiles_
   constexpr int WA = tile_words<T, XC, BM, BK>(), WB = tile_words<T, XC, BN, BK>();
   constexpr int WT = (WA + WB + 3) / 4 * 4;
   static_assert(2 * WT + 64 * BN == dw_persistent_lds_words<T>(), "LDS size helper out of step");
-  float* stage = reinterpret_cast<float*>(smem + 2 * WT);       // 64 rows of the fp32 output tile
+  float* stage = reinterpret_cast<float*>(smem + 2 * WT);       // two buffers of 32 rows of the fp32 output tile
 
   const bool producer = threadIdx.x >= kMBlock;
   const int tid = threadIdx.x & (kMBlock - 1);
@@ -766,6 +766,19 @@ __device__ __forceinline__ void dw_persistent_body(const GemmArgs& g, int tiles_
     return true;
   };
   auto k_tiles = [&](int w) { return (int)((g.row_off[w + 1] - g.row_off[w]) / BK); };
+  // Write-out in four passes of 32 rows: two consumer wavefronts put their MFMA
+  // row block into one of two staging buffers, and after the barrier all 512
+  // threads (the producers have nothing else to do here) copy it out as whole
+  // 512-byte row segments while the next pass is written into the other buffer.
+  auto read_out = [&](int ps, float* Cw, int m0, int n0) {
+    constexpr int CPR = BN * 4 / 16;                           // 16-byte chunks per row
+    const float* buf = stage + (ps & 1) * 32 * BN;
+    for (int c = threadIdx.x; c < 32 * CPR; c += kGemmThreads) {
+      const int rl = c / CPR, ch = c - rl * CPR;
+      const f32x4 q = *reinterpret_cast<const f32x4*>(buf + rl * BN + ch * 4);
+      *reinterpret_cast<f32x4*>(Cw + (int64_t)(m0 + ps * 32 + rl) * g.ldc + n0 + ch * 4) = q;
+    }
+  };
 
   if (producer) {
     // per-thread byte offsets inside a tile do not depend on the tile
@@ -825,11 +838,12 @@ __device__ __forceinline__ void dw_persistent_body(const GemmArgs& g, int tiles_
           __syncthreads();
         }
       }
-      // the consumers write the tile out: four barriers of theirs to keep step with
-      __syncthreads();
-      __syncthreads();
-      __syncthreads();
-      __syncthreads();
+      float* Cw = reinterpret_cast<float*>(g.c[w]);
+#pragma unroll
+      for (int ps = 0; ps < 4; ++ps) {
+        __syncthreads();
+        read_out(ps, Cw, m0, n0);
+      }
     }
   } else {
     __syncthreads();                               // stream step 0 is in half 0
@@ -892,26 +906,19 @@ __device__ __forceinline__ void dw_persistent_body(const GemmArgs& g, int tiles_
       // filling the operand halves meanwhile)
       float* Cw = reinterpret_cast<float*>(g.c[w]);
 #pragma unroll
-      for (int ps = 0; ps < 2; ++ps) {
-        if (wm == ps) {
+      for (int ps = 0; ps < 4; ++ps) {
+        if (wm == (ps >> 1)) {
+          float* buf = stage + (ps & 1) * 32 * BN;
 #pragma unroll
-          for (int i = 0; i < TM; ++i)
+          for (int jj = 0; jj < TN; ++jj) {
+            float* sp = buf + (gk * 4) * BN + wn * 64 + jj * 32 + xi;
 #pragma unroll
-            for (int jj = 0; jj < TN; ++jj) {
-              float* sp = stage + (i * 32 + gk * 4) * BN + wn * 64 + jj * 32 + xi;
-#pragma unroll
-              for (int v = 0; v < 16; ++v) sp[((v >> 2) * 8 + (v & 3)) * BN] = acc[i][jj][v];
-              __builtin_amdgcn_sched_barrier(0);
-            }
+            for (int v = 0; v < 16; ++v) sp[((v >> 2) * 8 + (v & 3)) * BN] = acc[ps & 1][jj][v];
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
         __syncthreads();
-        constexpr int CPR = BN * 4 / 16;                       // 16-byte chunks per row
-        for (int c = tid; c < 64 * CPR; c += kMBlock) {
-          const int rl = c / CPR, ch = c - rl * CPR;
-          const f32x4 q = *reinterpret_cast<const f32x4*>(stage + rl * BN + ch * 4);
-          *reinterpret_cast<f32x4*>(Cw + (int64_t)(m0 + ps * 64 + rl) * g.ldc + n0 + ch * 4) = q;
-        }
-        __syncthreads();
+        read_out(ps, Cw, m0, n0);
       }
       if (want_colsum && tid < BN) Cw[g.colsum_off + n0 + tid] = colsum;
     }
