@@ -17,6 +17,9 @@ the definition of what each step of the path computes:
               a ReLU MLP with softmax cross-entropy on a set of rows, the
               sliced/aggregated evaluation of Sec. 5.1 and the worker reduce of
               Sec. 3.2 step 3.
+  convblock   a second such function: a 3x3 convolution + batch-normalisation
+              block with the ending of the scaling study's network (Sec. 6),
+              evaluated per slice the same way.
   reduce      Sec. 3.1 "Build Functions" (a reduce/gather op per output),
               Sec. 3.3 step 2 (all-reduce of the flat gradient).
   collectives Sec. 3.2 "Shared Variable Management" (broadcast, all-reduce,
@@ -36,7 +39,7 @@ hand-worked single elements where they do not, torch.bfloat16 casts) and the pap
 invariant (Sec. 1.1): aggregating independent calls over any subdivision of
 the data equals the one full-batch call.
 
-Parity unpinned: mlp.function(..., bf16_points=True) beyond (a) its rounding
+Parity unpinned: mlp.function and convblock.function with bf16_points=True beyond (a) the rounding
 primitive, pinned against torch.bfloat16, and (b) staying close to the float64
 result (loss within 2e-2, gradient within 1e-1 in the Frobenius norm).
 """

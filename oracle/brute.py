@@ -83,3 +83,54 @@ def rmsprop_constant_gradient(p0, g, lr, rho, eps, k):
         a, b = float(a), float(b)
         out.append(a - lr * b * sum(1.0 / math.sqrt((1.0 - rho ** j) * b * b + eps) for j in range(1, k + 1)))
     return out
+
+
+def conv3x3_point(X, Wc, i, h, w, o):
+    """One output value of the 3x3 convolution with zero padding 1, from its
+    definition: the sum over the 3x3 neighbourhood of pixel (h, w), taking
+    pixels outside the image as zero.  X: [n][H][W][C_in] nested sequences,
+    Wc: [3][3][C_in][C_out]."""
+    H, W, C = len(X[0]), len(X[0][0]), len(X[0][0][0])
+    s = 0.0
+    for dh in (-1, 0, 1):
+        for dw in (-1, 0, 1):
+            hh, ww = h + dh, w + dw
+            if hh < 0 or hh >= H or ww < 0 or ww >= W:
+                continue
+            for c in range(C):
+                s += float(X[i][hh][ww][c]) * float(Wc[dh + 1][dw + 1][c][o])
+    return s
+
+
+def convblock_loss(theta, shape, X, y, eps):
+    """The conv + BN block's mean loss with scalar loops only (no gradient).
+    X: [n][H][W][C_in]."""
+    H, W, cin, cout, classes = shape
+    n = len(X)
+    oWc, og = 0, 9 * cin * cout
+    ob = og + cout
+    oWf = ob + cout
+    obf = oWf + cout * classes
+    Wc = [[[[float(theta[oWc + ((kh * 3 + kw) * cin + c) * cout + o]) for o in range(cout)]
+            for c in range(cin)] for kw in range(3)] for kh in range(3)]
+    z = [[[[conv3x3_point(X, Wc, i, h, w, o) for o in range(cout)] for w in range(W)]
+          for h in range(H)] for i in range(n)]
+    cnt = n * H * W
+    p = [[0.0] * cout for _ in range(n)]
+    for o in range(cout):
+        mu = sum(z[i][h][w][o] for i in range(n) for h in range(H) for w in range(W)) / cnt
+        var = sum((z[i][h][w][o] - mu) ** 2 for i in range(n) for h in range(H) for w in range(W)) / cnt
+        for i in range(n):
+            acc = 0.0
+            for h in range(H):
+                for w in range(W):
+                    v = float(theta[og + o]) * (z[i][h][w][o] - mu) / math.sqrt(var + eps) + float(theta[ob + o])
+                    acc += max(v, 0.0)
+            p[i][o] = acc / (H * W)
+    total = 0.0
+    for i in range(n):
+        logits = [float(theta[obf + k]) + sum(p[i][o] * float(theta[oWf + o * classes + k]) for o in range(cout))
+                  for k in range(classes)]
+        m = max(logits)
+        total += m + math.log(sum(math.exp(t - m) for t in logits)) - logits[int(y[i])]
+    return total / n

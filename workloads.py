@@ -1,4 +1,4 @@
-"""Seeded synthetic inputs for the five workload configurations.
+"""Seeded synthetic inputs for the workload configurations.
 
 Input generation only: no arithmetic of the method lives here (no split, no
 gather, no loss, no update).  Both the test/bench side that drives the HIP
@@ -132,3 +132,38 @@ def config5(rows=65536, classes=1000, n_slices=64, salt=0):
     logits = rng.standard_normal((rows, classes), dtype=np.float32) * np.float32(2.0)
     labels = rng.integers(0, classes, rows).astype(np.int32)
     return dict(name="cfg5_slice_aggregation", logits=logits, labels=labels, n_slices=n_slices)
+
+
+def convblock_param_count(shape):
+    H, W, cin, cout, classes = shape
+    return 9 * cin * cout + 2 * cout + cout * classes + classes
+
+
+def convblock_init(shape, rng):
+    """One flat float32 array: Wc [3 x 3 x C_in x C_out] ~ N(0, 2/(9 C_in)),
+    gamma ~ U[0.5, 1.5), beta ~ N(0, 0.1^2), Wf [C_out x classes] ~
+    N(0, 1/C_out), bf = 0."""
+    H, W, cin, cout, classes = shape
+    return np.concatenate([
+        (rng.standard_normal(9 * cin * cout) * np.sqrt(2.0 / (9 * cin))).astype(np.float32),
+        (0.5 + rng.random(cout)).astype(np.float32),
+        (rng.standard_normal(cout) * 0.1).astype(np.float32),
+        (rng.standard_normal(cout * classes) * np.sqrt(1.0 / cout)).astype(np.float32),
+        np.zeros(classes, dtype=np.float32)])
+
+
+def config6(n_data=256, batch=64, shape=(56, 56, 64, 64, 1000), n_workers=8, n_slices=1, compute="bf16"):
+    """Convolution + batch-normalisation block at the shape of the 3x3
+    convolutions in the first stage of ResNet-50 (56 x 56 positions, 64 -> 64
+    channels; the scaling study's batch of 64 images over 8 workers, no input
+    slicing): images ~N(0,1) fp32 stored channels-last as rows of H*W*C_in
+    values (the study's inputs are random single-precision arrays), labels
+    U{0..classes-1}, batch of seeded random indices."""
+    rng = rng_for(6)
+    H, W, cin, cout, classes = shape
+    data = rng.standard_normal((n_data, H * W * cin), dtype=np.float32)
+    labels = rng.integers(0, classes, n_data).astype(np.int32)
+    idx = rng.integers(0, n_data, batch).astype(np.int32)
+    return dict(name="cfg6_conv_bn_block", shape=tuple(shape), compute=compute, data=data, labels=labels,
+                idx=idx, theta=convblock_init(shape, rng), n_workers=n_workers, n_slices=n_slices,
+                eps=1e-5, lr=0.1, momentum=0.9, weight_decay=1e-4)
