@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4, 5],
+    ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4, 5, 6],
                     help="0 = plain copy of known size (calibrates the rocprofv3 byte counters)")
     ap.add_argument("--rule", default="momentum", choices=["momentum", "nesterov", "rmsprop", "adam"],
                     help="config 3 only: the update rule fused with the N-way average (Sec. 3.3)")
@@ -403,6 +403,73 @@ class EvalStep:
         return n / (time.perf_counter() - t0), "4096 of the 65536 rows, 4 slices (the argmax loop is pure Python)"
 
 
+class ConvStep:
+    """Config 6: the whole step with the conv + batch-norm block as the function."""
+
+    def __init__(self, torch, synk):
+        import numpy as np
+        import workloads
+        from oracle import split as osplit           # host-side share sizes for buffer allocation only
+        self.torch, self.s, self.np = torch, synk, np
+        c = self.c = workloads.config6()
+        rng = np.random.default_rng(6)
+        idx_sets = [c["idx"]] + [rng.integers(0, c["data"].shape[0], len(c["idx"])).astype(np.int32) for _ in range(3)]
+        self.shape, self.N, self.S = c["shape"], c["n_workers"], c["n_slices"]
+        H, W, cin, cout, classes = self.shape
+        self.bf16 = c["compute"] == "bf16"
+        self.cd = synk.SYNK_BF16 if self.bf16 else synk.SYNK_F32
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        self.data, self.labels = up(c["data"]), up(c["labels"])
+        self.B = len(c["idx"])
+        self.P = synk.synk_convblock_param_count(self.shape)
+        self.p, self.v = up(c["theta"]), torch.zeros(self.P, device="cuda")
+        self.rows = osplit.share_sizes(self.B, self.N)
+        xdt = torch.bfloat16 if self.bf16 else torch.float32
+        self.x = [torch.zeros((n, H * W * cin), dtype=xdt, device="cuda") for n in self.rows]
+        self.y = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in self.rows]
+        self.grad = [torch.zeros(self.P, device="cuda") for _ in self.rows]
+        self.loss = torch.zeros(self.N, device="cuda")
+        self.loss_out = torch.zeros(1, device="cuda")
+        self.ws = torch.empty(synk.synk_sliced_grad_conv_workspace_bytes(self.shape, self.cd, self.rows, self.S,
+                                                                         c["eps"]), dtype=torch.uint8, device="cuda")
+        self.units, self.unit = self.B, "samples/s"
+        self.dtype = "bf16" if self.bf16 else "f32"
+        self.workload = ("config 6: conv3x3 + batch-norm + ReLU block %dx%dx%d -> %d, pool, %d-way softmax; step "
+                         "with batch %d over %d worker shares x %d slice, bf16 contraction inputs / fp32 "
+                         "accumulate" % (H, W, cin, cout, classes, self.B, self.N, self.S))
+        # dominant kernel: the forward convolution, a [pixels x 9 C_in] . [9 C_in x C_out] contraction
+        self.dom_name = "conv3x3_fwd_kernel"
+        self.dom_bound, self.dom_unit = "mfma", "TFLOP/s"
+        self.dom_peak = 2500.0 if self.bf16 else 157.3
+        self.dom_work = 2.0 * self.B * H * W * 9 * cin * cout       # flops per launch
+        self.dom_bytes = self.B * H * W * (cin * (2 if self.bf16 else 4) + cout * 4)
+        s = synk
+        self.call_gather = [s.prepare(s.synk_gather_rows, self.data, up(ix), self.x, labels=self.labels,
+                                      dst_labels=self.y) for ix in idx_sets]
+        self.call_grad = s.prepare(s.synk_sliced_grad_conv, self.shape, self.cd, c["eps"], self.p, self.x, self.y,
+                                   self.rows, self.S, s.SYNK_MEAN, self.grad, self.loss, self.ws)
+        self.call_update = s.prepare(s.synk_reduce_sgd_update, self.grad, self.p, self.v, c["lr"], c["momentum"],
+                                     c["weight_decay"], loss_in=self.loss, loss_out=self.loss_out)
+
+    def step(self, i, timer):
+        self.call_gather[i % len(self.call_gather)]()
+        timer.bracket(self.call_grad)
+        self.call_update()
+
+    def cpu_baseline(self):
+        from oracle import convblock as oconv, gather as ogather, update as oupdate
+        c, np = self.c, self.np
+        theta, v = c["theta"].astype(np.float64), np.zeros(self.P)
+        n = self.rows[0]
+        t0 = time.perf_counter()
+        for k in range(2):
+            ix = c["idx"][k * n:(k + 1) * n]
+            _, g = oconv.function(theta, self.shape, ogather.gather_rows(c["data"], ix),
+                                  ogather.gather_rows(c["labels"], ix), c["eps"])
+            oupdate.sgd_momentum(theta, v, g, c["lr"], c["momentum"], c["weight_decay"])
+        return 2 * n / (time.perf_counter() - t0), "2 of the 8 worker shares (8 images each): function + update"
+
+
 class CopyStep:
     """Config 0: a plain copy kernel of known size (1 GiB in, 1 GiB out), against which the
     FETCH_SIZE / WRITE_SIZE counters of the other kernels are scaled."""
@@ -435,8 +502,8 @@ def main():
 
     wl = {0: lambda: CopyStep(torch, synk), 1: lambda: MlpStep(torch, synk, 1, a.batch), 2: lambda: MlpStep(torch, synk, 2, a.batch),
           3: lambda: (CollectiveStep(torch, synk, a.collective) if a.collective else ReduceStep(torch, synk, a.rule)), 4: lambda: GatherStep(torch, synk, a.indexing),
-          5: lambda: EvalStep(torch, synk)}[a.config]()
-    steps = a.steps if a.steps is not None else {0: 50, 1: 2000, 2: 1000, 3: 300, 4: 1000, 5: 1000}[a.config]
+          5: lambda: EvalStep(torch, synk), 6: lambda: ConvStep(torch, synk)}[a.config]()
+    steps = a.steps if a.steps is not None else {0: 50, 1: 2000, 2: 1000, 3: 300, 4: 1000, 5: 1000, 6: 300}[a.config]
     warmup = a.warmup if a.warmup is not None else 20
 
     timer = Timer(torch, synk, steps)
@@ -453,15 +520,19 @@ def main():
     # The event pair sits on the kernel's own dispatch: begin-to-end time of the kernel, the same
     # quantity as the kernel duration in a rocprofv3 kernel trace.
     dom_ms = timer.mean_ms()
-    achieved = wl.dom_bytes / (dom_ms * 1e-3) / 1e9
+    bound = getattr(wl, "dom_bound", "hbm")
+    if bound == "hbm":
+        achieved, peak, unit = wl.dom_bytes / (dom_ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
+    else:
+        achieved, peak, unit = wl.dom_work / (dom_ms * 1e-3) / 1e12, wl.dom_peak, wl.dom_unit
     out = {
         "metric": "samples/sec for gather+sliced grad+reduce+SGD step; HBM GB/s and MFMA % of peak",
         "value": wl.units * steps / dt, "unit": wl.unit, "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.workload, "units_per_step": wl.units},
-        "roofline": {"bound": "hbm", "kernel": wl.dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+        "roofline": {"bound": bound, "kernel": wl.dom_name, "achieved": achieved, "peak": peak,
+                     "unit": unit, "frac": achieved / peak,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (a.rule == "momentum" and not a.collective and a.indexing == "list" and a.batch is None) else None, "traffic_unit": "HBM bytes per launch",
                      "bytes_per_launch": wl.dom_bytes, "ms_per_launch": dom_ms},
     }

@@ -11,7 +11,8 @@
  *                           the same with a slice for a list, the scatter of an
  *                           array over the workers (Sec. 4.3), and indexing of
  *                           shares that already live on the workers (Sec. 5.2)
- *   synk_sliced_grad        the gradient function run over every worker's
+ *   synk_sliced_grad, synk_sliced_grad_conv
+ *                           the gradient function run over every worker's
  *                           share in slices, slice results aggregated on the
  *                           GPU (Sec. 5.1), one flat gradient per worker
  *                           (Sec. 3.3 step 1)
@@ -257,6 +258,65 @@ int synk_sliced_grad(const synk_mlp_desc* m, const float* params, const void* pa
                      int n_workers, int n_slices, int grad_op,
                      float* const* grad, float* loss,
                      void* ws, size_t ws_bytes, void* stream);
+
+/* A second function for the same sliced call (Sec. 3.2, 5.1; Sec. 3.3 step 1):
+ * one block of the network family the scaling study trains (Sec. 6), a 3x3
+ * convolution + batch normalisation + ReLU, closed the way that network ends
+ * (global average pool, one affine layer, softmax cross-entropy).
+ *
+ * Function on an image set R (n images, each H x W x C_in, channels last, i.e.
+ * a row of H*W*C_in values as synk_gather_rows writes it):
+ *   z = conv3x3(X, Wc), stride 1, zero padding 1, no bias;
+ *   mu_c, var_c = mean and biased variance of z[..., c] over all n*H*W positions
+ *   of R;  xhat = (z - mu) / sqrt(var + eps);  a = relu(gamma * xhat + beta);
+ *   p_i = mean of a_i over its H*W positions;  logits = p Wf + bf;
+ *   l_i = logsumexp(logits_i) - logits_i[y_i];  loss_R = mean_i l_i;
+ *   g_R = d loss_R / d params.  relu'(0) = 0.
+ * Every slice is one call of the function (Sec. 5.1), so mu and var are those
+ * of the slice; aggregation over a worker's slices as in synk_sliced_grad
+ * (SYNK_MEAN: weights |R_s|/|R_w|; SYNK_SUM).  All slices see the same
+ * parameter values.
+ *
+ *   d.compute_dtype SYNK_F32: fp32 contraction operands; SYNK_BF16: X, Wc and
+ *                   dz are rounded (nearest-even) to bf16 where they enter a
+ *                   contraction, products accumulate in fp32; everything else
+ *                   (statistics, normalisation, pooling, the affine layer, the
+ *                   loss) is fp32 in both modes
+ *   params          device float[P]: Wc [3 x 3 x C_in x C_out] (tap-major: the
+ *                   [9 C_in x C_out] matrix of the convolution written as a
+ *                   product), gamma [C_out], beta [C_out], Wf [C_out x
+ *                   classes] row-major, bf [classes]; 16-byte aligned
+ *   x               host array[n_workers] of device [rows[w] x H*W*C_in]
+ *                   buffers in compute_dtype, 16-byte aligned
+ *   y               host array[n_workers] of device int32[rows[w]]; a label
+ *                   outside [0, classes) contributes as if no class were the
+ *                   target (never reads out of bounds)
+ *   rows            host int64[n_workers] images per worker, >= 0, not all 0
+ *   grad            host array[n_workers] of device float[P], 16-byte aligned;
+ *                   fully overwritten (a worker with no images gets zeros)
+ *   loss            device float[n_workers]
+ *   ws              synk_sliced_grad_conv_workspace_bytes(...)
+ * Limits: C_in and C_out multiples of 8, C_out <= 512, classes <= 4096, H, W,
+ * C_in <= 4096, n_workers * n_slices <= 65535, total pixels (images * H * W)
+ * below 2^29.
+ * Errors: NULL -> ERR_NULL; limits, rows < 0, all rows zero, n_workers out of
+ * range, n_slices <= 0, eps < 0 -> ERR_SHAPE; compute_dtype -> ERR_DTYPE;
+ * grad_op not SUM/MEAN -> ERR_OP; alignment -> ERR_ALIGN; ws -> ERR_WORKSPACE.
+ */
+typedef struct {
+  int height, width, c_in, c_out, classes;
+  int compute_dtype;
+  float eps;
+} synk_convblock_desc;
+
+int synk_convblock_param_count(const synk_convblock_desc* d, int64_t* count);
+int synk_sliced_grad_conv_workspace_bytes(const synk_convblock_desc* d, const int64_t* rows,
+                                          int n_workers, int n_slices, size_t* bytes);
+int synk_sliced_grad_conv(const synk_convblock_desc* d, const float* params,
+                          const void* const* x, const int32_t* const* y, const int64_t* rows,
+                          int n_workers, int n_slices, int grad_op,
+                          float* const* grad, float* loss,
+                          void* ws, size_t ws_bytes, void* stream);
 
 /* out[i] = bf16(in[i]), round-to-nearest-even; device float[len] -> device
  * bf16[len].  Makes the params_lp array for a first step. */

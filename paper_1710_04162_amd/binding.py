@@ -22,6 +22,7 @@ __all__ = [
     "synk_sgd_update", "synk_reduce_sgd_update", "synk_reduce_update",
     "synk_broadcast", "synk_all_reduce", "synk_all_gather",
     "synk_gather_slice", "synk_scatter_rows", "synk_gather_resident", "synk_profile_next_launch",
+    "synk_convblock_param_count", "synk_sliced_grad_conv_workspace_bytes", "synk_sliced_grad_conv",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsynk.so")
@@ -55,6 +56,11 @@ class UpdateDesc(ctypes.Structure):
                 ("beta2", _f32), ("eps", _f32), ("weight_decay", _f32), ("step", _i64)]
 
 
+class ConvBlockDesc(ctypes.Structure):
+    _fields_ = [("height", _int), ("width", _int), ("c_in", _int), ("c_out", _int), ("classes", _int),
+                ("compute_dtype", _int), ("eps", _f32)]
+
+
 SYNK_RULE_MOMENTUM, SYNK_RULE_NESTEROV, SYNK_RULE_RMSPROP, SYNK_RULE_ADAM = 0, 1, 2, 3
 RULE = dict(momentum=SYNK_RULE_MOMENTUM, nesterov=SYNK_RULE_NESTEROV, rmsprop=SYNK_RULE_RMSPROP,
             adam=SYNK_RULE_ADAM)
@@ -83,6 +89,13 @@ lib.synk_sliced_grad_workspace_bytes.argtypes = [ctypes.POINTER(MlpDesc), _pi64,
                                                  ctypes.POINTER(_sz)]
 lib.synk_sliced_grad.argtypes = [ctypes.POINTER(MlpDesc), _vp, _vp, _pp, _pp, _pi64, _int, _int,
                                  _int, _pp, _vp, _vp, _sz, _vp]
+lib.synk_convblock_param_count.argtypes = [ctypes.POINTER(ConvBlockDesc), _pi64]
+lib.synk_sliced_grad_conv_workspace_bytes.argtypes = [ctypes.POINTER(ConvBlockDesc), _pi64, _int, _int,
+                                                      ctypes.POINTER(_sz)]
+lib.synk_sliced_grad_conv.argtypes = [ctypes.POINTER(ConvBlockDesc), _vp, _pp, _pp, _pi64, _int, _int, _int, _pp,
+                                      _vp, _vp, _sz, _vp]
+for _n in ("synk_convblock_param_count", "synk_sliced_grad_conv_workspace_bytes", "synk_sliced_grad_conv"):
+    getattr(lib, _n).restype = _int
 lib.synk_cast_bf16.argtypes = [_vp, _vp, _i64, _vp]
 lib.synk_sliced_eval_workspace_bytes.argtypes = [_i64, _i64, _int, ctypes.POINTER(_sz)]
 lib.synk_sliced_eval.argtypes = [_vp, _vp, _i64, _i64, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
@@ -245,6 +258,39 @@ def synk_sliced_grad(dims, compute_dtype, params, params_lp, x, y, rows, n_slice
             tg, _ptr(loss), wsp, wsb, _stream(stream))
     return _run(lib.synk_sliced_grad, args, (desc, params, params_lp, x, y, r, grad, loss, ws, tx, ty, tg),
                 "synk_sliced_grad", _prepare)
+
+
+def _conv_desc(shape, compute_dtype, eps):
+    H, W, cin, cout, classes = [int(v) for v in shape]
+    return ConvBlockDesc(H, W, cin, cout, classes, compute_dtype, float(eps))
+
+
+def synk_convblock_param_count(shape, compute_dtype=SYNK_F32, eps=1e-5):
+    out = ctypes.c_int64(0)
+    _check(lib.synk_convblock_param_count(ctypes.byref(_conv_desc(shape, compute_dtype, eps)), ctypes.byref(out)),
+           "synk_convblock_param_count")
+    return out.value
+
+
+def synk_sliced_grad_conv_workspace_bytes(shape, compute_dtype, rows, n_slices, eps=1e-5):
+    out = _sz(0)
+    r = (ctypes.c_int64 * len(rows))(*[int(x) for x in rows])
+    _check(lib.synk_sliced_grad_conv_workspace_bytes(ctypes.byref(_conv_desc(shape, compute_dtype, eps)), r,
+                                                     len(rows), n_slices, ctypes.byref(out)),
+           "synk_sliced_grad_conv_workspace_bytes")
+    return out.value
+
+
+def synk_sliced_grad_conv(shape, compute_dtype, eps, params, x, y, rows, n_slices, grad_op, grad, loss, ws,
+                          stream=None, _prepare=False):
+    r = (ctypes.c_int64 * len(rows))(*[int(v) for v in rows])
+    wsp, wsb = _ws(ws)
+    desc = _conv_desc(shape, compute_dtype, eps)
+    tx, ty, tg = _table(x), _table(y), _table(grad)
+    args = (ctypes.byref(desc), _ptr(params), tx, ty, r, len(rows), n_slices, grad_op, tg, _ptr(loss), wsp, wsb,
+            _stream(stream))
+    return _run(lib.synk_sliced_grad_conv, args, (desc, params, x, y, r, grad, loss, ws, tx, ty, tg),
+                "synk_sliced_grad_conv", _prepare)
 
 
 def synk_cast_bf16(src, dst, stream=None):

@@ -166,6 +166,47 @@ def test_sliced_grad_argument_checks_and_workspace():
     assert call(x=_tbl(FAKE, None)) == -1
 
 
+def test_sliced_grad_conv_argument_checks_and_workspace():
+    shape = (6, 5, 8, 16, 10)
+    assert synk.synk_convblock_param_count(shape) == 9 * 8 * 16 + 2 * 16 + 16 * 10 + 10
+    assert synk.synk_convblock_param_count((56, 56, 64, 64, 1000)) == 9 * 64 * 64 + 128 + 64 * 1000 + 1000
+    b32 = synk.synk_sliced_grad_conv_workspace_bytes(shape, synk.SYNK_F32, [5, 0, 7], 2)
+    b16 = synk.synk_sliced_grad_conv_workspace_bytes(shape, synk.SYNK_BF16, [5, 0, 7], 2)
+    assert b32 > b16 > 0 and b32 % 256 == 0 and b16 % 256 == 0
+    for bad, status in [((6, 5, 7, 16, 10), -2), ((6, 5, 8, 12, 10), -2), ((0, 5, 8, 16, 10), -2),
+                        ((6, 5, 8, 520, 10), -2), ((6, 5, 8, 16, 5000), -2), ((6, 5, 8, 16, 0), -2)]:
+        with pytest.raises(synk.SynkError) as e:
+            synk.synk_sliced_grad_conv_workspace_bytes(bad, synk.SYNK_F32, [4], 1)
+        assert e.value.status == status
+    with pytest.raises(synk.SynkError) as e:
+        synk.synk_sliced_grad_conv_workspace_bytes(shape, synk.SYNK_F32, [0, 0], 1)
+    assert e.value.status == -2
+    with pytest.raises(synk.SynkError) as e:
+        synk.synk_sliced_grad_conv_workspace_bytes(shape, synk.SYNK_U8, [4], 1)
+    assert e.value.status == -3
+    with pytest.raises(synk.SynkError) as e:
+        synk.synk_sliced_grad_conv_workspace_bytes(shape, synk.SYNK_F32, [4], 1, eps=-1.0)
+    assert e.value.status == -2
+
+    f = lib.synk_sliced_grad_conv
+    d = synk._conv_desc(shape, synk.SYNK_F32, 1e-5)
+    rows = (ctypes.c_int64 * 2)(4, 4)
+    t2 = _tbl(FAKE, FAKE)
+
+    def call(desc=d, params=FAKE, x=t2, y=t2, r=rows, nw=2, ns=2, op=1, grad=t2, loss=FAKE, ws=FAKE,
+             wsb=1 << 30):
+        return f(ctypes.byref(desc), params, x, y, r, nw, ns, op, grad, loss, ws, wsb, None)
+
+    assert call(params=None) == -1 and call(x=None) == -1 and call(loss=None) == -1 and call(r=None) == -1
+    assert call(ns=0) == -2 and call(nw=0) == -2 and call(nw=65) == -2
+    assert call(r=(ctypes.c_int64 * 2)(4, -1)) == -2
+    assert call(op=2) == -4
+    assert call(ws=None) == -6 and call(wsb=16) == -6 and call(ws=FAKE + 16) == -6
+    assert call(grad=_tbl(FAKE, FAKE + 4)) == -5 and call(x=_tbl(FAKE + 8, FAKE)) == -5
+    assert call(params=FAKE + 4) == -5
+    assert call(x=_tbl(FAKE, None)) == -1 and call(y=_tbl(None, FAKE)) == -1
+
+
 def test_sliced_eval_argument_checks_and_workspace():
     assert synk.synk_sliced_eval_workspace_bytes(65536, 1000, 64) >= 64 * 1000 * 4
     for bad in [(0, 10, 1), (10, 0, 1), (10, 5000, 1), (10, 10, 0)]:

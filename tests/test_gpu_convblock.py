@@ -1,0 +1,150 @@
+"""GPU parity of the conv + batch-norm block as the sliced gradient function
+(synk_sliced_grad_conv) against the CPU oracle, through the C ABI.
+
+fp32 cases are held to 1e-4, bf16-input cases to 2e-2, per tensor as
+max|got-ref|/max|ref|.  For bf16 the reference is the oracle with its values
+rounded to bfloat16 at the same points as the kernels (X, Wc and dz)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from helpers import TOL_BF16, TOL_F32, rel_err
+from oracle import convblock as oconv, gather as ogather, split as osplit
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def synk():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1710_04162_amd import binding
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def tensors(flat, shape):
+    H, W, cin, cout, classes = shape
+    b = np.cumsum([0, 9 * cin * cout, cout, cout, cout * classes, classes])
+    return [(n, flat[b[i]:b[i + 1]]) for i, n in enumerate(["Wc", "gamma", "beta", "Wf", "bf"])]
+
+
+def small_cfg(shape, n_data, seed):
+    rng = np.random.default_rng(seed)
+    H, W, cin, cout, classes = shape
+    theta = workloads.convblock_init(shape, rng)
+    theta[-classes:] = (rng.standard_normal(classes) * 0.1).astype(np.float32)
+    return dict(shape=shape, data=rng.standard_normal((n_data, H * W * cin)).astype(np.float32),
+                labels=rng.integers(0, classes, n_data).astype(np.int32), theta=theta)
+
+
+def run_gpu(synk, cfg, idx, n_workers, n_slices, op, bf16, eps=1e-5, rows=None):
+    shape = cfg["shape"]
+    cd = synk.SYNK_BF16 if bf16 else synk.SYNK_F32
+    P = synk.synk_convblock_param_count(shape)
+    assert P == cfg["theta"].size
+    rows = osplit.share_sizes(len(idx), n_workers) if rows is None else rows
+    xdt = torch.bfloat16 if bf16 else torch.float32
+    x = [torch.zeros((n, cfg["data"].shape[1]), dtype=xdt, device="cuda") for n in rows]
+    y = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in rows]
+    synk.synk_gather_rows(dev(cfg["data"]), dev(idx), x, labels=dev(cfg["labels"]), dst_labels=y)
+    grad = [torch.full((P,), 123.0, device="cuda") for _ in rows]
+    loss = torch.full((len(rows),), -1.0, device="cuda")
+    ws = torch.empty(synk.synk_sliced_grad_conv_workspace_bytes(shape, cd, rows, n_slices, eps),
+                     dtype=torch.uint8, device="cuda")
+    synk.synk_sliced_grad_conv(shape, cd, eps, dev(cfg["theta"]), x, y, rows, n_slices, synk.OP[op], grad, loss, ws)
+    torch.cuda.synchronize()
+    return [g.cpu().numpy() for g in grad], loss.cpu().numpy()
+
+
+def check(cfg, idx, n_workers, n_slices, op, bf16, got_g, got_l, eps=1e-5):
+    tol = TOL_BF16 if bf16 else TOL_F32
+    ref = oconv.sliced(cfg["theta"], cfg["shape"], cfg["data"], cfg["labels"], idx, n_workers, n_slices,
+                       grad_op=op, eps=eps, bf16_points=bf16)
+    for w in range(n_workers):
+        for (name, g), (_, r) in zip(tensors(got_g[w], cfg["shape"]), tensors(ref["worker_grads"][w], cfg["shape"])):
+            assert rel_err(g, r) < tol, (w, name, rel_err(g, r))
+        assert abs(got_l[w] - ref["worker_losses"][w]) < tol * max(1.0, abs(ref["worker_losses"][w])), w
+
+
+@pytest.mark.parametrize("shape,B,N,S,op", [
+    ((4, 4, 8, 8, 5), 6, 2, 1, "mean"),
+    ((5, 7, 8, 24, 10), 13, 3, 2, "mean"),      # ragged shares, ragged slices, odd image sizes
+    ((5, 7, 8, 24, 10), 13, 3, 2, "sum"),
+    ((9, 6, 16, 8, 3), 7, 2, 3, "mean"),
+    ((1, 1, 8, 8, 4), 9, 2, 2, "mean"),         # one-pixel images: only the centre tap
+    ((3, 1, 8, 16, 4), 5, 1, 1, "mean"),        # one column: no left / right neighbours
+    ((12, 12, 72, 72, 17), 5, 2, 1, "mean"),    # channels beyond one 64-wide tile, chunk with few rows
+    ((20, 20, 8, 8, 300), 4, 2, 2, "sum"),      # more than one chunk of pixels per image, classes > 256
+])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_sliced_conv_block_matches_oracle(synk, shape, B, N, S, op, bf16):
+    cfg = small_cfg(shape, 24, seed=sum(shape) + B)
+    idx = np.random.default_rng(B).integers(0, 24, B).astype(np.int32)
+    g, l = run_gpu(synk, cfg, idx, N, S, op, bf16)
+    check(cfg, idx, N, S, op, bf16, g, l)
+
+
+def test_workers_without_images_get_zeros(synk):
+    shape = (4, 5, 8, 8, 6)
+    cfg = small_cfg(shape, 10, seed=3)
+    idx = np.array([1, 7], dtype=np.int32)           # 2 images over 4 workers: two workers are empty
+    g, l = run_gpu(synk, cfg, idx, 4, 2, "mean", False)
+    check(cfg, idx, 4, 2, "mean", False, g, l)
+    for w in (2, 3):
+        assert not g[w].any() and l[w] == 0.0
+
+
+def test_label_out_of_range_means_no_target_class(synk):
+    shape = (3, 3, 8, 8, 4)
+    cfg = small_cfg(shape, 6, seed=4)
+    cfg["labels"][2] = 9
+    idx = np.array([0, 2, 3], dtype=np.int32)
+    g, l = run_gpu(synk, cfg, idx, 1, 1, "mean", False)
+    assert np.isfinite(g[0]).all() and np.isfinite(l).all()
+    # the other images' labels still act: against an oracle call with image 2's
+    # loss term replaced by logsumexp alone the bias gradient sums to 1/3
+    assert abs(g[0][-4:].sum() - 1.0 / 3.0) < 1e-5
+
+
+def test_two_calls_reuse_the_workspace(synk):
+    shape = (6, 6, 8, 16, 5)
+    cfg = small_cfg(shape, 12, seed=5)
+    idx = np.arange(8, dtype=np.int32)
+    a = run_gpu(synk, cfg, idx, 2, 2, "mean", True)
+    b = run_gpu(synk, cfg, idx, 2, 2, "mean", True)
+    for x, y in zip(a[0], b[0]):
+        assert np.array_equal(x, y)      # run-to-run reproducible: fixed summation orders
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_mid_size_block_spans_many_tiles(synk, bf16):
+    # 3 workers x 2 slices, 28 x 28 x 64 -> 64: several 128-pixel tiles per unit with a ragged
+    # last one, a full 64-wide channel tile, several runs of the weight gradient
+    shape = (28, 28, 64, 64, 100)
+    cfg = small_cfg(shape, 16, seed=6)
+    idx = np.random.default_rng(6).integers(0, 16, 11).astype(np.int32)
+    g, l = run_gpu(synk, cfg, idx, 3, 2, "mean", bf16)
+    check(cfg, idx, 3, 2, "mean", bf16, g, l)
+
+
+def test_full_size_config6_sampled_against_oracle(synk):
+    # the bench's launch configuration; the oracle computes two of the eight workers
+    cfg = workloads.config6()
+    bf16 = cfg["compute"] == "bf16"
+    g, l = run_gpu(synk, cfg, cfg["idx"], cfg["n_workers"], cfg["n_slices"], "mean", bf16, eps=cfg["eps"])
+    bounds = osplit.share_bounds(len(cfg["idx"]), cfg["n_workers"])
+    for w in (0, 5):
+        a, b = bounds[w]
+        lr, gr = oconv.function(cfg["theta"], cfg["shape"], ogather.gather_rows(cfg["data"], cfg["idx"][a:b]),
+                                ogather.gather_rows(cfg["labels"], cfg["idx"][a:b]), eps=cfg["eps"],
+                                bf16_points=bf16)
+        for (name, gg), (_, r) in zip(tensors(g[w], cfg["shape"]), tensors(gr, cfg["shape"])):
+            assert rel_err(gg, r) < TOL_BF16, (w, name, rel_err(gg, r))
+        assert abs(l[w] - lr) < TOL_BF16 * max(1.0, abs(lr))
+    for w in range(cfg["n_workers"]):
+        assert np.isfinite(g[w]).all()
+        assert abs(g[w][-cfg["shape"][4]:].sum()) < 1e-5      # softmax: the last bias gradient sums to zero
