@@ -437,12 +437,13 @@ class ConvStep:
         self.workload = ("config 6: conv3x3 + batch-norm + ReLU block %dx%dx%d -> %d, pool, %d-way softmax; step "
                          "with batch %d over %d worker shares x %d slice, bf16 contraction inputs / fp32 "
                          "accumulate" % (H, W, cin, cout, classes, self.B, self.N, self.S))
-        # dominant kernel: the forward convolution, a [pixels x 9 C_in] . [9 C_in x C_out] contraction
-        self.dom_name = "conv3x3_fwd_kernel"
+        # dominant kernel: the weight gradient of the convolution, a [9 C_in x pixels] . [pixels x C_out]
+        # contraction (as many flops as the forward convolution)
+        self.dom_name = "conv3x3_dw_rows_kernel"
         self.dom_bound, self.dom_unit = "mfma", "TFLOP/s"
         self.dom_peak = 2500.0 if self.bf16 else 157.3
         self.dom_work = 2.0 * self.B * H * W * 9 * cin * cout       # flops per launch
-        self.dom_bytes = self.B * H * W * (cin * (2 if self.bf16 else 4) + cout * 4)
+        self.dom_bytes = self.B * H * W * (cin + cout) * (2 if self.bf16 else 4)
         s = synk
         self.call_gather = [s.prepare(s.synk_gather_rows, self.data, up(ix), self.x, labels=self.labels,
                                       dst_labels=self.y) for ix in idx_sets]

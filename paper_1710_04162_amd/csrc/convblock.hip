@@ -82,6 +82,17 @@ __device__ __forceinline__ f32x16 zero16() {
   return a;
 }
 
+// 16 bytes at base + byte_off if ok, else zeros.  The load itself is unconditional (a refused
+// vector reads `base`, which must be a valid address) and the zeroing is a bit mask: a select
+// would let the compiler fold the pair into a branch around the load, and a load inside a
+// branch is waited for before the next one is issued.
+__device__ __forceinline__ u32x4 load_or_zero(const void* base, int64_t byte_off, bool ok) {
+  const int64_t m = -(int64_t)ok;
+  const u32x4 v = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(base) + (byte_off & m));
+  const uint32_t k = (uint32_t)m;
+  return u32x4{v.x & k, v.y & k, v.z & k, v.w & k};
+}
+
 // One 16-byte operand pair -> the MFMAs it feeds.  bf16: 8 contraction steps in
 // one instruction.  fp32: lane group g holds steps 4g..4g+3 of an 8-step run;
 // instruction j takes element j of both operands (any pairing of steps works
@@ -110,6 +121,26 @@ __global__ __launch_bounds__(kThreads) void conv_weight_kernel(const float* __re
   const float v = params[(int64_t)k * cout + o];
   if (sizeof(T) == 2) reinterpret_cast<uint16_t*>(wmat)[i] = f32_to_bf16(v);
   else reinterpret_cast<float*>(wmat)[i] = v;
+}
+
+// The same operand in the order the padded-patch kernel's wavefronts read it:
+// one 1 KB block per (tap, 64-channel input chunk, 32-wide output tile, step
+// kk): lane (xi, gk) owns the 8 values Wc[tap*C_in + chunk*64 + kk*16 + gk*8 +
+// e][tile*32 + xi], so that a wavefront's operand load is one contiguous KB.
+// Output channels past C_out read as zero.
+__global__ __launch_bounds__(kThreads) void conv_weight_frag_kernel(const float* __restrict__ params,
+                                                                    uint16_t* __restrict__ wfrag, int cin,
+                                                                    int cout, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;   // one bf16 value
+  if (i >= total) return;
+  const int e = (int)(i & 7), lane = (int)((i >> 3) & 63), kk = (int)((i >> 9) & 3);
+  const int64_t blk = i >> 11;                 // (tap * chunks + chunk) * tiles + tile
+  const int tiles = (cout + 31) / 32, chunks = cin / 64;
+  const int tile = (int)(blk % tiles);
+  const int64_t tc = blk / tiles;
+  const int chunk = (int)(tc % chunks), tap = (int)(tc / chunks);
+  const int k = tap * cin + chunk * 64 + kk * 16 + (lane >> 5) * 8 + e, o = tile * 32 + (lane & 31);
+  wfrag[i] = o < cout ? f32_to_bf16(params[(int64_t)k * cout + o]) : (uint16_t)0;
 }
 
 // ------------------------------------------------------------ forward conv
@@ -180,16 +211,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_kernel(WorkerTable ta
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       const bool ok = cok && ((amask[it] & need) == need);
-      const T* p = ok ? arow[it] + delta : xw;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(p);
-      ra[it] = ok ? v : zero;
+      ra[it] = load_or_zero(xw, ((arow[it] - xw) + delta) * (int64_t)sizeof(T), ok);
     }
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
       const bool ok = cok && bok[it];
-      const T* p = ok ? brow[it] + tap * sh.cin + c : wmat;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(p);
-      rb[it] = ok ? v : zero;
+      rb[it] = load_or_zero(wmat, ((brow[it] - wmat) + tap * sh.cin + c) * (int64_t)sizeof(T), ok);
     }
   };
   auto lstore = [&](int buf) {
@@ -232,6 +259,138 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_kernel(WorkerTable ta
       for (int v = 0; v < 16; ++v) {
         const int row = r0 + (v >> 2) * 8 + (v & 3);
         if (row < M) zu[(int64_t)row * sh.cout + col] = acc[i][v];
+      }
+    }
+  }
+}
+
+// The same contraction for bf16 with C_in a multiple of 64 and rows of at most
+// 61 pixels, in the coordinates of the zero-padded image: position u = hp * Wp +
+// wp on the (H+2) x (W+2) grid, Wp = W + 2.  There a tap is the plain shift
+// (kh-1) * Wp + (kw-1) of the position index, with no case distinction at the
+// border.  A workgroup takes 256 consecutive positions of one image (from the
+// first real pixel on; border positions in between are computed and dropped)
+// and lays the positions it can reach, one 64-channel chunk at a time, into LDS
+// once, zeros included; the nine taps then read shifted rows of that patch.
+// Wave (row half, column tile) owns 128 positions x 32 channels; its slice of
+// the weights comes straight from memory in operand order
+// (conv_weight_frag_kernel), one tap ahead, so the tap loop has no barrier.
+constexpr int kPatchTile = 256, kPatchMaxRows = kPatchTile + 2 * 64;
+
+__global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_patch_kernel(WorkerTable tab, ConvShape sh,
+                                                                        const bf16_t* __restrict__ wmat,
+                                                                        float* __restrict__ z) {
+  __shared__ __attribute__((aligned(16))) char patch[kPatchMaxRows * kLdsRow];
+  __shared__ int zrow[kPatchTile];
+
+  const int img = blockIdx.z, tile = blockIdx.x, n0 = blockIdx.y * 64;
+  int w = 0;
+  while (w + 1 < sh.n_workers && tab.row_off[w + 1] <= img) ++w;
+  const bf16_t* __restrict__ xi_ = reinterpret_cast<const bf16_t*>(tab.x[w]) +
+                                   (int64_t)(img - tab.row_off[w]) * sh.HW * sh.cin;
+  const int Wp = sh.W + 2;
+  const int first = Wp + 1;                       // position of pixel (0, 0)
+  const int n_out = sh.H * Wp - 2;                // positions from the first to the last real pixel
+  const int prow = kPatchTile + 2 * Wp + 2;       // patch rows: the tile and Wp + 1 positions either side
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int xi = lane & 31, gk = lane >> 5, rh = wv >> 1, ct = wv & 1;
+  const int kv = tid & 7, ur = tid >> 3;
+
+  // output row of every position of the tile (-1: border position or past the image)
+  {
+    const int r = tile * kPatchTile + tid;
+    const int u = first + r;
+    const int hp = u / Wp, wp = u - hp * Wp;
+    zrow[tid] = (r < n_out && wp >= 1 && wp <= sh.W) ? (hp - 1) * sh.W + (wp - 1) : -1;
+  }
+
+  // this wave's operand blocks: tile index fixed, (tap, chunk) advance by `wstep` vectors
+  const int tiles32 = (sh.cout + 31) / 32;
+  const int my_tile = min(blockIdx.y * 2 + ct, tiles32 - 1);
+  const u32x4* __restrict__ wfrag = reinterpret_cast<const u32x4*>(wmat) + (int64_t)my_tile * 256 + lane;
+  const int wstep = tiles32 * 256;                 // vectors from one (tap, chunk) to the next
+  const int chunks = sh.cin / 64;
+
+  f32x16 acc[4] = {zero16(), zero16(), zero16(), zero16()};
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  constexpr int kAhead = 4;          // taps whose weights are in flight ahead of the one in use
+  for (int cc = 0; cc < sh.cin; cc += 64) {
+    if (cc > 0) __syncthreads();     // every wave is done with the previous chunk's patch
+    u32x4 b[kAhead + 1][4];
+#pragma unroll
+    for (int tp = 0; tp < kAhead; ++tp)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) b[tp][kk] = wfrag[(int64_t)(tp * chunks + cc / 64) * wstep + kk * 64];
+    // patch row j holds position tile*256 + j (that is first + tile*256 + j - (Wp+1)); all of a
+    // thread's loads are issued before the first of them is stored
+    {
+      constexpr int NIT = kPatchMaxRows / 32;
+      int up = tile * kPatchTile + ur;
+      int hp = up / Wp, wp = up - hp * Wp;
+      const int adv_h = 32 / Wp, adv_w = 32 - adv_h * Wp;
+      u32x4 rv[NIT];
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        const bool real = ur + it * 32 < prow && hp >= 1 && hp <= sh.H && wp >= 1 && wp <= sh.W;
+        rv[it] = load_or_zero(xi_, (((int64_t)(hp - 1) * sh.W + (wp - 1)) * sh.cin + cc + kv * 8) * 2, real);
+        wp += adv_w;
+        hp += adv_h;
+        if (wp >= Wp) { wp -= Wp; ++hp; }
+      }
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        const int j = ur + it * 32;
+        if (j < prow) *reinterpret_cast<u32x4*>(&patch[j * kLdsRow + kv * 16]) = rv[it];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      if (tap + kAhead < 9) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+          b[(tap + kAhead) % (kAhead + 1)][kk] = wfrag[(int64_t)((tap + kAhead) * chunks + cc / 64) * wstep + kk * 64];
+      }
+      const int d = (tap / 3 - 1) * Wp + (tap % 3 - 1);
+      const char* A = patch + (rh * 128 + xi + first + d) * kLdsRow + gk * 16;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) {
+          const u32x4 a = *reinterpret_cast<const u32x4*>(A + rt * 32 * kLdsRow + kk * 32);
+          acc[rt] = mma(bf16_t(), a, b[tap % (kAhead + 1)][kk], acc[rt]);
+        }
+      }
+    }
+  }
+
+  // Output through LDS, one half of the tile (128 positions x 64 channels fp32) at a time, so
+  // that z is written in whole 256-byte rows.  Row pitch 72 floats: the two lane groups of a
+  // wavefront (rows 4 apart) land in different banks.
+  constexpr int kPitch = 72;
+  float* stage = reinterpret_cast<float*>(patch);
+  float* __restrict__ zi = z + (int64_t)img * sh.HW * sh.cout;
+  for (int h = 0; h < 2; ++h) {
+    __syncthreads();       // the patch (h = 0) or the first half's rows (h = 1) have been read
+    if (rh == h) {
+#pragma unroll
+      for (int rt = 0; rt < 4; ++rt) {
+        float* sp = stage + (rt * 32 + gk * 4) * kPitch + ct * 32 + xi;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sp[((v >> 2) * 8 + (v & 3)) * kPitch] = acc[rt][v];
+      }
+    }
+    __syncthreads();
+    const int c4 = tid & 15, rr = tid >> 4;
+    if (n0 + c4 * 4 < sh.cout) {
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int r = it * 16 + rr;
+        const int row = zrow[h * 128 + r];
+        if (row >= 0)
+          *reinterpret_cast<f32x4*>(zi + (int64_t)row * sh.cout + n0 + c4 * 4) =
+              *reinterpret_cast<const f32x4*>(stage + r * kPitch + c4 * 4);
       }
     }
   }
@@ -319,28 +478,51 @@ __global__ __launch_bounds__(kThreads) void bn_stats_chunk_kernel(WorkerTable ta
   }
 }
 
-// Per (unit, channel): the chunks' (count, mean, centred sum of squares) are
-// merged pairwise in image / chunk order -> mu and 1 / sqrt(var + eps).
+// Merge of two (count, mean, centred sum of squares) summaries.
+__device__ __forceinline__ void merge_stats(float& na, float& mean, float& m2, float nb, float mb, float m2b) {
+  const float nn = na + nb;
+  if (nn > 0.0f) {
+    const float d = mb - mean;
+    mean += d * (nb / nn);
+    m2 += m2b + d * d * (na * nb / nn);
+    na = nn;
+  }
+}
+
+// Per (unit, channel), one wavefront: lane l merges the chunk summaries l,
+// l + 64, ... in that order, then the 64 lanes merge over a fixed butterfly ->
+// mu and 1 / sqrt(var + eps).
 __global__ __launch_bounds__(kThreads) void bn_stats_unit_kernel(WorkerTable tab, ConvShape sh,
                                                                  const float* __restrict__ statp,
                                                                  float* __restrict__ mu, float* __restrict__ rstd) {
-  const int unit = blockIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int item = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  if (item >= sh.n_workers * sh.n_slices * sh.cout) return;
+  const int unit = item / sh.cout, ch = item - unit * sh.cout;
   const int w = unit / sh.n_slices, s = unit - w * sh.n_slices;
   int img0, nimg;
   slice_bounds(tab.rows[w], sh.n_slices, s, &img0, &nimg);
   img0 += tab.row_off[w];
-  for (int ch = threadIdx.x; ch < sh.cout; ch += kThreads) {
-    float na = 0.0f, mean = 0.0f, m2 = 0.0f;
-    for (int i = 0; i < nimg; ++i) {
-      for (int k = 0; k < sh.n_chunks; ++k) {
-        const float* p = statp + (((int64_t)(img0 + i) * sh.n_chunks + k) * sh.cout + ch) * 2;
-        const float nb = (float)min(kChunkRows, sh.HW - k * kChunkRows);
-        const float d = p[0] - mean, nn = na + nb;
-        mean += d * (nb / nn);
-        m2 += p[1] + d * d * (na * nb / nn);
-        na = nn;
-      }
+  const int n_ent = nimg * sh.n_chunks;
+  float na = 0.0f, mean = 0.0f, m2 = 0.0f;
+  for (int e = lane; e < n_ent; e += 64) {
+    const int k = e % sh.n_chunks;
+    const float* p = statp + (((int64_t)img0 * sh.n_chunks + e) * sh.cout + ch) * 2;
+    merge_stats(na, mean, m2, (float)min(kChunkRows, sh.HW - k * kChunkRows), p[0], p[1]);
+  }
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const float nb = __shfl_xor(na, off), mb = __shfl_xor(mean, off), m2b = __shfl_xor(m2, off);
+    // both partners must compute the same merge: order the pair by lane
+    if (lane & off) {
+      float n0 = nb, me0 = mb, q0 = m2b;
+      merge_stats(n0, me0, q0, na, mean, m2);
+      na = n0; mean = me0; m2 = q0;
+    } else {
+      merge_stats(na, mean, m2, nb, mb, m2b);
     }
+  }
+  if (lane == 0) {
     mu[(int64_t)unit * sh.cout + ch] = mean;
     rstd[(int64_t)unit * sh.cout + ch] = nimg > 0 ? 1.0f / sqrtf(m2 / na + sh.eps) : 0.0f;
   }
@@ -381,6 +563,47 @@ __global__ __launch_bounds__(kThreads) void bn_relu_pool_kernel(WorkerTable tab,
 }
 
 // ------------------------------------------------------------------- head
+constexpr int kImgTile = 8;   // images whose head work shares one pass over Wf
+
+// Pooled features and logits for kImgTile images x 256 classes per workgroup:
+// a thread owns one class and reads its column of Wf once for all the images.
+__global__ __launch_bounds__(kThreads) void head_logits_kernel(ConvShape sh, const float* __restrict__ params,
+                                                               const float* __restrict__ poolp,
+                                                               float* __restrict__ pooled,
+                                                               float* __restrict__ logits) {
+  __shared__ float sp[kImgTile][kMaxCout];
+  const int i0 = blockIdx.y * kImgTile, tid = threadIdx.x;
+  const int k = blockIdx.x * kThreads + tid;
+  const ParamOff po = param_off(sh.cin, sh.cout, sh.classes);
+  for (int e = tid; e < kImgTile * sh.cout; e += kThreads) {
+    const int i = e / sh.cout, ch = e - i * sh.cout;
+    float a = 0.0f;
+    if (i0 + i < sh.total_images) {
+#pragma unroll 8
+      for (int c = 0; c < sh.n_chunks; ++c) a += poolp[((int64_t)(i0 + i) * sh.n_chunks + c) * sh.cout + ch];
+      a /= (float)sh.HW;
+      if (blockIdx.x == 0) pooled[(int64_t)(i0 + i) * sh.cout + ch] = a;
+    }
+    sp[i][ch] = a;
+  }
+  __syncthreads();
+  if (k >= sh.classes) return;
+  const float* __restrict__ Wf = params + po.wf + k;
+  float acc[kImgTile];
+  const float b = params[po.bf + k];
+#pragma unroll
+  for (int i = 0; i < kImgTile; ++i) acc[i] = b;
+#pragma unroll 8
+  for (int ch = 0; ch < sh.cout; ++ch) {
+    const float wf = Wf[(int64_t)ch * sh.classes];
+#pragma unroll
+    for (int i = 0; i < kImgTile; ++i) acc[i] = fmaf(sp[i][ch], wf, acc[i]);
+  }
+#pragma unroll
+  for (int i = 0; i < kImgTile; ++i)
+    if (i0 + i < sh.total_images) logits[(int64_t)(i0 + i) * sh.classes + k] = acc[i];
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
@@ -392,19 +615,13 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-// One workgroup per image: pooled features, logits, loss, d loss / d logits
-// (scaled by the image's weight in its worker's aggregate) and d loss / d p.
-// The image weight is 1/|R_w| for MEAN (slice weight |R_s|/|R_w| times the
-// slice mean's 1/|R_s|) and 1/|R_s| for SUM.
-__global__ __launch_bounds__(kThreads) void head_image_kernel(WorkerTable tab, ConvShape sh,
-                                                              const float* __restrict__ params,
-                                                              const float* __restrict__ poolp,
-                                                              float* __restrict__ pooled,
-                                                              float* __restrict__ dlogits,
-                                                              float* __restrict__ dpooled,
-                                                              float* __restrict__ row_loss) {
-  __shared__ float sp[kMaxCout];
-  __shared__ float sl[kMaxClasses];
+// One workgroup per image: loss and d loss / d logits (in place of the
+// logits), both scaled by the image's weight in its worker's aggregate: 1/|R_w|
+// for MEAN (slice weight |R_s|/|R_w| times the slice mean's 1/|R_s|), 1/|R_s|
+// for SUM.
+__global__ __launch_bounds__(kThreads) void head_softmax_kernel(WorkerTable tab, ConvShape sh,
+                                                                float* __restrict__ dlogits,
+                                                                float* __restrict__ row_loss) {
   __shared__ float sred[8];
   const int img = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   int w = 0;
@@ -416,61 +633,83 @@ __global__ __launch_bounds__(kThreads) void head_image_kernel(WorkerTable tab, C
   int s0, sn;
   slice_bounds(tab.rows[w], sh.n_slices, s, &s0, &sn);
   const float scale = sh.grad_op == SYNK_MEAN ? 1.0f / (float)tab.rows[w] : 1.0f / (float)sn;
-  const ParamOff po = param_off(sh.cin, sh.cout, sh.classes);
-  const float* __restrict__ Wf = params + po.wf;
-
-  for (int ch = tid; ch < sh.cout; ch += kThreads) {
-    float a = 0.0f;
-    for (int k = 0; k < sh.n_chunks; ++k) a += poolp[((int64_t)img * sh.n_chunks + k) * sh.cout + ch];
-    a /= (float)sh.HW;
-    sp[ch] = a;
-    pooled[(int64_t)img * sh.cout + ch] = a;
-  }
-  __syncthreads();
-
+  float* __restrict__ row = dlogits + (int64_t)img * sh.classes;
+  constexpr int PER = kMaxClasses / kThreads;
+  float l[PER];
   float mx = -INFINITY;
-  for (int k = tid; k < sh.classes; k += kThreads) {
-    float a = params[po.bf + k];
-    for (int ch = 0; ch < sh.cout; ++ch) a = fmaf(sp[ch], Wf[(int64_t)ch * sh.classes + k], a);
-    sl[k] = a;
-    mx = fmaxf(mx, a);
+#pragma unroll
+  for (int q = 0; q < PER; ++q) {
+    const int k = q * kThreads + tid;
+    l[q] = k < sh.classes ? row[k] : -INFINITY;
+    mx = fmaxf(mx, l[q]);
   }
   mx = wave_max(mx);
   if (lane == 0) sred[wv] = mx;
   __syncthreads();
   mx = fmaxf(fmaxf(sred[0], sred[1]), fmaxf(sred[2], sred[3]));
   float se = 0.0f;
-  for (int k = tid; k < sh.classes; k += kThreads) se += expf(sl[k] - mx);
+#pragma unroll
+  for (int q = 0; q < PER; ++q) {
+    l[q] = expf(l[q] - mx);   // exp(-inf) = 0 for the classes that do not exist
+    se += l[q];
+  }
   se = wave_sum(se);
   if (lane == 0) sred[4 + wv] = se;
   __syncthreads();
   se = (sred[4] + sred[5]) + (sred[6] + sred[7]);
   const int y = tab.y[w][j];
   const bool yok = y >= 0 && y < sh.classes;
-  if (tid == 0) row_loss[img] = (mx + logf(se) - (yok ? sl[y] : 0.0f)) * scale;
-  __syncthreads();   // sl[y] read before sl is overwritten
+  if (tid == 0) row_loss[img] = (mx + logf(se) - (yok ? row[y] : 0.0f)) * scale;
+  __syncthreads();   // row[y] is read before any thread overwrites the row
   const float inv = 1.0f / se;
-  for (int k = tid; k < sh.classes; k += kThreads) {
-    const float d = (expf(sl[k] - mx) * inv - ((yok && k == y) ? 1.0f : 0.0f)) * scale;
-    sl[k] = d;
-    dlogits[(int64_t)img * sh.classes + k] = d;
+#pragma unroll
+  for (int q = 0; q < PER; ++q) {
+    const int k = q * kThreads + tid;
+    if (k < sh.classes) row[k] = (l[q] * inv - ((yok && k == y) ? 1.0f : 0.0f)) * scale;
   }
-  __syncthreads();
-  for (int ch = wv; ch < sh.cout; ch += kThreads / 64) {
-    float a = 0.0f;
-    for (int k = lane; k < sh.classes; k += 64) a = fmaf(sl[k], Wf[(int64_t)ch * sh.classes + k], a);
-    a = wave_sum(a);
-    if (lane == 0) dpooled[(int64_t)img * sh.cout + ch] = a;
+}
+
+// d loss / d p for kImgTile images: one wavefront per channel reads its row of
+// Wf once for all the images.
+__global__ __launch_bounds__(kThreads) void head_dpool_kernel(ConvShape sh, const float* __restrict__ params,
+                                                              const float* __restrict__ dlogits,
+                                                              float* __restrict__ dpooled) {
+  const int i0 = blockIdx.y * kImgTile, lane = threadIdx.x & 63;
+  const int ch = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  if (ch >= sh.cout) return;
+  const ParamOff po = param_off(sh.cin, sh.cout, sh.classes);
+  const float* __restrict__ Wf = params + po.wf + (int64_t)ch * sh.classes;
+  const int n = min(kImgTile, sh.total_images - i0);
+  // rows past the last image re-read the last one (their sums are not stored): every load is
+  // unconditional, so that the loads of several k are in flight together
+  const float* rows[kImgTile];
+#pragma unroll
+  for (int i = 0; i < kImgTile; ++i) rows[i] = dlogits + (int64_t)(i0 + min(i, n - 1)) * sh.classes;
+  float acc[kImgTile];
+#pragma unroll
+  for (int i = 0; i < kImgTile; ++i) acc[i] = 0.0f;
+#pragma unroll 4
+  for (int k = lane; k < sh.classes; k += 64) {
+    const float wf = Wf[k];
+#pragma unroll
+    for (int i = 0; i < kImgTile; ++i) acc[i] = fmaf(rows[i][k], wf, acc[i]);
+  }
+#pragma unroll
+  for (int i = 0; i < kImgTile; ++i) {
+    const float a = wave_sum(acc[i]);
+    if (lane == 0 && i < n) dpooled[(int64_t)(i0 + i) * sh.cout + ch] = a;
   }
 }
 
 // Per worker and class k: dWf[:, k], dbf[k] over the worker's images in image
-// order; workgroup (0, w) also folds the image losses into loss[w].
+// order, kImgTile images at a time held in registers; workgroup (0, w) also
+// folds the image losses into loss[w].
 __global__ __launch_bounds__(kThreads) void head_worker_kernel(WorkerTable tab, ConvShape sh,
                                                                const float* __restrict__ pooled,
                                                                const float* __restrict__ dlogits,
                                                                const float* __restrict__ row_loss,
                                                                float* __restrict__ loss) {
+  __shared__ float sp[kImgTile][kMaxCout];
   const int w = blockIdx.y, k = blockIdx.x * kThreads + threadIdx.x;
   const int i0 = tab.row_off[w], n = tab.rows[w];
   const ParamOff po = param_off(sh.cin, sh.cout, sh.classes);
@@ -480,16 +719,33 @@ __global__ __launch_bounds__(kThreads) void head_worker_kernel(WorkerTable tab, 
     for (int i = 0; i < n; ++i) a += row_loss[i0 + i];
     loss[w] = a;
   }
-  if (k >= sh.classes) return;
+  const bool live = k < sh.classes;
   float b = 0.0f;
-  for (int i = 0; i < n; ++i) b += dlogits[(int64_t)(i0 + i) * sh.classes + k];
-  g[po.bf + k] = b;
-  for (int ch = 0; ch < sh.cout; ++ch) {
-    float a = 0.0f;
-    for (int i = 0; i < n; ++i)
-      a = fmaf(pooled[(int64_t)(i0 + i) * sh.cout + ch], dlogits[(int64_t)(i0 + i) * sh.classes + k], a);
-    g[po.wf + (int64_t)ch * sh.classes + k] = a;
+  for (int t0 = 0; t0 < n || t0 == 0; t0 += kImgTile) {
+    const int nt = min(kImgTile, n - t0);
+    __syncthreads();
+    for (int e = threadIdx.x; e < kImgTile * sh.cout; e += kThreads) {
+      const int i = e / sh.cout, ch = e - i * sh.cout;
+      sp[i][ch] = i < nt ? pooled[(int64_t)(i0 + t0 + i) * sh.cout + ch] : 0.0f;
+    }
+    __syncthreads();
+    if (live) {
+      float d[kImgTile];
+#pragma unroll
+      for (int i = 0; i < kImgTile; ++i) {
+        d[i] = i < nt ? dlogits[(int64_t)(i0 + t0 + i) * sh.classes + k] : 0.0f;
+        b += d[i];
+      }
+      for (int ch = 0; ch < sh.cout; ++ch) {
+        float a = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kImgTile; ++i) a = fmaf(sp[i][ch], d[i], a);
+        float* o = g + po.wf + (int64_t)ch * sh.classes + k;
+        *o = t0 == 0 ? a : *o + a;
+      }
+    }
   }
+  if (live) g[po.bf + k] = b;
 }
 
 // ------------------------------------------------------ batch-norm backward
@@ -537,36 +793,43 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_chunk_kernel(WorkerTable tab,
   }
 }
 
-// Per worker and channel: the slices' sums in slice / image / chunk order ->
-// each slice's means (for dz) and the worker's d gamma, d beta.
+// Per (worker, channel), one wavefront: for every slice the lanes add the chunk
+// sums l, l + 64, ... and a fixed butterfly adds the lanes -> the slice's means
+// (for dz); the slices add up in slice order to the worker's d gamma, d beta.
 __global__ __launch_bounds__(kThreads) void bn_bwd_worker_kernel(WorkerTable tab, ConvShape sh,
                                                                  const float* __restrict__ bwdp,
                                                                  float* __restrict__ bmean) {
-  const int w = blockIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int item = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  if (item >= sh.n_workers * sh.cout) return;
+  const int w = item / sh.cout, ch = item - w * sh.cout;
   const ParamOff po = param_off(sh.cin, sh.cout, sh.classes);
-  float* __restrict__ g = tab.grad[w];
-  for (int ch = threadIdx.x; ch < sh.cout; ch += kThreads) {
-    float gb = 0.0f, gg = 0.0f;
-    for (int s = 0; s < sh.n_slices; ++s) {
-      int img0, nimg;
-      slice_bounds(tab.rows[w], sh.n_slices, s, &img0, &nimg);
-      img0 += tab.row_off[w];
-      float sb = 0.0f, sg = 0.0f;
-      for (int i = 0; i < nimg; ++i)
-        for (int k = 0; k < sh.n_chunks; ++k) {
-          const float* p = bwdp + (((int64_t)(img0 + i) * sh.n_chunks + k) * sh.cout + ch) * 2;
-          sb += p[0];
-          sg += p[1];
-        }
-      const float cnt = (float)(nimg * sh.HW);
+  float gb = 0.0f, gg = 0.0f;
+  for (int s = 0; s < sh.n_slices; ++s) {
+    int img0, nimg;
+    slice_bounds(tab.rows[w], sh.n_slices, s, &img0, &nimg);
+    img0 += tab.row_off[w];
+    const int n_ent = nimg * sh.n_chunks;
+    float sb = 0.0f, sg = 0.0f;
+    for (int e = lane; e < n_ent; e += 64) {
+      const float* p = bwdp + (((int64_t)img0 * sh.n_chunks + e) * sh.cout + ch) * 2;
+      sb += p[0];
+      sg += p[1];
+    }
+    sb = wave_sum(sb);
+    sg = wave_sum(sg);
+    const float cnt = (float)(nimg * sh.HW);
+    if (lane == 0) {
       float* o = bmean + ((int64_t)(w * sh.n_slices + s) * sh.cout + ch) * 2;
       o[0] = nimg > 0 ? sb / cnt : 0.0f;
       o[1] = nimg > 0 ? sg / cnt : 0.0f;
-      gb += sb;
-      gg += sg;
     }
-    g[po.beta + ch] = gb;
-    g[po.gamma + ch] = gg;
+    gb += sb;
+    gg += sg;
+  }
+  if (lane == 0) {
+    tab.grad[w][po.beta + ch] = gb;
+    tab.grad[w][po.gamma + ch] = gg;
   }
 }
 
@@ -679,12 +942,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_kernel(WorkerTable tab
       const bool nb = (kh != 0 || ph[e] > 0) && (kh != 2 || ph[e] < sh.H - 1) && (kw != 0 || pw[e] > 0) &&
                       (kw != 2 || pw[e] < sh.W - 1);
       const bool okx = in && nb && xcok, okd = in && dcok;
-      const T* px = okx ? xw + (int64_t)q * sh.cin + delta + c0 + uv * V : xw;
-      const T* pd = okd ? dw_ + (int64_t)q * sh.cout + n0 + uv * V : dw_;
-      const u32x4 vx = *reinterpret_cast<const u32x4*>(px);
-      const u32x4 vd = *reinterpret_cast<const u32x4*>(pd);
-      rx[e] = okx ? vx : zero;
-      rd[e] = okd ? vd : zero;
+      rx[e] = load_or_zero(xw, ((int64_t)q * sh.cin + delta + c0 + uv * V) * (int64_t)sizeof(T), okx);
+      rd[e] = load_or_zero(dw_, ((int64_t)q * sh.cout + n0 + uv * V) * (int64_t)sizeof(T), okd);
       // next step's position
       pw[e] += adv_w;
       ph[e] += adv_h;
@@ -762,6 +1021,204 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_kernel(WorkerTable tab
   }
 }
 
+// The weight gradient for bf16 with C_in a multiple of 64, in padded
+// coordinates: a worker's positions form one stream s = image * H*Wp + (hp-1) *
+// Wp + wp over the rows hp = 1..H of the padded images (Wp = W + 2; dz is zero
+// at the border columns), and the three taps of one kernel row kh are the
+// shifts -1, 0, +1 of s in X taken one image row up / level / down.  A
+// workgroup owns (kh, 64 x 64 tile of (c, o), run of the stream).  Per step of
+// 64 positions it lays into LDS, pixel pairs interleaved per 32-bit word: dz,
+// X paired as (2q, 2q+1) [taps -1 and +1 start on such a pair] and X paired as
+// (2q+1, 2q+2) [tap 0].  Wave (c half, position half) holds the 3 taps x 2
+// output-channel halves of its 32 input channels; the two position halves are
+// added through LDS at the end.
+constexpr int kRowsBR = 64;
+constexpr int kRowsPitch = 72;   // words per pixel-pair row: 64 + 8, so that the two lane groups (4 rows apart) use different banks
+constexpr int kRowsLdsWords = (33 + 32 + 32) * kRowsPitch;
+
+__global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_rows_kernel(WorkerTable tab, ConvShape sh,
+                                                                      const bf16_t* __restrict__ dz,
+                                                                      float* __restrict__ dwp, int n_runs,
+                                                                      int run_len) {
+  __shared__ __attribute__((aligned(16))) uint32_t smem[2][kRowsLdsWords];
+  const int w = blockIdx.z, run = blockIdx.y;
+  const int ct = (sh.cin + 63) / 64, ot = (sh.cout + 63) / 64;
+  const int kh = blockIdx.x / (ct * ot);
+  const int rest = blockIdx.x - kh * (ct * ot);
+  const int c0 = (rest / ot) * 64, n0 = (rest % ot) * 64;
+  const int Wp = sh.W + 2, PI = sh.H * Wp;
+  const int S = tab.rows[w] * PI;
+  const int s_begin = min(run * run_len, S), s_end = min(s_begin + run_len, S);
+  const int n_steps = (s_end - s_begin + kRowsBR - 1) / kRowsBR;
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int xi = lane & 31, gk = lane >> 5, cti = wv & 1, uh = wv >> 1;
+  const int kv = tid & 7, pr = tid >> 3;       // this thread's 8 channels and its pixel pair
+
+  const bf16_t* __restrict__ xw = reinterpret_cast<const bf16_t*>(tab.x[w]);
+  const bf16_t* __restrict__ dzw = dz + (int64_t)tab.row_off[w] * sh.HW * sh.cout;
+  const bool xcok = c0 + kv * 8 < sh.cin, dcok = n0 + kv * 8 < sh.cout;
+
+  // state of X row l = 2*pr of the current step: stream position s, and its (image pixel base,
+  // hp, wp).  Decoded one image ahead so that s = -1 (a border position) needs no special case.
+  int ps = s_begin - 1 + 2 * pr;
+  int pimg, php, pwp;
+  {
+    const int sp = ps + PI;
+    const int i = sp / PI, rem = sp - i * PI;
+    php = rem / Wp;
+    pwp = rem - php * Wp;
+    php += 1;
+    pimg = (i - 1) * sh.HW;
+  }
+  const int adv_h = kRowsBR / Wp, adv_w = kRowsBR - adv_h * Wp;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  // one step's loads: X rows l .. l+2 (and, for pair 0, rows 64, 65); dz at the positions of rows l+1, l+2
+  struct Set { u32x4 rx[5], rd[2]; };
+  Set setA, setB;
+
+  auto x_load = [&](int s, int img, int hp, int wp) -> u32x4 {
+    const int hx = hp + kh - 1;
+    const bool ok = xcok && s >= 0 && s < S && wp >= 1 && wp <= sh.W && hx >= 1 && hx <= sh.H;
+    return load_or_zero(xw, (((int64_t)img + (hx - 1) * sh.W + (wp - 1)) * sh.cin + c0 + kv * 8) * 2, ok);
+  };
+  auto d_load = [&](int s, int img, int hp, int wp) -> u32x4 {
+    const bool ok = dcok && s >= s_begin && s < s_end && wp >= 1 && wp <= sh.W;
+    return load_or_zero(dzw, (((int64_t)img + (hp - 1) * sh.W + (wp - 1)) * sh.cout + n0 + kv * 8) * 2, ok);
+  };
+  auto next_pos = [&](int& img, int& hp, int& wp) {   // one position on
+    if (++wp >= Wp) {
+      wp = 0;
+      if (++hp > sh.H) { hp = 1; img += sh.HW; }
+    }
+  };
+  auto gload = [&](Set& st) {
+    u32x4 (&rx)[5] = st.rx;
+    u32x4 (&rd)[2] = st.rd;
+    int img = pimg, hp = php, wp = pwp;
+    rx[0] = x_load(ps, img, hp, wp);
+    next_pos(img, hp, wp);
+    rx[1] = x_load(ps + 1, img, hp, wp);
+    rd[0] = d_load(ps + 1, img, hp, wp);
+    next_pos(img, hp, wp);
+    rx[2] = x_load(ps + 2, img, hp, wp);
+    rd[1] = d_load(ps + 2, img, hp, wp);
+    // advance the state by one step; for pair 0 the new state is row 64 of this step
+    ps += kRowsBR;
+    pwp += adv_w;
+    php += adv_h;
+    if (pwp >= Wp) { pwp -= Wp; ++php; }
+    while (php > sh.H) { php -= sh.H; pimg += sh.HW; }
+    if (pr == 0) {
+      img = pimg; hp = php; wp = pwp;
+      rx[3] = x_load(ps, img, hp, wp);
+      next_pos(img, hp, wp);
+      rx[4] = x_load(ps + 1, img, hp, wp);
+    }
+  };
+  auto interleave = [](const u32x4& a, const u32x4& b, u32x4* lo, u32x4* hi) {
+    // word j = (a[j], b[j]) as (low half, high half)
+    lo->x = __builtin_amdgcn_perm(b.x, a.x, 0x05040100u); lo->y = __builtin_amdgcn_perm(b.x, a.x, 0x07060302u);
+    lo->z = __builtin_amdgcn_perm(b.y, a.y, 0x05040100u); lo->w = __builtin_amdgcn_perm(b.y, a.y, 0x07060302u);
+    hi->x = __builtin_amdgcn_perm(b.z, a.z, 0x05040100u); hi->y = __builtin_amdgcn_perm(b.z, a.z, 0x07060302u);
+    hi->z = __builtin_amdgcn_perm(b.w, a.w, 0x05040100u); hi->w = __builtin_amdgcn_perm(b.w, a.w, 0x07060302u);
+  };
+  auto put = [&](uint32_t* base, int row, const u32x4& a, const u32x4& b) {
+    u32x4 lo, hi;
+    interleave(a, b, &lo, &hi);
+    u32x4* d = reinterpret_cast<u32x4*>(base + row * kRowsPitch + kv * 8);
+    d[0] = lo;
+    d[1] = hi;
+  };
+  auto lstore = [&](int buf, const Set& st) {
+    const u32x4 (&rx)[5] = st.rx;
+    const u32x4 (&rd)[2] = st.rd;
+    uint32_t* E = smem[buf];
+    put(E, pr, rx[0], rx[1]);
+    put(E + 33 * kRowsPitch, pr, rx[1], rx[2]);
+    put(E + 65 * kRowsPitch, pr, rd[0], rd[1]);
+    if (pr == 0) put(E, 32, rx[3], rx[4]);
+  };
+
+  f32x16 acc[3][2];
+#pragma unroll
+  for (int a = 0; a < 3; ++a) { acc[a][0] = zero16(); acc[a][1] = zero16(); }
+
+  auto compute = [&](int buf) {
+    constexpr int P = kRowsPitch;
+    const uint32_t* E = smem[buf] + cti * 32 + xi;
+    const uint32_t* O = E + 33 * P;
+    const uint32_t* D = smem[buf] + 65 * P + xi;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int r = ((uh * 2 + q) * 8 + gk * 4) * P;       // first pair row of this lane's 8 positions
+      const u32x4 d0 = {D[r], D[r + P], D[r + 2 * P], D[r + 3 * P]};
+      const u32x4 d1 = {D[r + 32], D[r + P + 32], D[r + 2 * P + 32], D[r + 3 * P + 32]};
+      const uint32_t e4 = E[r + 4 * P];
+      const u32x4 xa = {E[r], E[r + P], E[r + 2 * P], E[r + 3 * P]};     // tap -1
+      const u32x4 xc = {xa.y, xa.z, xa.w, e4};                            // tap +1: one pair further
+      const u32x4 xb = {O[r], O[r + P], O[r + 2 * P], O[r + 3 * P]};     // tap 0
+      acc[0][0] = mma(bf16_t(), xa, d0, acc[0][0]);
+      acc[0][1] = mma(bf16_t(), xa, d1, acc[0][1]);
+      acc[1][0] = mma(bf16_t(), xb, d0, acc[1][0]);
+      acc[1][1] = mma(bf16_t(), xb, d1, acc[1][1]);
+      acc[2][0] = mma(bf16_t(), xc, d0, acc[2][0]);
+      acc[2][1] = mma(bf16_t(), xc, d1, acc[2][1]);
+    }
+  };
+
+  // Loads run two steps ahead of the MFMAs: step t+1 sits in one register set, step t+2 in the
+  // other, while step t is computed out of LDS.  A set is stored to LDS one step before its
+  // use and refilled at once with the step after next.
+  if (n_steps > 0) {
+    gload(setA);
+    lstore(0, setA);
+    if (n_steps > 1) gload(setA);
+    if (n_steps > 2) gload(setB);
+  }
+  __syncthreads();
+  for (int t = 0; t < n_steps; t += 2) {
+    compute(0);
+    if (t + 1 < n_steps) lstore(1, setA);
+    if (t + 3 < n_steps) gload(setA);
+    __syncthreads();
+    if (t + 1 < n_steps) {
+      compute(1);
+      if (t + 2 < n_steps) lstore(0, setB);
+      if (t + 4 < n_steps) gload(setB);
+      __syncthreads();
+    }
+  }
+
+  // add the two position halves: waves 2, 3 hand their sums to waves 0, 1
+  float* red = reinterpret_cast<float*>(&smem[0][0]);     // 2 waves x 6 tiles x 16 x 64 floats = 48 KB
+  if (uh == 1) {
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[((cti * 6 + a * 2 + b) * 16 + v) * 64 + lane] = acc[a][b][v];
+  }
+  __syncthreads();
+  if (uh == 0) {
+    const int K = 9 * sh.cin;
+    float* __restrict__ out = dwp + ((int64_t)(w * n_runs + run) * K + (int64_t)kh * 3 * sh.cin) * sh.cout;
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const int col = n0 + b * 32 + xi;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int c = c0 + cti * 32 + gk * 4 + (v >> 2) * 8 + (v & 3);
+          const float sum = acc[a][b][v] + red[((cti * 6 + a * 2 + b) * 16 + v) * 64 + lane];
+          if (c < sh.cin && col < sh.cout) out[((int64_t)a * sh.cin + c) * sh.cout + col] = sum;
+        }
+      }
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void conv_dw_fold_kernel(WorkerTable tab, const float* __restrict__ dwp,
                                                                 int n_runs, int64_t len) {
   const int w = blockIdx.y;
@@ -778,7 +1235,7 @@ struct Plan {
   ConvShape sh;
   WorkerTable tab;
   int64_t K, P;
-  int max_unit_images, max_rows, n_units, n_runs, run_rows;
+  int max_unit_images, max_rows, n_units, n_runs, run_rows, n_runs_rows, run_len_rows;
   size_t elem;
   // workspace offsets in bytes
   size_t o_wmat, o_z, o_dz, o_statp, o_mu, o_rstd, o_poolp, o_pooled, o_dpooled, o_dlogits, o_row_loss, o_bwdp,
@@ -836,6 +1293,20 @@ int make_plan(const synk_convblock_desc* d, const int64_t* rows, int n_workers, 
   rr = (rr + BR - 1) / BR * BR;
   p->n_runs = (int)runs;
   p->run_rows = (int)rr;
+  {
+    // the padded-stream kernel: one workgroup per (kernel row, tile, run, worker), about two per CU
+    const int64_t t3 = tiles / 3 * n_workers;
+    const int64_t max_s = (int64_t)p->max_rows * sh.H * (sh.W + 2);
+    int64_t r2 = (2 * kNumCU) / t3;               // at most two workgroups per CU: one round
+    const int64_t cap = (max_s + 4 * kRowsBR - 1) / (4 * kRowsBR);
+    if (r2 > cap) r2 = cap;
+    if (r2 > 64) r2 = 64;
+    if (r2 < 1) r2 = 1;
+    int64_t rl = (max_s + r2 - 1) / r2;
+    rl = (rl + kRowsBR - 1) / kRowsBR * kRowsBR;
+    p->n_runs_rows = (int)r2;
+    p->run_len_rows = (int)rl;
+  }
 
   const int64_t R = total, px = total * sh.HW;
   size_t at = 0;
@@ -844,7 +1315,7 @@ int make_plan(const synk_convblock_desc* d, const int64_t* rows, int n_workers, 
     at += round_up(bytes, 256);
     return o;
   };
-  p->o_wmat = take((size_t)p->K * sh.cout * p->elem);
+  p->o_wmat = take((size_t)p->K * round_up((size_t)sh.cout, 32) * p->elem);
   p->o_z = take((size_t)px * sh.cout * 4);
   p->o_dz = take((size_t)px * sh.cout * p->elem);
   p->o_statp = take((size_t)R * sh.n_chunks * sh.cout * 2 * 4);
@@ -857,7 +1328,7 @@ int make_plan(const synk_convblock_desc* d, const int64_t* rows, int n_workers, 
   p->o_row_loss = take((size_t)R * 4);
   p->o_bwdp = take((size_t)R * sh.n_chunks * sh.cout * 2 * 4);
   p->o_bmean = take((size_t)p->n_units * sh.cout * 2 * 4);
-  p->o_dwp = take((size_t)n_workers * p->n_runs * p->K * sh.cout * 4);
+  p->o_dwp = take((size_t)n_workers * (p->n_runs > p->n_runs_rows ? p->n_runs : p->n_runs_rows) * p->K * sh.cout * 4);
   p->total = at;
   return SYNK_OK;
 }
@@ -882,24 +1353,47 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   float* dwp = reinterpret_cast<float*>(ws + p.o_dwp);
 
   const int64_t wn = p.K * sh.cout;
-  hipLaunchKernelGGL(conv_weight_kernel<T>, dim3((unsigned)((wn + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
-                     params, wmat, (int)p.K, sh.cout);
+  const bool patch_ok = sizeof(T) == 2 && sh.cin % 64 == 0 && sh.W + 2 <= 63 && sh.total_images <= 65535;
+  if (patch_ok) {
+    const int64_t total = p.K * (int64_t)round_up((size_t)sh.cout, 32);
+    hipLaunchKernelGGL(conv_weight_frag_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads),
+                       0, st, params, reinterpret_cast<uint16_t*>(wmat), sh.cin, sh.cout, total);
+  } else {
+    hipLaunchKernelGGL(conv_weight_kernel<T>, dim3((unsigned)((wn + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+                       st, params, wmat, (int)p.K, sh.cout);
+  }
   SYNK_LAUNCH_CHECK();
   const dim3 gf((unsigned)(((int64_t)p.max_unit_images * sh.HW + kFwdBM - 1) / kFwdBM),
                 (unsigned)((sh.cout + kFwdBN - 1) / kFwdBN), (unsigned)p.n_units);
-  SYNK_LAUNCH_TIMED(conv3x3_fwd_kernel<T>, gf, dim3(kThreads), 0, st, tab, sh, (const T*)wmat, z);
+  if (patch_ok) {
+    const dim3 gp((unsigned)((sh.H * (sh.W + 2) - 2 + kPatchTile - 1) / kPatchTile),
+                  (unsigned)((sh.cout + 63) / 64), (unsigned)sh.total_images);
+    hipLaunchKernelGGL(conv3x3_fwd_patch_kernel, gp, dim3(kThreads), 0, st, tab, sh,
+                       reinterpret_cast<const bf16_t*>(wmat), z);
+  } else {
+    hipLaunchKernelGGL(conv3x3_fwd_kernel<T>, gf, dim3(kThreads), 0, st, tab, sh, (const T*)wmat, z);
+  }
   SYNK_LAUNCH_CHECK();
   const dim3 gc((unsigned)((int64_t)sh.total_images * sh.n_chunks));
   hipLaunchKernelGGL(bn_stats_chunk_kernel, gc, dim3(kThreads), 0, st, tab, sh, (const float*)z, statp);
   SYNK_LAUNCH_CHECK();
-  hipLaunchKernelGGL(bn_stats_unit_kernel, dim3((unsigned)p.n_units), dim3(kThreads), 0, st, tab, sh,
+  hipLaunchKernelGGL(bn_stats_unit_kernel, dim3((unsigned)(((int64_t)p.n_units * sh.cout + 3) / 4)), dim3(kThreads), 0,
+                     st, tab, sh,
                      (const float*)statp, mu, rstd);
   SYNK_LAUNCH_CHECK();
   hipLaunchKernelGGL(bn_relu_pool_kernel, gc, dim3(kThreads), 0, st, tab, sh, params, (const float*)z,
                      (const float*)mu, (const float*)rstd, poolp);
   SYNK_LAUNCH_CHECK();
-  hipLaunchKernelGGL(head_image_kernel, dim3((unsigned)sh.total_images), dim3(kThreads), 0, st, tab, sh, params,
-                     (const float*)poolp, pooled, dlogits, dpooled, row_loss);
+  const unsigned img_tiles = (unsigned)((sh.total_images + kImgTile - 1) / kImgTile);
+  const unsigned class_tiles = (unsigned)((sh.classes + kThreads - 1) / kThreads);
+  hipLaunchKernelGGL(head_logits_kernel, dim3(class_tiles, img_tiles), dim3(kThreads), 0, st, sh, params,
+                     (const float*)poolp, pooled, dlogits);
+  SYNK_LAUNCH_CHECK();
+  hipLaunchKernelGGL(head_softmax_kernel, dim3((unsigned)sh.total_images), dim3(kThreads), 0, st, tab, sh, dlogits,
+                     row_loss);
+  SYNK_LAUNCH_CHECK();
+  hipLaunchKernelGGL(head_dpool_kernel, dim3((unsigned)((sh.cout + 3) / 4), img_tiles), dim3(kThreads), 0, st, sh,
+                     params, (const float*)dlogits, dpooled);
   SYNK_LAUNCH_CHECK();
   hipLaunchKernelGGL(head_worker_kernel, dim3((unsigned)((sh.classes + kThreads - 1) / kThreads), (unsigned)sh.n_workers),
                      dim3(kThreads), 0, st, tab, sh, (const float*)pooled, (const float*)dlogits,
@@ -908,7 +1402,8 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   hipLaunchKernelGGL(bn_bwd_chunk_kernel, gc, dim3(kThreads), 0, st, tab, sh, params, (const float*)z,
                      (const float*)mu, (const float*)rstd, (const float*)dpooled, bwdp);
   SYNK_LAUNCH_CHECK();
-  hipLaunchKernelGGL(bn_bwd_worker_kernel, dim3((unsigned)sh.n_workers), dim3(kThreads), 0, st, tab, sh,
+  hipLaunchKernelGGL(bn_bwd_worker_kernel, dim3((unsigned)((sh.n_workers * sh.cout + 3) / 4)), dim3(kThreads), 0, st,
+                     tab, sh,
                      (const float*)bwdp, bmean);
   SYNK_LAUNCH_CHECK();
   hipLaunchKernelGGL(bn_bwd_dz_kernel<T>, gc, dim3(kThreads), 0, st, tab, sh, params, (const float*)z,
@@ -916,11 +1411,18 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   SYNK_LAUNCH_CHECK();
   const dim3 gd((unsigned)(9 * ((sh.cin + 63) / 64) * ((sh.cout + 63) / 64)), (unsigned)p.n_runs,
                 (unsigned)sh.n_workers);
-  hipLaunchKernelGGL(conv3x3_dw_kernel<T>, gd, dim3(kThreads), 0, st, tab, sh, (const T*)dz, dwp, p.n_runs,
-                     p.run_rows);
+  if (patch_ok) {
+    const dim3 gr((unsigned)(3 * ((sh.cin + 63) / 64) * ((sh.cout + 63) / 64)), (unsigned)p.n_runs_rows,
+                  (unsigned)sh.n_workers);
+    hipLaunchKernelGGL(conv3x3_dw_rows_kernel, gr, dim3(kThreads), 0, st, tab, sh,
+                       reinterpret_cast<const bf16_t*>(dz), dwp, p.n_runs_rows, p.run_len_rows);
+  } else {
+    hipLaunchKernelGGL(conv3x3_dw_kernel<T>, gd, dim3(kThreads), 0, st, tab, sh, (const T*)dz, dwp, p.n_runs,
+                       p.run_rows);
+  }
   SYNK_LAUNCH_CHECK();
   hipLaunchKernelGGL(conv_dw_fold_kernel, dim3((unsigned)((wn / 4 + kThreads - 1) / kThreads), (unsigned)sh.n_workers),
-                     dim3(kThreads), 0, st, tab, (const float*)dwp, p.n_runs, wn);
+                     dim3(kThreads), 0, st, tab, (const float*)dwp, patch_ok ? p.n_runs_rows : p.n_runs, wn);
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;
 }

@@ -79,6 +79,9 @@ def check(cfg, idx, n_workers, n_slices, op, bf16, got_g, got_l, eps=1e-5):
     ((3, 1, 8, 16, 4), 5, 1, 1, "mean"),        # one column: no left / right neighbours
     ((12, 12, 72, 72, 17), 5, 2, 1, "mean"),    # channels beyond one 64-wide tile, chunk with few rows
     ((20, 20, 8, 8, 300), 4, 2, 2, "sum"),      # more than one chunk of pixels per image, classes > 256
+    ((7, 5, 128, 72, 6), 5, 2, 2, "mean"),      # two 64-channel input chunks, a ragged output-channel tile
+    ((3, 61, 64, 64, 4), 3, 1, 1, "mean"),      # the widest rows the padded-patch kernels take
+    ((2, 62, 64, 64, 4), 3, 1, 1, "mean"),      # one pixel wider: the general kernels
 ])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_sliced_conv_block_matches_oracle(synk, shape, B, N, S, op, bf16):
