@@ -20,6 +20,8 @@
 // No floating-point atomics: every sum has a fixed order.
 #include <math.h>
 
+#include <algorithm>
+
 #include "common.h"
 
 namespace synk {
@@ -1170,6 +1172,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_rows_kernel(WorkerTabl
   // Loads run two steps ahead of the MFMAs: step t+1 sits in one register set, step t+2 in the
   // other, while step t is computed out of LDS.  A set is stored to LDS one step before its
   // use and refilled at once with the step after next.
+  // Loads run two steps ahead of the MFMAs: step t+1 sits in one register set, step t+2 in the
+  // other, while step t is computed out of LDS.  A set is stored to LDS one step before its
+  // use and refilled at once with the step after next.
   if (n_steps > 0) {
     gload(setA);
     lstore(0, setA);
@@ -1328,7 +1333,8 @@ int make_plan(const synk_convblock_desc* d, const int64_t* rows, int n_workers, 
   p->o_row_loss = take((size_t)R * 4);
   p->o_bwdp = take((size_t)R * sh.n_chunks * sh.cout * 2 * 4);
   p->o_bmean = take((size_t)p->n_units * sh.cout * 2 * 4);
-  p->o_dwp = take((size_t)n_workers * (p->n_runs > p->n_runs_rows ? p->n_runs : p->n_runs_rows) * p->K * sh.cout * 4);
+  const int runs_max = std::max(p->n_runs, p->n_runs_rows);
+  p->o_dwp = take((size_t)n_workers * runs_max * p->K * sh.cout * 4);
   p->total = at;
   return SYNK_OK;
 }
@@ -1411,18 +1417,20 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   SYNK_LAUNCH_CHECK();
   const dim3 gd((unsigned)(9 * ((sh.cin + 63) / 64) * ((sh.cout + 63) / 64)), (unsigned)p.n_runs,
                 (unsigned)sh.n_workers);
+  int fold_runs = p.n_runs;
   if (patch_ok) {
+    fold_runs = p.n_runs_rows;
     const dim3 gr((unsigned)(3 * ((sh.cin + 63) / 64) * ((sh.cout + 63) / 64)), (unsigned)p.n_runs_rows,
                   (unsigned)sh.n_workers);
-    hipLaunchKernelGGL(conv3x3_dw_rows_kernel, gr, dim3(kThreads), 0, st, tab, sh,
-                       reinterpret_cast<const bf16_t*>(dz), dwp, p.n_runs_rows, p.run_len_rows);
+    SYNK_LAUNCH_TIMED(conv3x3_dw_rows_kernel, gr, dim3(kThreads), 0, st, tab, sh,
+                      reinterpret_cast<const bf16_t*>(dz), dwp, p.n_runs_rows, p.run_len_rows);
   } else {
-    hipLaunchKernelGGL(conv3x3_dw_kernel<T>, gd, dim3(kThreads), 0, st, tab, sh, (const T*)dz, dwp, p.n_runs,
-                       p.run_rows);
+    SYNK_LAUNCH_TIMED(conv3x3_dw_kernel<T>, gd, dim3(kThreads), 0, st, tab, sh, (const T*)dz, dwp, p.n_runs,
+                      p.run_rows);
   }
   SYNK_LAUNCH_CHECK();
   hipLaunchKernelGGL(conv_dw_fold_kernel, dim3((unsigned)((wn / 4 + kThreads - 1) / kThreads), (unsigned)sh.n_workers),
-                     dim3(kThreads), 0, st, tab, (const float*)dwp, patch_ok ? p.n_runs_rows : p.n_runs, wn);
+                     dim3(kThreads), 0, st, tab, (const float*)dwp, fold_runs, wn);
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;
 }

@@ -81,6 +81,8 @@ def check(cfg, idx, n_workers, n_slices, op, bf16, got_g, got_l, eps=1e-5):
     ((20, 20, 8, 8, 300), 4, 2, 2, "sum"),      # more than one chunk of pixels per image, classes > 256
     ((7, 5, 128, 72, 6), 5, 2, 2, "mean"),      # two 64-channel input chunks, a ragged output-channel tile
     ((3, 61, 64, 64, 4), 3, 1, 1, "mean"),      # the widest rows the padded-patch kernels take
+    ((5, 33, 64, 72, 6), 5, 2, 2, "mean"),      # padded-stream weight gradient, ragged output-channel tile
+    ((14, 31, 128, 64, 4), 6, 2, 1, "sum"),     # the same over several runs, two input chunks
     ((2, 62, 64, 64, 4), 3, 1, 1, "mean"),      # one pixel wider: the general kernels
 ])
 @pytest.mark.parametrize("bf16", [False, True])
