@@ -1043,10 +1043,18 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_rows_kernel(WorkerTabl
                                                                       float* __restrict__ dwp, int n_runs,
                                                                       int run_len) {
   __shared__ __attribute__((aligned(16))) uint32_t smem[2][kRowsLdsWords];
-  const int w = blockIdx.z, run = blockIdx.y;
+  // Workgroups go to the 8 XCDs round-robin in launch order.  The three kernel rows of one
+  // (tile, run, worker) read the same X and dz: they sit 8 apart in launch order, i.e. on one
+  // XCD at about the same time, so that two of the three find the data in that XCD's L2.
   const int ct = (sh.cin + 63) / 64, ot = (sh.cout + 63) / 64;
-  const int kh = blockIdx.x / (ct * ot);
-  const int rest = blockIdx.x - kh * (ct * ot);
+  const int groups = ct * ot * n_runs * sh.n_workers;
+  const int slot = blockIdx.x >> 3;
+  const int grp = (slot / 3) * 8 + (blockIdx.x & 7);
+  if (grp >= groups) return;
+  const int kh = slot % 3;
+  const int w = grp / (ct * ot * n_runs);
+  const int run = (grp / (ct * ot)) % n_runs;
+  const int rest = grp % (ct * ot);
   const int c0 = (rest / ot) * 64, n0 = (rest % ot) * 64;
   const int Wp = sh.W + 2, PI = sh.H * Wp;
   const int S = tab.rows[w] * PI;
@@ -1420,8 +1428,8 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   int fold_runs = p.n_runs;
   if (patch_ok) {
     fold_runs = p.n_runs_rows;
-    const dim3 gr((unsigned)(3 * ((sh.cin + 63) / 64) * ((sh.cout + 63) / 64)), (unsigned)p.n_runs_rows,
-                  (unsigned)sh.n_workers);
+    const int64_t groups = (int64_t)((sh.cin + 63) / 64) * ((sh.cout + 63) / 64) * p.n_runs_rows * sh.n_workers;
+    const dim3 gr((unsigned)(3 * ((groups + 7) / 8) * 8));
     SYNK_LAUNCH_TIMED(conv3x3_dw_rows_kernel, gr, dim3(kThreads), 0, st, tab, sh,
                       reinterpret_cast<const bf16_t*>(dz), dwp, p.n_runs_rows, p.run_len_rows);
   } else {
