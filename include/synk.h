@@ -278,11 +278,13 @@ int synk_sliced_grad(const synk_mlp_desc* m, const float* params, const void* pa
  * (SYNK_MEAN: weights |R_s|/|R_w|; SYNK_SUM).  All slices see the same
  * parameter values.
  *
- *   d.compute_dtype SYNK_F32: fp32 contraction operands; SYNK_BF16: X, Wc and
- *                   dz are rounded (nearest-even) to bf16 where they enter a
- *                   contraction, products accumulate in fp32; everything else
- *                   (statistics, normalisation, pooling, the affine layer, the
- *                   loss) is fp32 in both modes
+ *   d.compute_dtype SYNK_F32: fp32 throughout; SYNK_BF16: X, Wc and dz are
+ *                   rounded (nearest-even) to bf16 where they enter a
+ *                   contraction, products accumulate in fp32, and the
+ *                   convolution's output z is stored in bf16 (statistics and
+ *                   normalisation read the rounded z); the arithmetic of the
+ *                   statistics, normalisation, pooling, the affine layer and
+ *                   the loss is fp32 in both modes
  *   params          device float[P]: Wc [3 x 3 x C_in x C_out] (tap-major: the
  *                   [9 C_in x C_out] matrix of the convolution written as a
  *                   product), gamma [C_out], beta [C_out], Wf [C_out x

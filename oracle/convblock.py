@@ -25,7 +25,9 @@ the [9 C_in x C_out] matrix of the convolution written as a product), gamma
 [C_out], beta [C_out], Wf [C_out x classes], bf [classes].
 
 All arithmetic is float64.  `bf16_points=True` additionally rounds to bfloat16
-what a bf16-input contraction would be fed: X, Wc, and dz; the rest stays
+what a bf16 pipeline keeps in bfloat16: the operands of the two contractions
+(X, Wc, dz) and the convolution's output z as stored (statistics,
+normalisation and everything after it see the rounded z); the rest stays
 float64.
 """
 import numpy as np
@@ -111,7 +113,7 @@ def function(theta, shape, X, y, eps=1e-5, bf16_points=False, trace=None):
     gWc, ggamma, gbeta, gWf, gbf = unpack(grad, shape)
 
     Xq = _q(X, bf16_points)
-    z = conv3x3(Xq, _q(Wc, bf16_points))
+    z = _q(conv3x3(Xq, _q(Wc, bf16_points)), bf16_points)
     mu = z.mean(axis=(0, 1, 2))
     var = ((z - mu) ** 2).mean(axis=(0, 1, 2))
     rstd = 1.0 / np.sqrt(var + eps)

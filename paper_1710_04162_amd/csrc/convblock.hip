@@ -95,6 +95,19 @@ __device__ __forceinline__ u32x4 load_or_zero(const void* base, int64_t byte_off
   return u32x4{v.x & k, v.y & k, v.z & k, v.w & k};
 }
 
+// z (the convolution's output) is kept in the compute type.  Four consecutive channels as
+// floats, and one value.
+__device__ __forceinline__ f32x4 load_z4(const float* z, int64_t i) { return *reinterpret_cast<const f32x4*>(z + i); }
+__device__ __forceinline__ f32x4 load_z4(const bf16_t* z, int64_t i) {
+  const u32x2 q = *reinterpret_cast<const u32x2*>(z + i);
+  return f32x4{__uint_as_float(q.x << 16), __uint_as_float(q.x & 0xffff0000u), __uint_as_float(q.y << 16),
+               __uint_as_float(q.y & 0xffff0000u)};
+}
+__device__ __forceinline__ float load_z1(const float* z, int64_t i) { return z[i]; }
+__device__ __forceinline__ float load_z1(const bf16_t* z, int64_t i) { return bf16_to_f32(z[i]); }
+__device__ __forceinline__ void store_z1(float* z, int64_t i, float v) { z[i] = v; }
+__device__ __forceinline__ void store_z1(bf16_t* z, int64_t i, float v) { z[i] = f32_to_bf16(v); }
+
 // One 16-byte operand pair -> the MFMAs it feeds.  bf16: 8 contraction steps in
 // one instruction.  fp32: lane group g holds steps 4g..4g+3 of an 8-step run;
 // instruction j takes element j of both operands (any pairing of steps works
@@ -154,7 +167,7 @@ constexpr int kFwdBM = 128, kFwdBN = 64, kLdsRow = 144;
 template <typename T>
 __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_kernel(WorkerTable tab, ConvShape sh,
                                                                   const T* __restrict__ wmat,
-                                                                  float* __restrict__ z) {
+                                                                  T* __restrict__ z) {
   constexpr int V = EL<T>::V, BK = 8 * V;
   __shared__ __attribute__((aligned(16))) char smem[2][(kFwdBM + kFwdBN) * kLdsRow];
 
@@ -251,7 +264,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_kernel(WorkerTable ta
   }
 
   // accumulator v of lane (xi, gk) is row gk*4 + (v>>2)*8 + (v&3), column xi
-  float* __restrict__ zu = z + ((int64_t)(tab.row_off[w] + img0) * sh.HW) * sh.cout;
+  T* __restrict__ zu = z + ((int64_t)(tab.row_off[w] + img0) * sh.HW) * sh.cout;
   const int col = n0 + wn * 32 + xi;
   if (col < sh.cout) {
 #pragma unroll
@@ -260,7 +273,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_kernel(WorkerTable ta
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = r0 + (v >> 2) * 8 + (v & 3);
-        if (row < M) zu[(int64_t)row * sh.cout + col] = acc[i][v];
+        if (row < M) store_z1(zu, (int64_t)row * sh.cout + col, acc[i][v]);
       }
     }
   }
@@ -281,7 +294,7 @@ constexpr int kPatchTile = 256, kPatchMaxRows = kPatchTile + 2 * 64;
 
 __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_patch_kernel(WorkerTable tab, ConvShape sh,
                                                                         const bf16_t* __restrict__ wmat,
-                                                                        float* __restrict__ z) {
+                                                                        bf16_t* __restrict__ z) {
   __shared__ __attribute__((aligned(16))) char patch[kPatchMaxRows * kLdsRow];
   __shared__ int zrow[kPatchTile];
 
@@ -368,11 +381,11 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_patch_kernel(WorkerTa
   }
 
   // Output through LDS, one half of the tile (128 positions x 64 channels fp32) at a time, so
-  // that z is written in whole 256-byte rows.  Row pitch 72 floats: the two lane groups of a
-  // wavefront (rows 4 apart) land in different banks.
+  // that z is written in whole 128-byte rows of bf16.  Row pitch 72 floats: the two lane groups
+  // of a wavefront (rows 4 apart) land in different banks.
   constexpr int kPitch = 72;
   float* stage = reinterpret_cast<float*>(patch);
-  float* __restrict__ zi = z + (int64_t)img * sh.HW * sh.cout;
+  bf16_t* __restrict__ zi = z + (int64_t)img * sh.HW * sh.cout;
   for (int h = 0; h < 2; ++h) {
     __syncthreads();       // the patch (h = 0) or the first half's rows (h = 1) have been read
     if (rh == h) {
@@ -384,15 +397,19 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_patch_kernel(WorkerTa
       }
     }
     __syncthreads();
-    const int c4 = tid & 15, rr = tid >> 4;
-    if (n0 + c4 * 4 < sh.cout) {
+    const int c8 = tid & 7, rr = tid >> 3;
+    if (n0 + c8 * 8 < sh.cout) {
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int r = it * 16 + rr;
+      for (int it = 0; it < 4; ++it) {
+        const int r = it * 32 + rr;
         const int row = zrow[h * 128 + r];
-        if (row >= 0)
-          *reinterpret_cast<f32x4*>(zi + (int64_t)row * sh.cout + n0 + c4 * 4) =
-              *reinterpret_cast<const f32x4*>(stage + r * kPitch + c4 * 4);
+        if (row >= 0) {
+          const f32x4 a = *reinterpret_cast<const f32x4*>(stage + r * kPitch + c8 * 8);
+          const f32x4 b = *reinterpret_cast<const f32x4*>(stage + r * kPitch + c8 * 8 + 4);
+          const u32x4 q = {pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(b[0], b[1]),
+                           pack_bf16x2(b[2], b[3])};
+          *reinterpret_cast<u32x4*>(zi + (int64_t)row * sh.cout + n0 + c8 * 8) = q;
+        }
       }
     }
   }
@@ -451,29 +468,45 @@ __device__ __forceinline__ float fold_sum(const float* red, int q, int n_rg, int
   return s;
 }
 
+// f(r, four channels of row r) for this thread's rows r = rg, rg + n_rg, ... of the chunk, eight
+// loads at a time: a row past the end re-reads the last row and is dropped, so that the loads
+// carry no condition and are all in flight together.
+template <typename Tz, typename F>
+__device__ __forceinline__ void for_rows(const Chunk& c, const Tz* __restrict__ z, int64_t base, int cout, F f) {
+  for (int r0 = c.rg; r0 < c.nrows; r0 += 8 * c.n_rg) {
+    f32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = load_z4(z, base + (int64_t)min(r0 + u * c.n_rg, c.nrows - 1) * cout);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (r0 + u * c.n_rg < c.nrows) f(r0 + u * c.n_rg, v[u]);
+  }
+}
+
 // Per (image, chunk, channel): mean and centred sum of squares of z, computed
 // about the chunk's first row so that nothing cancels.
+template <typename Tz>
 __global__ __launch_bounds__(kThreads) void bn_stats_chunk_kernel(WorkerTable tab, ConvShape sh,
-                                                                  const float* __restrict__ z,
+                                                                  const Tz* __restrict__ z,
                                                                   float* __restrict__ statp) {
   __shared__ __attribute__((aligned(16))) float red[2 * kThreads * 4];
   const Chunk c = chunk_of(tab, sh);
   f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
   if (c.active) {
-    const float* p = z + c.row0 * sh.cout + c.c4 * 4;
-    const f32x4 k = *reinterpret_cast<const f32x4*>(p);
-    for (int r = c.rg; r < c.nrows; r += c.n_rg) {
-      const f32x4 d = *reinterpret_cast<const f32x4*>(p + (int64_t)r * sh.cout) - k;
+    const int64_t p = c.row0 * sh.cout + c.c4 * 4;
+    const f32x4 k = load_z4(z, p);
+    for_rows(c, z, p, sh.cout, [&](int, const f32x4& zz) {
+      const f32x4 d = zz - k;
       acc[0] += d;
       acc[1] += d * d;
-    }
+    });
   }
   fold_store<2>(red, c, sh.cout, acc);
   __syncthreads();
   const float n = (float)c.nrows;
   for (int ch = threadIdx.x; ch < sh.cout; ch += kThreads) {
     const float s1 = fold_sum(red, 0, c.n_rg, sh.cout, ch), s2 = fold_sum(red, 1, c.n_rg, sh.cout, ch);
-    const float k = z[c.row0 * sh.cout + ch];
+    const float k = load_z1(z, c.row0 * sh.cout + ch);
     float* o = statp + ((int64_t)blockIdx.x * sh.cout + ch) * 2;
     o[0] = k + s1 / n;
     o[1] = fmaxf(s2 - s1 * s1 / n, 0.0f);
@@ -532,9 +565,10 @@ __global__ __launch_bounds__(kThreads) void bn_stats_unit_kernel(WorkerTable tab
 
 // Per (image, chunk, channel): sum over the chunk's pixels of
 // relu(gamma * xhat + beta).
+template <typename Tz>
 __global__ __launch_bounds__(kThreads) void bn_relu_pool_kernel(WorkerTable tab, ConvShape sh,
                                                                 const float* __restrict__ params,
-                                                                const float* __restrict__ z,
+                                                                const Tz* __restrict__ z,
                                                                 const float* __restrict__ mu,
                                                                 const float* __restrict__ rstd,
                                                                 float* __restrict__ poolp) {
@@ -551,12 +585,11 @@ __global__ __launch_bounds__(kThreads) void bn_relu_pool_kernel(WorkerTable tab,
     }
     m = *reinterpret_cast<const f32x4*>(mu + (int64_t)c.unit * sh.cout + c.c4 * 4);
     rs = *reinterpret_cast<const f32x4*>(rstd + (int64_t)c.unit * sh.cout + c.c4 * 4);
-    const float* p = z + c.row0 * sh.cout + c.c4 * 4;
-    for (int r = c.rg; r < c.nrows; r += c.n_rg) {
-      const f32x4 zz = *reinterpret_cast<const f32x4*>(p + (int64_t)r * sh.cout);
+    const int64_t p = c.row0 * sh.cout + c.c4 * 4;
+    for_rows(c, z, p, sh.cout, [&](int, const f32x4& zz) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[0][e] += fmaxf(g[e] * ((zz[e] - m[e]) * rs[e]) + b[e], 0.0f);
-    }
+    });
   }
   fold_store<1>(red, c, sh.cout, acc);
   __syncthreads();
@@ -753,9 +786,10 @@ __global__ __launch_bounds__(kThreads) void head_worker_kernel(WorkerTable tab, 
 // ------------------------------------------------------ batch-norm backward
 // dy = (dp / HW) [gamma*xhat + beta > 0].  Per (image, chunk, channel): sum of
 // dy and of dy * xhat.
+template <typename Tz>
 __global__ __launch_bounds__(kThreads) void bn_bwd_chunk_kernel(WorkerTable tab, ConvShape sh,
                                                                 const float* __restrict__ params,
-                                                                const float* __restrict__ z,
+                                                                const Tz* __restrict__ z,
                                                                 const float* __restrict__ mu,
                                                                 const float* __restrict__ rstd,
                                                                 const float* __restrict__ dpooled,
@@ -774,9 +808,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_chunk_kernel(WorkerTable tab,
     }
     m = *reinterpret_cast<const f32x4*>(mu + (int64_t)c.unit * sh.cout + c.c4 * 4);
     rs = *reinterpret_cast<const f32x4*>(rstd + (int64_t)c.unit * sh.cout + c.c4 * 4);
-    const float* p = z + c.row0 * sh.cout + c.c4 * 4;
-    for (int r = c.rg; r < c.nrows; r += c.n_rg) {
-      const f32x4 zz = *reinterpret_cast<const f32x4*>(p + (int64_t)r * sh.cout);
+    const int64_t p = c.row0 * sh.cout + c.c4 * 4;
+    for_rows(c, z, p, sh.cout, [&](int, const f32x4& zz) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const float xh = (zz[e] - m[e]) * rs[e];
@@ -784,7 +817,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_chunk_kernel(WorkerTable tab,
         acc[0][e] += dy;
         acc[1][e] += dy * xh;
       }
-    }
+    });
   }
   fold_store<2>(red, c, sh.cout, acc);
   __syncthreads();
@@ -840,7 +873,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_worker_kernel(WorkerTable tab
 template <typename T>
 __global__ __launch_bounds__(kThreads) void bn_bwd_dz_kernel(WorkerTable tab, ConvShape sh,
                                                              const float* __restrict__ params,
-                                                             const float* __restrict__ z,
+                                                             const T* __restrict__ z,
                                                              const float* __restrict__ mu,
                                                              const float* __restrict__ rstd,
                                                              const float* __restrict__ dpooled,
@@ -861,8 +894,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_dz_kernel(WorkerTable tab, Co
   m = *reinterpret_cast<const f32x4*>(mu + (int64_t)c.unit * sh.cout + c.c4 * 4);
   rs = *reinterpret_cast<const f32x4*>(rstd + (int64_t)c.unit * sh.cout + c.c4 * 4);
   const int64_t e0 = c.row0 * sh.cout + c.c4 * 4;
-  for (int r = c.rg; r < c.nrows; r += c.n_rg) {
-    const f32x4 zz = *reinterpret_cast<const f32x4*>(z + e0 + (int64_t)r * sh.cout);
+  for_rows(c, z, e0, sh.cout, [&](int r, const f32x4& zz) {
     f32x4 o;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -876,7 +908,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_dz_kernel(WorkerTable tab, Co
     } else {
       *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(dz) + e0 + (int64_t)r * sh.cout) = o;
     }
-  }
+  });
 }
 
 // -------------------------------------------------------- weight gradient
@@ -1329,7 +1361,7 @@ int make_plan(const synk_convblock_desc* d, const int64_t* rows, int n_workers, 
     return o;
   };
   p->o_wmat = take((size_t)p->K * round_up((size_t)sh.cout, 32) * p->elem);
-  p->o_z = take((size_t)px * sh.cout * 4);
+  p->o_z = take((size_t)px * sh.cout * p->elem);
   p->o_dz = take((size_t)px * sh.cout * p->elem);
   p->o_statp = take((size_t)R * sh.n_chunks * sh.cout * 2 * 4);
   p->o_mu = take((size_t)p->n_units * sh.cout * 4);
@@ -1352,7 +1384,7 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   const ConvShape& sh = p.sh;
   const WorkerTable& tab = p.tab;
   T* wmat = reinterpret_cast<T*>(ws + p.o_wmat);
-  float* z = reinterpret_cast<float*>(ws + p.o_z);
+  T* z = reinterpret_cast<T*>(ws + p.o_z);
   T* dz = reinterpret_cast<T*>(ws + p.o_dz);
   float* statp = reinterpret_cast<float*>(ws + p.o_statp);
   float* mu = reinterpret_cast<float*>(ws + p.o_mu);
@@ -1383,19 +1415,19 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
     const dim3 gp((unsigned)((sh.H * (sh.W + 2) - 2 + kPatchTile - 1) / kPatchTile),
                   (unsigned)((sh.cout + 63) / 64), (unsigned)sh.total_images);
     hipLaunchKernelGGL(conv3x3_fwd_patch_kernel, gp, dim3(kThreads), 0, st, tab, sh,
-                       reinterpret_cast<const bf16_t*>(wmat), z);
+                       reinterpret_cast<const bf16_t*>(wmat), reinterpret_cast<bf16_t*>(z));
   } else {
     hipLaunchKernelGGL(conv3x3_fwd_kernel<T>, gf, dim3(kThreads), 0, st, tab, sh, (const T*)wmat, z);
   }
   SYNK_LAUNCH_CHECK();
   const dim3 gc((unsigned)((int64_t)sh.total_images * sh.n_chunks));
-  hipLaunchKernelGGL(bn_stats_chunk_kernel, gc, dim3(kThreads), 0, st, tab, sh, (const float*)z, statp);
+  hipLaunchKernelGGL(bn_stats_chunk_kernel<T>, gc, dim3(kThreads), 0, st, tab, sh, (const T*)z, statp);
   SYNK_LAUNCH_CHECK();
   hipLaunchKernelGGL(bn_stats_unit_kernel, dim3((unsigned)(((int64_t)p.n_units * sh.cout + 3) / 4)), dim3(kThreads), 0,
                      st, tab, sh,
                      (const float*)statp, mu, rstd);
   SYNK_LAUNCH_CHECK();
-  hipLaunchKernelGGL(bn_relu_pool_kernel, gc, dim3(kThreads), 0, st, tab, sh, params, (const float*)z,
+  hipLaunchKernelGGL(bn_relu_pool_kernel<T>, gc, dim3(kThreads), 0, st, tab, sh, params, (const T*)z,
                      (const float*)mu, (const float*)rstd, poolp);
   SYNK_LAUNCH_CHECK();
   const unsigned img_tiles = (unsigned)((sh.total_images + kImgTile - 1) / kImgTile);
@@ -1413,14 +1445,14 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
                      dim3(kThreads), 0, st, tab, sh, (const float*)pooled, (const float*)dlogits,
                      (const float*)row_loss, loss);
   SYNK_LAUNCH_CHECK();
-  hipLaunchKernelGGL(bn_bwd_chunk_kernel, gc, dim3(kThreads), 0, st, tab, sh, params, (const float*)z,
+  hipLaunchKernelGGL(bn_bwd_chunk_kernel<T>, gc, dim3(kThreads), 0, st, tab, sh, params, (const T*)z,
                      (const float*)mu, (const float*)rstd, (const float*)dpooled, bwdp);
   SYNK_LAUNCH_CHECK();
   hipLaunchKernelGGL(bn_bwd_worker_kernel, dim3((unsigned)((sh.n_workers * sh.cout + 3) / 4)), dim3(kThreads), 0, st,
                      tab, sh,
                      (const float*)bwdp, bmean);
   SYNK_LAUNCH_CHECK();
-  hipLaunchKernelGGL(bn_bwd_dz_kernel<T>, gc, dim3(kThreads), 0, st, tab, sh, params, (const float*)z,
+  hipLaunchKernelGGL(bn_bwd_dz_kernel<T>, gc, dim3(kThreads), 0, st, tab, sh, params, (const T*)z,
                      (const float*)mu, (const float*)rstd, (const float*)dpooled, (const float*)bmean, dz);
   SYNK_LAUNCH_CHECK();
   const dim3 gd((unsigned)(9 * ((sh.cin + 63) / 64) * ((sh.cout + 63) / 64)), (unsigned)p.n_runs,
