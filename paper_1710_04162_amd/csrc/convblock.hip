@@ -598,47 +598,6 @@ __global__ __launch_bounds__(kThreads) void bn_relu_pool_kernel(WorkerTable tab,
 }
 
 // ------------------------------------------------------------------- head
-constexpr int kImgTile = 8;   // images whose head work shares one pass over Wf
-
-// Pooled features and logits for kImgTile images x 256 classes per workgroup:
-// a thread owns one class and reads its column of Wf once for all the images.
-__global__ __launch_bounds__(kThreads) void head_logits_kernel(ConvShape sh, const float* __restrict__ params,
-                                                               const float* __restrict__ poolp,
-                                                               float* __restrict__ pooled,
-                                                               float* __restrict__ logits) {
-  __shared__ float sp[kImgTile][kMaxCout];
-  const int i0 = blockIdx.y * kImgTile, tid = threadIdx.x;
-  const int k = blockIdx.x * kThreads + tid;
-  const ParamOff po = param_off(sh.cin, sh.cout, sh.classes);
-  for (int e = tid; e < kImgTile * sh.cout; e += kThreads) {
-    const int i = e / sh.cout, ch = e - i * sh.cout;
-    float a = 0.0f;
-    if (i0 + i < sh.total_images) {
-#pragma unroll 8
-      for (int c = 0; c < sh.n_chunks; ++c) a += poolp[((int64_t)(i0 + i) * sh.n_chunks + c) * sh.cout + ch];
-      a /= (float)sh.HW;
-      if (blockIdx.x == 0) pooled[(int64_t)(i0 + i) * sh.cout + ch] = a;
-    }
-    sp[i][ch] = a;
-  }
-  __syncthreads();
-  if (k >= sh.classes) return;
-  const float* __restrict__ Wf = params + po.wf + k;
-  float acc[kImgTile];
-  const float b = params[po.bf + k];
-#pragma unroll
-  for (int i = 0; i < kImgTile; ++i) acc[i] = b;
-#pragma unroll 8
-  for (int ch = 0; ch < sh.cout; ++ch) {
-    const float wf = Wf[(int64_t)ch * sh.classes];
-#pragma unroll
-    for (int i = 0; i < kImgTile; ++i) acc[i] = fmaf(sp[i][ch], wf, acc[i]);
-  }
-#pragma unroll
-  for (int i = 0; i < kImgTile; ++i)
-    if (i0 + i < sh.total_images) logits[(int64_t)(i0 + i) * sh.classes + k] = acc[i];
-}
-
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
@@ -650,14 +609,24 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-// One workgroup per image: loss and d loss / d logits (in place of the
-// logits), both scaled by the image's weight in its worker's aggregate: 1/|R_w|
-// for MEAN (slice weight |R_s|/|R_w| times the slice mean's 1/|R_s|), 1/|R_s|
-// for SUM.
-__global__ __launch_bounds__(kThreads) void head_softmax_kernel(WorkerTable tab, ConvShape sh,
-                                                                float* __restrict__ dlogits,
-                                                                float* __restrict__ row_loss) {
-  __shared__ float sred[8];
+// One workgroup of 1024 threads per image: pooled features, logits (a thread
+// owns a class and walks its column of Wf, eight loads in flight), loss and
+// d loss / d logits, both scaled by the image's weight in its worker's
+// aggregate (1/|R_w| for MEAN: slice weight |R_s|/|R_w| times the slice mean's
+// 1/|R_s|; 1/|R_s| for SUM), and d loss / d p (a wavefront owns a channel and
+// walks its row of Wf).
+constexpr int kHeadThreads = 1024;
+__global__ __launch_bounds__(kHeadThreads) void head_image_kernel(WorkerTable tab, ConvShape sh,
+                                                                  const float* __restrict__ params,
+                                                                  const float* __restrict__ poolp,
+                                                                  float* __restrict__ pooled,
+                                                                  float* __restrict__ dlogits,
+                                                                  float* __restrict__ dpooled,
+                                                                  float* __restrict__ row_loss) {
+  __shared__ float sp[kMaxCout];
+  __shared__ float sl[kMaxClasses];
+  __shared__ float sred[2 * kHeadThreads / 64];
+  constexpr int NW = kHeadThreads / 64, PER = kMaxClasses / kHeadThreads;
   const int img = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   int w = 0;
   while (w + 1 < sh.n_workers && tab.row_off[w + 1] <= img) ++w;
@@ -668,20 +637,40 @@ __global__ __launch_bounds__(kThreads) void head_softmax_kernel(WorkerTable tab,
   int s0, sn;
   slice_bounds(tab.rows[w], sh.n_slices, s, &s0, &sn);
   const float scale = sh.grad_op == SYNK_MEAN ? 1.0f / (float)tab.rows[w] : 1.0f / (float)sn;
-  float* __restrict__ row = dlogits + (int64_t)img * sh.classes;
-  constexpr int PER = kMaxClasses / kThreads;
+  const ParamOff po = param_off(sh.cin, sh.cout, sh.classes);
+  const float* __restrict__ Wf = params + po.wf;
+
+  for (int ch = tid; ch < sh.cout; ch += kHeadThreads) {
+    float a = 0.0f;
+#pragma unroll 8
+    for (int c = 0; c < sh.n_chunks; ++c) a += poolp[((int64_t)img * sh.n_chunks + c) * sh.cout + ch];
+    a /= (float)sh.HW;
+    sp[ch] = a;
+    pooled[(int64_t)img * sh.cout + ch] = a;
+  }
+  __syncthreads();
+
   float l[PER];
   float mx = -INFINITY;
 #pragma unroll
   for (int q = 0; q < PER; ++q) {
-    const int k = q * kThreads + tid;
-    l[q] = k < sh.classes ? row[k] : -INFINITY;
+    const int k = q * kHeadThreads + tid;
+    l[q] = -INFINITY;
+    if (k < sh.classes) {
+      float a = params[po.bf + k];
+#pragma unroll 8
+      for (int ch = 0; ch < sh.cout; ++ch) a = fmaf(sp[ch], Wf[(int64_t)ch * sh.classes + k], a);
+      l[q] = a;
+      sl[k] = a;
+    }
     mx = fmaxf(mx, l[q]);
   }
   mx = wave_max(mx);
   if (lane == 0) sred[wv] = mx;
   __syncthreads();
-  mx = fmaxf(fmaxf(sred[0], sred[1]), fmaxf(sred[2], sred[3]));
+  mx = sred[0];
+#pragma unroll
+  for (int i = 1; i < NW; ++i) mx = fmaxf(mx, sred[i]);
   float se = 0.0f;
 #pragma unroll
   for (int q = 0; q < PER; ++q) {
@@ -689,52 +678,37 @@ __global__ __launch_bounds__(kThreads) void head_softmax_kernel(WorkerTable tab,
     se += l[q];
   }
   se = wave_sum(se);
-  if (lane == 0) sred[4 + wv] = se;
+  if (lane == 0) sred[NW + wv] = se;
   __syncthreads();
-  se = (sred[4] + sred[5]) + (sred[6] + sred[7]);
+  se = 0.0f;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) se += sred[NW + i];
   const int y = tab.y[w][j];
   const bool yok = y >= 0 && y < sh.classes;
-  if (tid == 0) row_loss[img] = (mx + logf(se) - (yok ? row[y] : 0.0f)) * scale;
-  __syncthreads();   // row[y] is read before any thread overwrites the row
+  if (tid == 0) row_loss[img] = (mx + logf(se) - (yok ? sl[y] : 0.0f)) * scale;
+  __syncthreads();   // sl[y] is read before sl is overwritten
   const float inv = 1.0f / se;
 #pragma unroll
   for (int q = 0; q < PER; ++q) {
-    const int k = q * kThreads + tid;
-    if (k < sh.classes) row[k] = (l[q] * inv - ((yok && k == y) ? 1.0f : 0.0f)) * scale;
+    const int k = q * kHeadThreads + tid;
+    if (k < sh.classes) {
+      const float d = (l[q] * inv - ((yok && k == y) ? 1.0f : 0.0f)) * scale;
+      sl[k] = d;
+      dlogits[(int64_t)img * sh.classes + k] = d;
+    }
+  }
+  __syncthreads();
+  for (int ch = wv; ch < sh.cout; ch += NW) {
+    const float* __restrict__ wr = Wf + (int64_t)ch * sh.classes;
+    float a = 0.0f;
+#pragma unroll 4
+    for (int k = lane; k < sh.classes; k += 64) a = fmaf(sl[k], wr[k], a);
+    a = wave_sum(a);
+    if (lane == 0) dpooled[(int64_t)img * sh.cout + ch] = a;
   }
 }
 
-// d loss / d p for kImgTile images: one wavefront per channel reads its row of
-// Wf once for all the images.
-__global__ __launch_bounds__(kThreads) void head_dpool_kernel(ConvShape sh, const float* __restrict__ params,
-                                                              const float* __restrict__ dlogits,
-                                                              float* __restrict__ dpooled) {
-  const int i0 = blockIdx.y * kImgTile, lane = threadIdx.x & 63;
-  const int ch = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-  if (ch >= sh.cout) return;
-  const ParamOff po = param_off(sh.cin, sh.cout, sh.classes);
-  const float* __restrict__ Wf = params + po.wf + (int64_t)ch * sh.classes;
-  const int n = min(kImgTile, sh.total_images - i0);
-  // rows past the last image re-read the last one (their sums are not stored): every load is
-  // unconditional, so that the loads of several k are in flight together
-  const float* rows[kImgTile];
-#pragma unroll
-  for (int i = 0; i < kImgTile; ++i) rows[i] = dlogits + (int64_t)(i0 + min(i, n - 1)) * sh.classes;
-  float acc[kImgTile];
-#pragma unroll
-  for (int i = 0; i < kImgTile; ++i) acc[i] = 0.0f;
-#pragma unroll 4
-  for (int k = lane; k < sh.classes; k += 64) {
-    const float wf = Wf[k];
-#pragma unroll
-    for (int i = 0; i < kImgTile; ++i) acc[i] = fmaf(rows[i][k], wf, acc[i]);
-  }
-#pragma unroll
-  for (int i = 0; i < kImgTile; ++i) {
-    const float a = wave_sum(acc[i]);
-    if (lane == 0 && i < n) dpooled[(int64_t)(i0 + i) * sh.cout + ch] = a;
-  }
-}
+constexpr int kImgTile = 8;   // images held in registers at a time by head_worker_kernel
 
 // Per worker and class k: dWf[:, k], dbf[k] over the worker's images in image
 // order, kImgTile images at a time held in registers; workgroup (0, w) also
@@ -1430,16 +1404,8 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   hipLaunchKernelGGL(bn_relu_pool_kernel<T>, gc, dim3(kThreads), 0, st, tab, sh, params, (const T*)z,
                      (const float*)mu, (const float*)rstd, poolp);
   SYNK_LAUNCH_CHECK();
-  const unsigned img_tiles = (unsigned)((sh.total_images + kImgTile - 1) / kImgTile);
-  const unsigned class_tiles = (unsigned)((sh.classes + kThreads - 1) / kThreads);
-  hipLaunchKernelGGL(head_logits_kernel, dim3(class_tiles, img_tiles), dim3(kThreads), 0, st, sh, params,
-                     (const float*)poolp, pooled, dlogits);
-  SYNK_LAUNCH_CHECK();
-  hipLaunchKernelGGL(head_softmax_kernel, dim3((unsigned)sh.total_images), dim3(kThreads), 0, st, tab, sh, dlogits,
-                     row_loss);
-  SYNK_LAUNCH_CHECK();
-  hipLaunchKernelGGL(head_dpool_kernel, dim3((unsigned)((sh.cout + 3) / 4), img_tiles), dim3(kThreads), 0, st, sh,
-                     params, (const float*)dlogits, dpooled);
+  hipLaunchKernelGGL(head_image_kernel, dim3((unsigned)sh.total_images), dim3(kHeadThreads), 0, st, tab, sh, params,
+                     (const float*)poolp, pooled, dlogits, dpooled, row_loss);
   SYNK_LAUNCH_CHECK();
   hipLaunchKernelGGL(head_worker_kernel, dim3((unsigned)((sh.classes + kThreads - 1) / kThreads), (unsigned)sh.n_workers),
                      dim3(kThreads), 0, st, tab, sh, (const float*)pooled, (const float*)dlogits,
