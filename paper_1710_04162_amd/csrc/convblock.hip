@@ -1093,14 +1093,22 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_rows_kernel(WorkerTabl
   struct Set { u32x4 rx[5], rd[2]; };
   Set setA, setB;
 
+  // (unsigned compares fold the two-sided range checks; pixel indexes are 32-bit, the byte offset
+  // is one 32 x 32 -> 64-bit multiply-add)
+  const int xrow_b = sh.cin * 2, drow_b = sh.cout * 2;
+  const int xoff_b = (c0 + kv * 8) * 2, doff_b = (n0 + kv * 8) * 2;
   auto x_load = [&](int s, int img, int hp, int wp) -> u32x4 {
-    const int hx = hp + kh - 1;
-    const bool ok = xcok && s >= 0 && s < S && wp >= 1 && wp <= sh.W && hx >= 1 && hx <= sh.H;
-    return load_or_zero(xw, (((int64_t)img + (hx - 1) * sh.W + (wp - 1)) * sh.cin + c0 + kv * 8) * 2, ok);
+    const int hx = hp + kh - 2;                       // image row of the tap, 0-based
+    const bool ok = xcok && (unsigned)s < (unsigned)S && (unsigned)(wp - 1) < (unsigned)sh.W &&
+                    (unsigned)hx < (unsigned)sh.H;
+    const int pix = img + hx * sh.W + (wp - 1);
+    return load_or_zero(xw, (int64_t)pix * (int64_t)xrow_b + xoff_b, ok);
   };
   auto d_load = [&](int s, int img, int hp, int wp) -> u32x4 {
-    const bool ok = dcok && s >= s_begin && s < s_end && wp >= 1 && wp <= sh.W;
-    return load_or_zero(dzw, (((int64_t)img + (hp - 1) * sh.W + (wp - 1)) * sh.cout + n0 + kv * 8) * 2, ok);
+    const bool ok = dcok && (unsigned)(s - s_begin) < (unsigned)(s_end - s_begin) &&
+                    (unsigned)(wp - 1) < (unsigned)sh.W;
+    const int pix = img + (hp - 1) * sh.W + (wp - 1);
+    return load_or_zero(dzw, (int64_t)pix * (int64_t)drow_b + doff_b, ok);
   };
   auto next_pos = [&](int& img, int& hp, int& wp) {   // one position on
     if (++wp >= Wp) {
