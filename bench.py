@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 # HBM bytes per launch of each config's dominant kernel, from rocprofv3 --pmc FETCH_SIZE and
 # --pmc WRITE_SIZE runs of this file (10 steps), scaled by what the same counters read for the
 # plain copy of --config 0 (fetch x2.000, write x1.000).  Summaries: profiles/*_kernel_stats.txt.
-MEASURED_TRAFFIC_BYTES = {2: 210.37e6, 3: 1226.76e6, 4: 192.84e6, 5: 271.42e6, 6: 78.90e6}
+MEASURED_TRAFFIC_BYTES = {2: 210.37e6, 3: 1226.76e6, 4: 192.84e6, 5: 271.42e6, 6: 63.59e6}
 
 
 def parse():
@@ -437,9 +437,9 @@ class ConvStep:
         self.workload = ("config 6: conv3x3 + batch-norm + ReLU block %dx%dx%d -> %d, pool, %d-way softmax; step "
                          "with batch %d over %d worker shares x %d slice, bf16 contraction inputs / fp32 "
                          "accumulate" % (H, W, cin, cout, classes, self.B, self.N, self.S))
-        # dominant kernel: the weight gradient of the convolution, a [9 C_in x pixels] . [pixels x C_out]
-        # contraction (as many flops as the forward convolution)
-        self.dom_name = "conv3x3_dw_rows_kernel"
+        # dominant kernel: the forward convolution, a [pixels x 9 C_in] . [9 C_in x C_out] contraction (its
+        # weight gradient has as many flops and takes about as long)
+        self.dom_name = "conv3x3_fwd_patch_kernel"
         self.dom_bound, self.dom_unit = "mfma", "TFLOP/s"
         self.dom_peak = 2500.0 if self.bf16 else 157.3
         self.dom_work = 2.0 * self.B * H * W * 9 * cin * cout       # flops per launch

@@ -100,7 +100,7 @@ const char* synk_status_string(int status);
 /* For callers that time one kernel: the next launch, on this host thread, of
  * a call's main kernel (the fused reduce+update kernels, the reduce and
  * collective kernels, the uint8 gather, stage 1 of synk_sliced_eval, the
- * convolution weight gradient of synk_sliced_grad_conv) carries
+ * forward convolution of synk_sliced_grad_conv) carries
  * the two events (hipEvent_t created with timing enabled, passed as void*):
  * start_event takes the dispatch's begin timestamp and stop_event its end
  * timestamp, so hipEventElapsedTime between them is the kernel's duration

@@ -1246,14 +1246,198 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_rows_kernel(WorkerTabl
   }
 }
 
+// The weight gradient for bf16, C_in a multiple of 64 and image rows of 31..61
+// pixels: all nine taps in one workgroup of twelve wavefronts, one padded image
+// row per step.  A worker's padded rows g = image * (H+2) + hx (hx = 0 and H+1
+// are the zero rows) slide through a ring in LDS: a step with dz row g needs X
+// rows g-1, g, g+1, each laid out once as 66 entries b = wp + 1 (pixel pairs
+// interleaved per 32-bit word, zeros at the border), so that tap kw of dz entry
+// j = wp is X entry j + kw: taps 0 and 2 start on a word, tap 1 is the funnel
+// shift of two neighbouring words.  X and dz are read from memory once.  Wave
+// (kernel row kh, c half, o half) holds the three taps of its kernel row for a
+// 32 x 32 tile; per step it reads one X row and the dz row.  Threads 0..255
+// bring in the X row that enters the ring, threads 256..511 the dz row, two
+// 16-byte vectors each, three steps ahead of their use (three register sets
+// that take turns); the row decode is wave-uniform.
+constexpr int kRingThreads = 768;
+constexpr int kRingP = 72;                      // words per pixel-pair row (64 + 8: see kRowsPitch)
+constexpr int kRingXWords = 33 * kRingP, kRingDWords = 32 * kRingP;
+
+__global__ __launch_bounds__(kRingThreads, 1) void conv3x3_dw_ring_kernel(WorkerTable tab, ConvShape sh,
+                                                                         const bf16_t* __restrict__ dz,
+                                                                         float* __restrict__ dwp, int n_runs,
+                                                                         int run_rows) {
+  __shared__ __attribute__((aligned(16))) uint32_t xs[4][kRingXWords];   // X row r in slot (r + 4) & 3
+  __shared__ __attribute__((aligned(16))) uint32_t ds[2][kRingDWords];   // dz row r in slot r & 1
+  const int w = blockIdx.z, run = blockIdx.y;
+  const int ot = (sh.cout + 63) / 64;
+  const int c0 = (blockIdx.x / ot) * 64, n0 = (blockIdx.x % ot) * 64;
+  const int HP = sh.H + 2;
+  const int G = tab.rows[w] * HP;
+  const int g0 = min(run * run_rows, G), g1 = min(g0 + run_rows, G);
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int xi = lane & 31, gk = lane >> 5;
+  const int kh = wv >> 2, cti = wv & 1, coti = (wv >> 1) & 1;
+  // loaders: unit = (pixel pair pr, 8 channels kv) of the X row (role 0) or the dz row (role 1)
+  const int role = tid >> 8, kv = tid & 7, pr = (tid >> 3) & 31;
+
+  const bf16_t* __restrict__ xw = reinterpret_cast<const bf16_t*>(tab.x[w]);
+  const bf16_t* __restrict__ dzw = dz + (int64_t)tab.row_off[w] * sh.HW * sh.cout;
+  // the unit's two pixels: X entries b = 2pr, 2pr+1 are w = 2pr-2, 2pr-1; dz entries j = 2pr,
+  // 2pr+1 are w = 2pr-1, 2pr
+  const bool isx = role == 0, isd = role == 1;
+  const int wpx = 2 * pr - (isx ? 2 : 1);
+  const int chn = (isx ? c0 : n0) + kv * 8, nch = isx ? sh.cin : sh.cout;
+  const bool v0 = role < 2 && chn < nch && wpx >= 0 && wpx < sh.W;
+  const bool v1 = role < 2 && chn < nch && wpx + 1 >= 0 && wpx + 1 < sh.W;
+  const int64_t off0 = ((int64_t)wpx * nch + chn) * 2, off1 = off0 + (int64_t)nch * 2;
+  const int64_t row_bytes = (int64_t)sh.W * nch * 2;
+  const bf16_t* __restrict__ src = isx ? xw : dzw;
+
+  struct Row { int g, i, h; };     // padded row g = i * (H+2) + h (wave-uniform)
+  auto row_at = [&](int g) {
+    Row r;
+    r.g = g;
+    r.i = (g + HP) / HP - 1;
+    r.h = g - r.i * HP;
+    return r;
+  };
+  auto next_row = [&](Row& r) {
+    ++r.g;
+    if (++r.h == HP) { r.h = 0; ++r.i; }
+  };
+  struct Set { u32x4 a, b; };
+  // the X loaders take row xr, the dz loaders row dr (a dz row outside the run reads as zeros)
+  auto gload = [&](Set& s, const Row& xr, const Row& dr) {
+    const Row& r = isx ? xr : dr;
+    const bool ok = r.h >= 1 && r.h <= sh.H && (isx ? (r.g >= 0 && r.g < G) : (r.g >= g0 && r.g < g1));
+    const int64_t base = ((int64_t)r.i * sh.H + (r.h - 1)) * row_bytes;
+    s.a = load_or_zero(src, base + off0, ok && v0);
+    s.b = load_or_zero(src, base + off1, ok && v1);
+  };
+  auto lstore = [&](const Set& s, int xg, int dg) {
+    if (role < 2) {
+      // word j = (a[j], b[j]) as (low half, high half): entries 2pr and 2pr+1 of 8 channels
+      const u32x4& a = s.a;
+      const u32x4& b = s.b;
+      u32x4 lo, hi;
+      lo.x = __builtin_amdgcn_perm(b.x, a.x, 0x05040100u); lo.y = __builtin_amdgcn_perm(b.x, a.x, 0x07060302u);
+      lo.z = __builtin_amdgcn_perm(b.y, a.y, 0x05040100u); lo.w = __builtin_amdgcn_perm(b.y, a.y, 0x07060302u);
+      hi.x = __builtin_amdgcn_perm(b.z, a.z, 0x05040100u); hi.y = __builtin_amdgcn_perm(b.z, a.z, 0x07060302u);
+      hi.z = __builtin_amdgcn_perm(b.w, a.w, 0x05040100u); hi.w = __builtin_amdgcn_perm(b.w, a.w, 0x07060302u);
+      uint32_t* base = isx ? xs[(xg + 4) & 3] : ds[dg & 1];
+      u32x4* d = reinterpret_cast<u32x4*>(base + pr * kRingP + kv * 8);
+      d[0] = lo;
+      d[1] = hi;
+    }
+  };
+
+  f32x16 acc[3] = {zero16(), zero16(), zero16()};
+  auto compute = [&](int g) {
+    const uint32_t* D = ds[g & 1] + coti * 32 + xi;
+    const uint32_t* X = xs[(g + kh + 3) & 3] + cti * 32 + xi;     // X row g + kh - 1
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int r = (ks * 8 + gk * 4) * kRingP;
+      const u32x4 d = {D[r], D[r + kRingP], D[r + 2 * kRingP], D[r + 3 * kRingP]};
+      const uint32_t w0 = X[r], w1 = X[r + kRingP], w2 = X[r + 2 * kRingP], w3 = X[r + 3 * kRingP],
+                     w4 = X[r + 4 * kRingP];
+      const u32x4 t0 = {w0, w1, w2, w3};
+      const u32x4 t1 = {__builtin_amdgcn_alignbit(w1, w0, 16), __builtin_amdgcn_alignbit(w2, w1, 16),
+                        __builtin_amdgcn_alignbit(w3, w2, 16), __builtin_amdgcn_alignbit(w4, w3, 16)};
+      const u32x4 t2 = {w1, w2, w3, w4};
+      acc[0] = mma(bf16_t(), t0, d, acc[0]);
+      acc[1] = mma(bf16_t(), t1, d, acc[1]);
+      acc[2] = mma(bf16_t(), t2, d, acc[2]);
+    }
+  };
+
+  const int n_steps = g1 - g0;
+  if (n_steps > 0) {
+    // entries 64, 65 (pair row 32) of every X slot stay zero: rows are at most 61 pixels wide
+    for (int e = tid; e < 4 * 64; e += kRingThreads) xs[e >> 6][32 * kRingP + (e & 63)] = 0u;
+    // rows g0-1, g0, g0+1 of X and row g0 of dz go straight to LDS; the rows of the next two
+    // steps wait in registers
+    Set s0, s1, s2;
+    {
+      Set a, b;
+      Row q = row_at(g0 - 1);
+      const Row none = row_at(-1);     // no dz row: -1 is outside every run
+      gload(s0, q, row_at(g0));        // X g0-1, dz g0
+      next_row(q);
+      gload(a, q, none);               // X g0
+      next_row(q);
+      gload(b, q, none);               // X g0+1
+      lstore(s0, g0 - 1, g0);
+      if (isx) {
+        lstore(a, g0, 0);
+        lstore(b, g0 + 1, 0);
+      }
+    }
+    // xr, dr: the rows the next gload brings in.  Before the loop: (X g0+2, dz g0+1) -> s1,
+    // (X g0+3, dz g0+2) -> s2; step t then loads (X g0+t+4, dz g0+t+3).
+    Row xr = row_at(g0 + 2), dr = row_at(g0 + 1);
+    gload(s1, xr, dr);
+    next_row(xr); next_row(dr);
+    gload(s2, xr, dr);
+    next_row(xr); next_row(dr);
+    __syncthreads();
+
+    Row cur = row_at(g0);
+    // step: issue the loads of the rows three steps on, compute row cur, store the rows of the
+    // next step (loaded two steps ago), barrier.  Every step issues its loads and stores its
+    // set, also past the end of the run (rows outside it load as zeros and land in slots nobody
+    // reads), and the loop always does three steps per trip: each register set is back in its
+    // own registers at the back edge, so no loaded value is ever copied (a copy would force a
+    // wait for its load) and the wait before a store is for that set only.
+    auto step = [&](Set& issue, const Set& store) {
+      gload(issue, xr, dr);
+      next_row(xr); next_row(dr);
+      if (cur.g < g1 && cur.h >= 1 && cur.h <= sh.H) compute(cur.g);
+      lstore(store, cur.g + 2, cur.g + 1);
+      next_row(cur);
+      __syncthreads();
+    };
+    for (int t = 0; t < n_steps; t += 3) {
+      step(s0, s1);
+      step(s1, s2);
+      step(s2, s0);
+    }
+  }
+
+  const int K = 9 * sh.cin;
+  float* __restrict__ out = dwp + ((int64_t)(w * n_runs + run) * K + (int64_t)kh * 3 * sh.cin) * sh.cout;
+  const int col = n0 + coti * 32 + xi;
+  if (col < sh.cout) {
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int c = c0 + cti * 32 + gk * 4 + (v >> 2) * 8 + (v & 3);
+        if (c < sh.cin) out[((int64_t)a * sh.cin + c) * sh.cout + col] = acc[a][v];
+      }
+    }
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void conv_dw_fold_kernel(WorkerTable tab, const float* __restrict__ dwp,
                                                                 int n_runs, int64_t len) {
   const int w = blockIdx.y;
   const int64_t i = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
   if (i >= len) return;
   const float* p = dwp + (int64_t)w * n_runs * len + i;
-  f32x4 a = *reinterpret_cast<const f32x4*>(p);
-  for (int r = 1; r < n_runs; ++r) a += *reinterpret_cast<const f32x4*>(p + (int64_t)r * len);
+  // eight loads at a time (a run past the last re-reads the last one and is dropped), added in
+  // run order
+  f32x4 a = {0.f, 0.f, 0.f, 0.f};
+  for (int r0 = 0; r0 < n_runs; r0 += 8) {
+    f32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4*>(p + (int64_t)min(r0 + u, n_runs - 1) * len);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (r0 + u < n_runs) a += v[u];
+  }
   *reinterpret_cast<f32x4*>(tab.grad[w] + i) = a;
 }
 
@@ -1262,7 +1446,7 @@ struct Plan {
   ConvShape sh;
   WorkerTable tab;
   int64_t K, P;
-  int max_unit_images, max_rows, n_units, n_runs, run_rows, n_runs_rows, run_len_rows;
+  int max_unit_images, max_rows, n_units, n_runs, run_rows, n_runs_rows, run_len_rows, n_runs_ring, run_rows_ring;
   size_t elem;
   // workspace offsets in bytes
   size_t o_wmat, o_z, o_dz, o_statp, o_mu, o_rstd, o_poolp, o_pooled, o_dpooled, o_dlogits, o_row_loss, o_bwdp,
@@ -1333,6 +1517,17 @@ int make_plan(const synk_convblock_desc* d, const int64_t* rows, int n_workers, 
     rl = (rl + kRowsBR - 1) / kRowsBR * kRowsBR;
     p->n_runs_rows = (int)r2;
     p->run_len_rows = (int)rl;
+    // the ring kernel: one workgroup per (tile, run, worker), about one per CU, a dozen padded
+    // image rows or more per run
+    const int64_t t9 = tiles / 9 * n_workers;
+    const int64_t max_g = (int64_t)p->max_rows * (sh.H + 2);
+    int64_t r3 = (kNumCU + t9 - 1) / t9;
+    const int64_t cap3 = max_g / 12;
+    if (r3 > cap3) r3 = cap3;
+    if (r3 > 64) r3 = 64;
+    if (r3 < 1) r3 = 1;
+    p->n_runs_ring = (int)r3;
+    p->run_rows_ring = (int)((max_g + r3 - 1) / r3);
   }
 
   const int64_t R = total, px = total * sh.HW;
@@ -1355,7 +1550,7 @@ int make_plan(const synk_convblock_desc* d, const int64_t* rows, int n_workers, 
   p->o_row_loss = take((size_t)R * 4);
   p->o_bwdp = take((size_t)R * sh.n_chunks * sh.cout * 2 * 4);
   p->o_bmean = take((size_t)p->n_units * sh.cout * 2 * 4);
-  const int runs_max = std::max(p->n_runs, p->n_runs_rows);
+  const int runs_max = std::max(p->n_runs, std::max(p->n_runs_rows, p->n_runs_ring));
   p->o_dwp = take((size_t)n_workers * runs_max * p->K * sh.cout * 4);
   p->total = at;
   return SYNK_OK;
@@ -1396,10 +1591,10 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   if (patch_ok) {
     const dim3 gp((unsigned)((sh.H * (sh.W + 2) - 2 + kPatchTile - 1) / kPatchTile),
                   (unsigned)((sh.cout + 63) / 64), (unsigned)sh.total_images);
-    hipLaunchKernelGGL(conv3x3_fwd_patch_kernel, gp, dim3(kThreads), 0, st, tab, sh,
-                       reinterpret_cast<const bf16_t*>(wmat), reinterpret_cast<bf16_t*>(z));
+    SYNK_LAUNCH_TIMED(conv3x3_fwd_patch_kernel, gp, dim3(kThreads), 0, st, tab, sh,
+                      reinterpret_cast<const bf16_t*>(wmat), reinterpret_cast<bf16_t*>(z));
   } else {
-    hipLaunchKernelGGL(conv3x3_fwd_kernel<T>, gf, dim3(kThreads), 0, st, tab, sh, (const T*)wmat, z);
+    SYNK_LAUNCH_TIMED(conv3x3_fwd_kernel<T>, gf, dim3(kThreads), 0, st, tab, sh, (const T*)wmat, z);
   }
   SYNK_LAUNCH_CHECK();
   const dim3 gc((unsigned)((int64_t)sh.total_images * sh.n_chunks));
@@ -1431,16 +1626,22 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   SYNK_LAUNCH_CHECK();
   const dim3 gd((unsigned)(9 * ((sh.cin + 63) / 64) * ((sh.cout + 63) / 64)), (unsigned)p.n_runs,
                 (unsigned)sh.n_workers);
+  const bool ring_ok = patch_ok && sh.W >= 31;     // rows wide enough to fill most of a 64-position step
   int fold_runs = p.n_runs;
-  if (patch_ok) {
+  if (ring_ok) {
+    fold_runs = p.n_runs_ring;
+    const dim3 gg((unsigned)((sh.cin / 64) * ((sh.cout + 63) / 64)), (unsigned)p.n_runs_ring, (unsigned)sh.n_workers);
+    hipLaunchKernelGGL(conv3x3_dw_ring_kernel, gg, dim3(kRingThreads), 0, st, tab, sh,
+                       reinterpret_cast<const bf16_t*>(dz), dwp, p.n_runs_ring, p.run_rows_ring);
+  } else if (patch_ok) {
     fold_runs = p.n_runs_rows;
     const int64_t groups = (int64_t)((sh.cin + 63) / 64) * ((sh.cout + 63) / 64) * p.n_runs_rows * sh.n_workers;
     const dim3 gr((unsigned)(3 * ((groups + 7) / 8) * 8));
-    SYNK_LAUNCH_TIMED(conv3x3_dw_rows_kernel, gr, dim3(kThreads), 0, st, tab, sh,
-                      reinterpret_cast<const bf16_t*>(dz), dwp, p.n_runs_rows, p.run_len_rows);
+    hipLaunchKernelGGL(conv3x3_dw_rows_kernel, gr, dim3(kThreads), 0, st, tab, sh,
+                       reinterpret_cast<const bf16_t*>(dz), dwp, p.n_runs_rows, p.run_len_rows);
   } else {
-    SYNK_LAUNCH_TIMED(conv3x3_dw_kernel<T>, gd, dim3(kThreads), 0, st, tab, sh, (const T*)dz, dwp, p.n_runs,
-                      p.run_rows);
+    hipLaunchKernelGGL(conv3x3_dw_kernel<T>, gd, dim3(kThreads), 0, st, tab, sh, (const T*)dz, dwp, p.n_runs,
+                       p.run_rows);
   }
   SYNK_LAUNCH_CHECK();
   hipLaunchKernelGGL(conv_dw_fold_kernel, dim3((unsigned)((wn / 4 + kThreads - 1) / kThreads), (unsigned)sh.n_workers),
