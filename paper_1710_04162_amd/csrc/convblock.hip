@@ -213,7 +213,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_kernel(WorkerTable ta
 
   const int cpt = (sh.cin + BK - 1) / BK;   // k-tiles per tap
   const int n_kt = 9 * cpt;
-  const u32x4 zero = {0u, 0u, 0u, 0u};
   u32x4 ra[4], rb[2];
 
   auto gload = [&](int t) {
@@ -328,7 +327,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_patch_kernel(WorkerTa
   const int chunks = sh.cin / 64;
 
   f32x16 acc[4] = {zero16(), zero16(), zero16(), zero16()};
-  const u32x4 zero = {0u, 0u, 0u, 0u};
   constexpr int kAhead = 4;          // taps whose weights are in flight ahead of the one in use
   for (int cc = 0; cc < sh.cin; cc += 64) {
     if (cc > 0) __syncthreads();     // every wave is done with the previous chunk's patch
@@ -894,8 +892,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_dz_kernel(WorkerTable tab, Co
 // interleaved per 32-bit word), which is the form the MFMA operands gather
 // from.
 template <typename T> struct DwGeom;
-template <> struct DwGeom<bf16_t> { static constexpr int BR = 64, ROWS_PER_T = 2, LROWS = 32; };
-template <> struct DwGeom<float> { static constexpr int BR = 32, ROWS_PER_T = 2, LROWS = 32; };
+template <> struct DwGeom<bf16_t> { static constexpr int BR = 64, LROWS = 32; };
+template <> struct DwGeom<float> { static constexpr int BR = 32, LROWS = 32; };
 
 template <typename T>
 __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_kernel(WorkerTable tab, ConvShape sh,
@@ -939,7 +937,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_kernel(WorkerTable tab
   }
   const int adv_h = BR / sh.W, adv_w = BR - adv_h * sh.W;
   const int rl[2] = {rl0, rl1};
-  const u32x4 zero = {0u, 0u, 0u, 0u};
   u32x4 rx[2], rd[2];
 
   auto gload = [&](int r0) {
@@ -1088,7 +1085,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_rows_kernel(WorkerTabl
     pimg = (i - 1) * sh.HW;
   }
   const int adv_h = kRowsBR / Wp, adv_w = kRowsBR - adv_h * Wp;
-  const u32x4 zero = {0u, 0u, 0u, 0u};
   // one step's loads: X rows l .. l+2 (and, for pair 0, rows 64, 65); dz at the positions of rows l+1, l+2
   struct Set { u32x4 rx[5], rd[2]; };
   Set setA, setB;
@@ -1286,7 +1282,7 @@ __global__ __launch_bounds__(kRingThreads, 1) void conv3x3_dw_ring_kernel(Worker
   const bf16_t* __restrict__ dzw = dz + (int64_t)tab.row_off[w] * sh.HW * sh.cout;
   // the unit's two pixels: X entries b = 2pr, 2pr+1 are w = 2pr-2, 2pr-1; dz entries j = 2pr,
   // 2pr+1 are w = 2pr-1, 2pr
-  const bool isx = role == 0, isd = role == 1;
+  const bool isx = role == 0;
   const int wpx = 2 * pr - (isx ? 2 : 1);
   const int chn = (isx ? c0 : n0) + kv * 8, nch = isx ? sh.cin : sh.cout;
   const bool v0 = role < 2 && chn < nch && wpx >= 0 && wpx < sh.W;
