@@ -15,7 +15,7 @@
 // wave-uniform offset away from the pixel's own address.  Both contractions
 // (forward, weight gradient) run on the matrix cores (MFMA 32x32x16 bf16 or
 // 32x32x2 fp32, fp32 accumulators) out of LDS; everything between them is
-// fp32 streaming work over z.
+// streaming work over z (kept in the compute type) in fp32 arithmetic.
 //
 // No floating-point atomics: every sum has a fixed order.
 #include <math.h>
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_kernel(WorkerTable ta
 // once, zeros included; the nine taps then read shifted rows of that patch.
 // Wave (row half, column tile) owns 128 positions x 32 channels; its slice of
 // the weights comes straight from memory in operand order
-// (conv_weight_frag_kernel), one tap ahead, so the tap loop has no barrier.
+// (conv_weight_frag_kernel), a few taps ahead, so the tap loop has no barrier.
 constexpr int kPatchTile = 256, kPatchMaxRows = kPatchTile + 2 * 64;
 
 __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_patch_kernel(WorkerTable tab, ConvShape sh,
@@ -1187,9 +1187,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_rows_kernel(WorkerTabl
     }
   };
 
-  // Loads run two steps ahead of the MFMAs: step t+1 sits in one register set, step t+2 in the
-  // other, while step t is computed out of LDS.  A set is stored to LDS one step before its
-  // use and refilled at once with the step after next.
   // Loads run two steps ahead of the MFMAs: step t+1 sits in one register set, step t+2 in the
   // other, while step t is computed out of LDS.  A set is stored to LDS one step before its
   // use and refilled at once with the step after next.
