@@ -282,18 +282,19 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_kernel(WorkerTable ta
 // 61 pixels, in the coordinates of the zero-padded image: position u = hp * Wp +
 // wp on the (H+2) x (W+2) grid, Wp = W + 2.  There a tap is the plain shift
 // (kh-1) * Wp + (kw-1) of the position index, with no case distinction at the
-// border.  A workgroup takes 256 consecutive positions of one image (from the
+// border.  A workgroup takes TILE consecutive positions of one image (from the
 // first real pixel on; border positions in between are computed and dropped)
 // and lays the positions it can reach, one 64-channel chunk at a time, into LDS
 // once, zeros included; the nine taps then read shifted rows of that patch.
-// Wave (row half, column tile) owns 128 positions x 32 channels; its slice of
+// Wave (row half, column tile) owns TILE/2 positions x 32 channels; its slice of
 // the weights comes straight from memory in operand order
 // (conv_weight_frag_kernel), a few taps ahead, so the tap loop has no barrier.
-constexpr int kPatchTile = 256, kPatchMaxRows = kPatchTile + 2 * 64;
-
-__global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_patch_kernel(WorkerTable tab, ConvShape sh,
+template <int TILE, int MINB, int AHEAD>
+__global__ __launch_bounds__(kThreads, MINB) void conv3x3_fwd_patch_kernel(WorkerTable tab, ConvShape sh,
                                                                         const bf16_t* __restrict__ wmat,
                                                                         bf16_t* __restrict__ z) {
+  constexpr int kPatchTile = TILE, kPatchMaxRows = TILE + 2 * 64;
+  constexpr int RT = TILE / 64;                  // 32-row MFMA tiles per wavefront (it owns TILE/2 positions)
   __shared__ __attribute__((aligned(16))) char patch[kPatchMaxRows * kLdsRow];
   __shared__ int zrow[kPatchTile];
 
@@ -312,7 +313,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_patch_kernel(WorkerTa
   const int kv = tid & 7, ur = tid >> 3;
 
   // output row of every position of the tile (-1: border position or past the image)
-  {
+  if (tid < kPatchTile) {
     const int r = tile * kPatchTile + tid;
     const int u = first + r;
     const int hp = u / Wp, wp = u - hp * Wp;
@@ -326,8 +327,10 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_patch_kernel(WorkerTa
   const int wstep = tiles32 * 256;                 // vectors from one (tap, chunk) to the next
   const int chunks = sh.cin / 64;
 
-  f32x16 acc[4] = {zero16(), zero16(), zero16(), zero16()};
-  constexpr int kAhead = 4;          // taps whose weights are in flight ahead of the one in use
+  f32x16 acc[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) acc[rt] = zero16();
+  constexpr int kAhead = AHEAD;      // taps whose weights are in flight ahead of the one in use
   for (int cc = 0; cc < sh.cin; cc += 64) {
     if (cc > 0) __syncthreads();     // every wave is done with the previous chunk's patch
     u32x4 b[kAhead + 1][4];
@@ -335,7 +338,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_patch_kernel(WorkerTa
     for (int tp = 0; tp < kAhead; ++tp)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) b[tp][kk] = wfrag[(int64_t)(tp * chunks + cc / 64) * wstep + kk * 64];
-    // patch row j holds position tile*256 + j (that is first + tile*256 + j - (Wp+1)); all of a
+    // patch row j holds position tile*TILE + j (that is first + tile*TILE + j - (Wp+1)); all of a
     // thread's loads are issued before the first of them is stored
     {
       constexpr int NIT = kPatchMaxRows / 32;
@@ -366,11 +369,11 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_patch_kernel(WorkerTa
           b[(tap + kAhead) % (kAhead + 1)][kk] = wfrag[(int64_t)((tap + kAhead) * chunks + cc / 64) * wstep + kk * 64];
       }
       const int d = (tap / 3 - 1) * Wp + (tap % 3 - 1);
-      const char* A = patch + (rh * 128 + xi + first + d) * kLdsRow + gk * 16;
+      const char* A = patch + (rh * (TILE / 2) + xi + first + d) * kLdsRow + gk * 16;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
 #pragma unroll
-        for (int rt = 0; rt < 4; ++rt) {
+        for (int rt = 0; rt < RT; ++rt) {
           const u32x4 a = *reinterpret_cast<const u32x4*>(A + rt * 32 * kLdsRow + kk * 32);
           acc[rt] = mma(bf16_t(), a, b[tap % (kAhead + 1)][kk], acc[rt]);
         }
@@ -378,18 +381,19 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_patch_kernel(WorkerTa
     }
   }
 
-  // Output through LDS, one half of the tile (128 positions x 64 channels fp32) at a time, so
-  // that z is written in whole 128-byte rows of bf16.  Row pitch 72 floats: the two lane groups
-  // of a wavefront (rows 4 apart) land in different banks.
+  // Output through LDS, 128 positions x 64 channels fp32 at a time, so that z is written in whole
+  // 128-byte rows of bf16.  Row pitch 72 floats: the two lane groups of a wavefront (rows 4
+  // apart) land in different banks.
   constexpr int kPitch = 72;
   float* stage = reinterpret_cast<float*>(patch);
   bf16_t* __restrict__ zi = z + (int64_t)img * sh.HW * sh.cout;
-  for (int h = 0; h < 2; ++h) {
-    __syncthreads();       // the patch (h = 0) or the first half's rows (h = 1) have been read
-    if (rh == h) {
+  for (int h = 0; h < TILE / 128; ++h) {
+    __syncthreads();       // the patch (h = 0) or the pass before has been read
 #pragma unroll
-      for (int rt = 0; rt < 4; ++rt) {
-        float* sp = stage + (rt * 32 + gk * 4) * kPitch + ct * 32 + xi;
+    for (int rt = 0; rt < RT; ++rt) {
+      const int row0 = rh * (TILE / 2) + rt * 32;          // first position of this MFMA tile
+      if (row0 / 128 == h) {
+        float* sp = stage + (row0 % 128 + gk * 4) * kPitch + ct * 32 + xi;
 #pragma unroll
         for (int v = 0; v < 16; ++v) sp[((v >> 2) * 8 + (v & 3)) * kPitch] = acc[rt][v];
       }
@@ -1582,9 +1586,12 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   const dim3 gf((unsigned)(((int64_t)p.max_unit_images * sh.HW + kFwdBM - 1) / kFwdBM),
                 (unsigned)((sh.cout + kFwdBN - 1) / kFwdBN), (unsigned)p.n_units);
   if (patch_ok) {
-    const dim3 gp((unsigned)((sh.H * (sh.W + 2) - 2 + kPatchTile - 1) / kPatchTile),
-                  (unsigned)((sh.cout + 63) / 64), (unsigned)sh.total_images);
-    SYNK_LAUNCH_TIMED(conv3x3_fwd_patch_kernel, gp, dim3(kThreads), 0, st, tab, sh,
+    // 128 positions per workgroup, three workgroups per CU, weights two taps ahead: measured against
+    // 256 / two / four (30.7 vs 32.1 us at 64 images of 56 x 56 x 64)
+    constexpr int kTile = 128;
+    const dim3 gp((unsigned)((sh.H * (sh.W + 2) - 2 + kTile - 1) / kTile), (unsigned)((sh.cout + 63) / 64),
+                  (unsigned)sh.total_images);
+    SYNK_LAUNCH_TIMED((conv3x3_fwd_patch_kernel<kTile, 3, 2>), gp, dim3(kThreads), 0, st, tab, sh,
                       reinterpret_cast<const bf16_t*>(wmat), reinterpret_cast<bf16_t*>(z));
   } else {
     SYNK_LAUNCH_TIMED(conv3x3_fwd_kernel<T>, gf, dim3(kThreads), 0, st, tab, sh, (const T*)wmat, z);
