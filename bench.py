@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=None,
                     help="configs 1 and 2 only: minibatch size, to time worker shares that do not divide evenly "
                          "(default: the configuration's own, 256 / 1024)")
+    ap.add_argument("--conv-shape", default=None,
+                    help="config 6 at another block shape: H,W,C_in,C_out (e.g. 14,14,256,256)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -406,12 +408,16 @@ class EvalStep:
 class ConvStep:
     """Config 6: the whole step with the conv + batch-norm block as the function."""
 
-    def __init__(self, torch, synk):
+    def __init__(self, torch, synk, conv_shape=None):
         import numpy as np
         import workloads
         from oracle import split as osplit           # host-side share sizes for buffer allocation only
         self.torch, self.s, self.np = torch, synk, np
-        c = self.c = workloads.config6()
+        if conv_shape:
+            H, W, cin, cout = [int(v) for v in conv_shape.split(",")]
+            c = self.c = workloads.config6(shape=(H, W, cin, cout, 1000))
+        else:
+            c = self.c = workloads.config6()
         rng = np.random.default_rng(6)
         idx_sets = [c["idx"]] + [rng.integers(0, c["data"].shape[0], len(c["idx"])).astype(np.int32) for _ in range(3)]
         self.shape, self.N, self.S = c["shape"], c["n_workers"], c["n_slices"]
@@ -503,7 +509,7 @@ def main():
 
     wl = {0: lambda: CopyStep(torch, synk), 1: lambda: MlpStep(torch, synk, 1, a.batch), 2: lambda: MlpStep(torch, synk, 2, a.batch),
           3: lambda: (CollectiveStep(torch, synk, a.collective) if a.collective else ReduceStep(torch, synk, a.rule)), 4: lambda: GatherStep(torch, synk, a.indexing),
-          5: lambda: EvalStep(torch, synk), 6: lambda: ConvStep(torch, synk)}[a.config]()
+          5: lambda: EvalStep(torch, synk), 6: lambda: ConvStep(torch, synk, a.conv_shape)}[a.config]()
     steps = a.steps if a.steps is not None else {0: 50, 1: 2000, 2: 1000, 3: 300, 4: 1000, 5: 1000, 6: 300}[a.config]
     warmup = a.warmup if a.warmup is not None else 20
 
@@ -534,7 +540,7 @@ def main():
         "config": {"workload": wl.workload, "units_per_step": wl.units},
         "roofline": {"bound": bound, "kernel": wl.dom_name, "achieved": achieved, "peak": peak,
                      "unit": unit, "frac": achieved / peak,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (a.rule == "momentum" and not a.collective and a.indexing == "list" and a.batch is None) else None, "traffic_unit": "HBM bytes per launch",
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (a.rule == "momentum" and not a.collective and a.indexing == "list" and a.batch is None and not a.conv_shape) else None, "traffic_unit": "HBM bytes per launch",
                      "bytes_per_launch": wl.dom_bytes, "ms_per_launch": dom_ms},
     }
     if not a.no_cpu_baseline:
