@@ -711,21 +711,24 @@ __global__ __launch_bounds__(kHeadThreads) void head_image_kernel(WorkerTable ta
 }
 
 constexpr int kImgTile = 8;   // images held in registers at a time by head_worker_kernel
+constexpr int kWorkerChans = 64;
 
-// Per worker and class k: dWf[:, k], dbf[k] over the worker's images in image
-// order, kImgTile images at a time held in registers; workgroup (0, w) also
-// folds the image losses into loss[w].
+// Per worker, class k and group of kWorkerChans channels (blockIdx.z): dWf[group, k]
+// over the worker's images in image order, kImgTile images at a time held in
+// registers; group 0 also writes dbf[k], and its workgroup (0, w) folds the
+// image losses into loss[w].
 __global__ __launch_bounds__(kThreads) void head_worker_kernel(WorkerTable tab, ConvShape sh,
                                                                const float* __restrict__ pooled,
                                                                const float* __restrict__ dlogits,
                                                                const float* __restrict__ row_loss,
                                                                float* __restrict__ loss) {
-  __shared__ float sp[kImgTile][kMaxCout];
+  __shared__ float sp[kImgTile][kWorkerChans];
   const int w = blockIdx.y, k = blockIdx.x * kThreads + threadIdx.x;
+  const int ch0 = blockIdx.z * kWorkerChans, nch = min(kWorkerChans, sh.cout - ch0);
   const int i0 = tab.row_off[w], n = tab.rows[w];
   const ParamOff po = param_off(sh.cin, sh.cout, sh.classes);
   float* __restrict__ g = tab.grad[w];
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
+  if (blockIdx.z == 0 && blockIdx.x == 0 && threadIdx.x == 0) {
     float a = 0.0f;
     for (int i = 0; i < n; ++i) a += row_loss[i0 + i];
     loss[w] = a;
@@ -735,9 +738,9 @@ __global__ __launch_bounds__(kThreads) void head_worker_kernel(WorkerTable tab, 
   for (int t0 = 0; t0 < n || t0 == 0; t0 += kImgTile) {
     const int nt = min(kImgTile, n - t0);
     __syncthreads();
-    for (int e = threadIdx.x; e < kImgTile * sh.cout; e += kThreads) {
-      const int i = e / sh.cout, ch = e - i * sh.cout;
-      sp[i][ch] = i < nt ? pooled[(int64_t)(i0 + t0 + i) * sh.cout + ch] : 0.0f;
+    for (int e = threadIdx.x; e < kImgTile * nch; e += kThreads) {
+      const int i = e / nch, ch = e - i * nch;
+      sp[i][ch] = i < nt ? pooled[(int64_t)(i0 + t0 + i) * sh.cout + ch0 + ch] : 0.0f;
     }
     __syncthreads();
     if (live) {
@@ -747,16 +750,16 @@ __global__ __launch_bounds__(kThreads) void head_worker_kernel(WorkerTable tab, 
         d[i] = i < nt ? dlogits[(int64_t)(i0 + t0 + i) * sh.classes + k] : 0.0f;
         b += d[i];
       }
-      for (int ch = 0; ch < sh.cout; ++ch) {
+      for (int ch = 0; ch < nch; ++ch) {
         float a = 0.0f;
 #pragma unroll
         for (int i = 0; i < kImgTile; ++i) a = fmaf(sp[i][ch], d[i], a);
-        float* o = g + po.wf + (int64_t)ch * sh.classes + k;
+        float* o = g + po.wf + (int64_t)(ch0 + ch) * sh.classes + k;
         *o = t0 == 0 ? a : *o + a;
       }
     }
   }
-  if (live) g[po.bf + k] = b;
+  if (live && blockIdx.z == 0) g[po.bf + k] = b;
 }
 
 // ------------------------------------------------------ batch-norm backward
@@ -1610,7 +1613,9 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   hipLaunchKernelGGL(head_image_kernel, dim3((unsigned)sh.total_images), dim3(kHeadThreads), 0, st, tab, sh, params,
                      (const float*)poolp, pooled, dlogits, dpooled, row_loss);
   SYNK_LAUNCH_CHECK();
-  hipLaunchKernelGGL(head_worker_kernel, dim3((unsigned)((sh.classes + kThreads - 1) / kThreads), (unsigned)sh.n_workers),
+  hipLaunchKernelGGL(head_worker_kernel,
+                     dim3((unsigned)((sh.classes + kThreads - 1) / kThreads), (unsigned)sh.n_workers,
+                          (unsigned)((sh.cout + kWorkerChans - 1) / kWorkerChans)),
                      dim3(kThreads), 0, st, tab, sh, (const float*)pooled, (const float*)dlogits,
                      (const float*)row_loss, loss);
   SYNK_LAUNCH_CHECK();

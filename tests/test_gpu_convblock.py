@@ -85,6 +85,7 @@ def check(cfg, idx, n_workers, n_slices, op, bf16, got_g, got_l, eps=1e-5):
     ((14, 31, 128, 64, 4), 6, 2, 1, "sum"),     # the same over several runs, two input chunks
     ((2, 62, 64, 64, 4), 3, 1, 1, "mean"),      # one pixel wider: the general kernels
     ((3, 3, 8, 512, 4096), 3, 2, 1, "mean"),    # the largest channel and class counts the call takes
+    ((4, 4, 8, 256, 10), 7, 2, 2, "sum"),       # wide block: head workgroups of four images across workers / slices
 ])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_sliced_conv_block_matches_oracle(synk, shape, B, N, S, op, bf16):
