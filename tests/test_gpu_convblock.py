@@ -95,6 +95,30 @@ def test_sliced_conv_block_matches_oracle(synk, shape, B, N, S, op, bf16):
     check(cfg, idx, N, S, op, bf16, g, l)
 
 
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        H, W = int(rng.integers(1, 12)), int(rng.integers(1, 40))
+        cin = int(rng.choice([8, 16, 24, 64, 72, 128]))
+        cout = int(rng.choice([8, 24, 64, 72, 136]))
+        classes = int(rng.integers(2, 40))
+        N, S = int(rng.integers(1, 5)), int(rng.integers(1, 4))
+        B = int(rng.integers(1, 9))
+        cases.append(((H, W, cin, cout, classes), B, N, S, str(rng.choice(["mean", "sum"])), bool(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("shape,B,N,S,op,bf16", _random_cases(16, 20171004))
+def test_seeded_random_shapes_match_oracle(synk, shape, B, N, S, op, bf16):
+    # odd sizes, every kernel variant (general / padded-patch / row-of-taps / ring by width and
+    # channel count), empty workers and empty slices when B < N * S
+    cfg = small_cfg(shape, 12, seed=sum(shape) * 7 + B)
+    idx = np.random.default_rng(B + N).integers(0, 12, B).astype(np.int32)
+    g, l = run_gpu(synk, cfg, idx, N, S, op, bf16)
+    check(cfg, idx, N, S, op, bf16, g, l)
+
+
 def test_workers_without_images_get_zeros(synk):
     shape = (4, 5, 8, 8, 6)
     cfg = small_cfg(shape, 10, seed=3)
