@@ -11,8 +11,11 @@ default, and config 1); or the single stage a configuration isolates (3: reduce
 six-output sliced evaluation).  Prints ONE JSON line.
 
 `roofline` is for the dominant kernel of the step: algorithmic bytes per launch
-divided by that kernel's mean duration, measured here with events recorded on
-the launch stream around every launch of it inside the timed region.
+divided by that kernel's mean duration, measured here with events attached to
+its launches inside the timed region.  With --graph the K timed steps are
+replays of a HIP graph that holds the steps' launches (the calls of the library
+only launch kernels, so a caller can capture them; launch gaps shrink), and the
+dominant kernel is timed in a short eager pass before the timed region.
 `cpu_baseline` is the NumPy float64 oracle timed on this machine's host cores on a
 bounded sample of the same workload.
 """
@@ -53,6 +56,9 @@ def parse():
                          "(default: the configuration's own, 256 / 1024)")
     ap.add_argument("--conv-shape", default=None,
                     help="config 6 at another block shape: H,W,C_in,C_out (e.g. 14,14,256,256)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the steps (one per rotating input set) into one HIP graph and time its replays; "
+                         "the dominant kernel is then timed in a short eager pass before the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -155,6 +161,8 @@ class MlpStep:
         self.call_update = s.prepare(s.synk_reduce_sgd_update, self.grad, self.p, self.v, c["lr"], c["momentum"],
                                      c["weight_decay"], p_lp=self.p_lp, loss_in=self.loss, loss_out=self.loss_out)
 
+    cycle = 8          # distinct steps (rotating index sets)
+
     def step(self, i, timer):
         self.call_gather[i % len(self.call_gather)]()
         self.call_grad()
@@ -216,6 +224,8 @@ class ReduceStep:
             self.calls = [synk.prepare(synk.synk_reduce_update, rule, gs, self.p, self.v, self.s2, step=1000,
                                        loss_in=self.loss_in, loss_out=self.loss_out, **h)
                           for gs in self.grads]
+
+    cycle = 3
 
     def step(self, i, timer):
         timer.bracket(self.calls[i % 3])
@@ -344,6 +354,8 @@ class GatherStep:
             self.calls = [synk.prepare(synk.synk_gather_resident, shares, ls, self.dst, lut=self.lut, channels=3,
                                        labels=lshares, dst_labels=self.dl) for ls in self.lists]
 
+    cycle = 64
+
     def step(self, i, timer):
         timer.bracket(self.calls[i % 64])
 
@@ -391,6 +403,8 @@ class EvalStep:
         self.dom_bytes = self.rows * (4 * self.C + 8)
         self.calls = [synk.prepare(synk.synk_sliced_eval, lg, self.labels, self.S, *self.out, self.ws)
                       for lg in self.logits]
+
+    cycle = 4
 
     def step(self, i, timer):
         # the dominant kernel is one of the three this call launches; the bracket covers the call and
@@ -458,6 +472,8 @@ class ConvStep:
         self.call_update = s.prepare(s.synk_reduce_sgd_update, self.grad, self.p, self.v, c["lr"], c["momentum"],
                                      c["weight_decay"], loss_in=self.loss, loss_out=self.loss_out)
 
+    cycle = 4
+
     def step(self, i, timer):
         self.call_gather[i % len(self.call_gather)]()
         timer.bracket(self.call_grad)
@@ -490,6 +506,8 @@ class CopyStep:
         self.workload = "config 0: copy of 2^28 fp32 (synk_reduce_buffers with one buffer)"
         self.dom_name, self.dom_bytes = "reduce_kernel", 8 * n
 
+    cycle = 2
+
     def step(self, i, timer):
         timer.bracket(self.calls[i % 2])
 
@@ -507,22 +525,54 @@ def main():
     from paper_1710_04162_amd import binding as synk
     torch.cuda.set_device(0)
 
+    if a.graph:
+        # capture needs a stream of its own; the calls below are prepared on it
+        torch.cuda.set_stream(torch.cuda.Stream())
     wl = {0: lambda: CopyStep(torch, synk), 1: lambda: MlpStep(torch, synk, 1, a.batch), 2: lambda: MlpStep(torch, synk, 2, a.batch),
           3: lambda: (CollectiveStep(torch, synk, a.collective) if a.collective else ReduceStep(torch, synk, a.rule)), 4: lambda: GatherStep(torch, synk, a.indexing),
           5: lambda: EvalStep(torch, synk), 6: lambda: ConvStep(torch, synk, a.conv_shape)}[a.config]()
     steps = a.steps if a.steps is not None else {0: 50, 1: 2000, 2: 1000, 3: 300, 4: 1000, 5: 1000, 6: 300}[a.config]
     warmup = a.warmup if a.warmup is not None else 20
 
-    timer = Timer(torch, synk, steps)
-    for i in range(warmup):
-        wl.step(i, timer)
-    torch.cuda.synchronize()
-    timer.on = True
-    t0 = time.perf_counter()
-    for i in range(steps):
-        wl.step(i, timer)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    if a.graph:
+        # dominant kernel: a short eager pass with the events on its dispatches
+        probe = 50
+        timer = Timer(torch, synk, probe)
+        for i in range(warmup):
+            wl.step(i, timer)
+        torch.cuda.synchronize()
+        timer.on = True
+        for i in range(probe):
+            wl.step(i, timer)
+        torch.cuda.synchronize()
+        timer.on = False
+        # one graph holding `cycle` consecutive steps; K steps = K // cycle replays + the rest eagerly
+        cycle = getattr(wl, "cycle", 1)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=torch.cuda.current_stream()):
+            for i in range(cycle):
+                wl.step(i, timer)
+        for _ in range(max(1, warmup // cycle)):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps // cycle):
+            g.replay()
+        for i in range(steps % cycle):
+            wl.step(i, timer)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    else:
+        timer = Timer(torch, synk, steps)
+        for i in range(warmup):
+            wl.step(i, timer)
+        torch.cuda.synchronize()
+        timer.on = True
+        t0 = time.perf_counter()
+        for i in range(steps):
+            wl.step(i, timer)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
 
     # The event pair sits on the kernel's own dispatch: begin-to-end time of the kernel, the same
     # quantity as the kernel duration in a rocprofv3 kernel trace.
@@ -537,7 +587,7 @@ def main():
         "value": wl.units * steps / dt, "unit": wl.unit, "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": wl.workload, "units_per_step": wl.units},
+        "config": {"workload": wl.workload, "units_per_step": wl.units, "launch": "hip graph replay" if a.graph else "eager"},
         "roofline": {"bound": bound, "kernel": wl.dom_name, "achieved": achieved, "peak": peak,
                      "unit": unit, "frac": achieved / peak,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (a.rule == "momentum" and not a.collective and a.indexing == "list" and a.batch is None and not a.conv_shape) else None, "traffic_unit": "HBM bytes per launch",

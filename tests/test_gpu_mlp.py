@@ -291,3 +291,54 @@ def test_sliced_grad_is_bit_reproducible(synk):
     g1, l1 = st.sliced_grad(2, "mean")
     g2, l2 = st.sliced_grad(2, "mean")
     assert all(np.array_equal(a, b) for a, b in zip(g1, g2)) and np.array_equal(l1, l2)
+
+
+def test_step_captured_in_a_graph_replays_like_eager_steps(synk):
+    """The three calls of a step launch kernels only (no allocation, no memset, no
+    synchronisation), so a caller may capture them into a graph.  Every replay, with eager work
+    and synchronisations in between, must leave exactly what the eager step leaves."""
+    dims = [64, 48, 10]
+    cfg = small_cfg(dims, 200, "bf16", 21)
+    idx = np.random.default_rng(3).integers(0, 200, 96).astype(np.int32)
+    N, S = 4, 2
+
+    def make():
+        st = Step(synk, cfg)
+        st.rows = osplit.share_sizes(len(idx), N)
+        st.x = [torch.zeros((n, dims[0]), dtype=torch.bfloat16, device="cuda") for n in st.rows]
+        st.y = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in st.rows]
+        st.grad = [torch.zeros(st.P, device="cuda") for _ in st.rows]
+        st.loss = torch.zeros(N, device="cuda")
+        st.loss_out = torch.zeros(1, device="cuda")
+        st.ws = torch.empty(synk.synk_sliced_grad_workspace_bytes(dims, st.cd, st.rows), dtype=torch.uint8,
+                            device="cuda")
+        st.idx = dev(idx)
+        return st
+
+    def step(st, stream=None):
+        c = st.cfg
+        synk.synk_gather_rows(st.data, st.idx, st.x, labels=st.labels, dst_labels=st.y, stream=stream)
+        synk.synk_sliced_grad(dims, st.cd, st.p, st.p_lp, st.x, st.y, st.rows, S, synk.SYNK_MEAN, st.grad, st.loss,
+                              st.ws, stream=stream)
+        synk.synk_reduce_sgd_update(st.grad, st.p, st.v, c["lr"], c["momentum"], c["weight_decay"], p_lp=st.p_lp,
+                                    loss_in=st.loss, loss_out=st.loss_out, stream=stream)
+
+    eager, graphed = make(), make()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        step(graphed, stream=side.cuda_stream)
+    torch.cuda.synchronize()
+    # capture records, it does not run: the graphed state is still the initial one
+    assert torch.equal(graphed.p, eager.p)
+    scratch = torch.zeros(1 << 16, device="cuda")
+    for it in range(4):
+        step(eager)
+        g.replay()
+        scratch.add_(1.0)                    # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(graphed.p, eager.p), it
+        assert torch.equal(graphed.v, eager.v), it
+        assert torch.equal(graphed.p_lp, eager.p_lp), it
+        assert torch.equal(graphed.loss_out, eager.loss_out), it
