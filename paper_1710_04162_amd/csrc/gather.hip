@@ -92,7 +92,18 @@ __global__ __launch_bounds__(kGBlock) void gather_copy_kernel(
   const int64_t u0 = (int64_t)blockIdx.y * units_per_block;
   int64_t u1 = u0 + units_per_block;
   if (u1 > row_units) u1 = row_units;
-  for (int64_t u = u0 + threadIdx.x; u < u1; u += kGBlock) dst[u] = src[u];
+  // four loads in flight per thread: a unit past the end re-reads the last one and is dropped
+  for (int64_t u = u0 + threadIdx.x; u < u1; u += 4 * kGBlock) {
+    V v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int64_t uu = u + k * kGBlock;
+      v[k] = src[uu < u1 ? uu : u1 - 1];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (u + k * kGBlock < u1) dst[u + k * kGBlock] = v[k];
+  }
 }
 
 // float32 -> bfloat16 (nearest-even).  VEC: 4 floats in, 8 bytes out per lane.
@@ -111,16 +122,27 @@ __global__ __launch_bounds__(kGBlock) void gather_bf16_kernel(
   const int64_t u0 = (int64_t)blockIdx.y * units_per_block;
   int64_t u1 = u0 + units_per_block;
   if (u1 > units) u1 = units;
-  for (int64_t u = u0 + threadIdx.x; u < u1; u += kGBlock) {
-    if (VEC) {
-      const f32x4 a = reinterpret_cast<const f32x4*>(src)[u];
-      u32x2 q;
-      q.x = pack_bf16x2(a.x, a.y);
-      q.y = pack_bf16x2(a.z, a.w);
-      reinterpret_cast<u32x2*>(dst)[u] = q;
-    } else {
-      dst[u] = f32_to_bf16(src[u]);
+  if (VEC) {
+    // four loads in flight per thread: a unit past the end re-reads the last one and is dropped
+    for (int64_t u = u0 + threadIdx.x; u < u1; u += 4 * kGBlock) {
+      f32x4 a[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int64_t uu = u + k * kGBlock;
+        a[k] = reinterpret_cast<const f32x4*>(src)[uu < u1 ? uu : u1 - 1];
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (u + k * kGBlock < u1) {
+          u32x2 q;
+          q.x = pack_bf16x2(a[k].x, a[k].y);
+          q.y = pack_bf16x2(a[k].z, a[k].w);
+          reinterpret_cast<u32x2*>(dst)[u + k * kGBlock] = q;
+        }
+      }
     }
+  } else {
+    for (int64_t u = u0 + threadIdx.x; u < u1; u += kGBlock) dst[u] = f32_to_bf16(src[u]);
   }
 }
 
