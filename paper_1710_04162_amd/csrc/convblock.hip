@@ -292,13 +292,20 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_fwd_kernel(WorkerTable ta
 template <int TILE, int MINB, int AHEAD>
 __global__ __launch_bounds__(kThreads, MINB) void conv3x3_fwd_patch_kernel(WorkerTable tab, ConvShape sh,
                                                                         const bf16_t* __restrict__ wmat,
-                                                                        bf16_t* __restrict__ z) {
+                                                                        bf16_t* __restrict__ z,
+                                                                        int tiles_per_image, int n_tiles) {
   constexpr int kPatchTile = TILE, kPatchMaxRows = TILE + 2 * 64;
   constexpr int RT = TILE / 64;                  // 32-row MFMA tiles per wavefront (it owns TILE/2 positions)
   __shared__ __attribute__((aligned(16))) char patch[kPatchMaxRows * kLdsRow];
   __shared__ int zrow[kPatchTile];
 
-  const int img = blockIdx.z, tile = blockIdx.x, n0 = blockIdx.y * 64;
+  // Workgroups go to the 8 XCDs round-robin in launch order.  XCD k takes the k-th eighth of the
+  // (image, tile) list in order, so that tiles next to each other, which share their halo, run on
+  // one XCD at about the same time and the second fetch of the halo hits that XCD's L2.
+  const int per_xcd = (n_tiles + 7) / 8;
+  const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (item >= n_tiles) return;
+  const int img = item / tiles_per_image, tile = item - img * tiles_per_image, n0 = blockIdx.y * 64;
   int w = 0;
   while (w + 1 < sh.n_workers && tab.row_off[w + 1] <= img) ++w;
   const bf16_t* __restrict__ xi_ = reinterpret_cast<const bf16_t*>(tab.x[w]) +
@@ -1576,7 +1583,7 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   float* dwp = reinterpret_cast<float*>(ws + p.o_dwp);
 
   const int64_t wn = p.K * sh.cout;
-  const bool patch_ok = sizeof(T) == 2 && sh.cin % 64 == 0 && sh.W + 2 <= 63 && sh.total_images <= 65535;
+  const bool patch_ok = sizeof(T) == 2 && sh.cin % 64 == 0 && sh.W + 2 <= 63;
   if (patch_ok) {
     const int64_t total = p.K * (int64_t)round_up((size_t)sh.cout, 32);
     hipLaunchKernelGGL(conv_weight_frag_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads),
@@ -1592,10 +1599,12 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
     // 128 positions per workgroup, three workgroups per CU, weights two taps ahead: measured against
     // 256 / two / four (30.7 vs 32.1 us at 64 images of 56 x 56 x 64)
     constexpr int kTile = 128;
-    const dim3 gp((unsigned)((sh.H * (sh.W + 2) - 2 + kTile - 1) / kTile), (unsigned)((sh.cout + 63) / 64),
-                  (unsigned)sh.total_images);
+    const int tiles_per_image = (sh.H * (sh.W + 2) - 2 + kTile - 1) / kTile;
+    const int64_t n_tiles = (int64_t)tiles_per_image * sh.total_images;
+    const dim3 gp((unsigned)((n_tiles + 7) / 8 * 8), (unsigned)((sh.cout + 63) / 64));
     SYNK_LAUNCH_TIMED((conv3x3_fwd_patch_kernel<kTile, 3, 2>), gp, dim3(kThreads), 0, st, tab, sh,
-                      reinterpret_cast<const bf16_t*>(wmat), reinterpret_cast<bf16_t*>(z));
+                      reinterpret_cast<const bf16_t*>(wmat), reinterpret_cast<bf16_t*>(z), tiles_per_image,
+                      (int)n_tiles);
   } else {
     SYNK_LAUNCH_TIMED(conv3x3_fwd_kernel<T>, gf, dim3(kThreads), 0, st, tab, sh, (const T*)wmat, z);
   }
