@@ -20,9 +20,13 @@ struct ConcatTable {
 
 constexpr int kBlock = 256;
 
+// One 16-byte unit per thread up to 2^20 workgroups (the kernels stride over
+// the rest): workgroups then start in address order as earlier ones retire,
+// which measured faster than a resident grid striding over the array
+// (25.6 M parameters, 8 workers: 6.5 against 6.3 TB/s).
 static inline int stream_grid(int64_t units) {
   int64_t b = (units + kBlock - 1) / kBlock;
-  const int64_t cap = (int64_t)kNumCU * 8;
+  const int64_t cap = (int64_t)1 << 20;
   if (b > cap) b = cap;
   if (b < 1) b = 1;
   return (int)b;
