@@ -238,9 +238,14 @@ struct TileStage {
         lo.z = __builtin_amdgcn_perm(b.y, a.y, 0x05040100u); lo.w = __builtin_amdgcn_perm(b.y, a.y, 0x07060302u);
         hi.x = __builtin_amdgcn_perm(b.z, a.z, 0x05040100u); hi.y = __builtin_amdgcn_perm(b.z, a.z, 0x07060302u);
         hi.z = __builtin_amdgcn_perm(b.w, a.w, 0x05040100u); hi.w = __builtin_amdgcn_perm(b.w, a.w, 0x07060302u);
+        // A 16-byte LDS store goes out eight lanes at a time; the lanes' first
+        // halves would sit eight words apart and meet in four banks twice.  Lanes
+        // in the upper 32 words of a row store their halves in the other order.
         u32x4* d = reinterpret_cast<u32x4*>(lds + (kl / 2) * X + xl);
-        d[0] = lo;
-        d[1] = hi;
+        const bool sw = (xl & 32) != 0;
+        const u32x4 first = sw ? hi : lo, second = sw ? lo : hi;
+        d[sw ? 1 : 0] = first;
+        d[sw ? 0 : 1] = second;
       } else {
         *reinterpret_cast<u32x4*>(lds + kl * X + xl) = a;
       }
@@ -479,6 +484,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, unsigned lin, unsig
           nextA += in ? stepA : 0;
           nextB += in ? stepB : 0;
           __syncthreads();
+          // Keep every step's work in its step: hoisted into an earlier step,
+          // the byte permutes of a later stage wait for that stage's loads,
+          // the youngest in flight, and the ring drains.
+          __builtin_amdgcn_sched_barrier(0);
         }
       };
       for (; t + 8 < n_whole; t += 4) fast_round(t, std::false_type());
@@ -585,14 +594,20 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, unsigned lin, unsig
         const bool live = ALL || t + u < n_tiles, more = ALL || t + u + 1 < n_tiles;
         if (WHOLE) {
           __syncthreads();                           // tile t+u+1 is in its half
+          // Left alone, the scheduler pulls the products of tile t+u+1 up behind
+          // its fragment reads to shorten live ranges, which puts an LDS
+          // latency in front of every MFMA.
+          __builtin_amdgcn_sched_barrier(0);
           if (more) {
             read_tile(nxt, nxt + WA, (u + 1) & 1);
             column_sums(nxt + WA);
           }
+          __builtin_amdgcn_sched_barrier(0);
           if (live) {
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) mfma_step(u & 1, ks);
           }
+          __builtin_amdgcn_sched_barrier(0);
         } else {
           if (live) {
             column_sums(cur + WA);
