@@ -399,7 +399,7 @@ class EvalStep:
                          "counts, max, min, top-1 correct, argmax, aggregated over slices")
         # one call = three kernels (zero the per-slice counts, stage 1, stage 2); the bracket covers the
         # call, so the fraction below is the whole call's; profiles/ has the per-kernel split
-        self.dom_name = "eval_stage1_pipe_kernel"
+        self.dom_name = "eval_stage1_regular_kernel"
         self.dom_bytes = self.rows * (4 * self.C + 8)
         self.calls = [synk.prepare(synk.synk_sliced_eval, lg, self.labels, self.S, *self.out, self.ws)
                       for lg in self.logits]

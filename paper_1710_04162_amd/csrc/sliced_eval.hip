@@ -16,40 +16,48 @@ namespace synk {
 constexpr int kEBlock = 256;
 constexpr int kEWaves = kEBlock / kWave;
 constexpr int kRowsPerBlock = 32;
+// Rows of a workgroup of the branch-free kernel: 32 lanes a row, one row pair a wavefront.
+constexpr int kRegularG = 32, kRegularUPL = 8;
+constexpr int kRegularRows = kEWaves * (kWave / kRegularG);
 
 struct EvalWs {
   float* part_ce;        // [S x CH]
   float* part_max;       // [S x CH]
   float* part_min;       // [S x CH]
   int32_t* part_correct; // [S x CH]
-  int32_t* slice_counts; // [S x C]
 };
 
-static inline size_t eval_chunks(int64_t rows, int n_slices) {
+// Workgroups (= partial results) a slice takes at rows_per_block rows each.
+static inline size_t eval_chunks(int64_t rows, int n_slices, int rows_per_block) {
   const int64_t longest = (rows + n_slices - 1) / n_slices;
-  int64_t ch = (longest + kRowsPerBlock - 1) / kRowsPerBlock;
+  int64_t ch = (longest + rows_per_block - 1) / rows_per_block;
   return (size_t)(ch < 1 ? 1 : ch);
 }
 
 static inline size_t eval_ws_layout(int64_t rows, int64_t classes, int n_slices, void* ws,
                                     EvalWs* out) {
-  const size_t ch = eval_chunks(rows, n_slices);
+  const size_t ch = eval_chunks(rows, n_slices, kRegularRows);   // the finest split any kernel uses
   const size_t part = round_up((size_t)n_slices * ch * 4, 256);
-  const size_t counts = round_up((size_t)n_slices * (size_t)classes * 4, 256);
   if (out) {
     char* b = reinterpret_cast<char*>(ws);
     out->part_ce = reinterpret_cast<float*>(b);
     out->part_max = reinterpret_cast<float*>(b + part);
     out->part_min = reinterpret_cast<float*>(b + 2 * part);
     out->part_correct = reinterpret_cast<int32_t*>(b + 3 * part);
-    out->slice_counts = reinterpret_cast<int32_t*>(b + 4 * part);
   }
-  return 4 * part + counts;
+  return 4 * part;
 }
 
-__global__ __launch_bounds__(kEBlock) void zero_i32_kernel(int32_t* __restrict__ p, int64_t n) {
-  const int64_t stride = (int64_t)gridDim.x * kEBlock;
-  for (int64_t i = (int64_t)blockIdx.x * kEBlock + threadIdx.x; i < n; i += stride) p[i] = 0;
+// The first workgroup of stage 1 clears the class counts that stage 2 adds into
+// (a launch of its own for that costs more than the whole of stage 2).
+__device__ __forceinline__ void clear_counts(int32_t* __restrict__ class_counts, int classes) {
+  if (blockIdx.x == 0 && blockIdx.y == 0)
+    for (int c = threadIdx.x; c < classes; c += kEBlock) class_counts[c] = 0;
+}
+
+// A row without a largest element (NaN only) has no arg-max: class 0 stands in.
+__device__ __forceinline__ int in_range(int arg, int classes) {
+  return (unsigned)arg < (unsigned)classes ? arg : 0;
 }
 
 struct RowStat {
@@ -76,7 +84,8 @@ __device__ __forceinline__ void take(RowStat& st, float x, int c, int y) {
 // scalar loads, running (max, sum) pair merged over the 64 lanes.
 __global__ __launch_bounds__(kEBlock) void eval_stage1_generic_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ labels, int64_t rows, int classes,
-    int n_slices, int chunks, EvalWs ws, int32_t* __restrict__ argmax_out) {
+    int n_slices, int chunks, EvalWs ws, int32_t* __restrict__ argmax_out, int32_t* __restrict__ class_counts) {
+  clear_counts(class_counts, classes);
   const int slice = blockIdx.y, chunk = blockIdx.x;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t base = rows / n_slices, extra = rows % n_slices;
@@ -116,9 +125,9 @@ __global__ __launch_bounds__(kEBlock) void eval_stage1_generic_kernel(
       w_ce += (__logf(st.s) + st.m) - st.xy;
       w_max = fmaxf(w_max, st.m);
       w_min = fminf(w_min, st.mn);
-      w_correct += (st.arg == y) ? 1 : 0;
-      argmax_out[row] = st.arg;
-      atomicAdd(ws.slice_counts + (int64_t)slice * classes + st.arg, 1);
+      const int arg = in_range(st.arg, classes);
+      w_correct += (arg == y) ? 1 : 0;
+      argmax_out[row] = arg;
     }
   }
   __shared__ float s_ce[kEWaves], s_max[kEWaves], s_min[kEWaves];
@@ -155,10 +164,11 @@ __global__ __launch_bounds__(kEBlock) void eval_stage1_generic_kernel(
 template <int G, int UPL>
 __global__ __launch_bounds__(kEBlock) void eval_stage1_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ labels, int64_t rows, int classes,
-    int n_slices, int chunks, EvalWs ws, int32_t* __restrict__ argmax_out) {
+    int n_slices, int chunks, EvalWs ws, int32_t* __restrict__ argmax_out, int32_t* __restrict__ class_counts) {
   constexpr int RW = kWave / G;            // rows a wavefront handles at once
   constexpr int NACC = kEWaves * RW;       // per-block accumulators
   constexpr float kLog2e = 1.4426950408889634f;
+  clear_counts(class_counts, classes);
   const int slice = blockIdx.y, chunk = blockIdx.x;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int sub = lane % G, grp = lane / G;
@@ -231,9 +241,9 @@ __global__ __launch_bounds__(kEBlock) void eval_stage1_kernel(
       w_ce += (__logf(s) + m) - xy;
       w_max = fmaxf(w_max, m);
       w_min = fminf(w_min, mn);
+      arg = in_range(arg, classes);
       w_correct += (arg == y) ? 1 : 0;
       argmax_out[row] = arg;
-      atomicAdd(ws.slice_counts + (int64_t)slice * classes + arg, 1);
     }
   }
   __shared__ float s_ce[NACC], s_max[NACC], s_min[NACC];
@@ -262,175 +272,147 @@ __global__ __launch_bounds__(kEBlock) void eval_stage1_kernel(
   }
 }
 
-// The same stage 1 as a two-deep software pipeline, for the regular case: every
-// slice has a multiple of kRowsPerBlock rows and the row needs all UPL vectors
-// of a lane group ((UPL-1)*G < classes/4 <= UPL*G).  A workgroup owns NSETS
-// sets of 16 rows; while set s is reduced out of registers, the loads of set
-// s+1 are in flight into a second register buffer.  Every load is issued
-// unconditionally (the last vector's address is clamped into the row, its
-// padding applied when it is used), so the number of loads outstanding at
-// each wait is known and a wait for set s never waits for set s+1.
-template <int G, int UPL, int NSETS>
-__global__ __launch_bounds__(kEBlock) void eval_stage1_pipe_kernel(
+// The same stage 1 without a branch in the load path, for the regular case:
+// every slice is a whole number of row sets (kEWaves * 64/G rows, one set per
+// workgroup) and a row needs all UPL vectors of its lane group ((UPL-1)*G <
+// classes/4 <= UPL*G).  Every load is issued unconditionally before the first
+// use (the last vector's address is clamped into the row, its padding applied
+// when it is used), so nothing waits behind a condition.  Measured on 65,536
+// rows of 1,000 classes: many short-lived workgroups of one set each stream
+// faster than longer ones that pipeline several sets through two register
+// buffers (G = 32, one set: 43.5 us; G = 16, one / two / four / eight sets:
+// 47.1 / 48.3 / 49.7 / 52.5 us), and 32 lanes a row beat 16 and 64.
+template <int G, int UPL>
+__global__ __launch_bounds__(kEBlock) void eval_stage1_regular_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ labels, int64_t rows, int classes,
-    int n_slices, int chunks, EvalWs ws, int32_t* __restrict__ argmax_out) {
+    int n_slices, int chunks, EvalWs ws, int32_t* __restrict__ argmax_out, int32_t* __restrict__ class_counts) {
   constexpr int RW = kWave / G;            // rows a wavefront handles at once
-  constexpr int NACC = kEWaves * RW;       // rows of a set = per-block accumulators
-  static_assert(NSETS * NACC == kRowsPerBlock, "sets must tile the block's rows");
+  constexpr int NACC = kEWaves * RW;       // rows of the workgroup = per-block accumulators
   constexpr float kLog2e = 1.4426950408889634f;
+  clear_counts(class_counts, classes);
   const int slice = blockIdx.y, chunk = blockIdx.x;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int sub = lane % G, grp = lane / G;
   const int units = classes >> 2;
   const int64_t s_rows = rows / n_slices;                     // the same for every slice here
-  const int64_t first = s_rows * slice + (int64_t)chunk * kRowsPerBlock + wave * RW + grp;
+  const int64_t row = s_rows * slice + (int64_t)chunk * NACC + wave * RW + grp;
 
   const int u_last = (UPL - 1) * G + sub;                     // this lane's last vector
   const bool last_in = u_last < units;
   const int u_last_c = last_in ? u_last : units - 1;
   const float pad_ub = last_in ? INFINITY : -INFINITY;
 
-  int y[NSETS];
+  const int y = labels[row];
+  const f32x4* x = reinterpret_cast<const f32x4*>(logits + row * classes);
+  f32x4 q[UPL];
 #pragma unroll
-  for (int s = 0; s < NSETS; ++s) y[s] = labels[first + s * NACC];
+  for (int k = 0; k < UPL - 1; ++k) q[k] = __builtin_nontemporal_load(x + k * G + sub);
+  q[UPL - 1] = __builtin_nontemporal_load(x + u_last_c);
+  // label logit: one extra load of a line this wavefront has just requested
+  const float xy = logits[row * classes + ((y >= 0 && y < classes) ? y : 0)];
 
-  f32x4 q[2][UPL];
-  float xy[NSETS];
-  auto issue = [&](int s, int b) {
-    const int64_t row = first + s * NACC;
-    const f32x4* x = reinterpret_cast<const f32x4*>(logits + row * classes);
+  float m = -INFINITY, mn = INFINITY;
 #pragma unroll
-    for (int k = 0; k < UPL - 1; ++k) q[b][k] = __builtin_nontemporal_load(x + k * G + sub);
-    q[b][UPL - 1] = __builtin_nontemporal_load(x + u_last_c);
-  };
-
-  float w_ce = 0.0f, w_max = -INFINITY, w_min = INFINITY;
-  int w_correct = 0;
-  auto reduce_set = [&](int s, int b) {
-    const int64_t row = first + s * NACC;
-    float m = -INFINITY, mn = INFINITY;
-#pragma unroll
-    for (int k = 0; k < UPL - 1; ++k) {
-      m = fmaxf(m, fmaxf(fmaxf(q[b][k].x, q[b][k].y), fmaxf(q[b][k].z, q[b][k].w)));
-      mn = fminf(mn, fminf(fminf(q[b][k].x, q[b][k].y), fminf(q[b][k].z, q[b][k].w)));
-    }
-    {
-      // padding by arithmetic, not by a branch: the load above must stay unconditional
-      f32x4& v = q[b][UPL - 1];
-      const float lo = fminf(fminf(v.x, v.y), fminf(v.z, v.w));
-      mn = fminf(mn, fmaxf(lo, -pad_ub));                      // +inf where the lane holds padding
-      v = f32x4{fminf(v.x, pad_ub), fminf(v.y, pad_ub), fminf(v.z, pad_ub), fminf(v.w, pad_ub)};   // -inf there
-      m = fmaxf(m, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
-    }
-    // first position of the lane-local maximum (scan downwards, keep the last hit)
-    int arg = 0x7fffffff;
-#pragma unroll
-    for (int k = UPL - 1; k >= 0; --k) {
-      const int c = (k * G + sub) << 2;
-      if (q[b][k].w == m) arg = c + 3;
-      if (q[b][k].z == m) arg = c + 2;
-      if (q[b][k].y == m) arg = c + 1;
-      if (q[b][k].x == m) arg = c;
-    }
-#pragma unroll
-    for (int off = G / 2; off > 0; off >>= 1) {
-      const float om = __shfl_xor(m, off);
-      const int oarg = __shfl_xor(arg, off);
-      if (om > m || (om == m && oarg < arg)) arg = oarg;
-      m = fmaxf(m, om);
-    }
-    const float mb = m * kLog2e;
-    float sum = 0.0f;
-#pragma unroll
-    for (int k = 0; k < UPL; ++k) {
-      // arguments are <= 0: the raw hardware exp2 (no denormal fix-up) is exact enough
-      sum += __builtin_amdgcn_exp2f(fmaf(q[b][k].x, kLog2e, -mb)) + __builtin_amdgcn_exp2f(fmaf(q[b][k].y, kLog2e, -mb)) +
-             __builtin_amdgcn_exp2f(fmaf(q[b][k].z, kLog2e, -mb)) + __builtin_amdgcn_exp2f(fmaf(q[b][k].w, kLog2e, -mb));
-    }
-#pragma unroll
-    for (int off = G / 2; off > 0; off >>= 1) {
-      sum += __shfl_xor(sum, off);
-      mn = fminf(mn, __shfl_xor(mn, off));
-    }
-    if (sub == 0) {
-      const float label_logit = (y[s] >= 0 && y[s] < classes) ? xy[s] : 0.0f;
-      w_ce += (__logf(sum) + m) - label_logit;
-      w_max = fmaxf(w_max, m);
-      w_min = fminf(w_min, mn);
-      w_correct += (arg == y[s]) ? 1 : 0;
-      argmax_out[row] = arg;
-      atomicAdd(ws.slice_counts + (int64_t)slice * classes + arg, 1);
-    }
-  };
-
-  issue(0, 0);
-  __builtin_amdgcn_sched_barrier(0);
-  // the label logits of every set, asked for while the first set is still on its way: they
-  // hang on the label loads, and must not end up queued behind the loads of a later set
-#pragma unroll
-  for (int s = 0; s < NSETS; ++s) {
-    const int yc = (y[s] >= 0 && y[s] < classes) ? y[s] : 0;
-    xy[s] = logits[(first + s * NACC) * classes + yc];
+  for (int k = 0; k < UPL - 1; ++k) {
+    m = fmaxf(m, fmaxf(fmaxf(q[k].x, q[k].y), fmaxf(q[k].z, q[k].w)));
+    mn = fminf(mn, fminf(fminf(q[k].x, q[k].y), fminf(q[k].z, q[k].w)));
   }
-  __builtin_amdgcn_sched_barrier(0);
+  {
+    // padding by arithmetic, not by a branch: the load above must stay unconditional
+    f32x4& v = q[UPL - 1];
+    const float lo = fminf(fminf(v.x, v.y), fminf(v.z, v.w));
+    mn = fminf(mn, fmaxf(lo, -pad_ub));                      // +inf where the lane holds padding
+    v = f32x4{fminf(v.x, pad_ub), fminf(v.y, pad_ub), fminf(v.z, pad_ub), fminf(v.w, pad_ub)};   // -inf there
+    m = fmaxf(m, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
+  }
+  // first position of the lane-local maximum (scan downwards, keep the last hit)
+  int arg = 0x7fffffff;
 #pragma unroll
-  for (int s = 0; s < NSETS; ++s) {
-    if (s + 1 < NSETS) issue(s + 1, (s + 1) & 1);
-    __builtin_amdgcn_sched_barrier(0);     // keep the loads of later sets from drifting up here
-    reduce_set(s, s & 1);
-    __builtin_amdgcn_sched_barrier(0);
+  for (int k = UPL - 1; k >= 0; --k) {
+    const int c = (k * G + sub) << 2;
+    if (q[k].w == m) arg = c + 3;
+    if (q[k].z == m) arg = c + 2;
+    if (q[k].y == m) arg = c + 1;
+    if (q[k].x == m) arg = c;
+  }
+#pragma unroll
+  for (int off = G / 2; off > 0; off >>= 1) {
+    const float om = __shfl_xor(m, off);
+    const int oarg = __shfl_xor(arg, off);
+    if (om > m || (om == m && oarg < arg)) arg = oarg;
+    m = fmaxf(m, om);
+  }
+  const float mb = m * kLog2e;
+  float sum = 0.0f;
+#pragma unroll
+  for (int k = 0; k < UPL; ++k) {
+    // arguments are <= 0: the raw hardware exp2 (no denormal fix-up) is exact enough
+    sum += __builtin_amdgcn_exp2f(fmaf(q[k].x, kLog2e, -mb)) + __builtin_amdgcn_exp2f(fmaf(q[k].y, kLog2e, -mb)) +
+           __builtin_amdgcn_exp2f(fmaf(q[k].z, kLog2e, -mb)) + __builtin_amdgcn_exp2f(fmaf(q[k].w, kLog2e, -mb));
+  }
+#pragma unroll
+  for (int off = G / 2; off > 0; off >>= 1) {
+    sum += __shfl_xor(sum, off);
+    mn = fminf(mn, __shfl_xor(mn, off));
   }
 
   __shared__ float s_ce[NACC], s_max[NACC], s_min[NACC];
   __shared__ int s_cor[NACC];
   if (sub == 0) {
-    s_ce[wave * RW + grp] = w_ce;
-    s_max[wave * RW + grp] = w_max;
-    s_min[wave * RW + grp] = w_min;
-    s_cor[wave * RW + grp] = w_correct;
+    const float label_logit = (y >= 0 && y < classes) ? xy : 0.0f;
+    s_ce[wave * RW + grp] = (__logf(sum) + m) - label_logit;
+    s_max[wave * RW + grp] = m;
+    s_min[wave * RW + grp] = mn;
+    arg = in_range(arg, classes);
+    s_cor[wave * RW + grp] = (arg == y) ? 1 : 0;
+    argmax_out[row] = arg;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    float ce = s_ce[0], mx = s_max[0], mn = s_min[0];
+    float ce = s_ce[0], mx = s_max[0], mnb = s_min[0];
     int cor = s_cor[0];
     for (int w = 1; w < NACC; ++w) {
       ce += s_ce[w];
       mx = fmaxf(mx, s_max[w]);
-      mn = fminf(mn, s_min[w]);
+      mnb = fminf(mnb, s_min[w]);
       cor += s_cor[w];
     }
     const int64_t o = (int64_t)slice * chunks + chunk;
     ws.part_ce[o] = ce;
     ws.part_max[o] = mx;
-    ws.part_min[o] = mn;
+    ws.part_min[o] = mnb;
     ws.part_correct[o] = cor;
   }
 }
 
-// Stage 2.  Block 0 (1024 threads): one wavefront per slice folds that slice's
-// chunk partials (lanes stride over chunks, fixed shuffle tree), then the slice
-// results are folded with each output's op in slice order.  All blocks:
-// class_counts[c] = sum over slices of the slice's count, in slice order.
+// Stage 2.  All blocks: a histogram of the rows' arg-max classes, built in LDS
+// over the block's share of the rows and added into class_counts (integer
+// sums: any order gives the same counts; summed over slices, the counts do not
+// depend on where the slices are cut).  Block 0 then (1024 threads): one
+// wavefront per slice folds that slice's chunk partials (lanes stride over
+// chunks, fixed shuffle tree), and the slice results are folded with each
+// output's op in slice order.
 constexpr int kE2Block = 1024;
+constexpr int kE2RowsPerBlock = 2048;
+constexpr int kMaxClasses = 4096;
 
 __global__ __launch_bounds__(kE2Block) void eval_stage2_kernel(
-    EvalWs ws, int n_slices, int chunks, int classes, float* __restrict__ ce_sum,
+    EvalWs ws, int64_t rows, int n_slices, int chunks, int classes,
+    const int32_t* __restrict__ argmax, float* __restrict__ ce_sum,
     int32_t* __restrict__ class_counts, float* __restrict__ max_logit,
     float* __restrict__ min_logit, int32_t* __restrict__ n_correct) {
+  __shared__ int32_t hist[kMaxClasses];
+  for (int c = threadIdx.x; c < classes; c += kE2Block) hist[c] = 0;
+  __syncthreads();
   const int64_t stride = (int64_t)gridDim.x * kE2Block;
-  for (int64_t c = (int64_t)blockIdx.x * kE2Block + threadIdx.x; c < classes; c += stride) {
-    // integer sums: any order gives the same result, so 16 loads go out together
-    int32_t acc = 0;
-    int s = 0;
-    for (; s + 16 <= n_slices; s += 16) {
-      int32_t v[16];
-#pragma unroll
-      for (int k = 0; k < 16; ++k) v[k] = ws.slice_counts[(int64_t)(s + k) * classes + c];
-#pragma unroll
-      for (int k = 0; k < 16; ++k) acc += v[k];
-    }
-    for (; s < n_slices; ++s) acc += ws.slice_counts[(int64_t)s * classes + c];
-    class_counts[c] = acc;
+  for (int64_t r = (int64_t)blockIdx.x * kE2Block + threadIdx.x; r < rows; r += stride) {
+    const int a = argmax[r];
+    if ((unsigned)a < (unsigned)classes) atomicAdd(&hist[a], 1);
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < classes; c += kE2Block) {
+    const int32_t v = hist[c];
+    if (v != 0) atomicAdd(class_counts + c, v);
   }
   if (blockIdx.x != 0) return;
   constexpr int NW = kE2Block / kWave;
@@ -489,9 +471,9 @@ __global__ __launch_bounds__(kE2Block) void eval_stage2_kernel(
 using namespace synk;
 
 static int eval_check(int64_t rows, int64_t classes, int n_slices) {
-  if (rows < 1 || classes < 1 || classes > 4096 || n_slices < 1) return SYNK_ERR_SHAPE;
+  if (rows < 1 || classes < 1 || classes > kMaxClasses || n_slices < 1) return SYNK_ERR_SHAPE;
   if (n_slices > 65535) return SYNK_ERR_UNSUPPORTED;
-  if (eval_chunks(rows, n_slices) > 0x7fffffffULL) return SYNK_ERR_UNSUPPORTED;
+  if (eval_chunks(rows, n_slices, kRegularRows) > 0x7fffffffULL) return SYNK_ERR_UNSUPPORTED;
   return SYNK_OK;
 }
 
@@ -520,30 +502,28 @@ extern "C" int synk_sliced_eval(const float* logits, const int32_t* labels, int6
   const size_t need = eval_ws_layout(rows, classes, n_slices, ws, &w);
   if (!ws || !aligned_to(ws, 256) || ws_bytes < need) return SYNK_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  const int chunks = (int)eval_chunks(rows, n_slices);
-  const int64_t n_counts = (int64_t)n_slices * classes;
-  int zb = (int)((n_counts + kEBlock - 1) / kEBlock);
-  if (zb > kNumCU * 8) zb = kNumCU * 8;
-  hipLaunchKernelGGL(zero_i32_kernel, dim3(zb), dim3(kEBlock), 0, s, w.slice_counts, n_counts);
-  SYNK_LAUNCH_CHECK();
+  constexpr int kUnitsLo = (kRegularUPL - 1) * kRegularG, kUnitsHi = kRegularUPL * kRegularG;   // vectors a row
+  const bool regular = classes % 4 == 0 && aligned_to(logits, 16) && rows % ((int64_t)n_slices * kRegularRows) == 0 &&
+                       classes / 4 > kUnitsLo && classes / 4 <= kUnitsHi;
+  const int chunks = (int)eval_chunks(rows, n_slices, regular ? kRegularRows : kRowsPerBlock);
   const dim3 grid(chunks, n_slices);
-  const bool regular = rows % ((int64_t)n_slices * kRowsPerBlock) == 0 && classes > 960 && classes <= 1024;
-  if (classes % 4 == 0 && aligned_to(logits, 16) && regular)
-    SYNK_LAUNCH_TIMED((eval_stage1_pipe_kernel<16, 16, kRowsPerBlock / 16>), grid, dim3(kEBlock), 0, s, logits,
-                      labels, rows, (int)classes, n_slices, chunks, w, argmax);
+  if (regular)
+    SYNK_LAUNCH_TIMED((eval_stage1_regular_kernel<kRegularG, kRegularUPL>), grid, dim3(kEBlock), 0, s, logits,
+                      labels, rows, (int)classes, n_slices, chunks, w, argmax, class_counts);
   else if (classes % 4 == 0 && aligned_to(logits, 16) && classes <= 1024)
     SYNK_LAUNCH_TIMED((eval_stage1_kernel<16, 16>), grid, dim3(kEBlock), 0, s, logits, labels, rows,
-                       (int)classes, n_slices, chunks, w, argmax);
+                       (int)classes, n_slices, chunks, w, argmax, class_counts);
   else if (classes % 4 == 0 && aligned_to(logits, 16))
     SYNK_LAUNCH_TIMED((eval_stage1_kernel<64, 16>), grid, dim3(kEBlock), 0, s, logits, labels, rows,
-                       (int)classes, n_slices, chunks, w, argmax);
+                       (int)classes, n_slices, chunks, w, argmax, class_counts);
   else
     SYNK_LAUNCH_TIMED(eval_stage1_generic_kernel, grid, dim3(kEBlock), 0, s, logits, labels, rows,
-                       (int)classes, n_slices, chunks, w, argmax);
+                       (int)classes, n_slices, chunks, w, argmax, class_counts);
   SYNK_LAUNCH_CHECK();
-  int b2 = (int)((classes + kE2Block - 1) / kE2Block);
-  hipLaunchKernelGGL(eval_stage2_kernel, dim3(b2), dim3(kE2Block), 0, s, w, n_slices, chunks,
-                     (int)classes, ce_sum, class_counts, max_logit, min_logit, n_correct);
+  int64_t b2 = (rows + kE2RowsPerBlock - 1) / kE2RowsPerBlock;
+  if (b2 > kNumCU) b2 = kNumCU;
+  hipLaunchKernelGGL(eval_stage2_kernel, dim3((unsigned)b2), dim3(kE2Block), 0, s, w, rows, n_slices, chunks,
+                     (int)classes, argmax, ce_sum, class_counts, max_logit, min_logit, n_correct);
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;
 }

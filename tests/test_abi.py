@@ -208,7 +208,8 @@ def test_sliced_grad_conv_argument_checks_and_workspace():
 
 
 def test_sliced_eval_argument_checks_and_workspace():
-    assert synk.synk_sliced_eval_workspace_bytes(65536, 1000, 64) >= 64 * 1000 * 4
+    # four partial results per (slice, row set of 8 rows)
+    assert synk.synk_sliced_eval_workspace_bytes(65536, 1000, 64) >= 4 * 64 * (1024 // 8) * 4
     for bad in [(0, 10, 1), (10, 0, 1), (10, 5000, 1), (10, 10, 0)]:
         with pytest.raises(synk.SynkError) as e:
             synk.synk_sliced_eval_workspace_bytes(*bad)

@@ -523,11 +523,15 @@ def check_eval(got, ref):
     (5, 10, 8),          # more slices than rows
     (300, 4096, 2),      # widest rows
     (64, 1, 1),          # a single class
-    (512, 1024, 4),      # pipelined path: full last vector
-    (768, 964, 3),       # pipelined path: one valid vector slot in the last lane group
-    (256, 1000, 8),      # pipelined path: one block a slice
+    (512, 1024, 4),      # branch-free path: full last vector
+    (768, 964, 3),       # branch-free path: the last lane group half padding
+    (768, 900, 3),       # branch-free path: one valid vector slot in the last lane group
+    (256, 1000, 8),      # branch-free path: four blocks a slice
+    (72, 1000, 9),       # branch-free path: one block (8 rows) a slice
     (2080, 1000, 65),    # 32 rows a slice but 65 slices: still regular
-    (2048, 960, 64),     # just below the pipelined path's class range
+    (2048, 960, 64),     # branch-free path, 16 padded lanes
+    (2048, 896, 64),     # just below the branch-free path's class range
+    (1004, 1000, 251),   # 4 rows a slice: not a whole row set, the general path
 ])
 def test_sliced_eval_matches_oracle(synk, rows, classes, n_slices):
     c = workloads.config5(rows=rows, classes=classes, n_slices=n_slices)
@@ -546,7 +550,7 @@ def test_sliced_eval_ties_take_the_lowest_class(synk):
     check_eval(got, evalops.sliced(logits, labels, 5))
 
 
-def test_sliced_eval_pipelined_path_ties_and_bad_labels(synk):
+def test_sliced_eval_branch_free_path_ties_and_bad_labels(synk):
     rng = np.random.default_rng(19)
     logits = (rng.standard_normal((128, 1000)) * 2).astype(np.float32)
     for i in range(128):       # equal maxima in different lane groups / vector slots, also in the last vector
