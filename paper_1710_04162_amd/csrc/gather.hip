@@ -229,13 +229,15 @@ __global__ void norm_lut_kernel_args(float* __restrict__ lut, int channels, LutA
 __global__ void clear_word_kernel(uint32_t* w) { *w = 0u; }
 
 static int chunking(int64_t units, int* units_per_block, int* chunks) {
-  // up to 16 units per thread per block; at least one block per row
-  int64_t upb = (int64_t)kGBlock * 16;
+  // one batch of four units per thread per block (short-lived workgroups stream faster than
+  // ones that loop: 14.3 against 15.7 us on 64 rows of 200,704 floats); at least one block per row
+  int64_t upb = (int64_t)kGBlock * 4;
   if (units < upb) upb = (units + kGBlock - 1) / kGBlock * kGBlock;
   if (upb < kGBlock) upb = kGBlock;
+  while ((units + upb - 1) / upb > 65535 && upb < ((int64_t)1 << 30)) upb *= 2;   // grid.y limit: longer loops instead
   *units_per_block = (int)upb;
   const int64_t c = (units + upb - 1) / upb;
-  if (c > 65535) return SYNK_ERR_UNSUPPORTED;   // grid.y limit: rows beyond 4 Gi units
+  if (c > 65535) return SYNK_ERR_UNSUPPORTED;
   *chunks = c < 1 ? 1 : (int)c;
   return SYNK_OK;
 }
