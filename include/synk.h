@@ -338,9 +338,9 @@ int synk_cast_bf16(const float* in, void* out, int64_t len, void* stream);
  *   argmax       int32[rows]   a_i                                        CONCAT
  * logits: device float[rows x classes] row-major; labels: device int32[rows]
  * (a label outside [0,classes) adds only the logsumexp term and never counts
- * as correct).  Inputs must be finite (a row without a largest element, NaN
- * only, is given class 0; nothing faults).  All outputs are device pointers and
- * are fully overwritten.  rows >= 1, classes in [1, 4096], n_slices >= 1.
+ * as correct).  Inputs must be finite (other input never faults: a row of
+ * -inf only counts as class 0, a row of NaN as some class in range).  All
+ * outputs are device pointers and are fully overwritten.  rows >= 1, classes in [1, 4096], n_slices >= 1.
  */
 int synk_sliced_eval_workspace_bytes(int64_t rows, int64_t classes, int n_slices, size_t* bytes);
 int synk_sliced_eval(const float* logits, const int32_t* labels, int64_t rows, int64_t classes,

@@ -55,7 +55,7 @@ __device__ __forceinline__ void clear_counts(int32_t* __restrict__ class_counts,
     for (int c = threadIdx.x; c < classes; c += kEBlock) class_counts[c] = 0;
 }
 
-// A row without a largest element (NaN only) has no arg-max: class 0 stands in.
+// A row without a largest element has no arg-max: whatever the scan left is brought into range (class 0).
 __device__ __forceinline__ int in_range(int arg, int classes) {
   return (unsigned)arg < (unsigned)classes ? arg : 0;
 }

@@ -563,6 +563,27 @@ def test_sliced_eval_branch_free_path_ties_and_bad_labels(synk):
     check_eval(got, evalops.sliced(logits, labels, 2))
 
 
+@pytest.mark.parametrize("rows,classes,n_slices", [(64, 1000, 2), (60, 1000, 2), (20, 37, 2)])
+def test_sliced_eval_non_finite_rows_stay_in_range(synk, rows, classes, n_slices):
+    # outside the contract (inputs must be finite), but nothing may fault: a row of -inf only counts as
+    # class 0, a row of NaN only as some class in range; the other rows keep their arg-max
+    rng = np.random.default_rng(29)
+    logits = (rng.standard_normal((rows, classes)) * 2).astype(np.float32)
+    logits[3, :] = -np.inf
+    logits[rows - 2, :] = np.nan
+    labels = rng.integers(0, classes, rows).astype(np.int32)
+    got = run_eval(synk, logits, labels, n_slices)
+    arg = got["argmax"].astype(np.int64)
+    want = logits.argmax(axis=1)
+    ok = np.ones(rows, dtype=bool)
+    ok[rows - 2] = False
+    want[3] = 0
+    assert np.array_equal(arg[ok], want[ok])
+    assert 0 <= arg[rows - 2] < classes
+    assert np.array_equal(got["counts"].astype(np.int64), np.bincount(arg, minlength=classes))
+    assert int(got["n_correct"][0]) == int((arg == labels).sum())
+
+
 def test_streaming_kernels_are_reproducible(synk):
     c = workloads.config5(rows=4096, classes=1000, n_slices=16)
     a = run_eval(synk, c["logits"], c["labels"], 16)
