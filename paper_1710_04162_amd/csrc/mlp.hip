@@ -1072,6 +1072,7 @@ __global__ __launch_bounds__(kMBlock) void softmax_ce_kernel(CeArgs a) {
 // barrier.
 constexpr int kHeadMaxC = 16;
 constexpr int kHeadRowsPerBlock = 4;
+constexpr int kHeadCached = 2;   // 512-feature blocks of a row the last-layer kernel keeps in registers
 
 struct HeadArgs {
   const int32_t* y[SYNK_MAX_WORKERS];
@@ -1146,18 +1147,47 @@ __global__ __launch_bounds__(kMBlock) void mlp_head_kernel(HeadArgs a) {
     weight = 1.0f / (float)n_ws;
   }
 
+  // Up to kHeadCached * 512 features, a lane's features and weight blocks are
+  // loaded once, all of them before the first use, and stay in registers for
+  // the backward half (the kernel is a chain of memory round trips: this takes
+  // two of the four out).  A lane's block past the end is read at the row's
+  // last block and its features zeroed.
+  constexpr int NIT = kHeadCached;
+  const bool cached = K <= NIT * 512 && K >= 8;
+  float hc[NIT][8], wc[NIT][8 * C];
+
   // forward: each lane accumulates its features' share of every logit
   float acc[C];
 #pragma unroll
   for (int c = 0; c < C; ++c) acc[c] = 0.0f;
-  for (int k0 = lane * 8; k0 < K; k0 += 64 * 8) {
-    float hv[8], wv[8 * C];
-    Vec8<T>::load(h + k0, hv);
-    load_w_block<T, C>(Wg, k0, wv);
+  if (cached) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int it = 0; it < NIT; ++it) {
+      const int k0 = lane * 8 + it * 512;
+      const int kc = k0 < K ? k0 : K - 8;
+      Vec8<T>::load(h + kc, hc[it]);
+      load_w_block<T, C>(Wg, kc, wc[it]);
+    }
 #pragma unroll
-      for (int c = 0; c < C; ++c) acc[c] = fmaf(hv[j], wv[j * C + c], acc[c]);
+    for (int it = 0; it < NIT; ++it) {
+      const bool in = lane * 8 + it * 512 < K;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        hc[it][j] = in ? hc[it][j] : 0.0f;
+#pragma unroll
+        for (int c = 0; c < C; ++c) acc[c] = fmaf(hc[it][j], wc[it][j * C + c], acc[c]);
+      }
+    }
+  } else {
+    for (int k0 = lane * 8; k0 < K; k0 += 64 * 8) {
+      float hv[8], wv[8 * C];
+      Vec8<T>::load(h + k0, hv);
+      load_w_block<T, C>(Wg, k0, wv);
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int c = 0; c < C; ++c) acc[c] = fmaf(hv[j], wv[j * C + c], acc[c]);
+    }
   }
   float m = -INFINITY;
 #pragma unroll
@@ -1187,6 +1217,24 @@ __global__ __launch_bounds__(kMBlock) void mlp_head_kernel(HeadArgs a) {
 
   // backward through the last layer, masked by the relu below
   T* dzb = reinterpret_cast<T*>(a.dz_below) + row * K;
+  if (cached) {
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int k0 = lane * 8 + it * 512;
+      if (k0 < K) {
+        float dh[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          float d = 0.0f;
+#pragma unroll
+          for (int c = 0; c < C; ++c) d = fmaf(dzq[c], wc[it][j * C + c], d);
+          dh[j] = (hc[it][j] > 0.0f) ? d : 0.0f;
+        }
+        Vec8<T>::store(dzb + k0, dh);
+      }
+    }
+    return;
+  }
   for (int k0 = lane * 8; k0 < K; k0 += 64 * 8) {
     float hv[8], wv[8 * C], dh[8];
     Vec8<T>::load(h + k0, hv);
