@@ -385,10 +385,10 @@ __global__ __launch_bounds__(kEBlock) void eval_stage1_regular_kernel(
   }
 }
 
-// Stage 2.  All blocks: a histogram of the rows' arg-max classes, built in LDS
+// Stage 2.  All blocks but the last: a histogram of the rows' arg-max classes, built in LDS
 // over the block's share of the rows and added into class_counts (integer
 // sums: any order gives the same counts; summed over slices, the counts do not
-// depend on where the slices are cut).  Block 0 then (1024 threads): one
+// depend on where the slices are cut).  The last block meanwhile (1024 threads): one
 // wavefront per slice folds that slice's chunk partials (lanes stride over
 // chunks, fixed shuffle tree), and the slice results are folded with each
 // output's op in slice order.
@@ -401,20 +401,23 @@ __global__ __launch_bounds__(kE2Block) void eval_stage2_kernel(
     const int32_t* __restrict__ argmax, float* __restrict__ ce_sum,
     int32_t* __restrict__ class_counts, float* __restrict__ max_logit,
     float* __restrict__ min_logit, int32_t* __restrict__ n_correct) {
-  __shared__ int32_t hist[kMaxClasses];
-  for (int c = threadIdx.x; c < classes; c += kE2Block) hist[c] = 0;
-  __syncthreads();
-  const int64_t stride = (int64_t)gridDim.x * kE2Block;
-  for (int64_t r = (int64_t)blockIdx.x * kE2Block + threadIdx.x; r < rows; r += stride) {
-    const int a = argmax[r];
-    if ((unsigned)a < (unsigned)classes) atomicAdd(&hist[a], 1);
+  // the last block folds the partials while the others build the histogram
+  if (blockIdx.x + 1 != gridDim.x) {
+    __shared__ int32_t hist[kMaxClasses];
+    for (int c = threadIdx.x; c < classes; c += kE2Block) hist[c] = 0;
+    __syncthreads();
+    const int64_t stride = (int64_t)(gridDim.x - 1) * kE2Block;
+    for (int64_t r = (int64_t)blockIdx.x * kE2Block + threadIdx.x; r < rows; r += stride) {
+      const int a = argmax[r];
+      if ((unsigned)a < (unsigned)classes) atomicAdd(&hist[a], 1);
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < classes; c += kE2Block) {
+      const int32_t v = hist[c];
+      if (v != 0) atomicAdd(class_counts + c, v);
+    }
+    return;
   }
-  __syncthreads();
-  for (int c = threadIdx.x; c < classes; c += kE2Block) {
-    const int32_t v = hist[c];
-    if (v != 0) atomicAdd(class_counts + c, v);
-  }
-  if (blockIdx.x != 0) return;
   constexpr int NW = kE2Block / kWave;
   __shared__ float s_ce[NW], s_max[NW], s_min[NW];
   __shared__ int s_cor[NW];
@@ -522,7 +525,7 @@ extern "C" int synk_sliced_eval(const float* logits, const int32_t* labels, int6
   SYNK_LAUNCH_CHECK();
   int64_t b2 = (rows + kE2RowsPerBlock - 1) / kE2RowsPerBlock;
   if (b2 > kNumCU) b2 = kNumCU;
-  hipLaunchKernelGGL(eval_stage2_kernel, dim3((unsigned)b2), dim3(kE2Block), 0, s, w, rows, n_slices, chunks,
+  hipLaunchKernelGGL(eval_stage2_kernel, dim3((unsigned)b2 + 1), dim3(kE2Block), 0, s, w, rows, n_slices, chunks,
                      (int)classes, argmax, ce_sum, class_counts, max_logit, min_logit, n_correct);
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;
