@@ -1,12 +1,14 @@
 // Six-output evaluation over slices with on-GPU aggregation (Sec. 3.1: one
 // reduce/gather op per output; Sec. 5.1: slice results aggregated in place).
 //
-// Stage 1 (one pass over the logits, bound by HBM bandwidth): a group of 16
-// or 64 lanes holds a row in registers and computes arg-max, max, min and the
-// log-sum-exp, merged across the group with shuffles; a workgroup covers a run
-// of rows of ONE slice and leaves per-(slice, chunk) partial results.
+// Stage 1 (one pass over the logits, bound by HBM bandwidth): a group of 16,
+// 32 or 64 lanes holds a row in registers and computes arg-max, max, min and
+// the log-sum-exp, merged across the group with shuffles; a workgroup covers a
+// run of rows of ONE slice and leaves per-(slice, chunk) partial results and
+// the rows' arg-max classes.
 // Stage 2 folds chunk partials into slice results and slice results into the
-// outputs with each output's op, in a fixed order (no float atomics).
+// outputs with each output's op, in a fixed order (no float atomics), and
+// counts the arg-max classes (integer atomics: exact in any order).
 #include <math.h>
 
 #include "common.h"
