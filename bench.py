@@ -63,6 +63,16 @@ def parse():
     return ap.parse_args()
 
 
+def share_bounds(synk, count, parts):
+    """[(start, stop)] of each worker's share, by the library's own split rule (Sec. 3.2 step 1)."""
+    off = synk.synk_split(count, parts)
+    return list(zip(off[:-1], off[1:]))
+
+
+def share_sizes(synk, count, parts):
+    return [b - a for a, b in share_bounds(synk, count, parts)]
+
+
 def host_threads():
     try:
         from threadpoolctl import threadpool_info
@@ -107,7 +117,6 @@ class MlpStep:
     def __init__(self, torch, synk, cfg_no, batch=None):
         import numpy as np
         import workloads
-        from oracle import split as osplit           # host-side share sizes for buffer allocation only
         self.torch, self.s, self.np = torch, synk, np
         if cfg_no == 1:
             c = workloads.config1()
@@ -131,7 +140,7 @@ class MlpStep:
         self.p_lp = torch.zeros(self.P, dtype=torch.bfloat16, device="cuda") if self.bf16 else None
         if self.bf16:
             synk.synk_cast_bf16(self.p, self.p_lp)
-        self.rows = osplit.share_sizes(self.B, self.N)
+        self.rows = share_sizes(synk, self.B, self.N)
         xdt = torch.bfloat16 if self.bf16 else torch.float32
         self.x = [torch.zeros((n, self.dims[0]), dtype=xdt, device="cuda") for n in self.rows]
         self.y = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in self.rows]
@@ -270,8 +279,7 @@ class CollectiveStep:
             self.dom_name, self.dom_bytes = "broadcast_kernel", self.P * 4 * (1 + self.N)
             what = "broadcast of one array to the 8 copies"
         else:
-            from oracle import split as osplit
-            self.bounds = osplit.share_bounds(self.P, self.N)
+            self.bounds = share_bounds(synk, self.P, self.N)
             self.srcs = [up(c["p"][a:b]) for a, b in self.bounds]
             self.call = synk.prepare(synk.synk_all_gather, self.srcs, self.bufs)
             self.dom_name, self.dom_bytes = "all_gather_kernel", self.P * 4 * (1 + self.N)
@@ -303,7 +311,6 @@ class GatherStep:
     def __init__(self, torch, synk, indexing="list"):
         import numpy as np
         import workloads
-        from oracle import split as osplit
         self.torch, self.s, self.np, self.indexing = torch, synk, np, indexing
         small = workloads.config4(n_data=8, batch=8)             # mean/std recipe
         self.mean, self.std = small["mean"], small["std"]
@@ -321,7 +328,7 @@ class GatherStep:
                     for _ in range(64)]                          # fresh indexes every step
         self.lut = torch.empty(3 * 256, device="cuda")
         synk.synk_build_norm_lut(self.mean, self.std, self.lut)
-        rows = osplit.share_sizes(self.B, self.N)
+        rows = share_sizes(synk, self.B, self.N)
         self.dst = [torch.zeros((n, row), device="cuda") for n in rows]
         self.dl = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in rows]
         self.units, self.unit = self.B, "images/s"
@@ -346,7 +353,7 @@ class GatherStep:
             # allocation); every worker excerpts 32 rows of its own share with its own list
             self.workload = ("config 4 shape with resident shares: 8 workers x 32 own indexes into their 6250-image "
                              "uint8 share, normalise to fp32, with labels")
-            bounds = osplit.share_bounds(self.n_data, self.N)
+            bounds = share_bounds(synk, self.n_data, self.N)
             shares = [self.data[a:b] for a, b in bounds]
             lshares = [self.labels[a:b] for a, b in bounds]
             self.lists = [[torch.from_numpy(rng.integers(0, b - a, n).astype(np.int32)).cuda()
@@ -425,7 +432,6 @@ class ConvStep:
     def __init__(self, torch, synk, conv_shape=None):
         import numpy as np
         import workloads
-        from oracle import split as osplit           # host-side share sizes for buffer allocation only
         self.torch, self.s, self.np = torch, synk, np
         if conv_shape:
             H, W, cin, cout = [int(v) for v in conv_shape.split(",")]
@@ -443,7 +449,7 @@ class ConvStep:
         self.B = len(c["idx"])
         self.P = synk.synk_convblock_param_count(self.shape)
         self.p, self.v = up(c["theta"]), torch.zeros(self.P, device="cuda")
-        self.rows = osplit.share_sizes(self.B, self.N)
+        self.rows = share_sizes(synk, self.B, self.N)
         xdt = torch.bfloat16 if self.bf16 else torch.float32
         self.x = [torch.zeros((n, H * W * cin), dtype=xdt, device="cuda") for n in self.rows]
         self.y = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in self.rows]

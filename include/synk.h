@@ -9,7 +9,7 @@
  *                           list over workers (Sec. 3.2 step 1)
  *   synk_gather_slice, synk_scatter_rows, synk_gather_resident
  *                           the same with a slice for a list, the scatter of an
- *                           array over the workers (Sec. 4.3), and indexing of
+ *                           array over the workers (Sec. 4.2), and indexing of
  *                           shares that already live on the workers (Sec. 5.2)
  *   synk_sliced_grad, synk_sliced_grad_conv
  *                           the gradient function run over every worker's
@@ -30,8 +30,9 @@
  *
  * Conventions common to every call
  * --------------------------------
- * - Returns SYNK_OK (0) or a negative SYNK_ERR_* code; never throws, keeps no
- *   global state, and may be called from several host threads.
+ * - Returns SYNK_OK (0) or a negative SYNK_ERR_* code; never throws and may be
+ *   called from several host threads.  The only state kept between calls is
+ *   the pending event pair of synk_profile_next_launch, one per host thread.
  * - All argument checks run on the host BEFORE the first HIP call, so a call
  *   with invalid arguments returns its error code without touching a device.
  * - "device" pointers are device memory owned by the caller and stay owned by
@@ -45,9 +46,9 @@
  *   synk_poll_error.  Calls on one stream execute in call order.
  * - At most SYNK_MAX_WORKERS workers / buffers per call.
  * - Splitting `count` data points over `parts` workers or slices always uses
- *   the same rule (the paper says "equally (as possible)"): contiguous runs,
- *   share i has count/parts + (i < count%parts ? 1 : 0) points; shares may be
- *   empty.
+ *   the same rule (Sec. 3.2 asks for shares as equal as they can be and names
+ *   no remainder rule): contiguous runs, share i has
+ *   count/parts + (i < count%parts ? 1 : 0) points; shares may be empty.
  * - Float results are run-to-run reproducible: no floating-point atomics.
  */
 #ifndef SYNK_H
@@ -151,8 +152,8 @@ int synk_gather_rows(const void* data, int64_t n_rows, int64_t row_elems, int sr
                      const int32_t* labels, int32_t* const* dst_labels,
                      uint32_t flags, void* ws, size_t ws_bytes, void* stream);
 
-/* The same gather with the index list given as a slice (Sec. 5.2: "indexes
- * can make a slice or can be a list"): row j of the minibatch is
+/* The same gather with the index list given as a slice (Sec. 5.2 allows
+ * either form of indexes): row j of the minibatch is
  * data[start + j*step], j < ceil((stop-start)/step), step >= 1,
  * 0 <= start <= stop <= n_rows; the list is split over the workers as above.
  * Errors as synk_gather_rows; step < 1 -> ERR_SHAPE; start/stop outside the
@@ -163,7 +164,7 @@ int synk_gather_slice(const void* data, int64_t n_rows, int64_t row_elems, int s
                       const float* lut, int channels,
                       const int32_t* labels, int32_t* const* dst_labels, void* stream);
 
-/* The "scatter" collective (Sec. 4.3): an array is divided over the workers'
+/* The "scatter" collective (Sec. 4.2): an array is divided over the workers'
  * memories by its first dimension, shares as equal as possible, in order:
  * dst[w] receives rows [start_w, start_w + size_w) of data (split rule),
  * bit-exact, and dst_labels[w] the matching labels when labels != NULL.
@@ -172,9 +173,9 @@ int synk_scatter_rows(const void* data, int64_t n_rows, int64_t row_elems, int d
                       void* const* dst, int n_workers,
                       const int32_t* labels, int32_t* const* dst_labels, void* stream);
 
-/* Input indexing of data that already lives on the workers (Sec. 5.2: for
- * inputs stored on the devices "the same or different indexes can be applied
- * to each device"): worker w excerpts rows idx[w][0..n_idx[w]) of its own
+/* Input indexing of data that already lives on the workers (Sec. 5.2: every
+ * device may be given its own index list, or all of them the same one):
+ * worker w excerpts rows idx[w][0..n_idx[w]) of its own
  * share shares[w] ([share_rows[w] x row_elems]) into dst[w], in list order.
  * shares, share_rows, idx, n_idx, dst, labels, dst_labels: host arrays of
  * n_workers entries (idx[w], shares[w], labels[w] device pointers; pass the
@@ -237,7 +238,13 @@ int synk_poll_error(void* ws, void* stream);
  *   grad            host array[n_workers] of device float[P]; fully
  *                   overwritten (a worker with no rows gets zeros)
  *   loss            device float[n_workers]
- *   ws              synk_sliced_grad_workspace_bytes(m, rows, n_workers, &b)
+ *   ws              synk_sliced_grad_workspace_bytes(m, rows, n_workers, &b).
+ *                   All slices are evaluated in one pass, every row carrying
+ *                   the weight its slice has under grad_op, so the workspace
+ *                   holds the activations of ALL rows of all workers:
+ *                   n_slices changes the aggregation (and, for SYNK_SUM, the
+ *                   weights), not the workspace size; the memory-bounding
+ *                   effect slicing has in Sec. 5.1 is not reproduced.
  * Errors: NULL -> ERR_NULL; n_layers out of [1,SYNK_MAX_LAYERS], dims <= 0,
  * rows < 0, all rows zero, n_workers out of range, n_slices <= 0 -> ERR_SHAPE;
  * compute_dtype -> ERR_DTYPE; grad_op not SUM/MEAN -> ERR_OP; params, x[w] or
@@ -368,8 +375,8 @@ int synk_reduce_buffers(const void* const* bufs, int n, int64_t len, int dtype, 
                         const float* weights, const int64_t* lens, void* out, void* stream);
 
 /* ------------------------------------------------------------- collectives
- * The collectives over the N worker copies of a variable (Sec. 3.2 "Shared
- * Variable Management": broadcast, all-reduce and the other MPI-like
+ * The collectives over the N worker copies of a variable (Sec. 3.2, the
+ * part on shared variables, which lists broadcast and all-reduce among its
  * collectives; App. A: averaging the parameters over the workers).  Reduce-
  * to-one and gather-to-one are synk_reduce_buffers.  Elements are 4 bytes
  * (SYNK_F32 or SYNK_I32); pointer tables, lens and weights are host arrays

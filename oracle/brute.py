@@ -134,3 +134,74 @@ def convblock_loss(theta, shape, X, y, eps):
         m = max(logits)
         total += m + math.log(sum(math.exp(t - m) for t in logits)) - logits[int(y[i])]
     return total / n
+
+
+def bf16_rne(v):
+    """One number rounded the way a bf16-input pipeline receives it: to single
+    precision first (the precision the surrounding arithmetic runs in; the
+    struct module converts with round-to-nearest-even), then to the nearest
+    bfloat16, ties to the even neighbour.  Integer arithmetic on the 32-bit
+    pattern, one scalar at a time; finite inputs only."""
+    import struct
+    bits = struct.unpack("<I", struct.pack("<f", float(v)))[0]
+    top, low = bits >> 16, bits & 0xFFFF
+    if low > 0x8000 or (low == 0x8000 and (top & 1)):
+        top += 1                       # a carry into the exponent is the right next value
+    return struct.unpack("<f", struct.pack("<I", (top << 16) & 0xFFFFFFFF))[0]
+
+
+BF16_POINTS = ("x", "w", "h", "dz")
+
+
+def mlp_loss_grad_bf16_points(theta, dims, X, y, points=BF16_POINTS, rnd=bf16_rne):
+    """Loss and gradient of mean_i l_i for any number of layers, scalar loops
+    only, with the values a bf16-input contraction is fed rounded by `rnd`:
+      "x"   the input rows,
+      "w"   every W_l (in the forward product and in the backward product),
+      "h"   every hidden activation relu(z_l) as the next layer receives it,
+      "dz"  every dZ_l, before any of its three uses (dW_l, db_l, dZ_{l-1}).
+    Biases, the softmax, the relu mask (taken from the unrounded z_l) and all
+    sums stay in double precision.  `points` names the rounding points that
+    are active, so that a test can take one out or put one in the wrong place
+    ("b": also round the biases; "late_dz": round dZ_l only where it enters the
+    product with W_l^T, not for dW_l and db_l).
+    Returns (loss, flat gradient list laid out like theta)."""
+    q = lambda v, name: rnd(v) if name in points else float(v)
+    L = len(dims) - 1
+    rows = len(X)
+    offW, offB, at = [], [], 0
+    for l in range(L):
+        offW.append(at)
+        at += dims[l] * dims[l + 1]
+        offB.append(at)
+        at += dims[l + 1]
+    g = [0.0] * at
+    Wq = [[[q(theta[offW[l] + a * dims[l + 1] + j], "w") for j in range(dims[l + 1])]
+           for a in range(dims[l])] for l in range(L)]
+    bq = [[q(theta[offB[l] + j], "b") for j in range(dims[l + 1])] for l in range(L)]
+    total = 0.0
+    for i in range(rows):
+        h = [[q(t, "x") for t in X[i]]]                 # h[l]: what layer l+1's product receives
+        pos = []                                         # pos[l][j]: relu(z_{l+1})[j] > 0
+        for l in range(L):
+            z = [bq[l][j] + sum(h[l][a] * Wq[l][a][j] for a in range(dims[l])) for j in range(dims[l + 1])]
+            if l < L - 1:
+                pos.append([t > 0.0 for t in z])
+                h.append([q(max(t, 0.0), "h") for t in z])
+        m = max(z)
+        ex = [math.exp(t - m) for t in z]
+        se = sum(ex)
+        total += m + math.log(se) - z[int(y[i])]
+        dz_full = [(ex[c] / se - (1.0 if c == int(y[i]) else 0.0)) / rows for c in range(dims[L])]
+        for l in range(L - 1, -1, -1):
+            dz_q = [q(t, "dz") for t in dz_full]
+            dz_w = dz_full if "late_dz" in points else dz_q    # what dW_l and db_l are built from
+            dz_x = [rnd(t) for t in dz_full] if "late_dz" in points else dz_q
+            for j in range(dims[l + 1]):
+                g[offB[l] + j] += dz_w[j]
+                for a in range(dims[l]):
+                    g[offW[l] + a * dims[l + 1] + j] += h[l][a] * dz_w[j]
+            if l > 0:
+                dz_full = [sum(dz_x[j] * Wq[l][a][j] for j in range(dims[l + 1])) if pos[l - 1][a] else 0.0
+                           for a in range(dims[l])]
+    return total / rows, g

@@ -1,5 +1,5 @@
-"""The collectives over the N worker copies of a variable (Sec. 3.2 "Shared
-Variable Management": broadcast, all-reduce and the other MPI-like
+"""The collectives over the N worker copies of a variable (Sec. 3.2, the part
+on shared variables, which lists broadcast and all-reduce among its
 collectives; App. A: averaging the parameters over workers; Sec. 3.2 step 3:
 results reduced or gathered).  With the workers emulated as N buffers, each
 collective maps a list of N arrays to a list of N arrays:

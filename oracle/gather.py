@@ -1,7 +1,7 @@
 """Input indexing (Sec. 5.2): the minibatch is data[idx] for a list of row
 indexes, duplicates allowed, or for a slice start:stop:step; worker w receives
 the rows named by its contiguous share of the list.  For data that already
-lives on the workers (Sec. 5.2 last part, Sec. 4.3 "scatter": an array is
+lives on the workers (Sec. 5.2 last part, Sec. 4.2 "scatter": an array is
 divided over the workers by its first dimension), every worker indexes its own
 share with its own list, or all of them with the same one."""
 import numpy as np
@@ -39,7 +39,7 @@ def slice_indexes(start, stop, step):
 
 
 def scatter(data, n_workers):
-    """Sec. 4.3: the array divided over the workers by its first dimension,
+    """Sec. 4.2: the array divided over the workers by its first dimension,
     shares as equal as possible, in order."""
     data = np.asarray(data)
     return [data[a:b].copy() for (a, b) in split.share_bounds(data.shape[0], n_workers)]

@@ -1,5 +1,5 @@
-// The collectives over the N worker copies of a variable (Sec. 3.2 "Shared
-// Variable Management": broadcast, all-reduce and the other MPI-like
+// The collectives over the N worker copies of a variable (Sec. 3.2, the
+// part on shared variables, which lists broadcast and all-reduce among its
 // collectives; App. A: the parameter average), with the workers emulated as N
 // device buffers.  Streaming kernels bound by HBM bandwidth: every source
 // element is read once, every destination element written once, 16-byte

@@ -308,6 +308,30 @@ static int gather_impl(const void* data, int64_t n_rows, int64_t row_elems, int 
     t.dst[w] = dst[w];
     t.lab[w] = want_labels ? dst_labels[w] : nullptr;
   }
+  // Every check that can refuse the call is made before the first launch.
+  int upb = 0, chunks = 0, unit = 1, plane = 0;
+  bool vec = false;
+  int64_t row_units = 0;
+  if (n_idx > 0) {
+    if (mode == COPY) {
+      const int64_t row_bytes = row_elems * src_b;
+      if (row_bytes % 16 == 0 && src_aligned(16) && dst16) unit = 16;
+      else if (row_bytes % 4 == 0 && src_aligned(4) && dst4) unit = 4;
+      row_units = row_bytes / unit;
+      if (int rc = chunking(row_units, &upb, &chunks)) return rc;
+    } else if (mode == TO_BF16) {
+      vec = row_elems % 4 == 0 && src_aligned(16) && dst8;
+      if (int rc = chunking(vec ? row_elems / 4 : row_elems, &upb, &chunks)) return rc;
+    } else {
+      plane = (int)(row_elems / channels);
+      vec = plane % 4 == 0 && src_aligned(4) && dst16;
+      const int64_t units = vec ? row_elems / 4 : row_elems;
+      upb = kLBlock * 4;                                   // 4 units per thread: one unrolled batch
+      const int64_t nch = (units + upb - 1) / upb;
+      if (nch > 65535) return SYNK_ERR_UNSUPPORTED;
+      chunks = (int)nch;
+    }
+  }
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   if (err_word) {
     hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, s, err_word);
@@ -315,17 +339,9 @@ static int gather_impl(const void* data, int64_t n_rows, int64_t row_elems, int 
   }
   if (n_idx == 0) return SYNK_OK;
 
-
-  int upb, chunks;
   const dim3 gb(kGBlock), lb(kLBlock);
+  const dim3 grid((unsigned)n_idx, chunks);
   if (mode == COPY) {
-    const int64_t row_bytes = row_elems * src_b;
-    int unit = 1;
-    if (row_bytes % 16 == 0 && src_aligned(16) && dst16) unit = 16;
-    else if (row_bytes % 4 == 0 && src_aligned(4) && dst4) unit = 4;
-    const int64_t row_units = row_bytes / unit;
-    if (int rc = chunking(row_units, &upb, &chunks)) return rc;
-    const dim3 grid((unsigned)n_idx, chunks);
 #define SYNK_COPY(V, RES, RA)                                                                        \
   hipLaunchKernelGGL((gather_copy_kernel<RES, V>), grid, gb, 0, s, reinterpret_cast<const V*>(data), \
                      n_rows, row_units, idx, RA, n_idx, t, n_workers, labels, err_word, upb)
@@ -340,9 +356,6 @@ static int gather_impl(const void* data, int64_t n_rows, int64_t row_elems, int 
     }
 #undef SYNK_COPY
   } else if (mode == TO_BF16) {
-    const bool vec = row_elems % 4 == 0 && src_aligned(16) && dst8;
-    if (int rc = chunking(vec ? row_elems / 4 : row_elems, &upb, &chunks)) return rc;
-    const dim3 grid((unsigned)n_idx, chunks);
 #define SYNK_BF(VEC, RES, RA)                                                                            \
   hipLaunchKernelGGL((gather_bf16_kernel<RES, VEC>), grid, gb, 0, s, reinterpret_cast<const float*>(data), \
                      n_rows, row_elems, idx, RA, n_idx, t, n_workers, labels, err_word, upb)
@@ -355,14 +368,6 @@ static int gather_impl(const void* data, int64_t n_rows, int64_t row_elems, int 
     }
 #undef SYNK_BF
   } else {
-    const int plane = (int)(row_elems / channels);
-    const bool vec = plane % 4 == 0 && src_aligned(4) && dst16;
-    const int64_t units = vec ? row_elems / 4 : row_elems;
-    upb = kLBlock * 4;                                   // 4 units per thread: one unrolled batch
-    const int64_t nch = (units + upb - 1) / upb;
-    if (nch > 65535) return SYNK_ERR_UNSUPPORTED;
-    chunks = (int)nch;
-    const dim3 grid((unsigned)n_idx, chunks);
 #define SYNK_LUT(VEC, RES, RA)                                                                   \
   SYNK_LAUNCH_TIMED((gather_u8_lut_kernel<RES, VEC>), grid, lb, 0, s,                            \
                      reinterpret_cast<const uint8_t*>(data), n_rows, (int)row_elems, plane, idx, \

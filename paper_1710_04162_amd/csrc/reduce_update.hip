@@ -240,8 +240,9 @@ __device__ __forceinline__ T fold(T a, T b) {
 
 // out[i] = fold over buffers in order; MEAN is the weighted sum.
 template <typename T, int OP>
-__global__ __launch_bounds__(kBlock) void reduce_kernel(BufTable t, int n, int64_t len,
-                                                        T* __restrict__ out) {
+// `out` may be bufs[0] (every thread reads its element of every buffer before it writes), so it
+// carries no no-alias qualifier.
+__global__ __launch_bounds__(kBlock) void reduce_kernel(BufTable t, int n, int64_t len, T* out) {
   using V = typename Vec4<T>::type;
   const int64_t n_vec = len >> 2;
   const int64_t stride = (int64_t)gridDim.x * kBlock;
@@ -280,8 +281,7 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(BufTable t, int n, int64
 
 // Same kernel for buffers that are only 4-byte aligned.
 template <typename T, int OP>
-__global__ __launch_bounds__(kBlock) void reduce_kernel_scalar(BufTable t, int n, int64_t len,
-                                                               T* __restrict__ out) {
+__global__ __launch_bounds__(kBlock) void reduce_kernel_scalar(BufTable t, int n, int64_t len, T* out) {
   const int64_t stride = (int64_t)gridDim.x * kBlock;
   for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < len; e += stride) {
     T a = reinterpret_cast<const T*>(t.p[0])[e];

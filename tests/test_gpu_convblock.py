@@ -9,7 +9,7 @@ import pytest
 import torch
 
 import workloads
-from helpers import TOL_BF16, TOL_F32, rel_err
+from helpers import TOL_BF16, TOL_F32, lib_share_sizes, rel_err
 from oracle import convblock as oconv, gather as ogather, split as osplit
 
 pytestmark = pytest.mark.gpu
@@ -46,7 +46,7 @@ def run_gpu(synk, cfg, idx, n_workers, n_slices, op, bf16, eps=1e-5, rows=None):
     cd = synk.SYNK_BF16 if bf16 else synk.SYNK_F32
     P = synk.synk_convblock_param_count(shape)
     assert P == cfg["theta"].size
-    rows = osplit.share_sizes(len(idx), n_workers) if rows is None else rows
+    rows = lib_share_sizes(synk, len(idx), n_workers) if rows is None else rows   # the library's split rule
     xdt = torch.bfloat16 if bf16 else torch.float32
     x = [torch.zeros((n, cfg["data"].shape[1]), dtype=xdt, device="cuda") for n in rows]
     y = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in rows]
@@ -162,20 +162,33 @@ def test_mid_size_block_spans_many_tiles(synk, bf16):
     check(cfg, idx, 3, 2, "mean", bf16, g, l)
 
 
-def test_full_size_config6_sampled_against_oracle(synk):
-    # the bench's launch configuration; the oracle computes two of the eight workers
+def test_full_size_config6_every_worker_against_oracle(synk):
+    # the bench's launch configuration; the oracle computes all eight workers (about 2 s each)
     cfg = workloads.config6()
     bf16 = cfg["compute"] == "bf16"
     g, l = run_gpu(synk, cfg, cfg["idx"], cfg["n_workers"], cfg["n_slices"], "mean", bf16, eps=cfg["eps"])
     bounds = osplit.share_bounds(len(cfg["idx"]), cfg["n_workers"])
-    for w in (0, 5):
+    worst_mirror, worst_f64 = 0.0, {}
+    for w in range(cfg["n_workers"]):
         a, b = bounds[w]
         lr, gr = oconv.function(cfg["theta"], cfg["shape"], ogather.gather_rows(cfg["data"], cfg["idx"][a:b]),
                                 ogather.gather_rows(cfg["labels"], cfg["idx"][a:b]), eps=cfg["eps"],
                                 bf16_points=bf16)
         for (name, gg), (_, r) in zip(tensors(g[w], cfg["shape"]), tensors(gr, cfg["shape"])):
             assert rel_err(gg, r) < TOL_BF16, (w, name, rel_err(gg, r))
+            worst_mirror = max(worst_mirror, rel_err(gg, r))
         assert abs(l[w] - lr) < TOL_BF16 * max(1.0, abs(lr))
+        # second distance: against the all-float64 block (no rounding anywhere).  The oracle's own bf16 mode sits
+        # 4-5 % from it on the convolution weights at this shape (relu decisions of near-zero normalised values
+        # change; bounded on the CPU in tests/test_oracle_convblock.py) and below 2e-3 on the other tensors.
+        _, g64 = oconv.function(cfg["theta"], cfg["shape"], ogather.gather_rows(cfg["data"], cfg["idx"][a:b]),
+                                ogather.gather_rows(cfg["labels"], cfg["idx"][a:b]), eps=cfg["eps"])
+        for (name, gg), (_, r) in zip(tensors(g[w], cfg["shape"]), tensors(g64, cfg["shape"])):
+            e = rel_err(gg, r)
+            worst_f64[name] = max(worst_f64.get(name, 0.0), e)
+            assert e < (1e-1 if name == "Wc" else 1e-2) + TOL_BF16, (w, name, e)
+    print("config 6: worst per-tensor error against the oracle rounded at the bf16 points %.2e; against the "
+          "float64 oracle %s" % (worst_mirror, ", ".join("%s %.2e" % kv for kv in worst_f64.items())))
     for w in range(cfg["n_workers"]):
         assert np.isfinite(g[w]).all()
         assert abs(g[w][-cfg["shape"][4]:].sum()) < 1e-5      # softmax: the last bias gradient sums to zero

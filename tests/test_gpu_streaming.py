@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import workloads
-from helpers import TOL_F32, rel_err
+from helpers import TOL_F32, lib_share_bounds, lib_share_sizes, rel_err
 from oracle import collectives as ocoll, evalops, gather as ogather, reduce as oreduce, split as osplit, update as oupdate
 
 pytestmark = pytest.mark.gpu
@@ -23,7 +23,10 @@ def dev(a):
 
 
 def share_sizes(n, parts):
-    return osplit.share_sizes(n, parts)
+    """Buffer sizes of the HIP leg: the library's own split rule.  The oracle's split is used on
+    the checker side only (gather_shares and the reference bounds)."""
+    from paper_1710_04162_amd import binding
+    return lib_share_sizes(binding, n, parts)
 
 
 # ------------------------------------------------------------------ gather
@@ -483,9 +486,10 @@ def test_all_gather_is_bit_exact(synk, lens):
 
 
 def test_all_gather_in_place_segments_and_scatter_roundtrip(synk):
-    # each worker's share is the matching segment of its own destination (Sec. 6: scatter by first dimension)
+    # each worker's share is the matching segment of its own destination (Sec. 4.2: scatter by first dimension)
     whole = np.random.default_rng(72).standard_normal(4101).astype(np.float32)
-    bounds = osplit.share_bounds(4101, 4)
+    bounds = lib_share_bounds(synk, 4101, 4)
+    assert bounds == osplit.share_bounds(4101, 4)
     dsts = [torch.zeros(4101, device="cuda") for _ in range(4)]
     srcs = []
     for w, (a, b) in enumerate(bounds):
@@ -622,7 +626,7 @@ def test_config3_full_size_other_update_rules(synk, rule):
     G = oreduce.reduce_buffers(list(c["grads"]), "mean")
     rp, q1, q2 = oupdate.apply_rule(rule, c["p"], r1, r2, G, dict(h, t=7))
     gp, g1, g2 = p.cpu().numpy(), s1.cpu().numpy(), s2.cpu().numpy()
-    for t in range(0, 161, 8):                                # every 8th tensor, per tensor
+    for t in range(161):                                      # every tensor, per tensor
         a, b = int(c["offsets"][t]), int(c["offsets"][t + 1])
         assert rel_err(gp[a:b], rp[a:b]) < TOL_F32 and rel_err(g1[a:b], q1[a:b]) < TOL_F32, (rule, t)
         if rule == "adam":
@@ -636,14 +640,15 @@ def test_config3_full_size_collectives(synk):
     synk.synk_all_reduce(bufs, "mean")
     ref = oreduce.reduce_buffers(list(c["grads"]), "mean")
     got = bufs[5].cpu().numpy()
-    for t in range(0, 161, 8):
+    for t in range(161):                                      # every tensor; the other copies must equal this one
         a, b = int(c["offsets"][t]), int(c["offsets"][t + 1])
         assert rel_err(got[a:b], ref[a:b]) < TOL_F32, t
     assert all(torch.equal(b, bufs[0]) for b in bufs[1:])
     src = dev(c["p"])
     synk.synk_broadcast(src, bufs)
     assert all(torch.equal(b, src) for b in bufs)
-    bounds = osplit.share_bounds(P, n)                         # shares of 3,194,629: not a multiple of 4
+    bounds = lib_share_bounds(synk, P, n)                      # shares of 3,194,629: not a multiple of 4
+    assert bounds == osplit.share_bounds(P, n)
     synk.synk_all_gather([dev(c["v"][a:b] + np.float32(w)) for w, (a, b) in enumerate(bounds)], bufs)
     want = np.concatenate([c["v"][a:b] + np.float32(w) for w, (a, b) in enumerate(bounds)])
     assert np.array_equal(bufs[3].cpu().numpy(), want) and all(torch.equal(b, bufs[0]) for b in bufs[1:])

@@ -159,3 +159,108 @@ def test_bf16_points_mode_stays_near_float64():
     assert abs(l0 - l1) < 2e-2
     assert np.linalg.norm(g1 - g0) < 1e-1 * np.linalg.norm(g0)
     assert np.abs(g1 - g0).max() > 0.0
+
+
+# ------------------------------------------------- the bf16 mode, pinned by autograd on the CPU
+def _bf(t):
+    """float64 tensor -> single precision -> bfloat16 (torch's casts, nearest-even) -> float64."""
+    return t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+
+class _RoundOperand(torch.autograd.Function):
+    """A contraction operand stored in bfloat16: the forward value is rounded, the gradient with
+    respect to the unrounded value is passed through unchanged."""
+
+    @staticmethod
+    def forward(ctx, x):
+        return _bf(x)
+
+    @staticmethod
+    def backward(ctx, g):
+        return g
+
+
+class _RoundStoredZ(torch.autograd.Function):
+    """The convolution's output as a bf16 pipeline stores it.  Forward: everything after the
+    convolution sees the rounded z.  Backward: the gradient arriving here IS dz, the operand of the
+    weight-gradient contraction, so it is rounded on its way in.  `fwd` / `bwd` switch the two
+    roundings so that a test can misplace one."""
+
+    @staticmethod
+    def forward(ctx, z, fwd, bwd):
+        ctx.bwd = bwd
+        return _bf(z) if fwd else z.clone()
+
+    @staticmethod
+    def backward(ctx, g):
+        return (_bf(g) if ctx.bwd else g), None, None
+
+
+def _autograd_bf16_twin(theta, shape, X, y, eps, round_x=True, round_w=True, round_z=True, round_dz=True):
+    H, W, cin, cout, classes = shape
+    t = torch.from_numpy(theta.copy()).requires_grad_(True)
+    at = 0
+    wc = t[at:at + 9 * cin * cout].reshape(3, 3, cin, cout).permute(3, 2, 0, 1)
+    at += 9 * cin * cout
+    gamma = t[at:at + cout]; at += cout
+    beta = t[at:at + cout]; at += cout
+    wf = t[at:at + cout * classes].reshape(cout, classes); at += cout * classes
+    bf = t[at:]
+    xt = torch.from_numpy(X).permute(0, 3, 1, 2)
+    if round_x:
+        xt = _bf(xt)
+    if round_w:
+        wc = _RoundOperand.apply(wc)
+    z = torch.nn.functional.conv2d(xt, wc, padding=1)
+    z = _RoundStoredZ.apply(z, round_z, round_dz)
+    a = torch.relu(torch.nn.functional.batch_norm(z, None, None, gamma, beta, training=True, eps=eps))
+    logits = a.mean(dim=(2, 3)) @ wf + bf
+    lt = torch.nn.functional.cross_entropy(logits, torch.from_numpy(y))
+    lt.backward()
+    return lt.item(), t.grad.numpy()
+
+
+@pytest.mark.parametrize("shape,n", [((4, 5, 3, 6, 7), 4), ((6, 3, 8, 8, 10), 2), ((3, 3, 2, 4, 3), 5)])
+def test_bf16_points_mode_matches_autograd_with_rounded_operands(shape, n):
+    """bf16 mode of the block = the float64 block with X, Wc rounded where they enter the forward
+    contraction, z rounded as stored (statistics, normalisation and all later steps see the rounded
+    z) and dz rounded where it enters the weight-gradient contraction; restated with torch's
+    convolution, batch norm, cross-entropy, autograd and bfloat16 casts."""
+    theta, X, y = _tiny(shape, n, 21)
+    loss, grad = convblock.function(theta, shape, X, y, eps=1e-5, bf16_points=True)
+    tl, tg = _autograd_bf16_twin(theta, shape, X, y, 1e-5)
+    assert abs(loss - tl) < 1e-12
+    np.testing.assert_allclose(grad, tg, atol=1e-10, rtol=1e-9)
+
+
+@pytest.mark.parametrize("drop", ["round_x", "round_w", "round_z", "round_dz"])
+def test_a_misplaced_rounding_point_of_the_block_is_detected(drop):
+    shape, n = (4, 5, 3, 6, 7), 4
+    theta, X, y = _tiny(shape, n, 21)
+    loss, grad = convblock.function(theta, shape, X, y, eps=1e-5, bf16_points=True)
+    tl, tg = _autograd_bf16_twin(theta, shape, X, y, 1e-5, **{drop: False})
+    assert abs(loss - tl) + np.abs(grad - tg).max() > 1e-6
+
+
+def test_cost_of_storing_z_in_bf16_against_float64():
+    """What the bf16 mode costs against the all-float64 block, per tensor (max-norm, relative to the
+    tensor's largest entry), and how much of that is the rounding of the stored z.  The distance is
+    dominated by rounding X and Wc (relu decisions of near-zero normalised values change, and the
+    weight gradient of a normalised layer is what is left after its mean terms cancel); storing z in
+    bf16 as well does not add to it.  Bounded here so that the figures in the design notes stay true."""
+    shape = (14, 14, 64, 64, 10)
+    theta, X, y = _tiny(shape, 8, 22)
+    l0, g0 = convblock.function(theta, shape, X, y)
+    l1, g1 = convblock.function(theta, shape, X, y, bf16_points=True)
+    _, g_noz = _autograd_bf16_twin(theta, shape, X, y, 1e-5, round_z=False)     # operands only, z kept exact
+    names = ["Wc", "gamma", "beta", "Wf", "bf"]
+    band = dict(Wc=1e-1, gamma=1e-2, beta=1e-2, Wf=1e-2, bf=1e-3)
+    bounds = np.cumsum([0, 9 * 64 * 64, 64, 64, 64 * 10, 10])
+    err = lambda a, b: float(np.abs(a - b).max() / np.abs(b).max())
+    for k, name in enumerate(names):
+        a, b = bounds[k], bounds[k + 1]
+        with_z, without_z = err(g1[a:b], g0[a:b]), err(g_noz[a:b], g0[a:b])
+        print("%-5s bf16 mode vs float64 %.2e; operands only (z exact) %.2e" % (name, with_z, without_z))
+        assert with_z < band[name] and without_z < band[name]
+        assert with_z < 1.5 * without_z + 1e-3          # the stored-z rounding adds nothing material
+    assert abs(l1 - l0) < 1e-3 * abs(l0)

@@ -222,6 +222,108 @@ def test_bf16_points_mode_stays_near_float64():
     assert np.abs(g1 - g0).max() > 0      # the mode does something
 
 
+def test_scalar_bf16_rounding_matches_torch_cast():
+    rng = np.random.default_rng(31)
+    a = np.concatenate([rng.standard_normal(3000) * 10.0 ** rng.uniform(-8, 8, 3000),
+                        1.0 + np.arange(1, 512, 2) / 256.0,        # exact ties between bf16 neighbours
+                        [0.0, -0.0, 1.0, -1.0, 255.0 / 256.0, 3.3895313892515355e38]])
+    want = torch.from_numpy(a).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    got = np.array([brute.bf16_rne(v) for v in a])
+    assert np.array_equal(got, want)
+
+
+def _tiny_mlp(dims, rows, seed):
+    rng = np.random.default_rng(seed)
+    theta = rng.standard_normal(mlp.param_count(dims)) * 0.7     # biases non-zero on purpose
+    X = rng.standard_normal((rows, dims[0]))
+    y = rng.integers(0, dims[-1], rows)
+    return theta, X, y
+
+
+@pytest.mark.parametrize("dims,rows", [([5, 4, 3], 6), ([6, 5, 4, 3], 5), ([4, 3], 7), ([3, 4, 4, 4, 2], 4)])
+def test_bf16_points_mode_matches_scalar_loop_twin(dims, rows):
+    """The rounding points of the bf16 mode (input rows, every W_l, every hidden activation as fed
+    forward, every dZ_l before all three of its uses), restated with scalar loops and an
+    independent scalar rounding routine."""
+    theta, X, y = _tiny_mlp(dims, rows, sum(dims))
+    loss, grad = mlp.function(theta, dims, X, y, bf16_points=True)
+    tl, tg = brute.mlp_loss_grad_bf16_points(theta, dims, X.tolist(), y)
+    assert abs(loss - tl) < 1e-12
+    assert np.abs(grad - np.array(tg)).max() < 1e-12
+    # with no rounding point active the twin is the float64 function
+    l0, g0 = mlp.function(theta, dims, X, y)
+    ul, ug = brute.mlp_loss_grad_bf16_points(theta, dims, X.tolist(), y, points=())
+    assert abs(l0 - ul) < 1e-12 and np.abs(g0 - np.array(ug)).max() < 1e-12
+
+
+@pytest.mark.parametrize("points", [
+    ("x", "w", "h"),                    # dZ_l not rounded
+    ("x", "w", "dz"),                   # hidden activations not rounded
+    ("x", "h", "dz"),                   # weights not rounded
+    ("w", "h", "dz"),                   # inputs not rounded
+    ("x", "w", "h", "dz", "b"),         # biases rounded as well
+    ("x", "w", "h", "dz", "late_dz"),   # dZ_l rounded only on its way to dZ_{l-1}, not for dW_l / db_l
+])
+def test_a_misplaced_rounding_point_is_detected(points):
+    """Negative cases: a copy of the twin with one rounding point dropped, added or moved must
+    NOT agree with the oracle's bf16 mode (so the agreement above pins every point)."""
+    dims, rows = [6, 5, 4, 3], 5
+    theta, X, y = _tiny_mlp(dims, rows, sum(dims))
+    loss, grad = mlp.function(theta, dims, X, y, bf16_points=True)
+    tl, tg = brute.mlp_loss_grad_bf16_points(theta, dims, X.tolist(), y, points=points)
+    assert abs(loss - tl) + np.abs(grad - np.array(tg)).max() > 1e-5
+
+
+def test_bf16_tie_threshold_covers_single_precision_accumulation_noise():
+    """Where the GPU tests' threshold for "a hidden pre-activation that is zero up to rounding"
+    comes from, using the oracle only.  The kernels accumulate in single precision (the paper's
+    precision, Sec. 6), the oracle in double.  A first-layer pre-activation that differs in its last
+    single-precision bits can round to the neighbouring bfloat16 activation, which moves every
+    second-layer pre-activation that unit feeds by |w| * one bf16 step of h.  Measured here at the
+    wide configuration's layer widths: the largest such move is a few 1e-4, so 1e-3 covers it with
+    room, and the fraction of pre-activations within 1e-3 of zero stays ~1e-3."""
+    import workloads
+    cfg = workloads.config2(n_data=256, batch=128)
+    dims = cfg["dims"]
+    idx = cfg["idx"][:64]
+    X, y = gather.gather_rows(cfg["data"], idx), gather.gather_rows(cfg["labels"], idx)
+    tr = []
+    mlp.function(cfg["theta"], dims, X, y, bf16_points=True, trace=tr)
+    (W1, b1), (W2, b2), _ = mlp.unpack(cfg["theta"].astype(np.float64), dims)
+    q = lambda a: gather.round_to_bf16(a).astype(np.float64)
+    # the oracle's own first layer, re-accumulated in single precision
+    z1_single = (q(X).astype(np.float32) @ q(W1).astype(np.float32) + b1.astype(np.float32)).astype(np.float64)
+    assert np.abs(z1_single - tr[0]).max() < 1e-4                      # same numbers up to accumulation rounding
+    h1_double, h1_single = q(np.maximum(tr[0], 0.0)), q(np.maximum(z1_single, 0.0))
+    moved = h1_double != h1_single
+    assert 0 < moved.sum() < 0.01 * moved.size                         # a few activations take the other neighbour
+    dz2 = np.abs((h1_single - h1_double) @ q(W2))
+    assert 1e-5 < dz2.max() < 1e-3                                     # the threshold used on the GPU side
+    near = (np.abs(tr[1]) <= 1e-3).mean()
+    assert near < 5e-3
+
+
+def test_bf16_points_mode_distance_to_float64_at_the_wide_configuration():
+    """The band the GPU tests use for "bf16 result against the all-float64 oracle" (per tensor and
+    whole gradient), measured for the oracle alone at the wide configuration's full model and
+    per-worker row count."""
+    import sys, os
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    from helpers import BF16_VS_F64_FRO, BF16_VS_F64_MAX, mlp_tensors, rel_err
+    import workloads
+    cfg = workloads.config2(n_data=2048)
+    dims, idx = cfg["dims"], cfg["idx"]
+    worst, fro = 0.0, 0.0
+    for (a, b) in split.share_bounds(len(idx), cfg["n_workers"])[:3]:
+        X, y = gather.gather_rows(cfg["data"], idx[a:b]), gather.gather_rows(cfg["labels"], idx[a:b])
+        _, g0 = mlp.function(cfg["theta"], dims, X, y)
+        _, g1 = mlp.function(cfg["theta"], dims, X, y, bf16_points=True)
+        fro = max(fro, float(np.linalg.norm(g1 - g0) / np.linalg.norm(g0)))
+        for (_, t1), (_, t0) in zip(mlp_tensors(g1, dims), mlp_tensors(g0, dims)):
+            worst = max(worst, rel_err(t1, t0))
+    assert 1e-3 < worst < BF16_VS_F64_MAX and 1e-3 < fro < BF16_VS_F64_FRO, (worst, fro)
+
+
 def test_relu_tie_flag_changes_only_near_zero_units():
     dims = [3, 2, 2]
     theta = np.array([1, 1, -1, 1, 0, 0.5,   0, 0,   1, -1, 2, 1,   0, 0], dtype=np.float64)
@@ -327,7 +429,7 @@ def test_collectives_against_library_routines_and_invariants():
     ragged = [rng.standard_normal(k) for k in (3, 0, 7, 1)]
     g = collectives.all_gather(ragged)
     assert len(g) == 4 and all(np.array_equal(x, np.concatenate(ragged)) for x in g)
-    # gathering a scattered array returns the array (Sec. 6: scatter by first dimension)
+    # gathering a scattered array returns the array (Sec. 4.2: scatter by first dimension)
     whole = rng.standard_normal(23)
     parts = np.array_split(whole, 4)
     assert np.array_equal(collectives.all_gather(parts)[3], whole)
