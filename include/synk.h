@@ -40,7 +40,8 @@
  *   read during the call and may be freed when it returns.
  * - The library allocates nothing.  Scratch memory is a caller-provided
  *   workspace (ws, ws_bytes), sized by the matching *_workspace_bytes call,
- *   256-byte aligned; its contents are undefined between calls.
+ *   256-byte aligned; its contents are undefined between calls.  (One entry
+ *   point, synk_sliced_eval_static, uses a fixed array of its own instead.)
  * - Kernels are launched asynchronously on `stream` (a hipStream_t passed as
  *   void*; NULL = the default stream).  No call synchronises except
  *   synk_poll_error.  Calls on one stream execute in call order.
@@ -355,6 +356,33 @@ int synk_sliced_eval(const float* logits, const int32_t* labels, int64_t rows, i
                      float* ce_sum, int32_t* class_counts, float* max_logit, float* min_logit,
                      int32_t* n_correct, int32_t* argmax,
                      void* ws, size_t ws_bytes, void* stream);
+
+/* synk_sliced_eval for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid it): the same
+ * computation, kernels and results, with the per-(slice, chunk) partial results
+ * kept in a fixed array inside the library's device image instead of a
+ * caller's workspace.  The call allocates and frees nothing and calls no
+ * allocating routine; the caller still passes inputs and outputs.
+ *   Limit: synk_sliced_eval_workspace_bytes(rows, classes, n_slices) must not
+ *   exceed SYNK_SLICED_EVAL_STATIC_BYTES (1 MiB: e.g. 65,536 rows in 64 slices
+ *   takes 128 KiB; about 520,000 rows fit); beyond it -> ERR_WORKSPACE and
+ *   nothing is launched.  Each GPU the library runs on holds its own copy of
+ *   the array until the process ends.
+ *   Sharing: every call on a GPU uses that GPU's one array, which keeps the last
+ *   call's contents (nothing needs clearing: stage 1 rewrites every entry
+ *   stage 2 reads).  Calls that overlap in time on one GPU (different streams
+ *   or host threads) race on it: serialise them, or use synk_sliced_eval with
+ *   separate workspaces.
+ *   synk_static_scratch_init resolves the array's address for the CURRENT device
+ *   (once per device; the entry point does the same on its first call on a
+ *   device).  Call it before capturing the entry point into a graph.
+ * Other arguments, outputs and errors as synk_sliced_eval. */
+#define SYNK_SLICED_EVAL_STATIC_BYTES (1u << 20)
+int synk_static_scratch_init(void);
+int synk_sliced_eval_static(const float* logits, const int32_t* labels, int64_t rows, int64_t classes,
+                            int n_slices,
+                            float* ce_sum, int32_t* class_counts, float* max_logit, float* min_logit,
+                            int32_t* n_correct, int32_t* argmax, void* stream);
 
 /* ------------------------------------------------------------------ reduce
  * Reduce or gather N equally long worker results (Sec. 3.2 step 3; Sec. 3.3

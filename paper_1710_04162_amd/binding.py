@@ -18,7 +18,8 @@ __all__ = [
     "synk_version", "synk_status_string", "synk_split", "synk_gather_workspace_bytes",
     "synk_gather_rows", "synk_build_norm_lut", "synk_poll_error", "synk_mlp_param_count",
     "synk_sliced_grad_workspace_bytes", "synk_sliced_grad", "synk_cast_bf16",
-    "synk_sliced_eval_workspace_bytes", "synk_sliced_eval", "synk_reduce_buffers",
+    "synk_sliced_eval_workspace_bytes", "synk_sliced_eval", "synk_sliced_eval_static",
+    "synk_static_scratch_init", "synk_reduce_buffers",
     "synk_sgd_update", "synk_reduce_sgd_update", "synk_reduce_update",
     "synk_broadcast", "synk_all_reduce", "synk_all_gather",
     "synk_gather_slice", "synk_scatter_rows", "synk_gather_resident", "synk_profile_next_launch",
@@ -100,6 +101,10 @@ lib.synk_cast_bf16.argtypes = [_vp, _vp, _i64, _vp]
 lib.synk_sliced_eval_workspace_bytes.argtypes = [_i64, _i64, _int, ctypes.POINTER(_sz)]
 lib.synk_sliced_eval.argtypes = [_vp, _vp, _i64, _i64, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
                                  _vp]
+lib.synk_sliced_eval_static.argtypes = [_vp, _vp, _i64, _i64, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.synk_sliced_eval_static.restype = _int
+lib.synk_static_scratch_init.argtypes = []
+lib.synk_static_scratch_init.restype = _int
 lib.synk_reduce_buffers.argtypes = [_pp, _int, _i64, _int, _int, _pf32, _pi64, _vp, _vp]
 lib.synk_sgd_update.argtypes = [_vp, _vp, _vp, _i64, _f32, _f32, _f32, _vp, _vp]
 lib.synk_reduce_sgd_update.argtypes = [_pp, _int, _i64, _pf32, _vp, _vp, _f32, _f32, _f32, _vp, _vp,
@@ -313,6 +318,20 @@ def synk_sliced_eval(logits, labels, n_slices, ce_sum, class_counts, max_logit, 
     return _run(lib.synk_sliced_eval, args,
                 (logits, labels, ce_sum, class_counts, max_logit, min_logit, n_correct, argmax, ws),
                 "synk_sliced_eval", _prepare)
+
+
+def synk_static_scratch_init():
+    _check(lib.synk_static_scratch_init(), "synk_static_scratch_init")
+
+
+def synk_sliced_eval_static(logits, labels, n_slices, ce_sum, class_counts, max_logit, min_logit, n_correct,
+                            argmax, stream=None, _prepare=False):
+    rows, classes = logits.shape
+    args = (_ptr(logits), _ptr(labels), rows, classes, n_slices, _ptr(ce_sum), _ptr(class_counts),
+            _ptr(max_logit), _ptr(min_logit), _ptr(n_correct), _ptr(argmax), _stream(stream))
+    return _run(lib.synk_sliced_eval_static, args,
+                (logits, labels, ce_sum, class_counts, max_logit, min_logit, n_correct, argmax),
+                "synk_sliced_eval_static", _prepare)
 
 
 def synk_reduce_buffers(bufs, op, out, weights=None, stream=None, _prepare=False):

@@ -11,6 +11,8 @@
 // counts the arg-max classes (integer atomics: exact in any order).
 #include <math.h>
 
+#include <mutex>
+
 #include "common.h"
 
 namespace synk {
@@ -490,11 +492,10 @@ extern "C" int synk_sliced_eval_workspace_bytes(int64_t rows, int64_t classes, i
   return SYNK_OK;
 }
 
-extern "C" int synk_sliced_eval(const float* logits, const int32_t* labels, int64_t rows,
-                                int64_t classes, int n_slices, float* ce_sum,
-                                int32_t* class_counts, float* max_logit, float* min_logit,
-                                int32_t* n_correct, int32_t* argmax, void* ws, size_t ws_bytes,
-                                void* stream) {
+// Argument checks common to both entry points (no HIP call).
+static int eval_args_check(const float* logits, const int32_t* labels, int64_t rows, int64_t classes,
+                           int n_slices, float* ce_sum, int32_t* class_counts, float* max_logit,
+                           float* min_logit, int32_t* n_correct, int32_t* argmax) {
   if (!logits || !labels || !ce_sum || !class_counts || !max_logit || !min_logit || !n_correct ||
       !argmax)
     return SYNK_ERR_NULL;
@@ -503,10 +504,14 @@ extern "C" int synk_sliced_eval(const float* logits, const int32_t* labels, int6
       !aligned_to(class_counts, 4) || !aligned_to(ce_sum, 4) || !aligned_to(max_logit, 4) ||
       !aligned_to(min_logit, 4) || !aligned_to(n_correct, 4))
     return SYNK_ERR_ALIGN;
-  EvalWs w;
-  const size_t need = eval_ws_layout(rows, classes, n_slices, ws, &w);
-  if (!ws || !aligned_to(ws, 256) || ws_bytes < need) return SYNK_ERR_WORKSPACE;
-  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  return SYNK_OK;
+}
+
+// The two launches of a call, with the partial results in `w`.
+static int eval_launch(const float* logits, const int32_t* labels, int64_t rows, int64_t classes,
+                       int n_slices, float* ce_sum, int32_t* class_counts, float* max_logit,
+                       float* min_logit, int32_t* n_correct, int32_t* argmax, const EvalWs& w,
+                       hipStream_t s) {
   constexpr int kUnitsLo = (kRegularUPL - 1) * kRegularG, kUnitsHi = kRegularUPL * kRegularG;   // vectors a row
   const bool regular = classes % 4 == 0 && aligned_to(logits, 16) && rows % ((int64_t)n_slices * kRegularRows) == 0 &&
                        classes / 4 > kUnitsLo && classes / 4 <= kUnitsHi;
@@ -531,4 +536,72 @@ extern "C" int synk_sliced_eval(const float* logits, const int32_t* labels, int6
                      (int)classes, argmax, ce_sum, class_counts, max_logit, min_logit, n_correct);
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;
+}
+
+extern "C" int synk_sliced_eval(const float* logits, const int32_t* labels, int64_t rows,
+                                int64_t classes, int n_slices, float* ce_sum,
+                                int32_t* class_counts, float* max_logit, float* min_logit,
+                                int32_t* n_correct, int32_t* argmax, void* ws, size_t ws_bytes,
+                                void* stream) {
+  if (int rc = eval_args_check(logits, labels, rows, classes, n_slices, ce_sum, class_counts, max_logit,
+                               min_logit, n_correct, argmax))
+    return rc;
+  EvalWs w;
+  const size_t need = eval_ws_layout(rows, classes, n_slices, ws, &w);
+  if (!ws || !aligned_to(ws, 256) || ws_bytes < need) return SYNK_ERR_WORKSPACE;
+  return eval_launch(logits, labels, rows, classes, n_slices, ce_sum, class_counts, max_logit, min_logit,
+                     n_correct, argmax, w, reinterpret_cast<hipStream_t>(stream));
+}
+
+// ------------------------------------------------ the entry point that allocates nothing
+// Partial results live in a fixed array in the library's own device image instead
+// of a caller's workspace.  Every GPU the library runs on holds its own copy at
+// its own address; in host code the array's name is only a handle for
+// hipGetSymbolAddress, never an address to hand to a kernel.
+static __device__ __align__(256) unsigned char scratch[SYNK_SLICED_EVAL_STATIC_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];   // per device: where that device's copy of `scratch` lives
+
+// The current device's copy of `scratch` (resolved once per device, with that device current).
+int scratch_for_current_device(void** out) {
+  int dev = -1;
+  SYNK_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return SYNK_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    SYNK_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return SYNK_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SYNK_OK;
+}
+}  // namespace
+
+extern "C" int synk_static_scratch_init(void) {
+  void* ptr;
+  return scratch_for_current_device(&ptr);
+}
+
+extern "C" int synk_sliced_eval_static(const float* logits, const int32_t* labels, int64_t rows,
+                                       int64_t classes, int n_slices, float* ce_sum,
+                                       int32_t* class_counts, float* max_logit, float* min_logit,
+                                       int32_t* n_correct, int32_t* argmax, void* stream) {
+  if (int rc = eval_args_check(logits, labels, rows, classes, n_slices, ce_sum, class_counts, max_logit,
+                               min_logit, n_correct, argmax))
+    return rc;
+  if (eval_ws_layout(rows, classes, n_slices, nullptr, nullptr) > (size_t)SYNK_SLICED_EVAL_STATIC_BYTES)
+    return SYNK_ERR_WORKSPACE;   // more (slice, chunk) partial results than the fixed array holds
+  void* base = nullptr;
+  if (int rc = scratch_for_current_device(&base)) return rc;
+  EvalWs w;
+  eval_ws_layout(rows, classes, n_slices, base, &w);
+  // Nothing in the array needs clearing: stage 1 writes every (slice, chunk) entry that stage 2
+  // reads, whatever an earlier call left there.
+  return eval_launch(logits, labels, rows, classes, n_slices, ce_sum, class_counts, max_logit, min_logit,
+                     n_correct, argmax, w, reinterpret_cast<hipStream_t>(stream));
 }

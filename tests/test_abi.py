@@ -219,6 +219,13 @@ def test_sliced_eval_argument_checks_and_workspace():
     assert f(FAKE, FAKE, 8, 4, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, None) == -6
     assert f(FAKE, FAKE, 8, 4, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 8, None) == -6
     assert f(FAKE + 1, FAKE, 8, 4, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 20, None) == -5
+    # the variant with the fixed array: same checks, and a size limit instead of a workspace
+    g = lib.synk_sliced_eval_static
+    assert g(None, FAKE, 8, 4, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == -1
+    assert g(FAKE, FAKE, 0, 4, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == -2
+    assert g(FAKE + 1, FAKE, 8, 4, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == -5
+    assert synk.synk_sliced_eval_workspace_bytes(8 * 70000, 4, 1) > (1 << 20)
+    assert g(FAKE, FAKE, 8 * 70000, 4, 1, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == -6
 
 
 def test_binding_refuses_host_tensors():
