@@ -359,6 +359,17 @@ struct GemmArgs {
   float* task_loss;
 };
 
+}  // namespace synk
+#include "gemm_dma.h"
+namespace synk {
+
+// The whole-tile bf16 core as a kernel of its own (forward and dX products).
+template <int MODE, int BM, int BN, int NS>
+__global__ __launch_bounds__(gdma::kThreads) void mlp_gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[gdma::lds_bytes<BM, BN, NS>()];
+  gdma::tile<MODE, BM, BN, NS>(g, blockIdx.x, tiles_m, tiles_n, smem);
+}
+
 // Workgroups are dealt to the 8 XCDs round-robin by launch order.  Re-deal so
 // that each XCD (each L2) owns a contiguous run of tiles with the n-tile index
 // running fastest: tiles that differ only in their row range keep hitting the
@@ -961,7 +972,10 @@ struct GroupArgs {
   unsigned n_dwp, n_dx, n_dwl;          // workgroups of each grid (n_dwp and n_dx multiples of 8)
   unsigned dx_gx, dx_gy, dx_gz, dwl_gx, dwl_gy, dwl_gz;
   int tiles_m, tiles_n, n_workers;
+  int dx_whole;                         // dZ_{L-2} by the whole-tile core: dx_gx x dx_gy tiles of 64 x 64 over all rows
 };
+
+constexpr int kGroupDxStages = 4;   // LDS ring of the whole-tile dX core inside the group: 64 KB, what the dW walker takes
 
 template <typename T>
 __host__ __device__ constexpr int group_lds_words() {
@@ -969,6 +983,7 @@ __host__ __device__ constexpr int group_lds_words() {
   int m = dw_persistent_lds_words<T>();
   if (gemm_lds_words<T, MODE_DX, 64, 64, BKS>() > m) m = gemm_lds_words<T, MODE_DX, 64, 64, BKS>();
   if (gemm_lds_words<T, MODE_DW, 64, 64, BKS>() > m) m = gemm_lds_words<T, MODE_DW, 64, 64, BKS>();
+  if (sizeof(T) == 2 && gdma::lds_bytes<64, 64, kGroupDxStages>() / 4 > m) m = gdma::lds_bytes<64, 64, kGroupDxStages>() / 4;
   return m;
 }
 
@@ -983,8 +998,13 @@ __global__ __launch_bounds__(kGemmThreads, 4) void mlp_backward_group_kernel(Gro
   }
   b -= ga.n_dwp;
   if (b < ga.n_dx) {
-    if (b < ga.dx_gx * ga.dx_gy * ga.dx_gz)
+    if (sizeof(T) == 2 && ga.dx_whole) {
+      if (b < ga.dx_gx * ga.dx_gy)
+        gdma::tile<gdma::DX, 64, 64, kGroupDxStages>(ga.dx, b, (int)ga.dx_gy, (int)ga.dx_gx,
+                                                     reinterpret_cast<unsigned char*>(smem));
+    } else if (b < ga.dx_gx * ga.dx_gy * ga.dx_gz) {
       gemm_tile<T, MODE_DX, 64, 64, BKS, true, true>(ga.dx, b, ga.dx_gx, ga.dx_gy, ga.dx_gz, smem);
+    }
     return;
   }
   b -= ga.n_dx;
@@ -1362,11 +1382,47 @@ static inline unsigned dw_persistent_blocks(const GemmArgs& g, int64_t m_max, in
   return (unsigned)blocks;
 }
 
+// The whole-tile bf16 core applies (forward and dX): every worker holds whole tiles of rows, the
+// contraction is whole 64-deep tiles, everything takes 16-byte accesses, bf16 in and out.
+template <typename T, int MODE>
+static bool gemm_dma_ok(const GemmArgs& g, int n_workers, int bm, int bn) {
+  if (sizeof(T) != 2 || MODE == MODE_DW) return false;
+  if (gemm_alignment(g) != 2 || !g.c_vec) return false;
+  if (MODE == MODE_FWD && g.out_f32) return false;
+  if (g.k_fixed < 64 || g.k_fixed % 64 != 0 || g.n % bn != 0) return false;
+  if (g.lda % 8 != 0 || g.ldb % 8 != 0 || g.ldc % 8 != 0 || (MODE == MODE_DX && g.ldmask % 8 != 0)) return false;
+  if (g.row_off[n_workers] > (1 << 30) / 64) return false;      // tile indexes stay small integers
+  for (int w = 0; w < n_workers; ++w) {
+    const int64_t r = g.row_off[w + 1] - g.row_off[w];
+    if (r % bm != 0) return false;
+    if (r > 0 && (!aligned_to(g.a[w], 16) || !aligned_to(g.c[w], 16))) return false;
+  }
+  return true;
+}
+
 template <typename T, int MODE>
 static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStream_t s) {
   constexpr int BK_BIG = GemmTiling<T>::BK_BIG, BK_SMALL = GemmTiling<T>::BK_SMALL;
   const int64_t big = big_tiles(g, m_max, n_workers);
   const int al = gemm_alignment(g);
+  if (MODE != MODE_DW) {
+    constexpr int GM = MODE == MODE_FWD ? gdma::FWD : gdma::DX;
+    const int64_t R = g.row_off[n_workers];
+    if (gemm_dma_ok<T, MODE>(g, n_workers, 128, 128) && (R / 128) * (g.n / 128) >= 2 * kNumCU) {
+      const int tm = (int)(R / 128), tn = (int)(g.n / 128);
+      SYNK_LAUNCH_TIMED((mlp_gemm_dma_kernel<GM, 128, 128, 3>), dim3((unsigned)(tm * tn)), dim3(gdma::kThreads), 0, s,
+                        g, tm, tn);
+      SYNK_LAUNCH_CHECK();
+      return SYNK_OK;
+    }
+    if (gemm_dma_ok<T, MODE>(g, n_workers, 64, 64)) {
+      const int tm = (int)(R / 64), tn = (int)(g.n / 64);
+      SYNK_LAUNCH_TIMED((mlp_gemm_dma_kernel<GM, 64, 64, 6>), dim3((unsigned)(tm * tn)), dim3(gdma::kThreads), 0, s,
+                        g, tm, tn);
+      SYNK_LAUNCH_CHECK();
+      return SYNK_OK;
+    }
+  }
 #define SYNK_GEMM(BM_, BN_, BK_)                                                                              \
   do {                                                                                                       \
     if (al == 2)                                                                                             \
@@ -1558,9 +1614,15 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
       ga.tiles_m = (int)(p.d[L - 2] / 128);
       ga.tiles_n = (int)(p.d[L - 1] / 128);
       ga.n_workers = n_workers;
+      ga.dx_whole = gemm_dma_ok<T, MODE_DX>(ga.dx, n_workers, 64, 64) ? 1 : 0;
       ga.dx_gx = (unsigned)((ga.dx.n + 63) / 64);
-      ga.dx_gy = (unsigned)((p.max_rows + 63) / 64);
-      ga.dx_gz = (unsigned)n_workers;
+      if (ga.dx_whole) {
+        ga.dx_gy = (unsigned)(p.R / 64);           // row tiles over all workers' packed rows
+        ga.dx_gz = 1u;
+      } else {
+        ga.dx_gy = (unsigned)((p.max_rows + 63) / 64);
+        ga.dx_gz = (unsigned)n_workers;
+      }
       ga.n_dx = (ga.dx_gx * ga.dx_gy * ga.dx_gz + 7u) / 8u * 8u;
       ga.dwl_gx = (unsigned)((ga.dwl.n + 63) / 64);
       ga.dwl_gy = (unsigned)((p.d[L - 1] + 63) / 64);
