@@ -100,15 +100,31 @@ int synk_version(void);
 const char* synk_status_string(int status);
 
 /* For callers that time one kernel: the next launch, on this host thread, of
- * a call's main kernel (the fused reduce+update kernels, the reduce and
- * collective kernels, the uint8 gather, stage 1 of synk_sliced_eval, the
- * forward convolution of synk_sliced_grad_conv) carries
- * the two events (hipEvent_t created with timing enabled, passed as void*):
- * start_event takes the dispatch's begin timestamp and stop_event its end
- * timestamp, so hipEventElapsedTime between them is the kernel's duration
- * without the gaps around it.  Other kernels leave the pair pending.  Both
- * NULL cancels a pending pair; exactly one NULL -> ERR_NULL. */
+ * the selected kernel carries the two events (hipEvent_t created with timing
+ * enabled, passed as void*): start_event takes the dispatch's begin timestamp
+ * and stop_event its end timestamp, so hipEventElapsedTime between them is the
+ * kernel's duration without the gaps around it.  Other launches leave the pair
+ * pending (also past the end of a call that never launches the selected
+ * kernel).  Both NULL cancels a pending pair; exactly one NULL -> ERR_NULL.
+ *
+ * SYNK_KERNEL_MAIN selects a call's main kernel: the gather kernel of the
+ * gather calls, the fused reduce+update kernels, the reduce and collective
+ * kernels, stage 1 of synk_sliced_eval, the forward convolution of
+ * synk_sliced_grad_conv, the first layer's forward product of
+ * synk_sliced_grad.  The other ids select kernels of synk_sliced_grad:
+ * the forward product of layer l (1-based), the last layer's kernel (fused
+ * head or softmax), the launch that holds dW_L, dW_{L-1} and dZ_{L-2} together
+ * (when the shapes allow that grouping), and the weight-gradient or
+ * input-gradient product of layer l when it is launched on its own.
+ * synk_profile_next_launch(a, b) = synk_profile_next_launch_of(SYNK_KERNEL_MAIN, a, b). */
+#define SYNK_KERNEL_MAIN 0
+#define SYNK_KERNEL_MLP_HEAD 1
+#define SYNK_KERNEL_MLP_BACKWARD_GROUP 2
+#define SYNK_KERNEL_MLP_FORWARD(l) (16 + (l))
+#define SYNK_KERNEL_MLP_DW(l) (32 + (l))
+#define SYNK_KERNEL_MLP_DX(l) (48 + (l))
 int synk_profile_next_launch(void* start_event, void* stop_event);
+int synk_profile_next_launch_of(int kernel, void* start_event, void* stop_event);
 
 /* Host-side helper: the split rule above.  Writes parts+1 offsets
  * (start[0] = 0, start[parts] = count) into `start` (host). */

@@ -23,6 +23,8 @@ __all__ = [
     "synk_sgd_update", "synk_reduce_sgd_update", "synk_reduce_update",
     "synk_broadcast", "synk_all_reduce", "synk_all_gather",
     "synk_gather_slice", "synk_scatter_rows", "synk_gather_resident", "synk_profile_next_launch",
+    "synk_profile_next_launch_of", "SYNK_KERNEL_MAIN", "SYNK_KERNEL_MLP_HEAD", "SYNK_KERNEL_MLP_BACKWARD_GROUP",
+    "SYNK_KERNEL_MLP_FORWARD", "SYNK_KERNEL_MLP_DW", "SYNK_KERNEL_MLP_DX",
     "synk_convblock_param_count", "synk_sliced_grad_conv_workspace_bytes", "synk_sliced_grad_conv",
 ]
 
@@ -83,6 +85,8 @@ for _n in ("synk_gather_slice", "synk_scatter_rows", "synk_gather_resident"):
     getattr(lib, _n).restype = _int
 lib.synk_profile_next_launch.argtypes = [_vp, _vp]
 lib.synk_profile_next_launch.restype = _int
+lib.synk_profile_next_launch_of.argtypes = [_int, _vp, _vp]
+lib.synk_profile_next_launch_of.restype = _int
 lib.synk_build_norm_lut.argtypes = [_pf32, _pf32, _int, _vp, _vp]
 lib.synk_poll_error.argtypes = [_vp, _vp]
 lib.synk_mlp_param_count.argtypes = [ctypes.POINTER(MlpDesc), _pi64]
@@ -443,9 +447,28 @@ def synk_gather_resident(shares, idx, dst, lut=None, channels=0, labels=None, ds
                 "synk_gather_resident", _prepare)
 
 
+SYNK_KERNEL_MAIN, SYNK_KERNEL_MLP_HEAD, SYNK_KERNEL_MLP_BACKWARD_GROUP = 0, 1, 2
+
+
+def SYNK_KERNEL_MLP_FORWARD(l):
+    return 16 + l
+
+
+def SYNK_KERNEL_MLP_DW(l):
+    return 32 + l
+
+
+def SYNK_KERNEL_MLP_DX(l):
+    return 48 + l
+
+
 def synk_profile_next_launch(start, stop):
     """start, stop: torch.cuda.Event(enable_timing=True) that have been recorded once (torch creates
     the underlying hipEvent_t at the first record), or None, None to cancel."""
+    synk_profile_next_launch_of(SYNK_KERNEL_MAIN, start, stop)
+
+
+def synk_profile_next_launch_of(kernel, start, stop):
     a = start.cuda_event if start is not None else None
     b = stop.cuda_event if stop is not None else None
-    _check(lib.synk_profile_next_launch(a, b), "synk_profile_next_launch")
+    _check(lib.synk_profile_next_launch_of(int(kernel), a, b), "synk_profile_next_launch_of")

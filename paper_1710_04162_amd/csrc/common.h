@@ -19,23 +19,27 @@
 
 namespace synk {
 
-// Events handed in by synk_profile_next_launch (consumed by the first launch
-// made through SYNK_LAUNCH_TIMED on this host thread).
-bool take_profile_events(hipEvent_t* start, hipEvent_t* stop);
+// Events handed in by synk_profile_next_launch[_of] (consumed by the first launch
+// made on this host thread through SYNK_LAUNCH_TIMED_AS with the kernel id they
+// were handed in for).
+bool take_profile_events(int kernel_id, hipEvent_t* start, hipEvent_t* stop);
 
 }  // namespace synk
 
 // Launch of a kernel that a caller may want timed on its own: with events
 // pending, they are attached to this very dispatch (start/stop timestamps of
 // the kernel, not of the gaps around it).
-#define SYNK_LAUNCH_TIMED(KERNEL, GRID, BLOCK, SHMEM, STREAM, ...)                                   \
+#define SYNK_LAUNCH_TIMED_AS(ID, KERNEL, GRID, BLOCK, SHMEM, STREAM, ...)                            \
   do {                                                                                               \
     hipEvent_t e0_, e1_;                                                                             \
-    if (synk::take_profile_events(&e0_, &e1_))                                                       \
+    if (synk::take_profile_events(ID, &e0_, &e1_))                                                   \
       hipExtLaunchKernelGGL(KERNEL, GRID, BLOCK, SHMEM, STREAM, e0_, e1_, 0, __VA_ARGS__);           \
     else                                                                                             \
       hipLaunchKernelGGL(KERNEL, GRID, BLOCK, SHMEM, STREAM, __VA_ARGS__);                           \
   } while (0)
+// a call's main kernel
+#define SYNK_LAUNCH_TIMED(KERNEL, GRID, BLOCK, SHMEM, STREAM, ...) \
+  SYNK_LAUNCH_TIMED_AS(SYNK_KERNEL_MAIN, KERNEL, GRID, BLOCK, SHMEM, STREAM, __VA_ARGS__)
 
 namespace synk {
 

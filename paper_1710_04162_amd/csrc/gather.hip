@@ -343,7 +343,7 @@ static int gather_impl(const void* data, int64_t n_rows, int64_t row_elems, int 
   const dim3 grid((unsigned)n_idx, chunks);
   if (mode == COPY) {
 #define SYNK_COPY(V, RES, RA)                                                                        \
-  hipLaunchKernelGGL((gather_copy_kernel<RES, V>), grid, gb, 0, s, reinterpret_cast<const V*>(data), \
+  SYNK_LAUNCH_TIMED((gather_copy_kernel<RES, V>), grid, gb, 0, s, reinterpret_cast<const V*>(data),  \
                      n_rows, row_units, idx, RA, n_idx, t, n_workers, labels, err_word, upb)
     if (res) {
       if (unit == 16) SYNK_COPY(u32x4, true, ResArg<true>{*res});
@@ -357,7 +357,7 @@ static int gather_impl(const void* data, int64_t n_rows, int64_t row_elems, int 
 #undef SYNK_COPY
   } else if (mode == TO_BF16) {
 #define SYNK_BF(VEC, RES, RA)                                                                            \
-  hipLaunchKernelGGL((gather_bf16_kernel<RES, VEC>), grid, gb, 0, s, reinterpret_cast<const float*>(data), \
+  SYNK_LAUNCH_TIMED((gather_bf16_kernel<RES, VEC>), grid, gb, 0, s, reinterpret_cast<const float*>(data),  \
                      n_rows, row_elems, idx, RA, n_idx, t, n_workers, labels, err_word, upb)
     if (res) {
       if (vec) SYNK_BF(true, true, ResArg<true>{*res});

@@ -958,6 +958,97 @@ __global__ __launch_bounds__(kGemmThreads, 4) void mlp_dw_persistent_kernel(Gemm
   dw_persistent_body<T>(g, tiles_m, tiles_n, n_workers, blockIdx.x, gridDim.x, smem);
 }
 
+// ------------------------------------------------------- narrow last layer dW
+// dW_L[w] = H_{L-1}[w]^T dZ_L[w] and db_L[w] for a last layer of at most 16 outputs: a 10-column
+// product leaves the matrix cores nothing to do and its rows (20 bytes) take no vector loads, so it is
+// plain multiply-adds.  A workgroup of 512 threads owns one worker and 128 of the K inputs: thread
+// (kk, rg) walks the rows rg, rg+4, ... of the worker for input kk, the row's dZ_L (padded to 16 floats)
+// read from LDS at one address for all threads; the four row groups are then added in a fixed order.
+// The workgroup after the last one turns the row losses into the workers' slice-aggregated losses.
+constexpr int kNarrowMaxC = 16, kNarrowKB = 128, kNarrowRows = 256;
+__host__ __device__ constexpr int dw_narrow_lds_words() { return kNarrowRows * 16 + 4 * 16 * kNarrowKB; }
+
+static inline unsigned dw_narrow_blocks(int64_t K, int n_workers) {
+  return (unsigned)(n_workers * ((K + kNarrowKB - 1) / kNarrowKB) + 1);
+}
+
+template <typename T>
+__device__ __forceinline__ void dw_narrow_body(const GemmArgs& g, unsigned b, int n_workers,
+                                               uint32_t* __restrict__ smem) {
+  const int K = (int)g.m_fixed, C = (int)g.n;
+  const int kb = (K + kNarrowKB - 1) / kNarrowKB;
+  if (b >= (unsigned)(n_workers * kb)) {
+    if (b == (unsigned)(n_workers * kb) && g.task_z >= 0) {
+      float* s_mean = reinterpret_cast<float*>(smem);
+      for (int ww = 0; ww < g.task_workers; ++ww)
+        slice_loss_worker<kGemmThreads / 64>(g.task_row_loss, g.row_off, g.task_slices, g.task_op, ww, g.task_loss,
+                                             s_mean);
+    }
+    return;
+  }
+  const int w = b / kb, k0 = (b % kb) * kNarrowKB;
+  const int64_t rows_w = g.row_off[w + 1] - g.row_off[w];
+  float* sdz = reinterpret_cast<float*>(smem);          // [kNarrowRows][16]: a chunk of the worker's dZ_L rows
+  float* sred = sdz + kNarrowRows * 16;                 // [4 row groups][16][kNarrowKB]
+  const int t = threadIdx.x, kk = t & (kNarrowKB - 1), rg = t / kNarrowKB;
+  const bool live = k0 + kk < K;
+  const T* H = reinterpret_cast<const T*>(g.a[w]) + k0 + (live ? kk : 0);   // a dead thread reads input k0, unused
+  const T* dZ = reinterpret_cast<const T*>(g.b) + g.row_off[w] * g.ldb;
+  const bool want_colsum = g.colsum_off >= 0 && k0 == 0;
+  float acc[16];
+#pragma unroll
+  for (int c = 0; c < 16; ++c) acc[c] = 0.0f;
+  float bsum = 0.0f;
+  for (int64_t r0 = 0; r0 < rows_w; r0 += kNarrowRows) {
+    const int nr = (int)(rows_w - r0 < kNarrowRows ? rows_w - r0 : kNarrowRows);
+    __syncthreads();                                    // the chunk before has been used
+    for (int e = t; e < nr * 16; e += kGemmThreads) {
+      const int r = e >> 4, c = e & 15;
+      sdz[e] = c < C ? to_f32(dZ[(r0 + r) * g.ldb + c]) : 0.0f;
+    }
+    __syncthreads();
+    // eight of this thread's rows at a time: the loads first, then the multiply-adds, in row order
+    for (int rb = rg; rb < nr; rb += 32) {
+      float h[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int r = rb + 4 * u;
+        h[u] = to_f32(H[(r0 + (r < nr ? r : rb)) * g.lda]);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int r = rb + 4 * u;
+        if (r < nr) {
+          const float* d = sdz + r * 16;
+#pragma unroll
+          for (int c = 0; c < 16; ++c) acc[c] = fmaf(h[u], d[c], acc[c]);
+        }
+      }
+    }
+    if (want_colsum && t < 16)
+      for (int r = 0; r < nr; ++r) bsum += sdz[r * 16 + t];
+  }
+#pragma unroll
+  for (int c = 0; c < 16; ++c) sred[(rg * 16 + c) * kNarrowKB + kk] = acc[c];
+  __syncthreads();
+  float* Cw = reinterpret_cast<float*>(g.c[w]);
+  if (rg == 0 && live) {
+    for (int c = 0; c < C; ++c) {
+      float v = sred[c * kNarrowKB + kk];
+#pragma unroll
+      for (int q = 1; q < 4; ++q) v += sred[(q * 16 + c) * kNarrowKB + kk];
+      Cw[(int64_t)(k0 + kk) * g.ldc + c] = v;
+    }
+  }
+  if (want_colsum && t < C) Cw[g.colsum_off + t] = bsum;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kGemmThreads) void mlp_dw_narrow_kernel(GemmArgs g, int n_workers) {
+  __shared__ __attribute__((aligned(16))) uint32_t smem[dw_narrow_lds_words()];
+  dw_narrow_body<T>(g, blockIdx.x, n_workers, smem);
+}
+
 // ------------------------------------------------------- backward group
 // After the last-layer kernel both dZ_L and dZ_{L-1} exist, so dW_L, dW_{L-1}
 // and dZ_{L-2} = (dZ_{L-1} W_{L-1}^T) * [H_{L-2} > 0] do not depend on one
@@ -969,7 +1060,8 @@ struct GroupArgs {
   GemmArgs dwp;   // dW_{L-1}: the tile-walking kernel
   GemmArgs dx;    // dZ_{L-2}: 64 x 64 tiles
   GemmArgs dwl;   // dW_L (+ the slice losses): 64 x 64 tiles
-  unsigned n_dwp, n_dx, n_dwl;          // workgroups of each grid (n_dwp and n_dx multiples of 8)
+  unsigned n_dwp, n_dx, n_dwl;          // workgroups of each grid (all but the last one multiples of 8)
+  int dwl_narrow;                       // dW_L by the multiply-add kernel for narrow last layers
   unsigned dx_gx, dx_gy, dx_gz, dwl_gx, dwl_gy, dwl_gz;
   int tiles_m, tiles_n, n_workers;
   int dx_whole;                         // dZ_{L-2} by the whole-tile core: dx_gx x dx_gy tiles of 64 x 64 over all rows
@@ -983,6 +1075,7 @@ __host__ __device__ constexpr int group_lds_words() {
   int m = dw_persistent_lds_words<T>();
   if (gemm_lds_words<T, MODE_DX, 64, 64, BKS>() > m) m = gemm_lds_words<T, MODE_DX, 64, 64, BKS>();
   if (gemm_lds_words<T, MODE_DW, 64, 64, BKS>() > m) m = gemm_lds_words<T, MODE_DW, 64, 64, BKS>();
+  if (dw_narrow_lds_words() > m) m = dw_narrow_lds_words();
   if (sizeof(T) == 2 && gdma::lds_bytes<64, 64, kGroupDxStages>() / 4 > m) m = gdma::lds_bytes<64, 64, kGroupDxStages>() / 4;
   return m;
 }
@@ -991,12 +1084,17 @@ template <typename T, bool AL_B_LAST>
 __global__ __launch_bounds__(kGemmThreads, 4) void mlp_backward_group_kernel(GroupArgs ga) {
   constexpr int BKS = sizeof(T) == 2 ? 64 : 32;
   __shared__ __attribute__((aligned(16))) uint32_t smem[group_lds_words<T>()];
+  // Order of the parts = order in which workgroups get their place on the chip: the short ones first
+  // (dW_L of a narrow last layer with the slice losses, then the dZ_{L-2} product the next launch waits
+  // for), the tile walkers of dW_{L-1} beside and behind them.
   unsigned b = blockIdx.x;
-  if (b < ga.n_dwp) {
-    dw_persistent_body<T>(ga.dwp, ga.tiles_m, ga.tiles_n, ga.n_workers, b, ga.n_dwp, smem);
-    return;
+  if (ga.dwl_narrow) {
+    if (b < ga.n_dwl) {
+      dw_narrow_body<T>(ga.dwl, b, ga.n_workers, smem);
+      return;
+    }
+    b -= ga.n_dwl;
   }
-  b -= ga.n_dwp;
   if (b < ga.n_dx) {
     if (sizeof(T) == 2 && ga.dx_whole) {
       if (b < ga.dx_gx * ga.dx_gy)
@@ -1008,7 +1106,12 @@ __global__ __launch_bounds__(kGemmThreads, 4) void mlp_backward_group_kernel(Gro
     return;
   }
   b -= ga.n_dx;
-  if (b < ga.dwl_gx * ga.dwl_gy * ga.dwl_gz)
+  if (b < ga.n_dwp) {
+    dw_persistent_body<T>(ga.dwp, ga.tiles_m, ga.tiles_n, ga.n_workers, b, ga.n_dwp, smem);
+    return;
+  }
+  b -= ga.n_dwp;
+  if (!ga.dwl_narrow && b < ga.dwl_gx * ga.dwl_gy * ga.dwl_gz)
     gemm_tile<T, MODE_DW, 64, 64, BKS, true, AL_B_LAST>(ga.dwl, b, ga.dwl_gx, ga.dwl_gy, ga.dwl_gz, smem);
 }
 
@@ -1272,7 +1375,8 @@ __global__ __launch_bounds__(kMBlock) void mlp_head_kernel(HeadArgs a) {
 
 template <typename T>
 static int launch_head(const HeadArgs& ha, int C, dim3 grid, hipStream_t s) {
-#define SYNK_HEAD(CC) case CC: hipLaunchKernelGGL((mlp_head_kernel<T, CC>), grid, dim3(kMBlock), 0, s, ha); break
+#define SYNK_HEAD(CC) \
+  case CC: SYNK_LAUNCH_TIMED_AS(SYNK_KERNEL_MLP_HEAD, (mlp_head_kernel<T, CC>), grid, dim3(kMBlock), 0, s, ha); break
   switch (C) {
     SYNK_HEAD(1); SYNK_HEAD(2); SYNK_HEAD(3); SYNK_HEAD(4); SYNK_HEAD(5); SYNK_HEAD(6); SYNK_HEAD(7);
     SYNK_HEAD(8); SYNK_HEAD(9); SYNK_HEAD(10); SYNK_HEAD(11); SYNK_HEAD(12); SYNK_HEAD(13); SYNK_HEAD(14);
@@ -1401,7 +1505,7 @@ static bool gemm_dma_ok(const GemmArgs& g, int n_workers, int bm, int bn) {
 }
 
 template <typename T, int MODE>
-static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStream_t s) {
+static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStream_t s, int prof_id) {
   constexpr int BK_BIG = GemmTiling<T>::BK_BIG, BK_SMALL = GemmTiling<T>::BK_SMALL;
   const int64_t big = big_tiles(g, m_max, n_workers);
   const int al = gemm_alignment(g);
@@ -1410,15 +1514,15 @@ static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStrea
     const int64_t R = g.row_off[n_workers];
     if (gemm_dma_ok<T, MODE>(g, n_workers, 128, 128) && (R / 128) * (g.n / 128) >= 2 * kNumCU) {
       const int tm = (int)(R / 128), tn = (int)(g.n / 128);
-      SYNK_LAUNCH_TIMED((mlp_gemm_dma_kernel<GM, 128, 128, 3>), dim3((unsigned)(tm * tn)), dim3(gdma::kThreads), 0, s,
-                        g, tm, tn);
+      SYNK_LAUNCH_TIMED_AS(prof_id, (mlp_gemm_dma_kernel<GM, 128, 128, 3>), dim3((unsigned)(tm * tn)),
+                           dim3(gdma::kThreads), 0, s, g, tm, tn);
       SYNK_LAUNCH_CHECK();
       return SYNK_OK;
     }
     if (gemm_dma_ok<T, MODE>(g, n_workers, 64, 64)) {
       const int tm = (int)(R / 64), tn = (int)(g.n / 64);
-      SYNK_LAUNCH_TIMED((mlp_gemm_dma_kernel<GM, 64, 64, 6>), dim3((unsigned)(tm * tn)), dim3(gdma::kThreads), 0, s,
-                        g, tm, tn);
+      SYNK_LAUNCH_TIMED_AS(prof_id, (mlp_gemm_dma_kernel<GM, 64, 64, 6>), dim3((unsigned)(tm * tn)),
+                           dim3(gdma::kThreads), 0, s, g, tm, tn);
       SYNK_LAUNCH_CHECK();
       return SYNK_OK;
     }
@@ -1426,15 +1530,18 @@ static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStrea
 #define SYNK_GEMM(BM_, BN_, BK_)                                                                              \
   do {                                                                                                       \
     if (al == 2)                                                                                             \
-      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, BM_, BN_, BK_, true, true>), grid, dim3(kGemmThreads), 0, s, g);  \
+      SYNK_LAUNCH_TIMED_AS(prof_id, (mlp_gemm_kernel<T, MODE, BM_, BN_, BK_, true, true>), grid,             \
+                           dim3(kGemmThreads), 0, s, g);                                                     \
     else if (al == 1)                                                                                        \
-      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, BM_, BN_, BK_, true, false>), grid, dim3(kGemmThreads), 0, s, g); \
+      SYNK_LAUNCH_TIMED_AS(prof_id, (mlp_gemm_kernel<T, MODE, BM_, BN_, BK_, true, false>), grid,            \
+                           dim3(kGemmThreads), 0, s, g);                                                     \
     else                                                                                                     \
-      hipLaunchKernelGGL((mlp_gemm_kernel<T, MODE, BM_, BN_, BK_, false, false>), grid, dim3(kGemmThreads), 0, s, g);\
+      SYNK_LAUNCH_TIMED_AS(prof_id, (mlp_gemm_kernel<T, MODE, BM_, BN_, BK_, false, false>), grid,           \
+                           dim3(kGemmThreads), 0, s, g);                                                     \
   } while (0)
   if (MODE == MODE_DW && dw_persistent_ok<T>(g, m_max, n_workers)) {
-    hipLaunchKernelGGL((mlp_dw_persistent_kernel<T>), dim3(dw_persistent_blocks(g, m_max, n_workers)),
-                       dim3(kGemmThreads), 0, s, g, (int)(m_max / 128), (int)(g.n / 128), n_workers);
+    SYNK_LAUNCH_TIMED_AS(prof_id, (mlp_dw_persistent_kernel<T>), dim3(dw_persistent_blocks(g, m_max, n_workers)),
+                         dim3(kGemmThreads), 0, s, g, (int)(m_max / 128), (int)(g.n / 128), n_workers);
     SYNK_LAUNCH_CHECK();
     return SYNK_OK;
   }
@@ -1506,7 +1613,9 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
     g.a_vec = (K % V == 0) && (l == 1 ? x_vec : true);
     g.b_vec = (N % V == 0) && aligned_to(W, 16);
     g.c_vec = N % 8 == 0;     // workspace rows: 256-byte aligned base, rows a multiple of 16 bytes
-    if (int rc = launch_gemm<T, MODE_FWD>(g, p.max_rows, n_workers, s)) return rc;
+    if (int rc = launch_gemm<T, MODE_FWD>(g, p.max_rows, n_workers, s,
+                                          l == 1 ? SYNK_KERNEL_MAIN : SYNK_KERNEL_MLP_FORWARD(l)))
+      return rc;
   }
 
   // ---- loss and dZ_L
@@ -1536,7 +1645,7 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
     if (int rc = launch_head<T>(ha, (int)p.d[L], grid, s)) return rc;
   } else {
     const dim3 grid((unsigned)((p.max_rows + kCeRowsPerBlock - 1) / kCeRowsPerBlock), n_workers);
-    hipLaunchKernelGGL((softmax_ce_kernel<T>), grid, dim3(kMBlock), 0, s, ce);
+    SYNK_LAUNCH_TIMED_AS(SYNK_KERNEL_MLP_HEAD, (softmax_ce_kernel<T>), grid, dim3(kMBlock), 0, s, ce);
     SYNK_LAUNCH_CHECK();
   }
 
@@ -1606,7 +1715,8 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
     fill_dw(ga.dwp, L - 1, false);
     fill_dx(ga.dx, L - 1);
     const int al_last = gemm_alignment(ga.dwl);
-    const bool ok = al_last >= 1 && big_tiles(ga.dwl, p.d[L - 1], n_workers + 1) < 2 * kNumCU &&
+    ga.dwl_narrow = p.d[L] <= kNarrowMaxC ? 1 : 0;
+    const bool ok = (ga.dwl_narrow || (al_last >= 1 && big_tiles(ga.dwl, p.d[L - 1], n_workers + 1) < 2 * kNumCU)) &&
                     dw_persistent_ok<T>(ga.dwp, p.d[L - 2], n_workers) && gemm_alignment(ga.dx) == 2 &&
                     big_tiles(ga.dx, p.max_rows, n_workers) < 2 * kNumCU;
     if (ok) {
@@ -1627,23 +1737,38 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
       ga.dwl_gx = (unsigned)((ga.dwl.n + 63) / 64);
       ga.dwl_gy = (unsigned)((p.d[L - 1] + 63) / 64);
       ga.dwl_gz = (unsigned)(n_workers + 1);
-      ga.n_dwl = ga.dwl_gx * ga.dwl_gy * ga.dwl_gz;
-      const dim3 grid(ga.n_dwp + ga.n_dx + ga.n_dwl);
+      ga.n_dwl = ga.dwl_narrow ? (dw_narrow_blocks(p.d[L - 1], n_workers) + 7u) / 8u * 8u
+                               : ga.dwl_gx * ga.dwl_gy * ga.dwl_gz;
+      const dim3 grid(ga.n_dx + ga.n_dwp + ga.n_dwl);
       if (al_last == 2)
-        hipLaunchKernelGGL((mlp_backward_group_kernel<T, true>), grid, dim3(kGemmThreads), 0, s, ga);
+        SYNK_LAUNCH_TIMED_AS(SYNK_KERNEL_MLP_BACKWARD_GROUP, (mlp_backward_group_kernel<T, true>), grid,
+                             dim3(kGemmThreads), 0, s, ga);
       else
-        hipLaunchKernelGGL((mlp_backward_group_kernel<T, false>), grid, dim3(kGemmThreads), 0, s, ga);
+        SYNK_LAUNCH_TIMED_AS(SYNK_KERNEL_MLP_BACKWARD_GROUP, (mlp_backward_group_kernel<T, false>), grid,
+                             dim3(kGemmThreads), 0, s, ga);
       SYNK_LAUNCH_CHECK();
       l = L - 2;
     }
   }
   for (; l >= 1; --l) {
     fill_dw(g, l, l == L);
-    if (int rc = launch_gemm<T, MODE_DW>(g, p.d[l - 1], n_workers + (l == L ? 1 : 0), s)) return rc;
+    if (l == L && p.d[L] <= kNarrowMaxC) {
+      SYNK_LAUNCH_TIMED_AS(SYNK_KERNEL_MLP_DW(l), (mlp_dw_narrow_kernel<T>), dim3(dw_narrow_blocks(p.d[L - 1], n_workers)),
+                           dim3(kGemmThreads), 0, s, g, n_workers);
+      SYNK_LAUNCH_CHECK();
+      g.task_z = -1;
+      if (l > 1 && !use_head) {
+        fill_dx(g, l);
+        if (int rc = launch_gemm<T, MODE_DX>(g, p.max_rows, n_workers, s, SYNK_KERNEL_MLP_DX(l))) return rc;
+      }
+      continue;
+    }
+    if (int rc = launch_gemm<T, MODE_DW>(g, p.d[l - 1], n_workers + (l == L ? 1 : 0), s, SYNK_KERNEL_MLP_DW(l)))
+      return rc;
     g.task_z = -1;
     if (l > 1 && !(use_head && l == L)) {
       fill_dx(g, l);
-      if (int rc = launch_gemm<T, MODE_DX>(g, p.max_rows, n_workers, s)) return rc;
+      if (int rc = launch_gemm<T, MODE_DX>(g, p.max_rows, n_workers, s, SYNK_KERNEL_MLP_DX(l))) return rc;
     }
   }
   return SYNK_OK;

@@ -36,9 +36,10 @@ extern "C" int synk_split(int64_t count, int parts, int64_t* start) {
 // ---------------------------------------------------------------- profiling
 namespace synk {
 static thread_local hipEvent_t tl_start = nullptr, tl_stop = nullptr;
+static thread_local int tl_kernel = SYNK_KERNEL_MAIN;
 
-bool take_profile_events(hipEvent_t* start, hipEvent_t* stop) {
-  if (!tl_start) return false;
+bool take_profile_events(int kernel_id, hipEvent_t* start, hipEvent_t* stop) {
+  if (!tl_start || kernel_id != tl_kernel) return false;
   *start = tl_start;
   *stop = tl_stop;
   tl_start = tl_stop = nullptr;
@@ -46,9 +47,15 @@ bool take_profile_events(hipEvent_t* start, hipEvent_t* stop) {
 }
 }  // namespace synk
 
-extern "C" int synk_profile_next_launch(void* start_event, void* stop_event) {
+extern "C" int synk_profile_next_launch_of(int kernel, void* start_event, void* stop_event) {
   if ((start_event == nullptr) != (stop_event == nullptr)) return SYNK_ERR_NULL;
+  if (kernel < 0) return SYNK_ERR_SHAPE;
   synk::tl_start = reinterpret_cast<hipEvent_t>(start_event);
   synk::tl_stop = reinterpret_cast<hipEvent_t>(stop_event);
+  synk::tl_kernel = kernel;
   return SYNK_OK;
+}
+
+extern "C" int synk_profile_next_launch(void* start_event, void* stop_event) {
+  return synk_profile_next_launch_of(SYNK_KERNEL_MAIN, start_event, stop_event);
 }
