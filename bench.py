@@ -54,11 +54,18 @@ def parse():
     ap.add_argument("--batch", type=int, default=None,
                     help="configs 1 and 2 only: minibatch size, to time worker shares that do not divide evenly "
                          "(default: the configuration's own, 256 / 1024)")
+    ap.add_argument("--rows-per-worker", type=int, default=None,
+                    help="config 2 only, a labelled supplementary shape (not the configuration): the same model and "
+                         "kernels with this many rows per worker (e.g. 8192), to show what the products reach when "
+                         "the per-worker shape does not bound them")
     ap.add_argument("--conv-shape", default=None,
                     help="config 6 at another block shape: H,W,C_in,C_out (e.g. 14,14,256,256)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the steps (one per rotating input set) into one HIP graph and time its replays; "
                          "the dominant kernel is then timed in a short eager pass before the timed region")
+    ap.add_argument("--probe", default=None, choices=["mfma", "fill", "fetch"],
+                    help="config 0 only: instead of the copy, one of the library's peak probes (register-resident bf16 "
+                         "MFMA loop; plain 16-byte stores over 1 GiB; operand tiles from L2 straight into LDS)")
     ap.add_argument("--repeats", type=int, default=5,
                     help="the K timed steps are run this many times; value and ms_per_step are the median repeat's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -107,7 +114,12 @@ class Timer:
             a, b = self.pool[self.used]
             self.used += 1
             self.synk.synk_profile_next_launch_of(kernel, a, b)
-            self.samples.setdefault(name, []).append((a, b))
+            fn()
+            if self.synk.synk_profile_pending():      # the call did not launch that kernel: no sample
+                self.synk.synk_profile_next_launch_of(kernel, None, None)
+            else:
+                self.samples.setdefault(name, []).append((a, b))
+            return
         fn()
 
     def mean_ms(self, name="dominant"):
@@ -122,7 +134,7 @@ class Timer:
 class MlpStep:
     """Configs 1 and 2: the whole synchronous-SGD step."""
 
-    def __init__(self, torch, synk, cfg_no, batch=None):
+    def __init__(self, torch, synk, cfg_no, batch=None, rows_per_worker=None):
         import numpy as np
         import workloads
         self.torch, self.s, self.np = torch, synk, np
@@ -131,6 +143,10 @@ class MlpStep:
             c["idx_sets"] = [np.random.default_rng(i).permutation(4096)[:256].astype(np.int32) for i in range(8)]
         else:
             c = workloads.config2(n_index_sets=8)
+        if rows_per_worker is not None:
+            rng = np.random.default_rng(workloads.SEED_BASE + 2000)
+            c["idx_sets"] = [rng.integers(0, c["data"].shape[0], c["n_workers"] * rows_per_worker).astype(np.int32)
+                             for _ in range(2)]
         if batch is not None:
             if not 1 <= batch <= len(c["idx_sets"][0]):
                 raise SystemExit("--batch must be in [1, %d] for this configuration" % len(c["idx_sets"][0]))
@@ -164,6 +180,9 @@ class MlpStep:
                          "config 1: tiny MLP 784-256-10 step, batch %d, 2 worker shares x 4 slices, fp32" % self.B)
         if batch is not None:
             self.workload += " (worker shares %s)" % "/".join(str(r) for r in sorted(set(self.rows), reverse=True))
+        if rows_per_worker is not None:
+            self.workload = ("SUPPLEMENTARY shape, not a configuration: the config-2 model and kernels at %d rows per "
+                             "worker (batch %d)" % (rows_per_worker, self.B))
         # dominant kernel: the fused N-way reduce + momentum update.  Per parameter it reads N
         # gradients, reads and writes p and v (fp32) and, with bf16 compute, writes the bf16 copy.
         self.dom_name = "reduce_sgd_kernel"
@@ -259,7 +278,7 @@ class MlpStep:
         best = 1e30
         for rep in range(3):
             t0 = time.perf_counter()
-            loss, g = omlp.full(theta, self.dims, c["data"], c["labels"], c["idx_sets"][rep])
+            loss, g = omlp.full(theta, self.dims, c["data"], c["labels"], c["idx_sets"][rep % len(c["idx_sets"])])
             oupdate.sgd_momentum(theta, v, g, c["lr"], c["momentum"], c["weight_decay"])
             best = min(best, time.perf_counter() - t0)
         return self.B / best, "3 whole steps (full-batch oracle: gather, fwd/bwd, update), best of 3"
@@ -571,6 +590,39 @@ class ConvStep:
         return 2 * n / (time.perf_counter() - t0), "2 of the 8 worker shares (8 images each): function + update"
 
 
+class ProbeStep:
+    """Config 0 with --probe: a measured peak of the part (timing kernel of the library, nothing of the method)."""
+
+    def __init__(self, torch, synk, which):
+        self.s, self.which = synk, which
+        if which == "mfma":
+            self.buf, self.iters, pid = torch.zeros(64, device="cuda"), 20000, synk.SYNK_PROBE_MFMA_BF16
+            self.unit, self.dom_bound, self.dom_unit, self.dom_peak = "flop/s", "mfma", "TFLOP/s", 2500.0
+            self.workload = "probe: 512 workgroups x 8 wavefronts x 20000 x 4 bf16 32x32x16 MFMAs on registers"
+        elif which == "fill":
+            self.buf, self.iters, pid = torch.empty(1 << 28, device="cuda"), 1, synk.SYNK_PROBE_FILL
+            self.unit = "bytes/s"
+            self.workload = "probe: 1 GiB of 16-byte stores, one per thread, in address order"
+        else:
+            self.buf, self.iters, pid = torch.ones(2 << 20, device="cuda"), 48, synk.SYNK_PROBE_LDS_FETCH
+            self.unit = "bytes/s"
+            # nominal L1 fill rate: 64 B/clk per CU, 256 CUs, 2.4 GHz
+            self.dom_bound, self.dom_unit, self.dom_peak = "l2", "GB/s", 64 * 256 * 2.4
+            self.workload = ("probe: 256 workgroups each bringing 48 tiles of 128 rows x 128 B (pitch 6 KB) from L2 "
+                             "straight into LDS")
+        self.pid = pid
+        self.units = synk.synk_probe_launch(pid, self.buf, self.iters)      # work of one launch
+        self.dom_work, self.dom_bytes = self.units, self.units
+        self.dtype = "bf16" if which == "mfma" else "u8"
+        self.dom_name = "probe_%s_kernel" % which
+
+    def step(self, i, timer):
+        timer.bracket(lambda: self.s.synk_probe_launch(self.pid, self.buf, self.iters))
+
+    def cpu_baseline(self):
+        return 0.0, "none"
+
+
 class CopyStep:
     """Config 0: a plain copy kernel of known size (1 GiB in, 1 GiB out), against which the
     FETCH_SIZE / WRITE_SIZE counters of the other kernels are scaled."""
@@ -606,10 +658,12 @@ def main():
     if a.graph:
         # capture needs a stream of its own; the calls below are prepared on it
         torch.cuda.set_stream(torch.cuda.Stream())
-    wl = {0: lambda: CopyStep(torch, synk), 1: lambda: MlpStep(torch, synk, 1, a.batch), 2: lambda: MlpStep(torch, synk, 2, a.batch),
+    wl = {0: lambda: (ProbeStep(torch, synk, a.probe) if a.probe else CopyStep(torch, synk)), 1: lambda: MlpStep(torch, synk, 1, a.batch), 2: lambda: MlpStep(torch, synk, 2, a.batch, a.rows_per_worker),
           3: lambda: (CollectiveStep(torch, synk, a.collective) if a.collective else ReduceStep(torch, synk, a.rule)), 4: lambda: GatherStep(torch, synk, a.indexing),
           5: lambda: EvalStep(torch, synk), 6: lambda: ConvStep(torch, synk, a.conv_shape)}[a.config]()
     steps = a.steps if a.steps is not None else {0: 50, 1: 2000, 2: 1000, 3: 300, 4: 1000, 5: 1000, 6: 300}[a.config]
+    if a.rows_per_worker is not None and a.steps is None:
+        steps = 56
     warmup = a.warmup if a.warmup is not None else 20
 
     repeats = max(1, a.repeats)
@@ -662,10 +716,13 @@ def main():
     # quantity as the kernel duration in a rocprofv3 kernel trace.
     dom_ms = timer.mean_ms("reduce_update" if hasattr(wl, "targets") else "dominant")
     bound = getattr(wl, "dom_bound", "hbm")
+    if dom_ms <= 0:
+        dom_ms = float("nan")                          # too few steps to reach the dominant kernel's turn
     if bound == "hbm":
         achieved, peak, unit = wl.dom_bytes / (dom_ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
     else:
-        achieved, peak, unit = wl.dom_work / (dom_ms * 1e-3) / 1e12, wl.dom_peak, wl.dom_unit
+        scale = 1e12 if wl.dom_unit == "TFLOP/s" else 1e9
+        achieved, peak, unit = wl.dom_work / (dom_ms * 1e-3) / scale, wl.dom_peak, wl.dom_unit
     out = {
         "metric": "samples/sec for gather+sliced grad+reduce+SGD step; HBM GB/s and MFMA % of peak",
         "value": wl.units * steps / dt, "unit": wl.unit, "n_gpus": 1, "steps": steps, "warmup": warmup,
@@ -675,7 +732,7 @@ def main():
         "config": {"workload": wl.workload, "units_per_step": wl.units, "launch": "hip graph replay" if a.graph else "eager"},
         "roofline": {"bound": bound, "kernel": wl.dom_name, "achieved": achieved, "peak": peak,
                      "unit": unit, "frac": achieved / peak,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (a.rule == "momentum" and not a.collective and a.indexing == "list" and a.batch is None and not a.conv_shape) else None, "traffic_unit": "HBM bytes per launch",
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (a.rule == "momentum" and not a.collective and a.indexing == "list" and a.batch is None and not a.conv_shape and a.rows_per_worker is None) else None, "traffic_unit": "HBM bytes per launch",
                      "bytes_per_launch": wl.dom_bytes, "ms_per_launch": dom_ms},
     }
     if hasattr(wl, "kernel_report"):

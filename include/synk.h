@@ -125,6 +125,27 @@ const char* synk_status_string(int status);
 #define SYNK_KERNEL_MLP_DX(l) (48 + (l))
 int synk_profile_next_launch(void* start_event, void* stop_event);
 int synk_profile_next_launch_of(int kernel, void* start_event, void* stop_event);
+/* 1 while a pair handed in on this host thread has not been attached to a launch yet, else 0. */
+int synk_profile_pending(void);
+
+/* Measured peaks for the rooflines a caller reports (timing kernels only; nothing of
+ * the method).  Launches one probe on `stream`; *work receives what the launch
+ * does (flops or bytes), to be divided by the launch's duration, e.g. taken with
+ * synk_profile_next_launch.
+ *   SYNK_PROBE_MFMA_BF16  512 workgroups of 8 wavefronts, each iters x 4 32x32x16
+ *                         bf16 MFMAs on registers; buf: >= 4 bytes (never written
+ *                         in practice)
+ *   SYNK_PROBE_FILL       buf_bytes of 16-byte stores, one per thread, in address
+ *                         order
+ *   SYNK_PROBE_LDS_FETCH  256 workgroups, each bringing iters (<= 48) tiles of 128
+ *                         rows x 128 bytes (row pitch 6 KB) from buf straight into
+ *                         LDS; buf_bytes >= 768 KB, read only
+ * buf: device, 16-byte aligned.  Errors: NULL -> ERR_NULL; iters < 1, alignment ->
+ * ERR_SHAPE; buffer too small -> ERR_WORKSPACE; unknown probe -> ERR_UNSUPPORTED. */
+#define SYNK_PROBE_MFMA_BF16 0
+#define SYNK_PROBE_FILL 1
+#define SYNK_PROBE_LDS_FETCH 2
+int synk_probe_launch(int probe, void* buf, size_t buf_bytes, int iters, double* work, void* stream);
 
 /* Host-side helper: the split rule above.  Writes parts+1 offsets
  * (start[0] = 0, start[parts] = count) into `start` (host). */

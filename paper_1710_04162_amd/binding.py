@@ -23,7 +23,8 @@ __all__ = [
     "synk_sgd_update", "synk_reduce_sgd_update", "synk_reduce_update",
     "synk_broadcast", "synk_all_reduce", "synk_all_gather",
     "synk_gather_slice", "synk_scatter_rows", "synk_gather_resident", "synk_profile_next_launch",
-    "synk_profile_next_launch_of", "SYNK_KERNEL_MAIN", "SYNK_KERNEL_MLP_HEAD", "SYNK_KERNEL_MLP_BACKWARD_GROUP",
+    "synk_profile_next_launch_of", "synk_profile_pending", "synk_probe_launch",
+    "SYNK_PROBE_MFMA_BF16", "SYNK_PROBE_FILL", "SYNK_PROBE_LDS_FETCH", "SYNK_KERNEL_MAIN", "SYNK_KERNEL_MLP_HEAD", "SYNK_KERNEL_MLP_BACKWARD_GROUP",
     "SYNK_KERNEL_MLP_FORWARD", "SYNK_KERNEL_MLP_DW", "SYNK_KERNEL_MLP_DX",
     "synk_convblock_param_count", "synk_sliced_grad_conv_workspace_bytes", "synk_sliced_grad_conv",
 ]
@@ -85,6 +86,10 @@ for _n in ("synk_gather_slice", "synk_scatter_rows", "synk_gather_resident"):
     getattr(lib, _n).restype = _int
 lib.synk_profile_next_launch.argtypes = [_vp, _vp]
 lib.synk_profile_next_launch.restype = _int
+lib.synk_probe_launch.argtypes = [_int, _vp, _sz, _int, ctypes.POINTER(ctypes.c_double), _vp]
+lib.synk_probe_launch.restype = _int
+lib.synk_profile_pending.argtypes = []
+lib.synk_profile_pending.restype = _int
 lib.synk_profile_next_launch_of.argtypes = [_int, _vp, _vp]
 lib.synk_profile_next_launch_of.restype = _int
 lib.synk_build_norm_lut.argtypes = [_pf32, _pf32, _int, _vp, _vp]
@@ -466,6 +471,21 @@ def synk_profile_next_launch(start, stop):
     """start, stop: torch.cuda.Event(enable_timing=True) that have been recorded once (torch creates
     the underlying hipEvent_t at the first record), or None, None to cancel."""
     synk_profile_next_launch_of(SYNK_KERNEL_MAIN, start, stop)
+
+
+SYNK_PROBE_MFMA_BF16, SYNK_PROBE_FILL, SYNK_PROBE_LDS_FETCH = 0, 1, 2
+
+
+def synk_probe_launch(probe, buf, iters, stream=None):
+    """Launches one timing probe; returns the flops or bytes the launch does."""
+    work = ctypes.c_double(0.0)
+    _check(lib.synk_probe_launch(int(probe), _ptr(buf), buf.numel() * buf.element_size(), int(iters),
+                                 ctypes.byref(work), _stream(stream)), "synk_probe_launch")
+    return work.value
+
+
+def synk_profile_pending():
+    return bool(lib.synk_profile_pending())
 
 
 def synk_profile_next_launch_of(kernel, start, stop):

@@ -966,6 +966,7 @@ __global__ __launch_bounds__(kGemmThreads, 4) void mlp_dw_persistent_kernel(Gemm
 // read from LDS at one address for all threads; the four row groups are then added in a fixed order.
 // The workgroup after the last one turns the row losses into the workers' slice-aggregated losses.
 constexpr int kNarrowMaxC = 16, kNarrowKB = 128, kNarrowRows = 256;
+constexpr int64_t kNarrowMaxRows = 1024;   // rows a worker may have: one workgroup walks them all for its 128 inputs
 __host__ __device__ constexpr int dw_narrow_lds_words() { return kNarrowRows * 16 + 4 * 16 * kNarrowKB; }
 
 static inline unsigned dw_narrow_blocks(int64_t K, int n_workers) {
@@ -1512,6 +1513,16 @@ static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStrea
   if (MODE != MODE_DW) {
     constexpr int GM = MODE == MODE_FWD ? gdma::FWD : gdma::DX;
     const int64_t R = g.row_off[n_workers];
+    // large products: the operand fetch rate of a CU bounds them, so the tile with the most flops per
+    // fetched byte that still fills the chip: 256 x 128 (36 % of the bf16 peak at 65,536 x 1024 x 3072
+    // against 31 % for 128 x 128)
+    if (gemm_dma_ok<T, MODE>(g, n_workers, 256, 128) && (R / 256) * (g.n / 128) >= 4 * kNumCU) {
+      const int tm = (int)(R / 256), tn = (int)(g.n / 128);
+      SYNK_LAUNCH_TIMED_AS(prof_id, (mlp_gemm_dma_kernel<GM, 256, 128, 3>), dim3((unsigned)(tm * tn)),
+                           dim3(gdma::kThreads), 0, s, g, tm, tn);
+      SYNK_LAUNCH_CHECK();
+      return SYNK_OK;
+    }
     if (gemm_dma_ok<T, MODE>(g, n_workers, 128, 128) && (R / 128) * (g.n / 128) >= 2 * kNumCU) {
       const int tm = (int)(R / 128), tn = (int)(g.n / 128);
       SYNK_LAUNCH_TIMED_AS(prof_id, (mlp_gemm_dma_kernel<GM, 128, 128, 3>), dim3((unsigned)(tm * tn)),
@@ -1715,7 +1726,7 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
     fill_dw(ga.dwp, L - 1, false);
     fill_dx(ga.dx, L - 1);
     const int al_last = gemm_alignment(ga.dwl);
-    ga.dwl_narrow = p.d[L] <= kNarrowMaxC ? 1 : 0;
+    ga.dwl_narrow = (p.d[L] <= kNarrowMaxC && p.max_rows <= kNarrowMaxRows) ? 1 : 0;
     const bool ok = (ga.dwl_narrow || (al_last >= 1 && big_tiles(ga.dwl, p.d[L - 1], n_workers + 1) < 2 * kNumCU)) &&
                     dw_persistent_ok<T>(ga.dwp, p.d[L - 2], n_workers) && gemm_alignment(ga.dx) == 2 &&
                     big_tiles(ga.dx, p.max_rows, n_workers) < 2 * kNumCU;
@@ -1752,7 +1763,7 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
   }
   for (; l >= 1; --l) {
     fill_dw(g, l, l == L);
-    if (l == L && p.d[L] <= kNarrowMaxC) {
+    if (l == L && p.d[L] <= kNarrowMaxC && p.max_rows <= kNarrowMaxRows) {
       SYNK_LAUNCH_TIMED_AS(SYNK_KERNEL_MLP_DW(l), (mlp_dw_narrow_kernel<T>), dim3(dw_narrow_blocks(p.d[L - 1], n_workers)),
                            dim3(kGemmThreads), 0, s, g, n_workers);
       SYNK_LAUNCH_CHECK();

@@ -56,6 +56,8 @@ extern "C" int synk_profile_next_launch_of(int kernel, void* start_event, void* 
   return SYNK_OK;
 }
 
+extern "C" int synk_profile_pending(void) { return synk::tl_start != nullptr ? 1 : 0; }
+
 extern "C" int synk_profile_next_launch(void* start_event, void* stop_event) {
   return synk_profile_next_launch_of(SYNK_KERNEL_MAIN, start_event, stop_event);
 }

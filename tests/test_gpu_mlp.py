@@ -172,6 +172,22 @@ def test_large_tile_paths(synk, compute, dims, rows_per_worker, N):
         assert abs(losses[w] - r["loss"]) < tol * abs(r["loss"])
 
 
+def test_largest_tile_path_bf16(synk):
+    """32,768 rows: the forward and dX products of the 1024-wide layers take the 256 x 128 tiling."""
+    dims, rows_per_worker, N = [64, 1024, 1024, 10], 4096, 8
+    B = rows_per_worker * N
+    cfg = small_cfg(dims, B, "bf16", 9)
+    cfg["data"] = np.abs(cfg["data"])
+    idx = np.random.default_rng(2).permutation(B).astype(np.int32)
+    st = Step(synk, cfg)
+    st.gather(idx, N)
+    grads, losses = st.sliced_grad(2, "mean")
+    for w, r in enumerate(worker_refs(cfg, idx, N, True)):
+        e = rel_err_either_tie(grads[w], r["grad"], r["alt"], dims, r["skip"])
+        assert e < TOL_BF16, (w, e)
+        assert abs(losses[w] - r["loss"]) < TOL_BF16 * abs(r["loss"])
+
+
 @pytest.mark.parametrize("compute,rows", [
     ("bf16", [128, 0, 256, 128, 128, 0, 256, 128]),     # whole rounds of four 32-row k-tiles, two empty workers
     ("f32", [64, 192, 0, 64, 128, 64, 64, 64]),         # fp32: rounds of four 16-row k-tiles
