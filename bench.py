@@ -228,6 +228,13 @@ class MlpStep:
                      write_bytes=dW(L)["write_bytes"] + dW(L - 1)["write_bytes"] + B * d[L - 2] * e)
             work["backward_group"] = g
             rest = range(L - 2, 0, -1)
+        elif L == 2:
+            # dW_2 and dW_1 share one launch when the shapes allow it, else they are launched one by one:
+            # targets for both forms; the form that does not occur yields no samples
+            targets.append(("backward_group", "grad", s.SYNK_KERNEL_MLP_BACKWARD_GROUP))
+            work["backward_group"] = dict(flops=dW(2)["flops"] + dW(1)["flops"], bytes=dW(2)["bytes"] + dW(1)["bytes"],
+                                          write_bytes=dW(2)["write_bytes"] + dW(1)["write_bytes"])
+            rest = range(L, 0, -1)
         else:
             rest = range(L, 0, -1)
         for l in rest:

@@ -958,26 +958,117 @@ __global__ __launch_bounds__(kGemmThreads, 4) void mlp_dw_persistent_kernel(Gemm
   dw_persistent_body<T>(g, tiles_m, tiles_n, n_workers, blockIdx.x, gridDim.x, smem);
 }
 
+// ------------------------------------------------------- small forward (fp32)
+// H = act(X W + b) when the rows are so few that 64 x 64 tiles leave most of the chip idle and a
+// workgroup walks the whole contraction alone (the tiny configuration: 16 tiles, 25 serial k-steps
+// of 64-cycle fp32 MFMAs).  Plain multiply-adds instead, arranged so that a workgroup pays few memory
+// latencies: 16 wavefronts own 8 rows x 64 columns; the 8 x rows go into LDS once; wavefront q takes
+// the q-th sixteenth of the contraction, a lane one column, and asks for all its weights (one
+// coalesced 256-byte row segment per k) before the first multiply-add, in batches of 48; an x value
+// is an LDS read at one address for the whole wavefront.  The 16 partial sums meet in LDS and are
+// added in wavefront order (bit-reproducible).
+constexpr int kSmallRows = 8, kSmallCols = 64, kSmallWaves = 16, kSmallBatch = 56;
+constexpr int kSmallMaxK = 2048;   // the x tile (8 rows) stays within 64 KB of LDS
+
+__global__ __launch_bounds__(64 * kSmallWaves) void mlp_fwd_small_kernel(GemmArgs g, int row_tiles, int col_tiles) {
+  extern __shared__ __attribute__((aligned(16))) float small_lds[];
+  const int K = (int)g.k_fixed;
+  const int Kp = (K + 3) & ~3;                                 // x tile row pitch in LDS: [k][8 rows] is used instead
+  float* xs = small_lds;                                       // [Kp][8]
+  float* part = small_lds + (size_t)Kp * kSmallRows;           // [16][8][64]
+  const int w = blockIdx.y;
+  const int rt = blockIdx.x / col_tiles, ct = blockIdx.x % col_tiles;
+  const int64_t rows_w = g.row_off[w + 1] - g.row_off[w];
+  const int64_t r0 = (int64_t)rt * kSmallRows;
+  if (r0 >= rows_w) return;                                    // uniform for the workgroup
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int64_t N = g.n;
+  const int64_t n = (int64_t)ct * kSmallCols + lane;
+  const bool col_ok = n < N;
+  const float* X = reinterpret_cast<const float*>(g.a[w]);
+  const float* W = reinterpret_cast<const float*>(g.b) + (col_ok ? n : 0);
+  // this wavefront's part of the contraction
+  const int kc = (K + kSmallWaves - 1) / kSmallWaves;
+  const int kb = q * kc, ke = kb + kc < K ? kb + kc : K;
+  // its first batch of weights is asked for before the x tile is staged
+  float wv[kSmallBatch];
+#pragma unroll
+  for (int u = 0; u < kSmallBatch; ++u) wv[u] = W[(int64_t)(kb + u < ke ? kb + u : (kb < K ? kb : 0)) * g.ldb];
+  for (int k = threadIdx.x; k < K; k += 64 * kSmallWaves) {
+    float xv[kSmallRows];
+#pragma unroll
+    for (int r = 0; r < kSmallRows; ++r) xv[r] = X[(r0 + r < rows_w ? r0 + r : r0) * g.lda + k];   // a row past the end repeats row r0
+    *reinterpret_cast<f32x4*>(xs + k * kSmallRows) = f32x4{xv[0], xv[1], xv[2], xv[3]};
+    *reinterpret_cast<f32x4*>(xs + k * kSmallRows + 4) = f32x4{xv[4], xv[5], xv[6], xv[7]};
+  }
+  __syncthreads();
+  float acc[kSmallRows];
+#pragma unroll
+  for (int r = 0; r < kSmallRows; ++r) acc[r] = 0.0f;
+  for (int k0 = kb; k0 < ke; k0 += kSmallBatch) {
+    if (k0 > kb) {
+#pragma unroll
+      for (int u = 0; u < kSmallBatch; ++u) wv[u] = W[(int64_t)(k0 + u < ke ? k0 + u : k0) * g.ldb];
+    }
+#pragma unroll
+    for (int u = 0; u < kSmallBatch; ++u) {
+      if (k0 + u < ke) {
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(xs + (k0 + u) * kSmallRows);
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(xs + (k0 + u) * kSmallRows + 4);
+        acc[0] = fmaf(lo.x, wv[u], acc[0]); acc[1] = fmaf(lo.y, wv[u], acc[1]);
+        acc[2] = fmaf(lo.z, wv[u], acc[2]); acc[3] = fmaf(lo.w, wv[u], acc[3]);
+        acc[4] = fmaf(hi.x, wv[u], acc[4]); acc[5] = fmaf(hi.y, wv[u], acc[5]);
+        acc[6] = fmaf(hi.z, wv[u], acc[6]); acc[7] = fmaf(hi.w, wv[u], acc[7]);
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < kSmallRows; ++r) part[(q * kSmallRows + r) * kSmallCols + lane] = acc[r];
+  __syncthreads();
+  // wavefront r (< 8) finishes row r: the 16 partial sums in wavefront order
+  if (q < kSmallRows && col_ok && r0 + q < rows_w) {
+    float pv[kSmallWaves];
+#pragma unroll
+    for (int qq = 0; qq < kSmallWaves; ++qq) pv[qq] = part[(qq * kSmallRows + q) * kSmallCols + lane];
+    float v = pv[0];
+#pragma unroll
+    for (int qq = 1; qq < kSmallWaves; ++qq) v += pv[qq];
+    v += g.bias[n];
+    if (g.relu) v = fmaxf(v, 0.0f);
+    reinterpret_cast<float*>(g.c[w])[(r0 + q) * g.ldc + n] = v;
+  }
+}
+
+static inline size_t fwd_small_lds_bytes(int64_t K) {
+  return ((size_t)((K + 3) & ~(int64_t)3) * kSmallRows + (size_t)kSmallWaves * kSmallRows * kSmallCols) * 4;
+}
+
 // ------------------------------------------------------- narrow last layer dW
 // dW_L[w] = H_{L-1}[w]^T dZ_L[w] and db_L[w] for a last layer of at most 16 outputs: a 10-column
 // product leaves the matrix cores nothing to do and its rows (20 bytes) take no vector loads, so it is
-// plain multiply-adds.  A workgroup of 512 threads owns one worker and 128 of the K inputs: thread
-// (kk, rg) walks the rows rg, rg+4, ... of the worker for input kk, the row's dZ_L (padded to 16 floats)
-// read from LDS at one address for all threads; the four row groups are then added in a fixed order.
+// plain multiply-adds.  A workgroup of 512 threads owns one worker and KB = 128 (or 32) of the K inputs:
+// thread (kk, rg) walks the rows rg, rg + RG, ... of the worker for input kk (RG = 512 / KB row groups),
+// the row's dZ_L (padded to 16 floats) read from LDS at one address for all threads; the row groups
+// are then added in a fixed order.
 // The workgroup after the last one turns the row losses into the workers' slice-aggregated losses.
 constexpr int kNarrowMaxC = 16, kNarrowKB = 128, kNarrowRows = 256;
 constexpr int64_t kNarrowMaxRows = 1024;   // rows a worker may have: one workgroup walks them all for its 128 inputs
 __host__ __device__ constexpr int dw_narrow_lds_words() { return kNarrowRows * 16 + 4 * 16 * kNarrowKB; }
 
-static inline unsigned dw_narrow_blocks(int64_t K, int n_workers) {
-  return (unsigned)(n_workers * ((K + kNarrowKB - 1) / kNarrowKB) + 1);
+// KB: inputs a workgroup owns, 128 or 32 (with few workers and inputs, 32: four times the workgroups,
+// sixteen row groups instead of four)
+static inline int dw_narrow_kb(int64_t K, int n_workers) {
+  return n_workers * ((K + kNarrowKB - 1) / kNarrowKB) < 64 ? 32 : kNarrowKB;
+}
+static inline unsigned dw_narrow_blocks(int64_t K, int n_workers, int KB) {
+  return (unsigned)(n_workers * ((K + KB - 1) / KB) + 1);
 }
 
 template <typename T>
-__device__ __forceinline__ void dw_narrow_body(const GemmArgs& g, unsigned b, int n_workers,
+__device__ __forceinline__ void dw_narrow_body(const GemmArgs& g, unsigned b, int n_workers, int KB,
                                                uint32_t* __restrict__ smem) {
   const int K = (int)g.m_fixed, C = (int)g.n;
-  const int kb = (K + kNarrowKB - 1) / kNarrowKB;
+  const int kb = (K + KB - 1) / KB;
   if (b >= (unsigned)(n_workers * kb)) {
     if (b == (unsigned)(n_workers * kb) && g.task_z >= 0) {
       float* s_mean = reinterpret_cast<float*>(smem);
@@ -987,11 +1078,12 @@ __device__ __forceinline__ void dw_narrow_body(const GemmArgs& g, unsigned b, in
     }
     return;
   }
-  const int w = b / kb, k0 = (b % kb) * kNarrowKB;
+  const int w = b / kb, k0 = (b % kb) * KB;
+  const int RG = kGemmThreads / KB;                       // row groups: 4 or 16
   const int64_t rows_w = g.row_off[w + 1] - g.row_off[w];
   float* sdz = reinterpret_cast<float*>(smem);          // [kNarrowRows][16]: a chunk of the worker's dZ_L rows
-  float* sred = sdz + kNarrowRows * 16;                 // [4 row groups][16][kNarrowKB]
-  const int t = threadIdx.x, kk = t & (kNarrowKB - 1), rg = t / kNarrowKB;
+  float* sred = sdz + kNarrowRows * 16;                 // [row groups][16][KB]
+  const int t = threadIdx.x, kk = t % KB, rg = t / KB;
   const bool live = k0 + kk < K;
   const T* H = reinterpret_cast<const T*>(g.a[w]) + k0 + (live ? kk : 0);   // a dead thread reads input k0, unused
   const T* dZ = reinterpret_cast<const T*>(g.b) + g.row_off[w] * g.ldb;
@@ -1007,18 +1099,27 @@ __device__ __forceinline__ void dw_narrow_body(const GemmArgs& g, unsigned b, in
       const int r = e >> 4, c = e & 15;
       sdz[e] = c < C ? to_f32(dZ[(r0 + r) * g.ldb + c]) : 0.0f;
     }
-    __syncthreads();
-    // eight of this thread's rows at a time: the loads first, then the multiply-adds, in row order
-    for (int rb = rg; rb < nr; rb += 32) {
-      float h[8];
+    // eight of this thread's rows at a time: the loads first, then the multiply-adds, in row order; the
+    // first batch is asked for before the barrier that publishes the dZ chunk (rows past the end are
+    // clamped into the chunk and not used)
+    float h[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int r = rb + 4 * u;
-        h[u] = to_f32(H[(r0 + (r < nr ? r : rb)) * g.lda]);
+    for (int u = 0; u < 8; ++u) {
+      const int r = rg + RG * u;
+      h[u] = to_f32(H[(r0 + (r < nr ? r : nr - 1)) * g.lda]);
+    }
+    __syncthreads();                                    // the dZ chunk is in LDS
+    for (int rb = rg; rb < nr; rb += 8 * RG) {
+      if (rb != rg) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int r = rb + RG * u;
+          h[u] = to_f32(H[(r0 + (r < nr ? r : nr - 1)) * g.lda]);
+        }
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        const int r = rb + 4 * u;
+        const int r = rb + RG * u;
         if (r < nr) {
           const float* d = sdz + r * 16;
 #pragma unroll
@@ -1030,14 +1131,13 @@ __device__ __forceinline__ void dw_narrow_body(const GemmArgs& g, unsigned b, in
       for (int r = 0; r < nr; ++r) bsum += sdz[r * 16 + t];
   }
 #pragma unroll
-  for (int c = 0; c < 16; ++c) sred[(rg * 16 + c) * kNarrowKB + kk] = acc[c];
+  for (int c = 0; c < 16; ++c) sred[(rg * 16 + c) * KB + kk] = acc[c];
   __syncthreads();
   float* Cw = reinterpret_cast<float*>(g.c[w]);
   if (rg == 0 && live) {
     for (int c = 0; c < C; ++c) {
-      float v = sred[c * kNarrowKB + kk];
-#pragma unroll
-      for (int q = 1; q < 4; ++q) v += sred[(q * 16 + c) * kNarrowKB + kk];
+      float v = sred[c * KB + kk];
+      for (int q = 1; q < RG; ++q) v += sred[(q * 16 + c) * KB + kk];
       Cw[(int64_t)(k0 + kk) * g.ldc + c] = v;
     }
   }
@@ -1045,9 +1145,9 @@ __device__ __forceinline__ void dw_narrow_body(const GemmArgs& g, unsigned b, in
 }
 
 template <typename T>
-__global__ __launch_bounds__(kGemmThreads) void mlp_dw_narrow_kernel(GemmArgs g, int n_workers) {
+__global__ __launch_bounds__(kGemmThreads) void mlp_dw_narrow_kernel(GemmArgs g, int n_workers, int KB) {
   __shared__ __attribute__((aligned(16))) uint32_t smem[dw_narrow_lds_words()];
-  dw_narrow_body<T>(g, blockIdx.x, n_workers, smem);
+  dw_narrow_body<T>(g, blockIdx.x, n_workers, KB, smem);
 }
 
 // ------------------------------------------------------- backward group
@@ -1091,7 +1191,7 @@ __global__ __launch_bounds__(kGemmThreads, 4) void mlp_backward_group_kernel(Gro
   unsigned b = blockIdx.x;
   if (ga.dwl_narrow) {
     if (b < ga.n_dwl) {
-      dw_narrow_body<T>(ga.dwl, b, ga.n_workers, smem);
+      dw_narrow_body<T>(ga.dwl, b, ga.n_workers, kNarrowKB, smem);
       return;
     }
     b -= ga.n_dwl;
@@ -1114,6 +1214,36 @@ __global__ __launch_bounds__(kGemmThreads, 4) void mlp_backward_group_kernel(Gro
   b -= ga.n_dwp;
   if (!ga.dwl_narrow && b < ga.dwl_gx * ga.dwl_gy * ga.dwl_gz)
     gemm_tile<T, MODE_DW, 64, 64, BKS, true, AL_B_LAST>(ga.dwl, b, ga.dwl_gx, ga.dwl_gy, ga.dwl_gz, smem);
+}
+
+// dW_L of a narrow last layer and dW_{L-1} in one launch (two-layer networks, where no dX lies between
+// them: the last-layer kernel has already produced dZ_{L-1}).
+struct PairArgs {
+  GemmArgs narrow;   // dW_L (+ the slice losses)
+  GemmArgs dw;       // dW_{L-1}: 64 x 64 tiles
+  unsigned n_narrow; // workgroups of the first part, a multiple of 8
+  unsigned gx, gy, gz;
+  int n_workers, kb;
+};
+
+template <typename T>
+__host__ __device__ constexpr int pair_lds_words() {
+  constexpr int BKS = sizeof(T) == 2 ? 64 : 32;
+  return dw_narrow_lds_words() > gemm_lds_words<T, MODE_DW, 64, 64, BKS>() ? dw_narrow_lds_words()
+                                                                           : gemm_lds_words<T, MODE_DW, 64, 64, BKS>();
+}
+
+template <typename T>
+__global__ __launch_bounds__(kGemmThreads, 2) void mlp_dw_pair_kernel(PairArgs pa) {
+  constexpr int BKS = sizeof(T) == 2 ? 64 : 32;
+  __shared__ __attribute__((aligned(16))) uint32_t smem[pair_lds_words<T>()];
+  unsigned b = blockIdx.x;
+  if (b < pa.n_narrow) {
+    dw_narrow_body<T>(pa.narrow, b, pa.n_workers, pa.kb, smem);
+    return;
+  }
+  b -= pa.n_narrow;
+  if (b < pa.gx * pa.gy * pa.gz) gemm_tile<T, MODE_DW, 64, 64, BKS, true, true>(pa.dw, b, pa.gx, pa.gy, pa.gz, smem);
 }
 
 // ---------------------------------------------------------------- softmax CE
@@ -1624,9 +1754,17 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
     g.a_vec = (K % V == 0) && (l == 1 ? x_vec : true);
     g.b_vec = (N % V == 0) && aligned_to(W, 16);
     g.c_vec = N % 8 == 0;     // workspace rows: 256-byte aligned base, rows a multiple of 16 bytes
-    if (int rc = launch_gemm<T, MODE_FWD>(g, p.max_rows, n_workers, s,
-                                          l == 1 ? SYNK_KERNEL_MAIN : SYNK_KERNEL_MLP_FORWARD(l)))
-      return rc;
+    const int fwd_id = l == 1 ? SYNK_KERNEL_MAIN : SYNK_KERNEL_MLP_FORWARD(l);
+    // fp32 with so few rows that 64 x 64 tiles would occupy under a quarter of the CUs: multiply-add kernel
+    if (sizeof(T) == 4 && K <= kSmallMaxK && ((p.max_rows + 63) / 64) * ((N + 63) / 64) * n_workers < kNumCU / 4) {
+      const int row_tiles = (int)((p.max_rows + kSmallRows - 1) / kSmallRows);
+      const int col_tiles = (int)((N + kSmallCols - 1) / kSmallCols);
+      SYNK_LAUNCH_TIMED_AS(fwd_id, mlp_fwd_small_kernel, dim3((unsigned)(row_tiles * col_tiles), n_workers),
+                           dim3(64 * kSmallWaves), fwd_small_lds_bytes(K), s, g, row_tiles, col_tiles);
+      SYNK_LAUNCH_CHECK();
+      continue;
+    }
+    if (int rc = launch_gemm<T, MODE_FWD>(g, p.max_rows, n_workers, s, fwd_id)) return rc;
   }
 
   // ---- loss and dZ_L
@@ -1748,7 +1886,7 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
       ga.dwl_gx = (unsigned)((ga.dwl.n + 63) / 64);
       ga.dwl_gy = (unsigned)((p.d[L - 1] + 63) / 64);
       ga.dwl_gz = (unsigned)(n_workers + 1);
-      ga.n_dwl = ga.dwl_narrow ? (dw_narrow_blocks(p.d[L - 1], n_workers) + 7u) / 8u * 8u
+      ga.n_dwl = ga.dwl_narrow ? (dw_narrow_blocks(p.d[L - 1], n_workers, kNarrowKB) + 7u) / 8u * 8u
                                : ga.dwl_gx * ga.dwl_gy * ga.dwl_gz;
       const dim3 grid(ga.n_dx + ga.n_dwp + ga.n_dwl);
       if (al_last == 2)
@@ -1764,8 +1902,36 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
   for (; l >= 1; --l) {
     fill_dw(g, l, l == L);
     if (l == L && p.d[L] <= kNarrowMaxC && p.max_rows <= kNarrowMaxRows) {
-      SYNK_LAUNCH_TIMED_AS(SYNK_KERNEL_MLP_DW(l), (mlp_dw_narrow_kernel<T>), dim3(dw_narrow_blocks(p.d[L - 1], n_workers)),
-                           dim3(kGemmThreads), 0, s, g, n_workers);
+      const int KB = dw_narrow_kb(p.d[L - 1], n_workers);
+      if (use_head && l >= 2) {
+        // no dX of layer L is needed (the last-layer kernel made dZ_{L-1}): dW_{L-1} shares the launch when it
+        // takes 64 x 64 tiles with vector loads
+        PairArgs pa;
+        pa.narrow = g;
+        pa.dw = g;
+        fill_dw(pa.dw, l - 1, false);
+        if (gemm_alignment(pa.dw) == 2 && !dw_persistent_ok<T>(pa.dw, p.d[l - 2], n_workers) &&
+            big_tiles(pa.dw, p.d[l - 2], n_workers) < 2 * kNumCU) {
+          pa.n_narrow = (dw_narrow_blocks(p.d[L - 1], n_workers, KB) + 7u) / 8u * 8u;
+          pa.gx = (unsigned)((pa.dw.n + 63) / 64);
+          pa.gy = (unsigned)((p.d[l - 2] + 63) / 64);
+          pa.gz = (unsigned)n_workers;
+          pa.n_workers = n_workers;
+          pa.kb = KB;
+          SYNK_LAUNCH_TIMED_AS(SYNK_KERNEL_MLP_BACKWARD_GROUP, (mlp_dw_pair_kernel<T>),
+                               dim3(pa.n_narrow + pa.gx * pa.gy * pa.gz), dim3(kGemmThreads), 0, s, pa);
+          SYNK_LAUNCH_CHECK();
+          g.task_z = -1;
+          if (l - 1 > 1) {
+            fill_dx(g, l - 1);
+            if (int rc = launch_gemm<T, MODE_DX>(g, p.max_rows, n_workers, s, SYNK_KERNEL_MLP_DX(l - 1))) return rc;
+          }
+          --l;          // layer l-1 is done too
+          continue;
+        }
+      }
+      SYNK_LAUNCH_TIMED_AS(SYNK_KERNEL_MLP_DW(l), (mlp_dw_narrow_kernel<T>), dim3(dw_narrow_blocks(p.d[L - 1], n_workers, KB)),
+                           dim3(kGemmThreads), 0, s, g, n_workers, KB);
       SYNK_LAUNCH_CHECK();
       g.task_z = -1;
       if (l > 1 && !use_head) {
