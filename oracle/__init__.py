@@ -39,7 +39,8 @@ hand-worked single elements where they do not, torch.bfloat16 casts) and the pap
 invariant (Sec. 1.1): aggregating independent calls over any subdivision of
 the data equals the one full-batch call.
 
-Parity unpinned: mlp.function and convblock.function with bf16_points=True beyond (a) the rounding
-primitive, pinned against torch.bfloat16, and (b) staying close to the float64
-result (loss within 2e-2, gradient within 1e-1 in the Frobenius norm).
+The bfloat16 modes (mlp.function and convblock.function with bf16_points=True) are
+pinned too: a scalar-loop twin with its own rounding routine (brute.py) for the MLP,
+torch autograd with rounded operands for the block, each with negative cases in which
+one rounding point is dropped, added or moved.  No function here is unpinned.
 """
