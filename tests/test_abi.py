@@ -304,3 +304,25 @@ def test_profile_next_launch_argument_checks():
     assert f(FAKE, None) == -1 and f(None, FAKE) == -1
     assert f(FAKE, FAKE + 8) == 0
     assert f(None, None) == 0          # cancels the pending pair: nothing is left for a later launch
+
+
+def test_profile_next_launch_of_selects_a_kernel_and_reports_pending():
+    f, pending = lib.synk_profile_next_launch_of, lib.synk_profile_pending
+    assert pending() == 0
+    assert f(synk.SYNK_KERNEL_MLP_FORWARD(2), FAKE, None) == -1
+    assert f(-1, FAKE, FAKE + 8) == -2
+    assert f(synk.SYNK_KERNEL_MLP_FORWARD(2), FAKE, FAKE + 8) == 0 and pending() == 1
+    assert f(synk.SYNK_KERNEL_MAIN, None, None) == 0 and pending() == 0
+
+
+def test_probe_launch_argument_checks():
+    f = lib.synk_probe_launch
+    work = ctypes.c_double(0.0)
+    assert f(0, None, 64, 10, ctypes.byref(work), None) == -1
+    assert f(0, FAKE, 64, 10, None, None) == -1
+    assert f(0, FAKE, 64, 0, ctypes.byref(work), None) == -2
+    assert f(1, FAKE + 4, 1 << 20, 1, ctypes.byref(work), None) == -2          # misaligned buffer
+    assert f(0, FAKE, 2, 10, ctypes.byref(work), None) == -6                    # buffer too small
+    assert f(2, FAKE, 1 << 16, 48, ctypes.byref(work), None) == -6              # window of 768 KB not covered
+    assert f(2, FAKE, 1 << 20, 49, ctypes.byref(work), None) == -6              # more steps than the window holds
+    assert f(7, FAKE, 1 << 20, 1, ctypes.byref(work), None) == -9

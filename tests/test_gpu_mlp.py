@@ -378,3 +378,26 @@ def test_step_captured_in_a_graph_replays_like_eager_steps(synk):
         assert torch.equal(graphed.v, eager.v), it
         assert torch.equal(graphed.p_lp, eager.p_lp), it
         assert torch.equal(graphed.loss_out, eager.loss_out), it
+
+
+def test_profile_hook_selects_kernels_of_the_sliced_gradient(synk):
+    """An event pair handed in for one kernel of synk_sliced_grad is attached to that launch and to no
+    other: it is consumed when the call launches the kernel and stays pending when it does not."""
+    cfg = workloads.config2(n_data=1000, batch=256, dims=(128, 64, 64, 10), n_workers=2, n_slices=2)
+    st = Step(synk, cfg)
+    st.gather(cfg["idx"], 2)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(); b.record()
+    torch.cuda.synchronize()
+    ref, _ = st.sliced_grad(2, "mean")
+    for kernel, launched in [(synk.SYNK_KERNEL_MAIN, True), (synk.SYNK_KERNEL_MLP_FORWARD(2), True),
+                             (synk.SYNK_KERNEL_MLP_HEAD, True), (synk.SYNK_KERNEL_MLP_DW(1), True),
+                             (synk.SYNK_KERNEL_MLP_FORWARD(3), False), (synk.SYNK_KERNEL_MLP_DX(7), False)]:
+        synk.synk_profile_next_launch_of(kernel, a, b)
+        got, _ = st.sliced_grad(2, "mean")
+        assert synk.synk_profile_pending() == (not launched), kernel
+        synk.synk_profile_next_launch_of(kernel, None, None)
+        assert not synk.synk_profile_pending()
+        if launched:
+            assert 0.0005 < a.elapsed_time(b) < 1.0, kernel
+        assert all(np.array_equal(x, y) for x, y in zip(got, ref))       # a timed launch computes the same

@@ -699,3 +699,15 @@ def test_config5_full_size_properties_and_sampled_rows(synk):
     assert got["max_logit"][0] == logits.max() and got["min_logit"][0] == logits.min()
     ce = (scipy.special.logsumexp(logits.astype(np.float64), axis=1) - logits[np.arange(65536), labels]).sum()
     assert abs(got["ce_sum"][0] - ce) < TOL_F32 * abs(ce)
+
+
+def test_peak_probes_run_and_report_their_work(synk):
+    buf = torch.zeros(1 << 20, device="cuda")                         # 4 MiB
+    assert synk.synk_probe_launch(synk.SYNK_PROBE_MFMA_BF16, buf, 10) == 512 * 8 * 10 * 4 * 32768.0
+    assert synk.synk_probe_launch(synk.SYNK_PROBE_FILL, buf, 1) == float(4 << 20)
+    torch.cuda.synchronize()
+    assert torch.equal(buf.view(-1, 4), torch.tensor([1.0, 2.0, 3.0, 4.0], device="cuda").expand(1 << 18, 4))
+    before = buf.clone()
+    assert synk.synk_probe_launch(synk.SYNK_PROBE_LDS_FETCH, buf, 48) == 256 * 48 * 16384.0
+    torch.cuda.synchronize()
+    assert torch.equal(buf, before)                                   # the fetch probe only reads
