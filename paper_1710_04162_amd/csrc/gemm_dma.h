@@ -33,9 +33,20 @@ enum { FWD = 0, DX = 1 };
 
 // 16 bytes a lane from global memory straight into LDS at lds_addr + lane*16
 // (lds_addr wave-uniform).  Assembly, so that the compiler does not order later
-// LDS reads behind it: completion is waited for by hand (vmcnt).
+// LDS reads behind it: completion is waited for by hand (vmcnt).  The instruction
+// takes the LDS address from M0, a register the compiler manages: its value is
+// put back before the statement ends.
 __device__ __forceinline__ void load_to_lds16(const void* gptr, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+  unsigned saved_m0;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %2\n\t"
+      "global_load_lds_dwordx4 %1, off\n\t"
+      "s_nop 0\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(saved_m0)
+      : "v"(gptr), "s"(lds_addr)
+      : "memory");
 }
 
 // swizzle of a row whose contraction index is contiguous (rows of 128 bytes, 8 pieces)

@@ -51,7 +51,10 @@ __global__ __launch_bounds__(512) void probe_fetch_kernel(const char* __restrict
   for (int s = 0; s < steps; ++s) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(p[j]), "s"(lds0 + (s & 3) * 16384 + 8 * j * 1024)
+      unsigned saved_m0;   // M0 is the compiler's register: put back before the statement ends
+      asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %1, off\n\ts_nop 0\n\ts_mov_b32 m0, %0"
+                   : "=&s"(saved_m0)
+                   : "v"(p[j]), "s"(lds0 + (s & 3) * 16384 + 8 * j * 1024)
                    : "memory");
       p[j] += 128;
     }
