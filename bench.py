@@ -668,7 +668,7 @@ def main():
     wl = {0: lambda: (ProbeStep(torch, synk, a.probe) if a.probe else CopyStep(torch, synk)), 1: lambda: MlpStep(torch, synk, 1, a.batch), 2: lambda: MlpStep(torch, synk, 2, a.batch, a.rows_per_worker),
           3: lambda: (CollectiveStep(torch, synk, a.collective) if a.collective else ReduceStep(torch, synk, a.rule)), 4: lambda: GatherStep(torch, synk, a.indexing),
           5: lambda: EvalStep(torch, synk), 6: lambda: ConvStep(torch, synk, a.conv_shape)}[a.config]()
-    steps = a.steps if a.steps is not None else {0: 50, 1: 2000, 2: 1000, 3: 300, 4: 1000, 5: 1000, 6: 300}[a.config]
+    steps = a.steps if a.steps is not None else {0: 50, 1: 5000, 2: 4500, 3: 2800, 4: 5000, 5: 5000, 6: 3200}[a.config]   # >= 0.5 s a repeat
     if a.rows_per_worker is not None and a.steps is None:
         steps = 56
     warmup = a.warmup if a.warmup is not None else 20

@@ -71,21 +71,31 @@ __host__ __device__ constexpr int lds_bytes() { return NS * (BM + BN) * 128; }
 
 // Workgroup `lin` of a grid of tiles_m x tiles_n tiles whose first workgroup sits
 // on XCD 0 (workgroups go to the 8 XCDs round-robin): each XCD, i.e. each L2,
-// gets a compact block of tiles so that it fetches few operand slabs.
+// gets a compact block of tiles.  The 8 XCDs are arranged xr x xc over the tile
+// grid (xr * xc = 8, both dividing the grid) so that the operand rows an XCD
+// fetches, (tiles_m / xr) * BM of A plus (tiles_n / xc) * BN of B, are fewest.
+template <int BM, int BN>
 __device__ __forceinline__ void tile_of(unsigned lin, int tiles_m, int tiles_n, int* bm, int* bn) {
-  const int xcd = lin & 7, idx = lin >> 3;
-  if ((tiles_m & 1) == 0 && (tiles_n & 3) == 0) {
-    const int bw = tiles_n >> 2, bh = tiles_m >> 1;
-    *bm = (xcd >> 2) * bh + idx / bw;
-    *bn = (xcd & 3) * bw + idx % bw;
-  } else if ((tiles_m & 3) == 0 && (tiles_n & 1) == 0) {
-    const int bw = tiles_n >> 1, bh = tiles_m >> 2;
-    *bm = (xcd >> 1) * bh + idx / bw;
-    *bn = (xcd & 1) * bw + idx % bw;
-  } else {
+  int best_xr = 0;
+  long best = -1;
+#pragma unroll
+  for (int xr = 1; xr <= 8; xr *= 2) {
+    const int xc = 8 / xr;
+    if (tiles_m % xr == 0 && tiles_n % xc == 0) {
+      const long cost = (long)(tiles_m / xr) * BM + (long)(tiles_n / xc) * BN;
+      if (best < 0 || cost < best) { best = cost; best_xr = xr; }
+    }
+  }
+  if (best_xr == 0) {            // the grid does not divide over 8 XCDs: plain order
     *bm = lin / tiles_n;
     *bn = lin % tiles_n;
+    return;
   }
+  const int xr = best_xr, xc = 8 / xr;
+  const int xcd = lin & 7, idx = lin >> 3;
+  const int bh = tiles_m / xr, bw = tiles_n / xc;
+  *bm = (xcd / xc) * bh + idx / bw;
+  *bn = (xcd % xc) * bw + idx % bw;
 }
 
 // One BM x BN output tile.  Preconditions (checked on the host): K % 64 == 0,
@@ -108,7 +118,7 @@ __device__ __forceinline__ void tile(const ArgsT& g, unsigned lin, int tiles_m, 
   const int wm = wq >> 1, wn = wq & 1;
   const int x = lane & 31, gk = lane >> 5;
   int bm, bn;
-  tile_of(lin, tiles_m, tiles_n, &bm, &bn);
+  tile_of<BM, BN>(lin, tiles_m, tiles_n, &bm, &bn);
   const int64_t row0 = (int64_t)bm * BM;               // first packed row of the tile
   const int n0 = bn * BN;
   int w = 0;
