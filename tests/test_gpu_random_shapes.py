@@ -217,3 +217,39 @@ def test_sliced_grad_random_shapes(synk, dims, B, N, S, op, bf16):
         rl = omlp.aggregate_slices(ls, ns, op)
         assert rel_err_either_tie(g, ref, alt, dims, skip) < tol, (w, dims)
         assert abs(loss[w].item() - rl) < tol * max(abs(rl), 1e-6)
+
+
+# ------------------------------------------------------------- maximum worker count
+def test_maximum_worker_count_through_the_whole_step(synk):
+    """SYNK_MAX_WORKERS = 64 workers: gather, sliced gradient, N-way reduce fused with the update, all-reduce."""
+    N, S, B = synk.SYNK_MAX_WORKERS, 2, 200               # shares of 4 and 3 rows
+    dims = [24, 16, 10]
+    rng = np.random.default_rng(64)
+    data = rng.standard_normal((300, dims[0])).astype(np.float32)
+    labels = rng.integers(0, dims[-1], 300).astype(np.int32)
+    theta = workloads.mlp_init(dims, rng) + (rng.standard_normal(workloads.mlp_param_count(dims)) * 0.05).astype(np.float32)
+    idx = rng.integers(0, 300, B).astype(np.int32)
+    P = synk.synk_mlp_param_count(dims)
+    rows = lib_share_sizes(synk, B, N)
+    assert rows == osplit.share_sizes(B, N) and len(rows) == 64
+    x = [torch.zeros((n, dims[0]), device="cuda") for n in rows]
+    y = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in rows]
+    synk.synk_gather_rows(dev(data), dev(idx), x, labels=dev(labels), dst_labels=y)
+    p, v = dev(theta), torch.zeros(P, device="cuda")
+    grad = [torch.full((P,), 9.0, device="cuda") for _ in rows]
+    loss, loss_out = torch.zeros(N, device="cuda"), torch.zeros(1, device="cuda")
+    ws = torch.empty(synk.synk_sliced_grad_workspace_bytes(dims, synk.SYNK_F32, rows), dtype=torch.uint8, device="cuda")
+    synk.synk_sliced_grad(dims, synk.SYNK_F32, p, None, x, y, rows, S, synk.SYNK_MEAN, grad, loss, ws)
+    ref = omlp.sliced(theta, dims, data, labels, idx, N, S)
+    for w in range(N):
+        assert rel_err(grad[w].cpu().numpy(), ref["worker_grads"][w]) < TOL_F32, w
+    synk.synk_reduce_sgd_update(grad, p, v, 0.01, 0.9, 0.0, loss_in=loss, loss_out=loss_out)
+    rp, rv, _, rl = oupdate.reduce_and_update(theta, np.zeros(P), ref["worker_grads"], 0.01, 0.9, 0.0, None,
+                                              ref["worker_losses"])
+    assert rel_err(p.cpu().numpy(), rp) < TOL_F32 and rel_err(v.cpu().numpy(), rv) < TOL_F32
+    assert abs(loss_out.item() - rl) < TOL_F32 * abs(rl)
+    synk.synk_all_reduce(grad, "sum")
+    want = oreduce.reduce_buffers([g for g in ref["worker_grads"]], "sum")
+    assert rel_err(grad[63].cpu().numpy(), want) < TOL_F32 and all(torch.equal(g, grad[0]) for g in grad[1:])
+    with pytest.raises(synk.SynkError):                   # one more than the maximum is refused, nothing is launched
+        synk.synk_reduce_buffers(grad + [grad[0]], synk.SYNK_SUM, torch.zeros(P, device="cuda"))
