@@ -63,11 +63,13 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="capture the steps (one per rotating input set) into one HIP graph and time its replays; "
                          "the dominant kernel is then timed in a short eager pass before the timed region")
-    ap.add_argument("--probe", default=None, choices=["mfma", "fill", "fetch"],
+    ap.add_argument("--probe", default=None, choices=["mfma", "fill", "fetch", "read"],
                     help="config 0 only: instead of the copy, one of the library's peak probes (register-resident bf16 "
                          "MFMA loop; plain 16-byte stores over 1 GiB; operand tiles from L2 straight into LDS)")
     ap.add_argument("--repeats", type=int, default=5,
                     help="the K timed steps are run this many times; value and ms_per_step are the median repeat's")
+    ap.add_argument("--sample-every", type=int, default=None,
+                    help="put the per-kernel event pair on every N-th step only (default 8; 1 below 64 steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -94,9 +96,12 @@ def host_threads():
 class Timer:
     """HIP events attached to launches inside the timed region: the library puts the pair on the selected
     kernel's own dispatch (begin and end timestamps of that kernel on the launch stream).  A step arms at
-    most one pair, for one named target; targets rotate over the steps."""
+    most one pair, for one named target; targets rotate over the sampled steps.  Only every `every`-th
+    step is sampled: a dispatch that carries events costs about 4 us more than one that does not (measured:
+    config 5 at 53.4 us a call with a pair on every call, 49.4 without any), and that cost belongs to the
+    measurement, not to the step."""
 
-    def __init__(self, torch, synk, n):
+    def __init__(self, torch, synk, n, every=1):
         # events are created before the timed region: creating one costs more than a launch
         # (torch creates the underlying event at the first record)
         self.synk = synk
@@ -106,11 +111,15 @@ class Timer:
             a.record()
             b.record()
         torch.cuda.synchronize()
-        self.used, self.on, self.samples = 0, False, {}
+        self.used, self.on, self.samples, self.every = 0, False, {}, max(1, every)
+
+    def due(self, i):
+        """True when step i is one of the sampled steps."""
+        return self.on and i % self.every == 0
 
     def bracket(self, fn, name="dominant", kernel=0):
         """Runs fn(); with the timer on, the launch of `kernel` inside it carries the next event pair."""
-        if self.on and self.used < len(self.pool):
+        if self.used < len(self.pool):
             a, b = self.pool[self.used]
             self.used += 1
             self.synk.synk_profile_next_launch_of(kernel, a, b)
@@ -244,8 +253,13 @@ class MlpStep:
         return targets, work
 
     def step(self, i, timer):
-        name, call, kernel = self.targets[i % len(self.targets)]
         gather = self.call_gather[i % len(self.call_gather)]
+        if not timer.due(i):
+            gather()
+            self.call_grad()
+            self.call_update()
+            return
+        name, call, kernel = self.targets[(i // timer.every) % len(self.targets)]
         if call == "gather":
             timer.bracket(gather, name, kernel)
         else:
@@ -338,7 +352,10 @@ class ReduceStep:
     cycle = 3
 
     def step(self, i, timer):
-        timer.bracket(self.calls[i % 3])
+        if timer.due(i):
+            timer.bracket(self.calls[i % 3])
+        else:
+            self.calls[i % 3]()
 
     def cpu_baseline(self):
         from oracle import reduce as oreduce, update as oupdate
@@ -388,7 +405,10 @@ class CollectiveStep:
         self.workload = "config 3 shape (8 x 25,557,032 fp32): " + what
 
     def step(self, i, timer):
-        timer.bracket(self.call)
+        if timer.due(i):
+            timer.bracket(self.call)
+        else:
+            self.call()
 
     def cpu_baseline(self):
         from oracle import collectives as ocoll
@@ -465,7 +485,10 @@ class GatherStep:
     cycle = 64
 
     def step(self, i, timer):
-        timer.bracket(self.calls[i % 64])
+        if timer.due(i):
+            timer.bracket(self.calls[i % 64])
+        else:
+            self.calls[i % 64]()
 
     def cpu_baseline(self):
         from oracle import gather as og
@@ -514,7 +537,10 @@ class EvalStep:
     cycle = 4
 
     def step(self, i, timer):
-        timer.bracket(self.calls[i % 4])
+        if timer.due(i):
+            timer.bracket(self.calls[i % 4])
+        else:
+            self.calls[i % 4]()
 
     def cpu_baseline(self):
         from oracle import evalops
@@ -580,7 +606,10 @@ class ConvStep:
 
     def step(self, i, timer):
         self.call_gather[i % len(self.call_gather)]()
-        timer.bracket(self.call_grad)
+        if timer.due(i):
+            timer.bracket(self.call_grad)
+        else:
+            self.call_grad()
         self.call_update()
 
     def cpu_baseline(self):
@@ -610,6 +639,10 @@ class ProbeStep:
             self.buf, self.iters, pid = torch.empty(1 << 28, device="cuda"), 1, synk.SYNK_PROBE_FILL
             self.unit = "bytes/s"
             self.workload = "probe: 1 GiB of 16-byte stores, one per thread, in address order"
+        elif which == "read":
+            self.buf, self.iters, pid = torch.ones(1 << 28, device="cuda"), 1, synk.SYNK_PROBE_READ
+            self.unit = "bytes/s"
+            self.workload = "probe: 1 GiB of 16-byte loads, eight per thread, 32 KB a workgroup in address order"
         else:
             self.buf, self.iters, pid = torch.ones(2 << 20, device="cuda"), 48, synk.SYNK_PROBE_LDS_FETCH
             self.unit = "bytes/s"
@@ -624,7 +657,11 @@ class ProbeStep:
         self.dom_name = "probe_%s_kernel" % which
 
     def step(self, i, timer):
-        timer.bracket(lambda: self.s.synk_probe_launch(self.pid, self.buf, self.iters))
+        fn = lambda: self.s.synk_probe_launch(self.pid, self.buf, self.iters)
+        if timer.due(i):
+            timer.bracket(fn)
+        else:
+            fn()
 
     def cpu_baseline(self):
         return 0.0, "none"
@@ -646,7 +683,10 @@ class CopyStep:
     cycle = 2
 
     def step(self, i, timer):
-        timer.bracket(self.calls[i % 2])
+        if timer.due(i):
+            timer.bracket(self.calls[i % 2])
+        else:
+            self.calls[i % 2]()
 
     def cpu_baseline(self):
         return 0.0, "none"
@@ -705,7 +745,8 @@ def main():
             torch.cuda.synchronize()
             per_repeat.append(time.perf_counter() - t0)
     else:
-        timer = Timer(torch, synk, steps * repeats)
+        every = a.sample_every if a.sample_every else (8 if steps >= 64 else 1)
+        timer = Timer(torch, synk, steps * repeats // every + repeats + 1, every)
         for i in range(warmup):
             wl.step(i, timer)
         torch.cuda.synchronize()
@@ -740,7 +781,8 @@ def main():
         "roofline": {"bound": bound, "kernel": wl.dom_name, "achieved": achieved, "peak": peak,
                      "unit": unit, "frac": achieved / peak,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (a.rule == "momentum" and not a.collective and a.indexing == "list" and a.batch is None and not a.conv_shape and a.rows_per_worker is None) else None, "traffic_unit": "HBM bytes per launch",
-                     "bytes_per_launch": wl.dom_bytes, "ms_per_launch": dom_ms},
+                     "bytes_per_launch": wl.dom_bytes, "ms_per_launch": dom_ms,
+                     "events_on_every_nth_step": timer.every, "launches_timed": timer.used},
     }
     if hasattr(wl, "kernel_report"):
         # every kernel of the step, timed on its own dispatches inside the timed region (one target a step,

@@ -140,11 +140,17 @@ int synk_profile_pending(void);
  *   SYNK_PROBE_LDS_FETCH  256 workgroups, each bringing iters (<= 48) tiles of 128
  *                         rows x 128 bytes (row pitch 6 KB) from buf straight into
  *                         LDS; buf_bytes >= 768 KB, read only
+ *   SYNK_PROBE_READ       floor(buf_bytes / 32 KB) workgroups, each loading 32 KB in
+ *                         address order with 16-byte loads (eight per thread, all
+ *                         issued before the first use); buf: read only unless the
+ *                         XOR of a workgroup's words is 0x9e3779b9 (fill it with
+ *                         one repeated value); iters ignored
  * buf: device, 16-byte aligned.  Errors: NULL -> ERR_NULL; iters < 1, alignment ->
  * ERR_SHAPE; buffer too small -> ERR_WORKSPACE; unknown probe -> ERR_UNSUPPORTED. */
 #define SYNK_PROBE_MFMA_BF16 0
 #define SYNK_PROBE_FILL 1
 #define SYNK_PROBE_LDS_FETCH 2
+#define SYNK_PROBE_READ 3
 int synk_probe_launch(int probe, void* buf, size_t buf_bytes, int iters, double* work, void* stream);
 
 /* Host-side helper: the split rule above.  Writes parts+1 offsets

@@ -1,6 +1,6 @@
 // Measured peaks of the part, for the rooflines the benchmark reports: what the
-// matrix cores deliver from registers alone, what plain 16-byte stores reach,
-// and how fast a CU takes operand tiles from L2 straight into LDS.  Timing
+// matrix cores deliver from registers alone, what plain 16-byte stores and loads
+// reach, and how fast a CU takes operand tiles from L2 straight into LDS.  Timing
 // kernels only: they compute nothing of the method.  Every access stays inside
 // the caller's buffer (checked on the host).
 #include "common.h"
@@ -34,6 +34,18 @@ __global__ __launch_bounds__(512) void probe_mfma_kernel(float* __restrict__ sin
 __global__ __launch_bounds__(256) void probe_fill_kernel(f32x4* __restrict__ dst, int64_t units) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i < units) dst[i] = f32x4{1.0f, 2.0f, 3.0f, 4.0f};
+}
+
+// eight 16-byte loads per thread, all issued before the first use; a workgroup reads 32 KB in address order
+__global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict__ src, uint32_t* __restrict__ sink) {
+  const u32x4* p = src + (int64_t)blockIdx.x * 2048 + threadIdx.x;
+  u32x4 q[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) q[k] = __builtin_nontemporal_load(p + k * 256);
+  u32x4 x = q[0];
+#pragma unroll
+  for (int k = 1; k < 8; ++k) x ^= q[k];
+  if ((x.x ^ x.y ^ x.z ^ x.w) == 0x9e3779b9u) sink[0] = 1u;   // keeps the loads alive; the caller's data never gives this
 }
 
 // Every workgroup (8 wavefronts) streams tiles of 128 rows x 128 bytes (row pitch `pitch`) straight into a
@@ -89,6 +101,12 @@ extern "C" int synk_probe_launch(int probe, void* buf, size_t buf_bytes, int ite
     if (iters > 48 || buf_bytes < (size_t)(128 * pitch)) return SYNK_ERR_WORKSPACE;
     SYNK_LAUNCH_TIMED(probe_fetch_kernel, dim3(kNumCU), dim3(512), 0, s, reinterpret_cast<const char*>(buf), pitch, iters);
     *work = (double)kNumCU * (double)iters * 16384.0;                      // bytes brought into LDS
+  } else if (probe == SYNK_PROBE_READ) {
+    const int64_t blocks = (int64_t)(buf_bytes / 32768);
+    if (blocks < 1 || blocks > 0x7fffffff) return SYNK_ERR_SHAPE;
+    SYNK_LAUNCH_TIMED(probe_read_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
+                      reinterpret_cast<const u32x4*>(buf), reinterpret_cast<uint32_t*>(buf));
+    *work = (double)blocks * 32768.0;                                      // bytes loaded
   } else {
     return SYNK_ERR_UNSUPPORTED;
   }

@@ -23,13 +23,18 @@ constexpr int kRowsPerBlock = 32;
 // Rows of a workgroup of the branch-free kernel: 32 lanes a row, one row pair a wavefront.
 constexpr int kRegularG = 32, kRegularUPL = 8;
 constexpr int kRegularRows = kEWaves * (kWave / kRegularG);
+constexpr int kMaxClasses = 4096;
 
+// One workgroup's partial results: cross-entropy sum, max, min and (as bits) the
+// count of correct rows, in one 16-byte record so that stage 1 leaves them with one
+// store and stage 2 fetches them with one load.
 struct EvalWs {
-  float* part_ce;        // [S x CH]
-  float* part_max;       // [S x CH]
-  float* part_min;       // [S x CH]
-  int32_t* part_correct; // [S x CH]
+  f32x4* part;           // [S x CH] {ce, max, min, correct}
 };
+
+__device__ __forceinline__ f32x4 pack_partial(float ce, float mx, float mn, int correct) {
+  return f32x4{ce, mx, mn, __int_as_float(correct)};
+}
 
 // Workgroups (= partial results) a slice takes at rows_per_block rows each.
 static inline size_t eval_chunks(int64_t rows, int n_slices, int rows_per_block) {
@@ -41,15 +46,8 @@ static inline size_t eval_chunks(int64_t rows, int n_slices, int rows_per_block)
 static inline size_t eval_ws_layout(int64_t rows, int64_t classes, int n_slices, void* ws,
                                     EvalWs* out) {
   const size_t ch = eval_chunks(rows, n_slices, kRegularRows);   // the finest split any kernel uses
-  const size_t part = round_up((size_t)n_slices * ch * 4, 256);
-  if (out) {
-    char* b = reinterpret_cast<char*>(ws);
-    out->part_ce = reinterpret_cast<float*>(b);
-    out->part_max = reinterpret_cast<float*>(b + part);
-    out->part_min = reinterpret_cast<float*>(b + 2 * part);
-    out->part_correct = reinterpret_cast<int32_t*>(b + 3 * part);
-  }
-  return 4 * part;
+  if (out) out->part = reinterpret_cast<f32x4*>(ws);
+  return round_up((size_t)n_slices * ch * sizeof(f32x4), 1024);
 }
 
 // The first workgroup of stage 1 clears the class counts that stage 2 adds into
@@ -153,10 +151,7 @@ __global__ __launch_bounds__(kEBlock) void eval_stage1_generic_kernel(
       cor += s_cor[w];
     }
     const int64_t o = (int64_t)slice * chunks + chunk;
-    ws.part_ce[o] = ce;
-    ws.part_max[o] = mx;
-    ws.part_min[o] = mn;
-    ws.part_correct[o] = cor;
+    ws.part[o] = pack_partial(ce, mx, mn, cor);
   }
 }
 
@@ -269,10 +264,7 @@ __global__ __launch_bounds__(kEBlock) void eval_stage1_kernel(
       cor += s_cor[w];
     }
     const int64_t o = (int64_t)slice * chunks + chunk;
-    ws.part_ce[o] = ce;
-    ws.part_max[o] = mx;
-    ws.part_min[o] = mn;
-    ws.part_correct[o] = cor;
+    ws.part[o] = pack_partial(ce, mx, mn, cor);
   }
 }
 
@@ -285,9 +277,12 @@ __global__ __launch_bounds__(kEBlock) void eval_stage1_kernel(
 // rows of 1,000 classes: many short-lived workgroups of one set each stream
 // faster than longer ones that pipeline several sets through two register
 // buffers (G = 32, one set: 43.5 us; G = 16, one / two / four / eight sets:
-// 47.1 / 48.3 / 49.7 / 52.5 us), and 32 lanes a row beat 16 and 64.
+// 47.1 / 48.3 / 49.7 / 52.5 us), and 32 lanes a row beat 16 and 64.  The register
+// budget is set for five wavefronts per SIMD: whole call 45.1 us against 46.0 at the
+// seven the compiler picks by itself, 45.4 at six, 46.5 at four and 48.1 at eight
+// (16 rows per 512-thread workgroup: 45.1 as well).
 template <int G, int UPL>
-__global__ __launch_bounds__(kEBlock) void eval_stage1_regular_kernel(
+__global__ __launch_bounds__(kEBlock) __attribute__((amdgpu_waves_per_eu(1, 5))) void eval_stage1_regular_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ labels, int64_t rows, int classes,
     int n_slices, int chunks, EvalWs ws, int32_t* __restrict__ argmax_out, int32_t* __restrict__ class_counts) {
   constexpr int RW = kWave / G;            // rows a wavefront handles at once
@@ -382,36 +377,39 @@ __global__ __launch_bounds__(kEBlock) void eval_stage1_regular_kernel(
       cor += s_cor[w];
     }
     const int64_t o = (int64_t)slice * chunks + chunk;
-    ws.part_ce[o] = ce;
-    ws.part_max[o] = mx;
-    ws.part_min[o] = mnb;
-    ws.part_correct[o] = cor;
+    ws.part[o] = pack_partial(ce, mx, mnb, cor);
   }
 }
 
-// Stage 2.  All blocks but the last: a histogram of the rows' arg-max classes, built in LDS
-// over the block's share of the rows and added into class_counts (integer
-// sums: any order gives the same counts; summed over slices, the counts do not
-// depend on where the slices are cut).  The last block meanwhile (1024 threads): one
-// wavefront per slice folds that slice's chunk partials (lanes stride over
-// chunks, fixed shuffle tree), and the slice results are folded with each
-// output's op in slice order.
+// Stage 2.  Block 0 (dispatched first: it is the longer path) folds the partial
+// results: 16 lanes share a slice, every lane fetches its chunks' records in one
+// batch of 16-byte loads (eight at a time), a fixed 16-lane shuffle tree gives the
+// slice result, and the slice results are folded with each output's op in slice
+// order (per lane group, then over the 64 lane groups in order).  The other blocks
+// meanwhile: a histogram of the rows' arg-max classes, built in LDS over the
+// block's share of the rows and added into class_counts (integer sums: any order
+// gives the same counts; summed over slices, the counts do not depend on where
+// the slices are cut).  Measured on 65,536 rows in 64 slices (8,192 records),
+// time of the call beyond stage 1: an empty second launch 0.8 us, the histogram
+// blocks alone 2.2, a fold with one wavefront per slice and four 4-byte loads
+// per record 6.8, this fold 4.6 with 4-byte loads and 3.4 with 16-byte records.
 constexpr int kE2Block = 1024;
 constexpr int kE2RowsPerBlock = 2048;
-constexpr int kMaxClasses = 4096;
+constexpr int kFoldLanes = 16;                       // lanes that share a slice
+constexpr int kFoldPerWave = kWave / kFoldLanes;     // slices a wavefront folds at once
+constexpr int kFoldBatch = 8;                        // records a lane fetches before it uses the first
 
 __global__ __launch_bounds__(kE2Block) void eval_stage2_kernel(
     EvalWs ws, int64_t rows, int n_slices, int chunks, int classes,
     const int32_t* __restrict__ argmax, float* __restrict__ ce_sum,
     int32_t* __restrict__ class_counts, float* __restrict__ max_logit,
     float* __restrict__ min_logit, int32_t* __restrict__ n_correct) {
-  // the last block folds the partials while the others build the histogram
-  if (blockIdx.x + 1 != gridDim.x) {
+  if (blockIdx.x != 0) {
     __shared__ int32_t hist[kMaxClasses];
     for (int c = threadIdx.x; c < classes; c += kE2Block) hist[c] = 0;
     __syncthreads();
     const int64_t stride = (int64_t)(gridDim.x - 1) * kE2Block;
-    for (int64_t r = (int64_t)blockIdx.x * kE2Block + threadIdx.x; r < rows; r += stride) {
+    for (int64_t r = (int64_t)(blockIdx.x - 1) * kE2Block + threadIdx.x; r < rows; r += stride) {
       const int a = argmax[r];
       if ((unsigned)a < (unsigned)classes) atomicAdd(&hist[a], 1);
     }
@@ -423,23 +421,37 @@ __global__ __launch_bounds__(kE2Block) void eval_stage2_kernel(
     return;
   }
   constexpr int NW = kE2Block / kWave;
-  __shared__ float s_ce[NW], s_max[NW], s_min[NW];
-  __shared__ int s_cor[NW];
+  constexpr int NACC = NW * kFoldPerWave;            // lane groups of the block
+  __shared__ float s_ce[NACC], s_max[NACC], s_min[NACC];
+  __shared__ int s_cor[NACC];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  float ce = 0.0f, mx = -INFINITY, mn = INFINITY;   // this wavefront's slices, in slice order
+  const int sub = lane % kFoldLanes, grp = lane / kFoldLanes;
+  float ce = 0.0f, mx = -INFINITY, mn = INFINITY;   // this lane group's slices, in slice order
   int cor = 0;
-  for (int s = wave; s < n_slices; s += NW) {
+  for (int s0 = 0; s0 < n_slices; s0 += NACC) {
+    const int s = s0 + wave * kFoldPerWave + grp;
     float sce = 0.0f, smx = -INFINITY, smn = INFINITY;
     int scor = 0;
-    for (int k = lane; k < chunks; k += kWave) {
-      const int64_t o = (int64_t)s * chunks + k;
-      sce += ws.part_ce[o];
-      smx = fmaxf(smx, ws.part_max[o]);
-      smn = fminf(smn, ws.part_min[o]);
-      scor += ws.part_correct[o];
+    if (s < n_slices) {
+      const f32x4* rec = ws.part + (int64_t)s * chunks;
+      for (int k0 = sub; k0 < chunks; k0 += kFoldLanes * kFoldBatch) {
+        f32x4 q[kFoldBatch];
+#pragma unroll
+        for (int u = 0; u < kFoldBatch; ++u) {
+          const int k = k0 + u * kFoldLanes;
+          q[u] = k < chunks ? rec[k] : pack_partial(0.0f, -INFINITY, INFINITY, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < kFoldBatch; ++u) {
+          sce += q[u].x;
+          smx = fmaxf(smx, q[u].y);
+          smn = fminf(smn, q[u].z);
+          scor += __float_as_int(q[u].w);
+        }
+      }
     }
 #pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
+    for (int off = kFoldLanes / 2; off > 0; off >>= 1) {
       sce += __shfl_xor(sce, off);
       smx = fmaxf(smx, __shfl_xor(smx, off));
       smn = fminf(smn, __shfl_xor(smn, off));
@@ -450,17 +462,17 @@ __global__ __launch_bounds__(kE2Block) void eval_stage2_kernel(
     mn = fminf(mn, smn);    // op MIN
     cor += scor;            // op SUM (int)
   }
-  if (lane == 0) {
-    s_ce[wave] = ce;
-    s_max[wave] = mx;
-    s_min[wave] = mn;
-    s_cor[wave] = cor;
+  if (sub == 0) {
+    s_ce[wave * kFoldPerWave + grp] = ce;
+    s_max[wave * kFoldPerWave + grp] = mx;
+    s_min[wave * kFoldPerWave + grp] = mn;
+    s_cor[wave * kFoldPerWave + grp] = cor;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
     float tce = s_ce[0], tmx = s_max[0], tmn = s_min[0];
     int tcor = s_cor[0];
-    for (int k = 1; k < NW; ++k) {
+    for (int k = 1; k < NACC; ++k) {
       tce += s_ce[k];
       tmx = fmaxf(tmx, s_max[k]);
       tmn = fminf(tmn, s_min[k]);

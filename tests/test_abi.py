@@ -325,4 +325,5 @@ def test_probe_launch_argument_checks():
     assert f(0, FAKE, 2, 10, ctypes.byref(work), None) == -6                    # buffer too small
     assert f(2, FAKE, 1 << 16, 48, ctypes.byref(work), None) == -6              # window of 768 KB not covered
     assert f(2, FAKE, 1 << 20, 49, ctypes.byref(work), None) == -6              # more steps than the window holds
+    assert f(3, FAKE, 32767, 1, ctypes.byref(work), None) == -2                 # less than one 32 KB workgroup to read
     assert f(7, FAKE, 1 << 20, 1, ctypes.byref(work), None) == -9

@@ -711,3 +711,6 @@ def test_peak_probes_run_and_report_their_work(synk):
     assert synk.synk_probe_launch(synk.SYNK_PROBE_LDS_FETCH, buf, 48) == 256 * 48 * 16384.0
     torch.cuda.synchronize()
     assert torch.equal(buf, before)                                   # the fetch probe only reads
+    assert synk.synk_probe_launch(synk.SYNK_PROBE_READ, buf, 1) == float(4 << 20)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, before)                                   # and so does the read probe
