@@ -68,6 +68,9 @@ def parse():
                          "MFMA loop; plain 16-byte stores over 1 GiB; operand tiles from L2 straight into LDS)")
     ap.add_argument("--repeats", type=int, default=5,
                     help="the K timed steps are run this many times; value and ms_per_step are the median repeat's")
+    ap.add_argument("--separate-gather", action="store_true",
+                    help="configs 1 and 2: input indexing as a gather call of its own before the sliced call "
+                         "(default: folded into the sliced call)")
     ap.add_argument("--sample-every", type=int, default=None,
                     help="put the per-kernel event pair on every N-th step only (default 8; 1 below 64 steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -143,7 +146,7 @@ class Timer:
 class MlpStep:
     """Configs 1 and 2: the whole synchronous-SGD step."""
 
-    def __init__(self, torch, synk, cfg_no, batch=None, rows_per_worker=None):
+    def __init__(self, torch, synk, cfg_no, batch=None, rows_per_worker=None, separate_gather=False):
         import numpy as np
         import workloads
         self.torch, self.s, self.np = torch, synk, np
@@ -196,14 +199,32 @@ class MlpStep:
         # gradients, reads and writes p and v (fp32) and, with bf16 compute, writes the bf16 copy.
         self.dom_name = "reduce_sgd_kernel"
         self.dom_bytes = self.P * (4 * self.N + 16 + (2 if self.bf16 else 0))
+        # Input indexing: folded into the sliced call (the first product reads its rows through the index;
+        # the dataset is resident in the compute type), or with --separate-gather as a call of its own
+        # that converts from the fp32 dataset.
+        self.indexed = not separate_gather
+        self.workload += ("; input indexing inside the sliced call (dataset resident in %s)" % self.dtype
+                          if self.indexed else "; input indexing as a gather call of its own")
         self.targets, self.kernel_work = self._plan(synk)
 
-        # the three C calls of a step, arguments marshalled once (launch cost, not Python cost, per step)
+        # the C calls of a step, arguments marshalled once (launch cost, not Python cost, per step)
         s = synk
-        self.call_gather = [s.prepare(s.synk_gather_rows, self.data, ix, self.x, labels=self.labels,
-                                      dst_labels=self.y) for ix in self.idx]
-        self.call_grad = s.prepare(s.synk_sliced_grad, self.dims, self.cd, self.p, self.p_lp, self.x, self.y,
-                                   self.rows, self.S, s.SYNK_MEAN, self.grad, self.loss, self.ws)
+        if self.indexed:
+            self.data_c = self.data
+            if self.bf16:
+                self.data_c = torch.empty(self.data.shape, dtype=torch.bfloat16, device="cuda")
+                s.synk_cast_bf16(self.data, self.data_c)
+            self.ws = torch.empty(s.synk_sliced_grad_indexed_workspace_bytes(self.dims, self.cd, self.B, self.N),
+                                  dtype=torch.uint8, device="cuda")
+            self.call_gather = [None] * len(self.idx)
+            self.call_grads = [s.prepare(s.synk_sliced_grad_indexed, self.dims, self.cd, self.p, self.p_lp, self.data_c,
+                                         self.labels, ix, self.S, s.SYNK_MEAN, self.grad, self.loss, self.ws)
+                               for ix in self.idx]
+        else:
+            self.call_gather = [s.prepare(s.synk_gather_rows, self.data, ix, self.x, labels=self.labels,
+                                          dst_labels=self.y) for ix in self.idx]
+            self.call_grads = [s.prepare(s.synk_sliced_grad, self.dims, self.cd, self.p, self.p_lp, self.x, self.y,
+                                         self.rows, self.S, s.SYNK_MEAN, self.grad, self.loss, self.ws)] * len(self.idx)
         self.call_update = s.prepare(s.synk_reduce_sgd_update, self.grad, self.p, self.v, c["lr"], c["momentum"],
                                      c["weight_decay"], p_lp=self.p_lp, loss_in=self.loss, loss_out=self.loss_out)
 
@@ -221,8 +242,12 @@ class MlpStep:
         fwd = lambda l: dict(flops=2.0 * B * d[l - 1] * d[l], bytes=(B * d[l - 1] + d[l - 1] * d[l] + B * d[l]) * e)
         work = {"gather": dict(bytes=B * (d[0] * 4 + d[0] * e + 8)),
                 "reduce_update": dict(bytes=self.dom_bytes)}
-        targets = [("gather", "gather", s.SYNK_KERNEL_MAIN), ("forward_1", "grad", s.SYNK_KERNEL_MAIN)]
+        targets = [("forward_1", "grad", s.SYNK_KERNEL_MAIN)]
         work["forward_1"] = fwd(1)
+        if not self.indexed:
+            targets.insert(0, ("gather", "gather", s.SYNK_KERNEL_MAIN))
+        else:
+            work["forward_1"]["bytes"] += B * (d[0] * e + 8)       # it also leaves the rows and labels behind
         for l in range(2, L):
             targets.append(("forward_%d" % l, "grad", s.SYNK_KERNEL_MLP_FORWARD(l)))
             work["forward_%d" % l] = fwd(l)
@@ -254,20 +279,22 @@ class MlpStep:
 
     def step(self, i, timer):
         gather = self.call_gather[i % len(self.call_gather)]
+        call_grad = self.call_grads[i % len(self.call_grads)]
         if not timer.due(i):
-            gather()
-            self.call_grad()
+            if gather:
+                gather()
+            call_grad()
             self.call_update()
             return
         name, call, kernel = self.targets[(i // timer.every) % len(self.targets)]
         if call == "gather":
             timer.bracket(gather, name, kernel)
-        else:
+        elif gather:
             gather()
         if call == "grad":
-            timer.bracket(self.call_grad, name, kernel)
+            timer.bracket(call_grad, name, kernel)
         else:
-            self.call_grad()
+            call_grad()
         if call == "update":
             timer.bracket(self.call_update, name, kernel)
         else:
@@ -705,7 +732,7 @@ def main():
     if a.graph:
         # capture needs a stream of its own; the calls below are prepared on it
         torch.cuda.set_stream(torch.cuda.Stream())
-    wl = {0: lambda: (ProbeStep(torch, synk, a.probe) if a.probe else CopyStep(torch, synk)), 1: lambda: MlpStep(torch, synk, 1, a.batch), 2: lambda: MlpStep(torch, synk, 2, a.batch, a.rows_per_worker),
+    wl = {0: lambda: (ProbeStep(torch, synk, a.probe) if a.probe else CopyStep(torch, synk)), 1: lambda: MlpStep(torch, synk, 1, a.batch, separate_gather=a.separate_gather), 2: lambda: MlpStep(torch, synk, 2, a.batch, a.rows_per_worker, a.separate_gather),
           3: lambda: (CollectiveStep(torch, synk, a.collective) if a.collective else ReduceStep(torch, synk, a.rule)), 4: lambda: GatherStep(torch, synk, a.indexing),
           5: lambda: EvalStep(torch, synk), 6: lambda: ConvStep(torch, synk, a.conv_shape)}[a.config]()
     steps = a.steps if a.steps is not None else {0: 50, 1: 5000, 2: 4500, 3: 2800, 4: 5000, 5: 5000, 6: 3200}[a.config]   # >= 0.5 s a repeat

@@ -11,7 +11,7 @@
  *                           the same with a slice for a list, the scatter of an
  *                           array over the workers (Sec. 4.2), and indexing of
  *                           shares that already live on the workers (Sec. 5.2)
- *   synk_sliced_grad, synk_sliced_grad_conv
+ *   synk_sliced_grad, synk_sliced_grad_indexed, synk_sliced_grad_conv
  *                           the gradient function run over every worker's
  *                           share in slices, slice results aggregated on the
  *                           GPU (Sec. 5.1), one flat gradient per worker
@@ -310,6 +310,38 @@ int synk_sliced_grad(const synk_mlp_desc* m, const float* params, const void* pa
                      int n_workers, int n_slices, int grad_op,
                      float* const* grad, float* loss,
                      void* ws, size_t ws_bytes, void* stream);
+
+/* synk_sliced_grad with the input indexing folded in (Sec. 5.2: the data lives on
+ * the device and a call names the rows it uses; Sec. 3.2 step 1; Sec. 3.3 step 1):
+ * the minibatch is data[idx[0..n_idx)], split over n_workers by the split rule
+ * exactly as synk_gather_rows splits it, and the result equals
+ * synk_gather_rows(data, idx -> x, labels -> y) followed by synk_sliced_grad on
+ * those x, y and shares, bit for bit.  The workers' rows and labels are kept in the
+ * workspace.  Where the first forward product's kernel can read its rows through
+ * the index (bf16: shares that are whole 64-row tiles, d0 a multiple of 64, widths
+ * multiples of 64, 16-byte aligned data; fp32: the small-batch kernel) no gather
+ * launch takes place: that kernel also leaves the rows behind for the weight
+ * gradient; otherwise the call runs the gather itself first.
+ *   data      device, [n_data x d0] in compute_dtype (for SYNK_BF16 the dataset is
+ *             held in bf16: cast it once with synk_cast_bf16), row-major, dense
+ *   labels    device int32[n_data]
+ *   idx       device int32[n_idx], each in [0, n_data); an index outside the
+ *             range never reads out of bounds (the fused kernels read row 0 for
+ *             it, the gather launch leaves the row's previous workspace contents);
+ *             validate lists with synk_gather_rows + SYNK_FLAG_CHECK_INDEX
+ *   ws        synk_sliced_grad_indexed_workspace_bytes(m, n_idx, n_workers, &b)
+ * params, params_lp, n_slices, grad_op, grad, loss: as synk_sliced_grad.
+ * SYNK_KERNEL_MAIN selects the first forward product, or the gather launch when
+ * there is one.
+ * Errors: as synk_sliced_grad; n_idx < 1, n_data < 1 -> ERR_SHAPE. */
+int synk_sliced_grad_indexed_workspace_bytes(const synk_mlp_desc* m, int64_t n_idx, int n_workers,
+                                             size_t* bytes);
+int synk_sliced_grad_indexed(const synk_mlp_desc* m, const float* params, const void* params_lp,
+                             const void* data, const int32_t* labels, int64_t n_data,
+                             const int32_t* idx, int64_t n_idx,
+                             int n_workers, int n_slices, int grad_op,
+                             float* const* grad, float* loss,
+                             void* ws, size_t ws_bytes, void* stream);
 
 /* A second function for the same sliced call (Sec. 3.2, 5.1; Sec. 3.3 step 1):
  * one block of the network family the scaling study trains (Sec. 6), a 3x3

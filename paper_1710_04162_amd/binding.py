@@ -18,6 +18,7 @@ __all__ = [
     "synk_version", "synk_status_string", "synk_split", "synk_gather_workspace_bytes",
     "synk_gather_rows", "synk_build_norm_lut", "synk_poll_error", "synk_mlp_param_count",
     "synk_sliced_grad_workspace_bytes", "synk_sliced_grad", "synk_cast_bf16",
+    "synk_sliced_grad_indexed_workspace_bytes", "synk_sliced_grad_indexed",
     "synk_sliced_eval_workspace_bytes", "synk_sliced_eval", "synk_sliced_eval_static",
     "synk_static_scratch_init", "synk_reduce_buffers",
     "synk_sgd_update", "synk_reduce_sgd_update", "synk_reduce_update",
@@ -99,6 +100,11 @@ lib.synk_sliced_grad_workspace_bytes.argtypes = [ctypes.POINTER(MlpDesc), _pi64,
                                                  ctypes.POINTER(_sz)]
 lib.synk_sliced_grad.argtypes = [ctypes.POINTER(MlpDesc), _vp, _vp, _pp, _pp, _pi64, _int, _int,
                                  _int, _pp, _vp, _vp, _sz, _vp]
+lib.synk_sliced_grad_indexed_workspace_bytes.argtypes = [ctypes.POINTER(MlpDesc), _i64, _int, ctypes.POINTER(_sz)]
+lib.synk_sliced_grad_indexed_workspace_bytes.restype = _int
+lib.synk_sliced_grad_indexed.argtypes = [ctypes.POINTER(MlpDesc), _vp, _vp, _vp, _vp, _i64, _vp, _i64, _int, _int,
+                                         _int, _pp, _vp, _vp, _sz, _vp]
+lib.synk_sliced_grad_indexed.restype = _int
 lib.synk_convblock_param_count.argtypes = [ctypes.POINTER(ConvBlockDesc), _pi64]
 lib.synk_sliced_grad_conv_workspace_bytes.argtypes = [ctypes.POINTER(ConvBlockDesc), _pi64, _int, _int,
                                                       ctypes.POINTER(_sz)]
@@ -272,6 +278,25 @@ def synk_sliced_grad(dims, compute_dtype, params, params_lp, x, y, rows, n_slice
             tg, _ptr(loss), wsp, wsb, _stream(stream))
     return _run(lib.synk_sliced_grad, args, (desc, params, params_lp, x, y, r, grad, loss, ws, tx, ty, tg),
                 "synk_sliced_grad", _prepare)
+
+
+def synk_sliced_grad_indexed_workspace_bytes(dims, compute_dtype, n_idx, n_workers):
+    out = _sz(0)
+    _check(lib.synk_sliced_grad_indexed_workspace_bytes(ctypes.byref(_desc(dims, compute_dtype)), n_idx, n_workers,
+                                                        ctypes.byref(out)),
+           "synk_sliced_grad_indexed_workspace_bytes")
+    return out.value
+
+
+def synk_sliced_grad_indexed(dims, compute_dtype, params, params_lp, data, labels, idx, n_slices, grad_op, grad,
+                             loss, ws, stream=None, _prepare=False):
+    wsp, wsb = _ws(ws)
+    desc = _desc(dims, compute_dtype)
+    tg = _table(grad)
+    args = (ctypes.byref(desc), _ptr(params), _ptr(params_lp), _ptr(data), _ptr(labels), data.shape[0], _ptr(idx),
+            idx.numel(), len(grad), n_slices, grad_op, tg, _ptr(loss), wsp, wsb, _stream(stream))
+    return _run(lib.synk_sliced_grad_indexed, args, (desc, params, params_lp, data, labels, idx, grad, loss, ws, tg),
+                "synk_sliced_grad_indexed", _prepare)
 
 
 def _conv_desc(shape, compute_dtype, eps):

@@ -68,6 +68,12 @@ __host__ __device__ constexpr int lds_bytes() { return NS * (BM + BN) * 128; }
 // equal to the total); b (FWD: W [K x N], n contiguous; DX: W [N x K], k contiguous; pitch ldb);
 // mask (DX: activations of the layer below, packed [R x N] bf16, pitch ldmask); bias (FWD:
 // float[N]); n (output columns); k_fixed (contraction length); relu (FWD).
+// With GATHER (FWD only) the A rows are not in a[w] yet: row r of the packed batch is row
+// gather_idx[r] of gather_src ([gather_rows x K] bf16, pitch lda; an index outside
+// [0, gather_rows) reads row 0), and the kernel leaves the rows in a[w] for the kernels after it
+// (of a row tile's workgroups, the one in tile column bn copies the k tiles t with
+// t % tiles_n == bn) and their labels gather_labels[gather_idx[r]] in gather_y[r]
+// (tile column 0; gather_labels may be null).
 
 // Workgroup `lin` of a grid of tiles_m x tiles_n tiles whose first workgroup sits
 // on XCD 0 (workgroups go to the 8 XCDs round-robin): each XCD, i.e. each L2,
@@ -102,9 +108,10 @@ __device__ __forceinline__ void tile_of(unsigned lin, int tiles_m, int tiles_n, 
 // N % BN == 0, every worker's row count a multiple of BM, all bases 16-byte
 // aligned and all pitches multiples of 8 elements.  smem: lds_bytes<BM,BN,NS>()
 // bytes, 1024-byte aligned.  Called by all kThreads threads of a workgroup.
-template <int MODE, int BM, int BN, int NS, typename ArgsT>
+template <int MODE, int BM, int BN, int NS, typename ArgsT, bool GATHER = false>
 __device__ __forceinline__ void tile(const ArgsT& g, unsigned lin, int tiles_m, int tiles_n,
                                      unsigned char* __restrict__ smem) {
+  static_assert(!GATHER || MODE == FWD, "input indexing belongs to the forward product");
   constexpr int TM = BM / 64, TN = BN / 64;            // MFMA tiles of a quadrant
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
   constexpr int A_INSTR = A_BYTES / 1024 / kWaves, B_INSTR = B_BYTES / 1024 / kWaves;
@@ -129,12 +136,29 @@ __device__ __forceinline__ void tile(const ArgsT& g, unsigned lin, int tiles_m, 
   // ---- producer side: this lane's global address in tile 0; a constant step per tile
   const char* pa[A_INSTR];
   const char* pb[B_INSTR];
+  char* pd[A_INSTR];                                   // GATHER: where this lane's piece of tile 0 is left in a[w]
   const char* Ab = reinterpret_cast<const char*>(g.a[w]);
   const char* Bb = reinterpret_cast<const char*>(g.b);
 #pragma unroll
   for (int j = 0; j < A_INSTR; ++j) {
     const int row = 8 * (wave + kWaves * j) + (lane >> 3), phys = lane & 7;
-    pa[j] = Ab + ((rw + row) * g.lda) * 2 + (phys ^ swz_kc(row)) * 16;
+    const int64_t piece = (phys ^ swz_kc(row)) * 16;
+    if constexpr (GATHER) {
+      int64_t src = g.gather_idx[row0 + row];
+      if (src < 0 || src >= g.gather_rows) src = 0;
+      pa[j] = reinterpret_cast<const char*>(g.gather_src) + (src * g.lda) * 2 + piece;
+      pd[j] = const_cast<char*>(Ab) + ((rw + row) * g.lda) * 2 + piece;
+    } else {
+      pa[j] = Ab + ((rw + row) * g.lda) * 2 + piece;
+      pd[j] = nullptr;
+    }
+  }
+  if constexpr (GATHER) {
+    if (bn == 0 && g.gather_labels && tid < BM) {
+      int64_t src = g.gather_idx[row0 + tid];
+      if (src < 0 || src >= g.gather_rows) src = 0;
+      g.gather_y[row0 + tid] = g.gather_labels[src];
+    }
   }
   int64_t step_b;
   if (MODE == FWD) {
@@ -266,6 +290,15 @@ __device__ __forceinline__ void tile(const ArgsT& g, unsigned lin, int tiles_m, 
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // deeper rings than this code lists: wait for all
         __syncthreads();                 // every wavefront's part of tile t is in LDS; tile t-1 has been consumed
         if (t + NS - 1 < T) issue((u + NS - 1) % NS);           // into the stage tile t-1 used
+        if constexpr (GATHER) {
+          if (t % tiles_n == bn) {       // this workgroup's share of the rows' columns: its own pieces, LDS -> a[w]
+#pragma unroll
+            for (int j = 0; j < A_INSTR; ++j) {
+              const u32x4 q = *reinterpret_cast<const u32x4*>(smem + u * STAGE + (kWaves * j + wave) * 1024 + lane * 16);
+              *reinterpret_cast<u32x4*>(pd[j] + (int64_t)t * (kBK * 2)) = q;
+            }
+          }
+        }
         compute(u);
       }
     }

@@ -357,6 +357,15 @@ struct GemmArgs {
   int task_z, task_workers, task_slices, task_op;
   const float* task_row_loss;
   float* task_loss;
+  // Input indexing folded into the first forward product (gather_src == nullptr: a[w] holds the
+  // rows already).  Row r of the packed batch is row gather_idx[r] of gather_src ([gather_rows x K]
+  // of T, pitch lda); the forward kernel also leaves the rows in a[w] and, if gather_labels is
+  // given, their labels in gather_y (packed: entry r for packed row r), for the kernels after it.
+  const void* gather_src;
+  const int32_t* gather_idx;
+  const int32_t* gather_labels;
+  int64_t gather_rows;
+  int32_t* gather_y;
 };
 
 }  // namespace synk
@@ -364,10 +373,10 @@ struct GemmArgs {
 namespace synk {
 
 // The whole-tile bf16 core as a kernel of its own (forward and dX products).
-template <int MODE, int BM, int BN, int NS>
+template <int MODE, int BM, int BN, int NS, bool GATHER = false>
 __global__ __launch_bounds__(gdma::kThreads) void mlp_gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
   __shared__ __attribute__((aligned(1024))) unsigned char smem[gdma::lds_bytes<BM, BN, NS>()];
-  gdma::tile<MODE, BM, BN, NS>(g, blockIdx.x, tiles_m, tiles_n, smem);
+  gdma::tile<MODE, BM, BN, NS, GemmArgs, GATHER>(g, blockIdx.x, tiles_m, tiles_n, smem);
 }
 
 // Workgroups are dealt to the 8 XCDs round-robin by launch order.  Re-deal so
@@ -987,6 +996,21 @@ __global__ __launch_bounds__(64 * kSmallWaves) void mlp_fwd_small_kernel(GemmArg
   const bool col_ok = n < N;
   const float* X = reinterpret_cast<const float*>(g.a[w]);
   const float* W = reinterpret_cast<const float*>(g.b) + (col_ok ? n : 0);
+  // input indexing folded in: the 8 rows come from the resident data through the index
+  const bool gather = g.gather_src != nullptr;
+  const float* xrow[kSmallRows];
+#pragma unroll
+  for (int r = 0; r < kSmallRows; ++r) {
+    const int64_t rr = r0 + r < rows_w ? r0 + r : r0;          // a row past the end repeats row r0
+    if (gather) {
+      int64_t src = g.gather_idx[g.row_off[w] + rr];
+      if (src < 0 || src >= g.gather_rows) src = 0;
+      xrow[r] = reinterpret_cast<const float*>(g.gather_src) + src * g.lda;
+      if (ct == 0 && g.gather_labels && threadIdx.x == r && r0 + r < rows_w) g.gather_y[g.row_off[w] + rr] = g.gather_labels[src];
+    } else {
+      xrow[r] = X + rr * g.lda;
+    }
+  }
   // this wavefront's part of the contraction
   const int kc = (K + kSmallWaves - 1) / kSmallWaves;
   const int kb = q * kc, ke = kb + kc < K ? kb + kc : K;
@@ -997,9 +1021,17 @@ __global__ __launch_bounds__(64 * kSmallWaves) void mlp_fwd_small_kernel(GemmArg
   for (int k = threadIdx.x; k < K; k += 64 * kSmallWaves) {
     float xv[kSmallRows];
 #pragma unroll
-    for (int r = 0; r < kSmallRows; ++r) xv[r] = X[(r0 + r < rows_w ? r0 + r : r0) * g.lda + k];   // a row past the end repeats row r0
+    for (int r = 0; r < kSmallRows; ++r) xv[r] = xrow[r][k];
     *reinterpret_cast<f32x4*>(xs + k * kSmallRows) = f32x4{xv[0], xv[1], xv[2], xv[3]};
     *reinterpret_cast<f32x4*>(xs + k * kSmallRows + 4) = f32x4{xv[4], xv[5], xv[6], xv[7]};
+    // the rows are left in a[w] for the weight gradient: of a row tile's workgroups, column tile ct
+    // copies the 64-wide column blocks ct, ct + col_tiles, ...
+    if (gather && (k >> 6) % col_tiles == ct) {
+      float* Xo = const_cast<float*>(X);
+#pragma unroll
+      for (int r = 0; r < kSmallRows; ++r)
+        if (r0 + r < rows_w) Xo[(r0 + r) * g.lda + k] = xv[r];
+    }
   }
   __syncthreads();
   float acc[kSmallRows];
@@ -1533,6 +1565,8 @@ struct MlpPlan {
   size_t h[SYNK_MAX_LAYERS];                   // h[l], l = 1..L-1: activations of hidden layer l
   size_t dz[SYNK_MAX_LAYERS + 1];              // dz[l], l = 1..L
   size_t logits, row_loss, total;
+  // the indexed call keeps the gathered rows (packed [R x d0] of T) and labels in the workspace too
+  size_t xin, ylab, total_indexed;
 };
 
 static int make_plan(const synk_mlp_desc* m, const int64_t* rows, int n_workers, MlpPlan* p) {
@@ -1579,6 +1613,11 @@ static int make_plan(const synk_mlp_desc* m, const int64_t* rows, int n_workers,
     p->row_loss = o;
     o += round_up((size_t)p->R * 4, 256);
     p->total = o;
+    p->xin = o;
+    o += round_up((size_t)p->R * p->d[0] * p->elem, 256);
+    p->ylab = o;
+    o += round_up((size_t)p->R * 4, 256);
+    p->total_indexed = o;
   }
   return SYNK_OK;
 }
@@ -1635,6 +1674,20 @@ static bool gemm_dma_ok(const GemmArgs& g, int n_workers, int bm, int bn) {
   return true;
 }
 
+// Which whole-tile kernel a forward or dX product takes: 0 none, else 1 = 256 x 128, 2 = 128 x 128,
+// 3 = 64 x 64.  Large products: the operand fetch rate of a CU bounds them, so the tile with the most
+// flops per fetched byte that still fills the chip: 256 x 128 (36 % of the bf16 peak at 65,536 x 1024
+// x 3072 against 31 % for 128 x 128).
+template <typename T, int MODE>
+static int gemm_dma_choice(const GemmArgs& g, int n_workers) {
+  if (MODE == MODE_DW) return 0;
+  const int64_t R = g.row_off[n_workers];
+  if (gemm_dma_ok<T, MODE>(g, n_workers, 256, 128) && (R / 256) * (g.n / 128) >= 4 * kNumCU) return 1;
+  if (gemm_dma_ok<T, MODE>(g, n_workers, 128, 128) && (R / 128) * (g.n / 128) >= 2 * kNumCU) return 2;
+  if (gemm_dma_ok<T, MODE>(g, n_workers, 64, 64)) return 3;
+  return 0;
+}
+
 template <typename T, int MODE>
 static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStream_t s, int prof_id) {
   constexpr int BK_BIG = GemmTiling<T>::BK_BIG, BK_SMALL = GemmTiling<T>::BK_SMALL;
@@ -1642,32 +1695,29 @@ static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStrea
   const int al = gemm_alignment(g);
   if (MODE != MODE_DW) {
     constexpr int GM = MODE == MODE_FWD ? gdma::FWD : gdma::DX;
+    constexpr bool CAN_GATHER = MODE == MODE_FWD;
     const int64_t R = g.row_off[n_workers];
-    // large products: the operand fetch rate of a CU bounds them, so the tile with the most flops per
-    // fetched byte that still fills the chip: 256 x 128 (36 % of the bf16 peak at 65,536 x 1024 x 3072
-    // against 31 % for 128 x 128)
-    if (gemm_dma_ok<T, MODE>(g, n_workers, 256, 128) && (R / 256) * (g.n / 128) >= 4 * kNumCU) {
-      const int tm = (int)(R / 256), tn = (int)(g.n / 128);
-      SYNK_LAUNCH_TIMED_AS(prof_id, (mlp_gemm_dma_kernel<GM, 256, 128, 3>), dim3((unsigned)(tm * tn)),
-                           dim3(gdma::kThreads), 0, s, g, tm, tn);
-      SYNK_LAUNCH_CHECK();
-      return SYNK_OK;
-    }
-    if (gemm_dma_ok<T, MODE>(g, n_workers, 128, 128) && (R / 128) * (g.n / 128) >= 2 * kNumCU) {
-      const int tm = (int)(R / 128), tn = (int)(g.n / 128);
-      SYNK_LAUNCH_TIMED_AS(prof_id, (mlp_gemm_dma_kernel<GM, 128, 128, 3>), dim3((unsigned)(tm * tn)),
-                           dim3(gdma::kThreads), 0, s, g, tm, tn);
-      SYNK_LAUNCH_CHECK();
-      return SYNK_OK;
-    }
-    if (gemm_dma_ok<T, MODE>(g, n_workers, 64, 64)) {
-      const int tm = (int)(R / 64), tn = (int)(g.n / 64);
-      SYNK_LAUNCH_TIMED_AS(prof_id, (mlp_gemm_dma_kernel<GM, 64, 64, 6>), dim3((unsigned)(tm * tn)),
-                           dim3(gdma::kThreads), 0, s, g, tm, tn);
-      SYNK_LAUNCH_CHECK();
-      return SYNK_OK;
-    }
+    const int choice = gemm_dma_choice<T, MODE>(g, n_workers);
+    const bool gather = g.gather_src != nullptr;
+    if (gather && (!CAN_GATHER || choice == 0)) return SYNK_ERR_UNSUPPORTED;   // the caller gathers first in that case
+#define SYNK_GEMM_DMA(BM_, BN_, NS_)                                                                         \
+  do {                                                                                                       \
+    const int tm = (int)(R / BM_), tn = (int)(g.n / BN_);                                                    \
+    if (CAN_GATHER && gather)                                                                                \
+      SYNK_LAUNCH_TIMED_AS(prof_id, (mlp_gemm_dma_kernel<GM, BM_, BN_, NS_, CAN_GATHER>),                    \
+                           dim3((unsigned)(tm * tn)), dim3(gdma::kThreads), 0, s, g, tm, tn);                \
+    else                                                                                                     \
+      SYNK_LAUNCH_TIMED_AS(prof_id, (mlp_gemm_dma_kernel<GM, BM_, BN_, NS_>), dim3((unsigned)(tm * tn)),     \
+                           dim3(gdma::kThreads), 0, s, g, tm, tn);                                           \
+    SYNK_LAUNCH_CHECK();                                                                                     \
+    return SYNK_OK;                                                                                          \
+  } while (0)
+    if (choice == 1) SYNK_GEMM_DMA(256, 128, 3);
+    if (choice == 2) SYNK_GEMM_DMA(128, 128, 3);
+    if (choice == 3) SYNK_GEMM_DMA(64, 64, 6);
+#undef SYNK_GEMM_DMA
   }
+  if (g.gather_src != nullptr) return SYNK_ERR_UNSUPPORTED;
 #define SYNK_GEMM(BM_, BN_, BK_)                                                                              \
   do {                                                                                                       \
     if (al == 2)                                                                                             \
@@ -1698,11 +1748,22 @@ static int launch_gemm(const GemmArgs& g, int64_t m_max, int n_workers, hipStrea
   return SYNK_OK;
 }
 
+// The resident dataset and the index list of the indexed call (Sec. 5.2).
+struct GatherIn {
+  const void* data;        // [n_data x d0] of T
+  const int32_t* labels;   // [n_data]
+  int64_t n_data;
+  const int32_t* idx;      // [R]
+};
+
+// gin == nullptr: x[w], y[w] hold the workers' rows and labels.  Otherwise they are buffers the call
+// fills from the dataset first (the first forward product does it on its way where its kernel can,
+// else a gather launch of its own).
 template <typename T>
 static int run_sliced_grad(const MlpPlan& p, const float* params, const void* params_lp,
                            const void* const* x, const int32_t* const* y, const int64_t* rows,
                            int n_workers, int n_slices, int grad_op, float* const* grad,
-                           float* loss, char* ws, hipStream_t s) {
+                           float* loss, char* ws, hipStream_t s, const GatherIn* gin = nullptr) {
   constexpr int V = ET<T>::V;
   const T* wts = sizeof(T) == 4 ? reinterpret_cast<const T*>(params)
                                 : reinterpret_cast<const T*>(params_lp);
@@ -1719,6 +1780,10 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
   }
 
   GemmArgs g;
+  g.gather_src = nullptr;
+  g.gather_idx = g.gather_labels = nullptr;
+  g.gather_rows = 0;
+  g.gather_y = nullptr;
   g.task_z = -1;
   g.task_workers = g.task_slices = g.task_op = 0;
   g.task_row_loss = nullptr;
@@ -1756,15 +1821,36 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
     g.c_vec = N % 8 == 0;     // workspace rows: 256-byte aligned base, rows a multiple of 16 bytes
     const int fwd_id = l == 1 ? SYNK_KERNEL_MAIN : SYNK_KERNEL_MLP_FORWARD(l);
     // fp32 with so few rows that 64 x 64 tiles would occupy under a quarter of the CUs: multiply-add kernel
-    if (sizeof(T) == 4 && K <= kSmallMaxK && ((p.max_rows + 63) / 64) * ((N + 63) / 64) * n_workers < kNumCU / 4) {
+    const bool small = sizeof(T) == 4 && K <= kSmallMaxK &&
+                       ((p.max_rows + 63) / 64) * ((N + 63) / 64) * n_workers < kNumCU / 4;
+    if (l == 1 && gin) {
+      // input indexing: on the way into this product where its kernel reads rows through the index,
+      // else gathered by a launch of its own
+      const bool fused = small || (aligned_to(gin->data, 16) && gemm_dma_choice<T, MODE_FWD>(g, n_workers) != 0);
+      if (fused) {
+        g.gather_src = gin->data;
+        g.gather_idx = gin->idx;
+        g.gather_labels = gin->labels;
+        g.gather_rows = gin->n_data;
+        g.gather_y = const_cast<int32_t*>(y[0]);   // packed labels: y[w] = y[0] + row_off[w] in the indexed call
+      } else {
+        const int dt = sizeof(T) == 4 ? SYNK_F32 : SYNK_BF16;
+        if (int rc = synk_gather_rows(gin->data, gin->n_data, K, dt, gin->idx, p.R, const_cast<void* const*>(x), n_workers,
+                                      dt, nullptr, 0, gin->labels, const_cast<int32_t* const*>(y), 0, nullptr, 0, s))
+          return rc;
+      }
+    }
+    if (small) {
       const int row_tiles = (int)((p.max_rows + kSmallRows - 1) / kSmallRows);
       const int col_tiles = (int)((N + kSmallCols - 1) / kSmallCols);
       SYNK_LAUNCH_TIMED_AS(fwd_id, mlp_fwd_small_kernel, dim3((unsigned)(row_tiles * col_tiles), n_workers),
                            dim3(64 * kSmallWaves), fwd_small_lds_bytes(K), s, g, row_tiles, col_tiles);
       SYNK_LAUNCH_CHECK();
+      g.gather_src = nullptr;
       continue;
     }
     if (int rc = launch_gemm<T, MODE_FWD>(g, p.max_rows, n_workers, s, fwd_id)) return rc;
+    g.gather_src = nullptr;
   }
 
   // ---- loss and dZ_L
@@ -1970,6 +2056,64 @@ extern "C" int synk_sliced_grad_workspace_bytes(const synk_mlp_desc* m, const in
   if (int rc = make_plan(m, rows, n_workers, &p)) return rc;
   *bytes = p.total;
   return SYNK_OK;
+}
+
+extern "C" int synk_sliced_grad_indexed_workspace_bytes(const synk_mlp_desc* m, int64_t n_idx, int n_workers,
+                                                        size_t* bytes) {
+  if (!bytes) return SYNK_ERR_NULL;
+  if (n_workers < 1 || n_workers > SYNK_MAX_WORKERS || n_idx < 1) return SYNK_ERR_SHAPE;
+  int64_t rows[SYNK_MAX_WORKERS];
+  for (int w = 0; w < n_workers; ++w) {
+    int64_t start;
+    share(n_idx, n_workers, w, &start, &rows[w]);
+  }
+  MlpPlan p;
+  if (int rc = make_plan(m, rows, n_workers, &p)) return rc;
+  *bytes = p.total_indexed;
+  return SYNK_OK;
+}
+
+extern "C" int synk_sliced_grad_indexed(const synk_mlp_desc* m, const float* params, const void* params_lp,
+                                        const void* data, const int32_t* labels, int64_t n_data,
+                                        const int32_t* idx, int64_t n_idx, int n_workers, int n_slices,
+                                        int grad_op, float* const* grad, float* loss, void* ws,
+                                        size_t ws_bytes, void* stream) {
+  if (!m || !params || !data || !labels || !idx || !grad || !loss) return SYNK_ERR_NULL;
+  if (n_workers < 1 || n_workers > SYNK_MAX_WORKERS || n_idx < 1 || n_data < 1) return SYNK_ERR_SHAPE;
+  int64_t rows[SYNK_MAX_WORKERS];
+  for (int w = 0; w < n_workers; ++w) {
+    int64_t start;
+    share(n_idx, n_workers, w, &start, &rows[w]);
+  }
+  MlpPlan p;
+  if (int rc = make_plan(m, rows, n_workers, &p)) return rc;
+  if (n_slices < 1) return SYNK_ERR_SHAPE;
+  if (grad_op != SYNK_SUM && grad_op != SYNK_MEAN) return SYNK_ERR_OP;
+  if (m->compute_dtype == SYNK_BF16 && !params_lp) return SYNK_ERR_NULL;
+  if (!aligned_to(params, 4) || !aligned_to(loss, 4) || !aligned_to(data, p.elem) || !aligned_to(labels, 4) ||
+      !aligned_to(idx, 4))
+    return SYNK_ERR_ALIGN;
+  if (m->compute_dtype == SYNK_BF16 && !aligned_to(params_lp, 2)) return SYNK_ERR_ALIGN;
+  for (int w = 0; w < n_workers; ++w) {
+    if (!grad[w]) return SYNK_ERR_NULL;
+    if (!aligned_to(grad[w], 4)) return SYNK_ERR_ALIGN;
+  }
+  if (!ws || !aligned_to(ws, 256) || ws_bytes < p.total_indexed) return SYNK_ERR_WORKSPACE;
+  // the workers' gathered rows and labels live in the workspace, packed in worker order
+  char* wsb = reinterpret_cast<char*>(ws);
+  const void* x[SYNK_MAX_WORKERS];
+  const int32_t* y[SYNK_MAX_WORKERS];
+  for (int w = 0; w < n_workers; ++w) {
+    x[w] = wsb + p.xin + (size_t)p.row_off[w] * p.d[0] * p.elem;
+    y[w] = reinterpret_cast<const int32_t*>(wsb + p.ylab) + p.row_off[w];
+  }
+  const GatherIn gin{data, labels, n_data, idx};
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  if (m->compute_dtype == SYNK_F32)
+    return run_sliced_grad<float>(p, params, params_lp, x, y, rows, n_workers, n_slices, grad_op, grad, loss, wsb,
+                                  s, &gin);
+  return run_sliced_grad<bf16_t>(p, params, params_lp, x, y, rows, n_workers, n_slices, grad_op, grad, loss, wsb, s,
+                                 &gin);
 }
 
 extern "C" int synk_sliced_grad(const synk_mlp_desc* m, const float* params, const void* params_lp,

@@ -166,6 +166,35 @@ def test_sliced_grad_argument_checks_and_workspace():
     assert call(x=_tbl(FAKE, None)) == -1
 
 
+def test_sliced_grad_indexed_argument_checks_and_workspace():
+    dims = [20, 16, 10]
+    plain = synk.synk_sliced_grad_workspace_bytes(dims, synk.SYNK_F32, [4, 3])
+    b = synk.synk_sliced_grad_indexed_workspace_bytes(dims, synk.SYNK_F32, 7, 2)
+    assert b % 256 == 0 and b >= plain + 7 * 20 * 4 + 7 * 4       # + the gathered rows and their labels
+    with pytest.raises(synk.SynkError) as e:
+        synk.synk_sliced_grad_indexed_workspace_bytes(dims, synk.SYNK_F32, 0, 2)
+    assert e.value.status == -2
+    with pytest.raises(synk.SynkError):
+        synk.synk_sliced_grad_indexed_workspace_bytes(dims, synk.SYNK_F32, 7, 65)
+
+    f = lib.synk_sliced_grad_indexed
+    d = synk._desc(dims, synk.SYNK_F32)
+    t2 = _tbl(FAKE, FAKE)
+
+    def call(desc=d, params=FAKE, lp=None, data=FAKE, labels=FAKE, n_data=50, idx=FAKE, n_idx=7, nw=2, ns=2, op=1,
+             grad=t2, loss=FAKE, ws=FAKE, wsb=1 << 30):
+        return f(ctypes.byref(desc), params, lp, data, labels, n_data, idx, n_idx, nw, ns, op, grad, loss, ws, wsb,
+                 None)
+
+    assert call(params=None) == -1 and call(data=None) == -1 and call(labels=None) == -1 and call(idx=None) == -1
+    assert call(grad=None) == -1 and call(loss=None) == -1
+    assert call(n_idx=0) == -2 and call(n_data=0) == -2 and call(nw=0) == -2 and call(nw=65) == -2 and call(ns=0) == -2
+    assert call(op=2) == -4
+    assert call(desc=synk._desc(dims, synk.SYNK_BF16)) == -1          # bf16 needs params_lp
+    assert call(data=FAKE + 2) == -5 and call(idx=FAKE + 1) == -5 and call(grad=_tbl(FAKE, FAKE + 2)) == -5
+    assert call(ws=None) == -6 and call(wsb=b - 1) == -6 and call(ws=FAKE + 16) == -6
+
+
 def test_sliced_grad_conv_argument_checks_and_workspace():
     shape = (6, 5, 8, 16, 10)
     assert synk.synk_convblock_param_count(shape) == 9 * 8 * 16 + 2 * 16 + 16 * 10 + 10

@@ -401,3 +401,73 @@ def test_profile_hook_selects_kernels_of_the_sliced_gradient(synk):
         if launched:
             assert 0.0005 < a.elapsed_time(b) < 1.0, kernel
         assert all(np.array_equal(x, y) for x, y in zip(got, ref))       # a timed launch computes the same
+
+
+# ------------------------------------------------------------- input indexing folded into the call
+def _indexed_against_gather_then_grad(synk, dims, bf16, n_data, B, N, S, seed, bad_index=False):
+    """synk_sliced_grad_indexed == synk_gather_rows + synk_sliced_grad, bit for bit."""
+    rng = np.random.default_rng(seed)
+    cd = synk.SYNK_BF16 if bf16 else synk.SYNK_F32
+    data = torch.from_numpy(rng.standard_normal((n_data, dims[0])).astype(np.float32)).cuda()
+    if bf16:
+        data = data.bfloat16()
+    labels = dev(rng.integers(0, dims[-1], n_data).astype(np.int32))
+    theta = workloads.mlp_init(dims, rng) + (rng.standard_normal(workloads.mlp_param_count(dims)) * 0.05).astype(np.float32)
+    idx_h = rng.integers(0, n_data, B).astype(np.int32)
+    idx_ref = idx_h.copy()
+    if bad_index:                     # the fused kernels read row 0 for an index outside the data
+        idx_h[3], idx_h[B - 2] = n_data + 5, -7
+        idx_ref[3], idx_ref[B - 2] = 0, 0
+    P = synk.synk_mlp_param_count(dims)
+    p = dev(theta)
+    p_lp = torch.zeros(P, dtype=torch.bfloat16, device="cuda") if bf16 else None
+    if bf16:
+        synk.synk_cast_bf16(p, p_lp)
+    rows = lib_share_sizes(synk, B, N)
+    x = [torch.zeros((n, dims[0]), dtype=data.dtype, device="cuda") for n in rows]
+    y = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in rows]
+    synk.synk_gather_rows(data, dev(idx_ref), x, labels=labels, dst_labels=y)
+    ga = [torch.full((P,), 5.0, device="cuda") for _ in rows]
+    la = torch.full((N,), -1.0, device="cuda")
+    ws = torch.empty(synk.synk_sliced_grad_workspace_bytes(dims, cd, rows), dtype=torch.uint8, device="cuda")
+    synk.synk_sliced_grad(dims, cd, p, p_lp, x, y, rows, S, synk.SYNK_MEAN, ga, la, ws)
+    gb = [torch.full((P,), 7.0, device="cuda") for _ in rows]
+    lb = torch.full((N,), -2.0, device="cuda")
+    wsi = torch.full((synk.synk_sliced_grad_indexed_workspace_bytes(dims, cd, B, N),), 0x5A, dtype=torch.uint8,
+                     device="cuda")
+    for _ in range(2):                # the second call runs on a workspace the first has used
+        synk.synk_sliced_grad_indexed(dims, cd, p, p_lp, data, labels, dev(idx_h), S, synk.SYNK_MEAN, gb, lb, wsi)
+    torch.cuda.synchronize()
+    for w in range(N):
+        assert torch.equal(ga[w], gb[w]), (w, float((ga[w] - gb[w]).abs().max()))
+    assert torch.equal(la, lb)
+    return theta, data, labels, idx_ref, [g.cpu().numpy() for g in gb]
+
+
+@pytest.mark.parametrize("dims,bf16,n_data,B,N,S", [
+    ([128, 64, 64, 10], True, 900, 512, 8, 4),      # whole 64-row tiles: the whole-tile product reads through the index
+    ([192, 128, 10], True, 700, 256, 4, 2),         # two layers
+    ([256, 128, 128, 10], True, 3000, 2048, 8, 1),  # 256 rows a worker
+    ([100, 64, 10], False, 500, 256, 8, 4),         # fp32, few rows: the small-batch kernel reads through the index
+    ([784, 256, 10], False, 4096, 256, 8, 4),       # the tiny configuration's shape
+    ([130, 48, 10], False, 300, 61, 5, 3),          # ragged everything
+    ([3072, 1024, 1024, 10], True, 4096, 1024, 8, 4),   # the wide configuration as the benchmark launches it
+    ([784, 256, 10], False, 4096, 256, 2, 4),           # the tiny configuration as the benchmark launches it
+    ([512, 1024, 1024, 10], True, 9000, 8192, 8, 2),    # 128 x 128 tiles read through the index
+    ([512, 1024, 1024, 10], True, 40000, 32768, 8, 2),  # 256 x 128 tiles read through the index
+    ([128, 64, 64, 10], True, 900, 500, 8, 4),      # shares that are no whole tiles: the call gathers first
+    ([96, 64, 10], False, 5000, 4096, 4, 2),        # fp32 with many rows: MFMA product, the call gathers first
+])
+def test_indexed_call_equals_gather_then_sliced_grad(synk, dims, bf16, n_data, B, N, S):
+    _indexed_against_gather_then_grad(synk, dims, bf16, n_data, B, N, S, seed=B + N)
+
+
+def test_indexed_call_against_the_oracle_and_index_out_of_range(synk):
+    dims, n_data, B, N, S = [100, 64, 10], 500, 256, 8, 4
+    theta, data, labels, idx, grads = _indexed_against_gather_then_grad(synk, dims, False, n_data, B, N, S, seed=11)
+    ref = omlp.sliced(theta, dims, data.cpu().numpy(), labels.cpu().numpy(), idx, N, S)
+    for w in range(N):
+        assert rel_err(grads[w], ref["worker_grads"][w]) < TOL_F32, w
+    # an index outside the data reads row 0 in the kernels that read through the index: never out of bounds
+    _indexed_against_gather_then_grad(synk, dims, False, n_data, B, N, S, seed=12, bad_index=True)
+    _indexed_against_gather_then_grad(synk, [128, 64, 64, 10], True, 900, 512, 8, 4, seed=13, bad_index=True)
