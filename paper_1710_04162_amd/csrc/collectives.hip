@@ -24,10 +24,13 @@ constexpr int kCBlock = 256;
 // Workgroups per launch, measured per kernel at 25.6 M elements and 8 workers:
 // the in-place all-reduce is fastest with one unit per thread (4.9 against 4.8
 // TB/s at 2048 workgroups), the broadcast at 16384 workgroups (5.5 against 5.0
-// at 2048 and 5.1 at one unit per thread), the all-gather at 2048 per segment.
+// at 2048 and 5.1 at one unit per thread), the all-gather at 4096 or more per
+// segment (shares of 3,194,629 elements: 213 / 204 / 197 / 191 / 191 us at 512 /
+// 1024 / 2048 / 4096 / 16384; shares that are a multiple of 64 elements: 178 us;
+// the broadcast of the same bytes: 167 us).
 constexpr int64_t kAllReduceGridCap = (int64_t)1 << 20;
 constexpr int64_t kBroadcastGridCap = 16384;
-constexpr int64_t kAllGatherGridCap = 2048;
+constexpr int64_t kAllGatherGridCap = 4096;
 static inline int coll_grid(int64_t units, int64_t cap) {
   int64_t b = (units + kCBlock - 1) / kCBlock;
   if (b > cap) b = cap;
@@ -124,17 +127,30 @@ __global__ __launch_bounds__(kCBlock) void all_reduce_kernel(PtrTable t, int n_d
   }
 }
 
-// Four 4-byte elements that are only 4-byte aligned (the compiler picks the
-// widest load the target allows for that alignment).
-struct __attribute__((packed, aligned(4))) Quad {
-  uint32_t v[4];
-};
+// Body of a source that starts R elements past a 16-byte boundary: destination vector i is elements
+// R .. R+3 of the aligned source vectors i and i+1.
+template <int R>
+__device__ __forceinline__ void gather_body_shifted(const u32x4* __restrict__ al, const GatherTable& t, int n,
+                                                    int64_t dst_off, int64_t n_vec, int64_t i0, int64_t stride) {
+  for (int64_t i = i0; i < n_vec; i += stride) {
+    const u32x4 lo = __builtin_nontemporal_load(al + i), hi = __builtin_nontemporal_load(al + i + 1);
+    u32x4 v;
+    if (R == 1) v = u32x4{lo.y, lo.z, lo.w, hi.x};
+    else if (R == 2) v = u32x4{lo.z, lo.w, hi.x, hi.y};
+    else v = u32x4{lo.w, hi.x, hi.y, hi.z};
+    for (int w = 0; w < n; ++w) *reinterpret_cast<u32x4*>(t.dst[w] + dst_off + (i << 2)) = v;
+  }
+}
 
 // blockIdx.y = source worker b: its lens[b] elements go to offset start[b] of
 // every destination.  VEC (every destination base 16-byte aligned): the
 // segment is cut where the destination offset becomes a multiple of four
-// elements; the body is written with 16-byte stores, read from a source that
-// may sit at any 4-byte offset against them.
+// elements and the body is written with 16-byte stores.  The source may sit at
+// any 4-byte offset against that grid (shards of 3,194,629 elements do): a body
+// vector is then put together from the two aligned 16-byte source vectors that
+// hold it (neighbouring threads ask for the same lines, so memory is still read
+// once), and the first and last body vector, whose aligned neighbours may lie
+// outside the source, go with the head and tail in 4-byte units.
 template <bool VEC>
 __global__ __launch_bounds__(kCBlock) void all_gather_kernel(GatherTable t, int n) {
   const int b = blockIdx.y;
@@ -143,14 +159,30 @@ __global__ __launch_bounds__(kCBlock) void all_gather_kernel(GatherTable t, int 
   const int64_t off = t.start[b];
   const int64_t stride = (int64_t)gridDim.x * kCBlock;
   const int64_t i0 = (int64_t)blockIdx.x * kCBlock + threadIdx.x;
-  int64_t head = VEC ? ((4 - (off & 3)) & 3) : len;
+  int64_t head = VEC ? ((64 - (off & 63)) & 63) : len;   // to a 256-byte boundary of the destinations
   if (head > len) head = len;
-  const int64_t n_vec = (len - head) >> 2;
+  int64_t n_vec = (len - head) >> 2;
+  // elements by which the source of the body is past a 16-byte boundary (uniform for the source)
+  const int r = VEC ? (int)((reinterpret_cast<uintptr_t>(src + head) >> 2) & 3) : 0;
+  if (VEC && r != 0) {
+    if (n_vec >= 2) {
+      head += 4;
+      n_vec -= 2;
+    } else {
+      n_vec = 0;
+    }
+  }
   if (VEC) {
-    for (int64_t i = i0; i < n_vec; i += stride) {
-      const Quad q = *reinterpret_cast<const Quad*>(src + head + (i << 2));
-      const u32x4 v = {q.v[0], q.v[1], q.v[2], q.v[3]};
-      for (int w = 0; w < n; ++w) *reinterpret_cast<u32x4*>(t.dst[w] + off + head + (i << 2)) = v;
+    if (r == 0) {
+      for (int64_t i = i0; i < n_vec; i += stride) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + head) + i);
+        for (int w = 0; w < n; ++w) *reinterpret_cast<u32x4*>(t.dst[w] + off + head + (i << 2)) = v;
+      }
+    } else {
+      const u32x4* al = reinterpret_cast<const u32x4*>(src + head - r);   // inside the source: head >= 4 > r
+      if (r == 1) gather_body_shifted<1>(al, t, n, off + head, n_vec, i0, stride);
+      else if (r == 2) gather_body_shifted<2>(al, t, n, off + head, n_vec, i0, stride);
+      else gather_body_shifted<3>(al, t, n, off + head, n_vec, i0, stride);
     }
   }
   // head and tail (or everything, without VEC) in 4-byte units
