@@ -69,7 +69,7 @@ def parse():
     ap.add_argument("--repeats", type=int, default=5,
                     help="the K timed steps are run this many times; value and ms_per_step are the median repeat's")
     ap.add_argument("--separate-gather", action="store_true",
-                    help="configs 1 and 2: input indexing as a gather call of its own before the sliced call "
+                    help="configs 1, 2 and 6: input indexing as a gather call of its own before the sliced call "
                          "(default: folded into the sliced call)")
     ap.add_argument("--sample-every", type=int, default=None,
                     help="put the per-kernel event pair on every N-th step only (default 8; 1 below 64 steps)")
@@ -580,7 +580,7 @@ class EvalStep:
 class ConvStep:
     """Config 6: the whole step with the conv + batch-norm block as the function."""
 
-    def __init__(self, torch, synk, conv_shape=None):
+    def __init__(self, torch, synk, conv_shape=None, separate_gather=False):
         import numpy as np
         import workloads
         self.torch, self.s, self.np = torch, synk, np
@@ -622,21 +622,41 @@ class ConvStep:
         self.dom_work = 2.0 * self.B * H * W * 9 * cin * cout       # flops per launch
         self.dom_bytes = self.B * H * W * (cin + cout) * (2 if self.bf16 else 4)
         s = synk
-        self.call_gather = [s.prepare(s.synk_gather_rows, self.data, up(ix), self.x, labels=self.labels,
-                                      dst_labels=self.y) for ix in idx_sets]
-        self.call_grad = s.prepare(s.synk_sliced_grad_conv, self.shape, self.cd, c["eps"], self.p, self.x, self.y,
-                                   self.rows, self.S, s.SYNK_MEAN, self.grad, self.loss, self.ws)
+        # Input indexing inside the sliced call (the convolution kernels read the images through the index
+        # list; dataset resident in the compute type), or with --separate-gather as a call of its own.
+        self.indexed = not separate_gather
+        self.workload += ("; input indexing inside the sliced call (dataset resident in %s)" % self.dtype
+                          if self.indexed else "; input indexing as a gather call of its own")
+        if self.indexed:
+            self.data_c = self.data
+            if self.bf16:
+                self.data_c = torch.empty(self.data.shape, dtype=torch.bfloat16, device="cuda")
+                s.synk_cast_bf16(self.data, self.data_c)
+            self.ws = torch.empty(s.synk_sliced_grad_conv_indexed_workspace_bytes(self.shape, self.cd, self.B, self.N,
+                                                                                  self.S, c["eps"]),
+                                  dtype=torch.uint8, device="cuda")
+            self.call_gather = [None] * len(idx_sets)
+            self.call_grads = [s.prepare(s.synk_sliced_grad_conv_indexed, self.shape, self.cd, c["eps"], self.p,
+                                         self.data_c, self.labels, up(ix), self.S, s.SYNK_MEAN, self.grad, self.loss,
+                                         self.ws) for ix in idx_sets]
+        else:
+            self.call_gather = [s.prepare(s.synk_gather_rows, self.data, up(ix), self.x, labels=self.labels,
+                                          dst_labels=self.y) for ix in idx_sets]
+            self.call_grads = [s.prepare(s.synk_sliced_grad_conv, self.shape, self.cd, c["eps"], self.p, self.x, self.y,
+                                         self.rows, self.S, s.SYNK_MEAN, self.grad, self.loss, self.ws)] * len(idx_sets)
         self.call_update = s.prepare(s.synk_reduce_sgd_update, self.grad, self.p, self.v, c["lr"], c["momentum"],
                                      c["weight_decay"], loss_in=self.loss, loss_out=self.loss_out)
 
     cycle = 4
 
     def step(self, i, timer):
-        self.call_gather[i % len(self.call_gather)]()
+        k = i % len(self.call_gather)
+        if self.call_gather[k]:
+            self.call_gather[k]()
         if timer.due(i):
-            timer.bracket(self.call_grad)
+            timer.bracket(self.call_grads[k])
         else:
-            self.call_grad()
+            self.call_grads[k]()
         self.call_update()
 
     def cpu_baseline(self):
@@ -734,7 +754,7 @@ def main():
         torch.cuda.set_stream(torch.cuda.Stream())
     wl = {0: lambda: (ProbeStep(torch, synk, a.probe) if a.probe else CopyStep(torch, synk)), 1: lambda: MlpStep(torch, synk, 1, a.batch, separate_gather=a.separate_gather), 2: lambda: MlpStep(torch, synk, 2, a.batch, a.rows_per_worker, a.separate_gather),
           3: lambda: (CollectiveStep(torch, synk, a.collective) if a.collective else ReduceStep(torch, synk, a.rule)), 4: lambda: GatherStep(torch, synk, a.indexing),
-          5: lambda: EvalStep(torch, synk), 6: lambda: ConvStep(torch, synk, a.conv_shape)}[a.config]()
+          5: lambda: EvalStep(torch, synk), 6: lambda: ConvStep(torch, synk, a.conv_shape, a.separate_gather)}[a.config]()
     steps = a.steps if a.steps is not None else {0: 50, 1: 5000, 2: 4500, 3: 2800, 4: 5000, 5: 5000, 6: 3200}[a.config]   # >= 0.5 s a repeat
     if a.rows_per_worker is not None and a.steps is None:
         steps = 56

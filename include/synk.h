@@ -11,7 +11,8 @@
  *                           the same with a slice for a list, the scatter of an
  *                           array over the workers (Sec. 4.2), and indexing of
  *                           shares that already live on the workers (Sec. 5.2)
- *   synk_sliced_grad, synk_sliced_grad_indexed, synk_sliced_grad_conv
+ *   synk_sliced_grad, synk_sliced_grad_indexed, synk_sliced_grad_conv,
+ *   synk_sliced_grad_conv_indexed
  *                           the gradient function run over every worker's
  *                           share in slices, slice results aggregated on the
  *                           GPU (Sec. 5.1), one flat gradient per worker
@@ -331,8 +332,7 @@ int synk_sliced_grad(const synk_mlp_desc* m, const float* params, const void* pa
  *             validate lists with synk_gather_rows + SYNK_FLAG_CHECK_INDEX
  *   ws        synk_sliced_grad_indexed_workspace_bytes(m, n_idx, n_workers, &b)
  * params, params_lp, n_slices, grad_op, grad, loss: as synk_sliced_grad.
- * SYNK_KERNEL_MAIN selects the first forward product, or the gather launch when
- * there is one.
+ * SYNK_KERNEL_MAIN selects the first forward product (never the gather launch).
  * Errors: as synk_sliced_grad; n_idx < 1, n_data < 1 -> ERR_SHAPE. */
 int synk_sliced_grad_indexed_workspace_bytes(const synk_mlp_desc* m, int64_t n_idx, int n_workers,
                                              size_t* bytes);
@@ -403,6 +403,28 @@ int synk_sliced_grad_conv(const synk_convblock_desc* d, const float* params,
                           int n_workers, int n_slices, int grad_op,
                           float* const* grad, float* loss,
                           void* ws, size_t ws_bytes, void* stream);
+
+/* synk_sliced_grad_conv with the input indexing folded in, as synk_sliced_grad_indexed is
+ * for the MLP (Sec. 5.2; Sec. 3.2 step 1): the minibatch is data[idx[0..n_idx)], split over
+ * n_workers by the split rule, and the result equals synk_gather_rows followed by
+ * synk_sliced_grad_conv bit for bit.  Where both convolution kernels can read an image
+ * through the index list (compute_dtype SYNK_BF16, C_in a multiple of 64, 31 <= W <= 61) no
+ * gather takes place and no copy of the images is made; otherwise the call gathers into its
+ * workspace first.
+ *   data    device, [n_data x H*W*C_in] in compute_dtype, channels last, 16-byte aligned
+ *   labels  device int32[n_data];  idx: device int32[n_idx], each in [0, n_data) (an index
+ *           outside reads row 0 in the kernels that read through the list)
+ *   ws      synk_sliced_grad_conv_indexed_workspace_bytes(d, n_idx, n_workers, n_slices, &b)
+ * Other arguments, limits and errors as synk_sliced_grad_conv; n_idx < 1, n_data < 1 ->
+ * ERR_SHAPE. */
+int synk_sliced_grad_conv_indexed_workspace_bytes(const synk_convblock_desc* d, int64_t n_idx,
+                                                  int n_workers, int n_slices, size_t* bytes);
+int synk_sliced_grad_conv_indexed(const synk_convblock_desc* d, const float* params,
+                                  const void* data, const int32_t* labels, int64_t n_data,
+                                  const int32_t* idx, int64_t n_idx,
+                                  int n_workers, int n_slices, int grad_op,
+                                  float* const* grad, float* loss,
+                                  void* ws, size_t ws_bytes, void* stream);
 
 /* out[i] = bf16(in[i]), round-to-nearest-even; device float[len] -> device
  * bf16[len].  Makes the params_lp array for a first step. */

@@ -19,6 +19,7 @@ __all__ = [
     "synk_gather_rows", "synk_build_norm_lut", "synk_poll_error", "synk_mlp_param_count",
     "synk_sliced_grad_workspace_bytes", "synk_sliced_grad", "synk_cast_bf16",
     "synk_sliced_grad_indexed_workspace_bytes", "synk_sliced_grad_indexed",
+    "synk_sliced_grad_conv_indexed_workspace_bytes", "synk_sliced_grad_conv_indexed",
     "synk_sliced_eval_workspace_bytes", "synk_sliced_eval", "synk_sliced_eval_static",
     "synk_static_scratch_init", "synk_reduce_buffers",
     "synk_sgd_update", "synk_reduce_sgd_update", "synk_reduce_update",
@@ -105,6 +106,12 @@ lib.synk_sliced_grad_indexed_workspace_bytes.restype = _int
 lib.synk_sliced_grad_indexed.argtypes = [ctypes.POINTER(MlpDesc), _vp, _vp, _vp, _vp, _i64, _vp, _i64, _int, _int,
                                          _int, _pp, _vp, _vp, _sz, _vp]
 lib.synk_sliced_grad_indexed.restype = _int
+lib.synk_sliced_grad_conv_indexed_workspace_bytes.argtypes = [ctypes.POINTER(ConvBlockDesc), _i64, _int, _int,
+                                                              ctypes.POINTER(_sz)]
+lib.synk_sliced_grad_conv_indexed_workspace_bytes.restype = _int
+lib.synk_sliced_grad_conv_indexed.argtypes = [ctypes.POINTER(ConvBlockDesc), _vp, _vp, _vp, _i64, _vp, _i64, _int, _int,
+                                              _int, _pp, _vp, _vp, _sz, _vp]
+lib.synk_sliced_grad_conv_indexed.restype = _int
 lib.synk_convblock_param_count.argtypes = [ctypes.POINTER(ConvBlockDesc), _pi64]
 lib.synk_sliced_grad_conv_workspace_bytes.argtypes = [ctypes.POINTER(ConvBlockDesc), _pi64, _int, _int,
                                                       ctypes.POINTER(_sz)]
@@ -330,6 +337,25 @@ def synk_sliced_grad_conv(shape, compute_dtype, eps, params, x, y, rows, n_slice
             _stream(stream))
     return _run(lib.synk_sliced_grad_conv, args, (desc, params, x, y, r, grad, loss, ws, tx, ty, tg),
                 "synk_sliced_grad_conv", _prepare)
+
+
+def synk_sliced_grad_conv_indexed_workspace_bytes(shape, compute_dtype, n_idx, n_workers, n_slices, eps=1e-5):
+    out = _sz(0)
+    _check(lib.synk_sliced_grad_conv_indexed_workspace_bytes(ctypes.byref(_conv_desc(shape, compute_dtype, eps)), n_idx,
+                                                             n_workers, n_slices, ctypes.byref(out)),
+           "synk_sliced_grad_conv_indexed_workspace_bytes")
+    return out.value
+
+
+def synk_sliced_grad_conv_indexed(shape, compute_dtype, eps, params, data, labels, idx, n_slices, grad_op, grad, loss,
+                                  ws, stream=None, _prepare=False):
+    wsp, wsb = _ws(ws)
+    desc = _conv_desc(shape, compute_dtype, eps)
+    tg = _table(grad)
+    args = (ctypes.byref(desc), _ptr(params), _ptr(data), _ptr(labels), data.shape[0], _ptr(idx), idx.numel(),
+            len(grad), n_slices, grad_op, tg, _ptr(loss), wsp, wsb, _stream(stream))
+    return _run(lib.synk_sliced_grad_conv_indexed, args, (desc, params, data, labels, idx, grad, loss, ws, tg),
+                "synk_sliced_grad_conv_indexed", _prepare)
 
 
 def synk_cast_bf16(src, dst, stream=None):

@@ -24,6 +24,16 @@ namespace synk {
 // were handed in for).
 bool take_profile_events(int kernel_id, hipEvent_t* start, hipEvent_t* stop);
 
+// While one of these lives on this host thread no launch takes the pending pair: an entry point
+// that calls another one on the way (the gather inside an indexed call) keeps the pair for its
+// own kernels.
+struct ProfileHold {
+  ProfileHold();
+  ~ProfileHold();
+  ProfileHold(const ProfileHold&) = delete;
+  ProfileHold& operator=(const ProfileHold&) = delete;
+};
+
 }  // namespace synk
 
 // Launch of a kernel that a caller may want timed on its own: with events

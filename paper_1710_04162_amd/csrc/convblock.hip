@@ -54,7 +54,21 @@ struct WorkerTable {
   float* grad[SYNK_MAX_WORKERS];
   int32_t rows[SYNK_MAX_WORKERS];
   int32_t row_off[SYNK_MAX_WORKERS + 1];   // images held by the workers before w
+  // Input indexing folded into the call (gsrc == nullptr: x[w], y[w] hold the workers' images and
+  // labels): packed image i is row gidx[i] of the dataset gsrc ([grows x H*W*C_in] in the compute
+  // type), its label glabels[gidx[i]]; an index outside [0, grows) reads row 0.
+  const void* gsrc;
+  const int32_t* gidx;
+  const int32_t* glabels;
+  int32_t grows;
 };
+
+// Dataset row of packed image i under input indexing.
+__device__ __forceinline__ int64_t gathered_row(const WorkerTable& tab, int i) {
+  int64_t s = tab.gidx[i];
+  if (s < 0 || s >= tab.grows) s = 0;
+  return s;
+}
 
 // Offsets into the flat parameter / gradient array.
 struct ParamOff {
@@ -308,8 +322,9 @@ __global__ __launch_bounds__(kThreads, MINB) void conv3x3_fwd_patch_kernel(Worke
   const int img = item / tiles_per_image, tile = item - img * tiles_per_image, n0 = blockIdx.y * 64;
   int w = 0;
   while (w + 1 < sh.n_workers && tab.row_off[w + 1] <= img) ++w;
-  const bf16_t* __restrict__ xi_ = reinterpret_cast<const bf16_t*>(tab.x[w]) +
-                                   (int64_t)(img - tab.row_off[w]) * sh.HW * sh.cin;
+  const bf16_t* __restrict__ xi_ =
+      tab.gsrc ? reinterpret_cast<const bf16_t*>(tab.gsrc) + gathered_row(tab, img) * sh.HW * sh.cin
+               : reinterpret_cast<const bf16_t*>(tab.x[w]) + (int64_t)(img - tab.row_off[w]) * sh.HW * sh.cin;
   const int Wp = sh.W + 2;
   const int first = Wp + 1;                       // position of pixel (0, 0)
   const int n_out = sh.H * Wp - 2;                // positions from the first to the last real pixel
@@ -692,7 +707,7 @@ __global__ __launch_bounds__(kHeadThreads) void head_image_kernel(WorkerTable ta
   se = 0.0f;
 #pragma unroll
   for (int i = 0; i < NW; ++i) se += sred[NW + i];
-  const int y = tab.y[w][j];
+  const int y = tab.gsrc ? tab.glabels[gathered_row(tab, tab.row_off[w] + j)] : tab.y[w][j];
   const bool yok = y >= 0 && y < sh.classes;
   if (tid == 0) row_loss[img] = (mx + logf(se) - (yok ? sl[y] : 0.0f)) * scale;
   __syncthreads();   // sl[y] is read before sl is overwritten
@@ -1289,7 +1304,10 @@ __global__ __launch_bounds__(kRingThreads, 1) void conv3x3_dw_ring_kernel(Worker
   // loaders: unit = (pixel pair pr, 8 channels kv) of the X row (role 0) or the dz row (role 1)
   const int role = tid >> 8, kv = tid & 7, pr = (tid >> 3) & 31;
 
-  const bf16_t* __restrict__ xw = reinterpret_cast<const bf16_t*>(tab.x[w]);
+  // with input indexing the X rows come from the dataset: an image's first byte is looked up when
+  // the row counter enters the image (wave-uniform, once per H + 2 steps)
+  const bool gathered = tab.gsrc != nullptr;
+  const bf16_t* __restrict__ xw = reinterpret_cast<const bf16_t*>(gathered ? tab.gsrc : tab.x[w]);
   const bf16_t* __restrict__ dzw = dz + (int64_t)tab.row_off[w] * sh.HW * sh.cout;
   // the unit's two pixels: X entries b = 2pr, 2pr+1 are w = 2pr-2, 2pr-1; dz entries j = 2pr,
   // 2pr+1 are w = 2pr-1, 2pr
@@ -1301,25 +1319,31 @@ __global__ __launch_bounds__(kRingThreads, 1) void conv3x3_dw_ring_kernel(Worker
   const int64_t off0 = ((int64_t)wpx * nch + chn) * 2, off1 = off0 + (int64_t)nch * 2;
   const int64_t row_bytes = (int64_t)sh.W * nch * 2;
   const bf16_t* __restrict__ src = isx ? xw : dzw;
+  const int64_t image_bytes = (int64_t)sh.H * row_bytes;
 
-  struct Row { int g, i, h; };     // padded row g = i * (H+2) + h (wave-uniform)
+  struct Row { int g, i, h; int64_t ib; };     // padded row g = i * (H+2) + h (wave-uniform); ib: first byte of image i in src
+  auto image_base = [&](int i) -> int64_t {
+    if (!(gathered && isx)) return (int64_t)i * image_bytes;
+    return (i >= 0 && i < tab.rows[w]) ? gathered_row(tab, tab.row_off[w] + i) * image_bytes : 0;
+  };
   auto row_at = [&](int g) {
     Row r;
     r.g = g;
     r.i = (g + HP) / HP - 1;
     r.h = g - r.i * HP;
+    r.ib = image_base(r.i);
     return r;
   };
   auto next_row = [&](Row& r) {
     ++r.g;
-    if (++r.h == HP) { r.h = 0; ++r.i; }
+    if (++r.h == HP) { r.h = 0; ++r.i; r.ib = image_base(r.i); }
   };
   struct Set { u32x4 a, b; };
   // the X loaders take row xr, the dz loaders row dr (a dz row outside the run reads as zeros)
   auto gload = [&](Set& s, const Row& xr, const Row& dr) {
     const Row& r = isx ? xr : dr;
     const bool ok = r.h >= 1 && r.h <= sh.H && (isx ? (r.g >= 0 && r.g < G) : (r.g >= g0 && r.g < g1));
-    const int64_t base = ((int64_t)r.i * sh.H + (r.h - 1)) * row_bytes;
+    const int64_t base = r.ib + (int64_t)(r.h - 1) * row_bytes;
     s.a = load_or_zero(src, base + off0, ok && v0);
     s.b = load_or_zero(src, base + off1, ok && v1);
   };
@@ -1391,7 +1415,7 @@ __global__ __launch_bounds__(kRingThreads, 1) void conv3x3_dw_ring_kernel(Worker
     next_row(xr); next_row(dr);
     __syncthreads();
 
-    Row cur = row_at(g0);
+    Row cur = row_at(g0);          // only g and h of it are used
     // step: issue the loads of the rows three steps on, compute row cur, store the rows of the
     // next step (loaded two steps ago), barrier.  Every step issues its loads and stores its
     // set, also past the end of the run (rows outside it load as zeros and land in slots nobody
@@ -1458,7 +1482,18 @@ struct Plan {
   // workspace offsets in bytes
   size_t o_wmat, o_z, o_dz, o_statp, o_mu, o_rstd, o_poolp, o_pooled, o_dpooled, o_dlogits, o_row_loss, o_bwdp,
       o_bmean, o_dwp, total;
+  // the indexed call: room for the gathered images and labels (used when its kernels cannot read
+  // through the index list and the call gathers first)
+  size_t o_xin, o_ylab, total_indexed;
 };
+
+// Which convolution kernels a shape takes (both read the images through the index list).
+static inline bool patch_kernels_ok(const ConvShape& sh, size_t elem) {
+  return elem == 2 && sh.cin % 64 == 0 && sh.W + 2 <= 63;
+}
+static inline bool ring_kernel_ok(const ConvShape& sh, size_t elem) {
+  return patch_kernels_ok(sh, elem) && sh.W >= 31;     // rows wide enough to fill most of a 64-position step
+}
 
 int make_plan(const synk_convblock_desc* d, const int64_t* rows, int n_workers, int n_slices, Plan* p) {
   if (!d || !rows) return SYNK_ERR_NULL;
@@ -1560,6 +1595,13 @@ int make_plan(const synk_convblock_desc* d, const int64_t* rows, int n_workers, 
   const int runs_max = std::max(p->n_runs, std::max(p->n_runs_rows, p->n_runs_ring));
   p->o_dwp = take((size_t)n_workers * runs_max * p->K * sh.cout * 4);
   p->total = at;
+  p->o_xin = take((size_t)px * sh.cin * p->elem);
+  p->o_ylab = take((size_t)R * 4);
+  p->total_indexed = at;
+  p->tab.gsrc = nullptr;
+  p->tab.gidx = nullptr;
+  p->tab.glabels = nullptr;
+  p->tab.grows = 0;
   return SYNK_OK;
 }
 
@@ -1583,7 +1625,7 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   float* dwp = reinterpret_cast<float*>(ws + p.o_dwp);
 
   const int64_t wn = p.K * sh.cout;
-  const bool patch_ok = sizeof(T) == 2 && sh.cin % 64 == 0 && sh.W + 2 <= 63;
+  const bool patch_ok = patch_kernels_ok(sh, sizeof(T));
   if (patch_ok) {
     const int64_t total = p.K * (int64_t)round_up((size_t)sh.cout, 32);
     hipLaunchKernelGGL(conv_weight_frag_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads),
@@ -1640,7 +1682,7 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   SYNK_LAUNCH_CHECK();
   const dim3 gd((unsigned)(9 * ((sh.cin + 63) / 64) * ((sh.cout + 63) / 64)), (unsigned)p.n_runs,
                 (unsigned)sh.n_workers);
-  const bool ring_ok = patch_ok && sh.W >= 31;     // rows wide enough to fill most of a 64-position step
+  const bool ring_ok = ring_kernel_ok(sh, sizeof(T));
   int fold_runs = p.n_runs;
   if (ring_ok) {
     fold_runs = p.n_runs_ring;
@@ -1719,4 +1761,76 @@ extern "C" int synk_sliced_grad_conv(const synk_convblock_desc* d, const float* 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   if (d->compute_dtype == SYNK_BF16) return run<bf16_t>(p, params, loss, reinterpret_cast<char*>(ws), s);
   return run<float>(p, params, loss, reinterpret_cast<char*>(ws), s);
+}
+
+extern "C" int synk_sliced_grad_conv_indexed_workspace_bytes(const synk_convblock_desc* d, int64_t n_idx,
+                                                             int n_workers, int n_slices, size_t* bytes) {
+  if (!bytes) return SYNK_ERR_NULL;
+  if (n_workers < 1 || n_workers > SYNK_MAX_WORKERS || n_idx < 1) return SYNK_ERR_SHAPE;
+  int64_t rows[SYNK_MAX_WORKERS];
+  for (int w = 0; w < n_workers; ++w) {
+    int64_t start;
+    share(n_idx, n_workers, w, &start, &rows[w]);
+  }
+  Plan p;
+  const int st = make_plan(d, rows, n_workers, n_slices, &p);
+  if (st != SYNK_OK) return st;
+  *bytes = p.total_indexed;
+  return SYNK_OK;
+}
+
+extern "C" int synk_sliced_grad_conv_indexed(const synk_convblock_desc* d, const float* params, const void* data,
+                                             const int32_t* labels, int64_t n_data, const int32_t* idx,
+                                             int64_t n_idx, int n_workers, int n_slices, int grad_op,
+                                             float* const* grad, float* loss, void* ws, size_t ws_bytes,
+                                             void* stream) {
+  if (!d || !params || !data || !labels || !idx || !grad || !loss) return SYNK_ERR_NULL;
+  if (n_workers < 1 || n_workers > SYNK_MAX_WORKERS || n_idx < 1 || n_data < 1 || n_data > 0x7fffffff)
+    return SYNK_ERR_SHAPE;
+  int64_t rows[SYNK_MAX_WORKERS];
+  for (int w = 0; w < n_workers; ++w) {
+    int64_t start;
+    share(n_idx, n_workers, w, &start, &rows[w]);
+  }
+  Plan p;
+  const int st = make_plan(d, rows, n_workers, n_slices, &p);
+  if (st != SYNK_OK) return st;
+  if (grad_op != SYNK_SUM && grad_op != SYNK_MEAN) return SYNK_ERR_OP;
+  p.sh.grad_op = grad_op;
+  if (!aligned_to(params, 16) || !aligned_to(data, 16) || !aligned_to(labels, 4) || !aligned_to(idx, 4))
+    return SYNK_ERR_ALIGN;
+  for (int w = 0; w < n_workers; ++w) {
+    if (!grad[w]) return SYNK_ERR_NULL;
+    if (!aligned_to(grad[w], 16)) return SYNK_ERR_ALIGN;
+  }
+  if (!ws || !aligned_to(ws, 256) || ws_bytes < p.total_indexed) return SYNK_ERR_WORKSPACE;
+  char* wsb = reinterpret_cast<char*>(ws);
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const int64_t row_elems = (int64_t)p.sh.HW * p.sh.cin;
+  const bool through_index = ring_kernel_ok(p.sh, p.elem);   // both convolution kernels read through the list
+  void* xw[SYNK_MAX_WORKERS];
+  int32_t* yw[SYNK_MAX_WORKERS];
+  for (int w = 0; w < SYNK_MAX_WORKERS; ++w) {
+    const bool live = w < n_workers;
+    xw[w] = live ? wsb + p.o_xin + (size_t)p.tab.row_off[w] * row_elems * p.elem : nullptr;
+    yw[w] = live ? reinterpret_cast<int32_t*>(wsb + p.o_ylab) + p.tab.row_off[w] : nullptr;
+    p.tab.x[w] = through_index ? nullptr : xw[w];
+    p.tab.y[w] = through_index ? nullptr : yw[w];
+    p.tab.grad[w] = live ? grad[w] : nullptr;
+    if (!live) { p.tab.rows[w] = 0; p.tab.row_off[w + 1] = p.tab.row_off[n_workers]; }
+  }
+  if (through_index) {
+    p.tab.gsrc = data;
+    p.tab.gidx = idx;
+    p.tab.glabels = labels;
+    p.tab.grows = (int32_t)n_data;
+  } else {
+    const int dt = d->compute_dtype;
+    ProfileHold hold;   // a pending event pair is for the forward convolution, not for the gather
+    if (int rc = synk_gather_rows(data, n_data, row_elems, dt, idx, n_idx, xw, n_workers, dt, nullptr, 0, labels, yw,
+                                  0, nullptr, 0, stream))
+      return rc;
+  }
+  if (d->compute_dtype == SYNK_BF16) return run<bf16_t>(p, params, loss, wsb, s);
+  return run<float>(p, params, loss, wsb, s);
 }

@@ -1835,6 +1835,7 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
         g.gather_y = const_cast<int32_t*>(y[0]);   // packed labels: y[w] = y[0] + row_off[w] in the indexed call
       } else {
         const int dt = sizeof(T) == 4 ? SYNK_F32 : SYNK_BF16;
+        ProfileHold hold;   // a pending event pair is for the forward product, not for the gather
         if (int rc = synk_gather_rows(gin->data, gin->n_data, K, dt, gin->idx, p.R, const_cast<void* const*>(x), n_workers,
                                       dt, nullptr, 0, gin->labels, const_cast<int32_t* const*>(y), 0, nullptr, 0, s))
           return rc;

@@ -38,8 +38,13 @@ namespace synk {
 static thread_local hipEvent_t tl_start = nullptr, tl_stop = nullptr;
 static thread_local int tl_kernel = SYNK_KERNEL_MAIN;
 
+static thread_local int tl_held = 0;   // > 0: launches of a nested call leave the pending pair alone
+
+ProfileHold::ProfileHold() { ++tl_held; }
+ProfileHold::~ProfileHold() { --tl_held; }
+
 bool take_profile_events(int kernel_id, hipEvent_t* start, hipEvent_t* stop) {
-  if (!tl_start || kernel_id != tl_kernel) return false;
+  if (!tl_start || kernel_id != tl_kernel || tl_held > 0) return false;
   *start = tl_start;
   *stop = tl_stop;
   tl_start = tl_stop = nullptr;

@@ -236,6 +236,31 @@ def test_sliced_grad_conv_argument_checks_and_workspace():
     assert call(x=_tbl(FAKE, None)) == -1 and call(y=_tbl(None, FAKE)) == -1
 
 
+
+def test_sliced_grad_conv_indexed_argument_checks_and_workspace():
+    shape = (6, 5, 8, 16, 10)
+    plain = synk.synk_sliced_grad_conv_workspace_bytes(shape, synk.SYNK_F32, [4, 3], 2)
+    b = synk.synk_sliced_grad_conv_indexed_workspace_bytes(shape, synk.SYNK_F32, 7, 2, 2)
+    assert b % 256 == 0 and b >= plain + 7 * 6 * 5 * 8 * 4 + 7 * 4          # + the gathered images and labels
+    with pytest.raises(synk.SynkError) as e:
+        synk.synk_sliced_grad_conv_indexed_workspace_bytes(shape, synk.SYNK_F32, 0, 2, 2)
+    assert e.value.status == -2
+    f = lib.synk_sliced_grad_conv_indexed
+    d = synk._conv_desc(shape, synk.SYNK_F32, 1e-5)
+    t2 = _tbl(FAKE, FAKE)
+
+    def call(desc=d, params=FAKE, data=FAKE, labels=FAKE, n_data=50, idx=FAKE, n_idx=7, nw=2, ns=2, op=1, grad=t2,
+             loss=FAKE, ws=FAKE, wsb=1 << 30):
+        return f(ctypes.byref(desc), params, data, labels, n_data, idx, n_idx, nw, ns, op, grad, loss, ws, wsb, None)
+
+    assert call(params=None) == -1 and call(data=None) == -1 and call(labels=None) == -1 and call(idx=None) == -1
+    assert call(grad=None) == -1 and call(loss=None) == -1
+    assert call(n_idx=0) == -2 and call(n_data=0) == -2 and call(nw=0) == -2 and call(nw=65) == -2 and call(ns=0) == -2
+    assert call(op=2) == -4
+    assert call(data=FAKE + 8) == -5 and call(idx=FAKE + 2) == -5 and call(grad=_tbl(FAKE, FAKE + 4)) == -5
+    assert call(ws=None) == -6 and call(wsb=b - 1) == -6 and call(ws=FAKE + 16) == -6
+
+
 def test_sliced_eval_argument_checks_and_workspace():
     # four partial results per (slice, row set of 8 rows)
     assert synk.synk_sliced_eval_workspace_bytes(65536, 1000, 64) >= 4 * 64 * (1024 // 8) * 4

@@ -192,3 +192,47 @@ def test_full_size_config6_every_worker_against_oracle(synk):
     for w in range(cfg["n_workers"]):
         assert np.isfinite(g[w]).all()
         assert abs(g[w][-cfg["shape"][4]:].sum()) < 1e-5      # softmax: the last bias gradient sums to zero
+
+
+# ------------------------------------------------------------- input indexing folded into the call
+def _indexed_equals_gather_then_grad(synk, shape, n_data, B, N, S, bf16, seed, bad_index=False):
+    """synk_sliced_grad_conv_indexed == synk_gather_rows + synk_sliced_grad_conv, bit for bit."""
+    cfg = small_cfg(shape, n_data, seed)
+    rng = np.random.default_rng(seed + 1)
+    idx = rng.integers(0, n_data, B).astype(np.int32)
+    ref_idx = idx.copy()
+    if bad_index:                      # the kernels that read through the list take row 0 for such an index
+        idx[1], idx[B - 1] = n_data + 3, -2
+        ref_idx[1], ref_idx[B - 1] = 0, 0
+    ga, la = run_gpu(synk, cfg, ref_idx, N, S, "mean", bf16)
+    cd = synk.SYNK_BF16 if bf16 else synk.SYNK_F32
+    P = synk.synk_convblock_param_count(shape)
+    data = dev(cfg["data"])
+    if bf16:
+        data = data.bfloat16()
+    gb = [torch.full((P,), 7.0, device="cuda") for _ in range(N)]
+    lb = torch.full((N,), -2.0, device="cuda")
+    ws = torch.full((synk.synk_sliced_grad_conv_indexed_workspace_bytes(shape, cd, B, N, S),), 0x5A, dtype=torch.uint8,
+                    device="cuda")
+    for _ in range(2):                 # the second call runs on a workspace the first has used
+        synk.synk_sliced_grad_conv_indexed(shape, cd, 1e-5, dev(cfg["theta"]), data, dev(cfg["labels"]), dev(idx), S,
+                                           synk.SYNK_MEAN, gb, lb, ws)
+    torch.cuda.synchronize()
+    for w in range(N):
+        assert np.array_equal(gb[w].cpu().numpy().view(np.uint32), ga[w].view(np.uint32)), w
+    assert np.array_equal(lb.cpu().numpy().view(np.uint32), la.view(np.uint32))
+
+
+@pytest.mark.parametrize("shape,n_data,B,N,S,bf16", [
+    ((40, 33, 64, 64, 10), 30, 16, 4, 1, True),      # both convolution kernels read through the index list
+    ((34, 61, 128, 32, 7), 12, 9, 4, 2, True),       # two 64-channel chunks, ragged shares, two slices
+    ((56, 56, 64, 64, 1000), 70, 64, 8, 1, True),    # the configuration's shape
+    ((12, 12, 64, 16, 5), 20, 10, 3, 1, True),       # narrow images: the call gathers first
+    ((9, 11, 8, 16, 5), 20, 10, 3, 2, False),        # fp32: the call gathers first
+])
+def test_indexed_conv_call_equals_gather_then_call(synk, shape, n_data, B, N, S, bf16):
+    _indexed_equals_gather_then_grad(synk, shape, n_data, B, N, S, bf16, seed=sum(shape) + B)
+
+
+def test_indexed_conv_call_with_an_index_out_of_range(synk):
+    _indexed_equals_gather_then_grad(synk, (40, 33, 64, 64, 10), 30, 16, 4, 1, True, seed=5, bad_index=True)
