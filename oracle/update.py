@@ -1,7 +1,7 @@
 """Sec. 3.3 step 3: the update rule applied with the combined gradient on the
 flat parameter array.  The paper names the rules (momentum, Nesterov momentum,
-RMSProp, Adam, "as included in Lasagne") without formulas; the readings taken
-are the published forms of those rules as that library states them, with
+RMSProp, Adam) by reference to the Lasagne library, without formulas; the readings
+taken are the published forms of those rules as that library states them, with
 g = G + wd * p (coupled L2 weight decay on every element of the flat array):
 
   momentum   v' = m v - lr g ;            p' = p + v'
