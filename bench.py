@@ -72,7 +72,7 @@ def parse():
                     help="configs 1, 2 and 6: input indexing as a gather call of its own before the sliced call "
                          "(default: folded into the sliced call)")
     ap.add_argument("--sample-every", type=int, default=None,
-                    help="put the per-kernel event pair on every N-th step only (default 8; 1 below 64 steps)")
+                    help="put the per-kernel event pair on every N-th step only (default 8; 1 below 64 timed steps in all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -792,7 +792,7 @@ def main():
             torch.cuda.synchronize()
             per_repeat.append(time.perf_counter() - t0)
     else:
-        every = a.sample_every if a.sample_every else (8 if steps >= 64 else 1)
+        every = a.sample_every if a.sample_every else (8 if steps * repeats >= 64 else 1)
         timer = Timer(torch, synk, steps * repeats // every + repeats + 1, every)
         for i in range(warmup):
             wl.step(i, timer)
