@@ -76,18 +76,19 @@ static inline void share(int64_t count, int parts, int i, int64_t* start, int64_
   *start = base * i + (i < extra ? i : extra);
 }
 
-// float -> bfloat16 bits, round to nearest even (finite inputs; NaN kept quiet)
+// float -> bfloat16 bits, round to nearest even (NaN stays NaN): the conversion instruction of
+// gfx950 (v_cvt_pk_bf16_f32), which the compiler selects for these casts.
 __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+  return __builtin_bit_cast(uint16_t, (__bf16)f);
 }
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) {
   return __uint_as_float(((uint32_t)h) << 16);
 }
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 // Device-side form of the split rule: which share holds point j, and where

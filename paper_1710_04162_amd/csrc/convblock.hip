@@ -439,6 +439,261 @@ __global__ __launch_bounds__(kThreads, MINB) void conv3x3_fwd_patch_kernel(Worke
   }
 }
 
+// The same contraction for bf16 with 64 input channels and at most 64 output
+// channels: the whole right operand is 9 * 64 * 64 values, so a wavefront keeps
+// all of it in registers (72 operand vectors, most of them in the accumulation
+// registers, which the MFMA reads directly) for the life of the workgroup, and
+// the tap loop reads only positions from LDS: one 16-byte read per lane feeds
+// two MFMAs.  One workgroup per CU (one wavefront per SIMD, 512 registers)
+// takes units of work, a unit being a run of consecutive 128-position tiles of
+// one image.  The padded positions of the image slide through a ring of four
+// blocks of 128 positions: tile t needs blocks t and t + 1 (its taps reach at
+// most 2 (W + 3) <= 128 positions past its first); block t + 3 is asked for
+// during tile t and goes from registers to the ring during tile t + 1; one
+// barrier per tile.
+//
+// With one wavefront per SIMD nothing else hides the work around the MFMAs, so
+// it is cut into slices that sit between them (a slot = the two MFMAs of one
+// contraction step and what follows them): the ring stores and block loads, and
+// the output of the tile BEFORE this one, whose sums wait in a second set of
+// registers: pack to bf16 (the channels are the MFMA's M side, a lane holds four
+// consecutive channels of one position), through a staging area of the
+// wavefront's own (no barrier) into whole 128-byte rows, and out.  The stores
+// are buffer stores whose offset is out of range for a border position, so that
+// the tile body has no branch.
+constexpr int kHoldTile = 128, kHoldRing = 4 * kHoldTile;
+constexpr int kHoldStageRow = 144;     // bytes: 64 channels bf16 + 16, as kLdsRow
+constexpr uint32_t kHoldDrop = 0x80000000u;     // a store offset past every image
+
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void conv3x3_fwd_hold_kernel(WorkerTable tab, ConvShape sh, const float* __restrict__ params, bf16_t* __restrict__ z,
+                             int tiles_per_image, int per_img, int n_units) {
+  __shared__ __attribute__((aligned(16))) char ring[kHoldRing * kLdsRow];
+  __shared__ __attribute__((aligned(16))) char stage[(kThreads / 64) * 32 * kHoldStageRow];
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int xi = lane & 31, gk = lane >> 5;
+  const int kv = tid & 7, ur = tid >> 3, c8 = lane & 7;
+  const int H = sh.H, W = sh.W, Wp = W + 2, cout = sh.cout;
+  const int z_image_bytes = sh.HW * cout * 2;
+
+  // steps of a padded position by 8, 32 and 128: rows and columns of the (H+2) x (W+2) grid
+  const int a8h = 8 / Wp, a8w = 8 - a8h * Wp, a32h = 32 / Wp, a32w = 32 - a32h * Wp;
+  const int a128h = 128 / Wp, a128w = 128 - a128h * Wp;
+  auto adv = [&](int& hp, int& wp, int ah, int aw) {
+    wp += aw;
+    hp += ah;
+    if (wp >= Wp) { wp -= Wp; ++hp; }
+  };
+
+  // A block of 128 positions: thread (ur, kv) holds vector kv of positions ur + 32 it.  The loads
+  // carry no condition (a position outside the image reads the image's first vector) and the
+  // zeroing waits until the store, so that nothing waits for a load where it is issued.
+  struct Block { u32x4 v[4]; uint32_t keep[4]; };
+  const char* ximg = nullptr;
+  int lhp = 0, lwp = 0;                 // padded position of row ur of the next block to ask for
+  auto load_row = [&](int it, Block& blk, int hp, int wp) {
+    const uint32_t m = -(uint32_t)((unsigned)(hp - 1) < (unsigned)H & (unsigned)(wp - 1) < (unsigned)W);
+    const uint32_t off = (uint32_t)(((hp - 1) * W + (wp - 1)) * 128 + kv * 16) & m;
+    blk.v[it] = *reinterpret_cast<const u32x4*>(ximg + off);
+    blk.keep[it] = m;
+  };
+  auto load_block = [&](Block& blk) {   // the block at (lhp, lwp); moves on to the next block
+    int hp = lhp, wp = lwp;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      load_row(it, blk, hp, wp);
+      adv(hp, wp, a32h, a32w);
+    }
+    adv(lhp, lwp, a128h, a128w);
+  };
+  auto store_row = [&](int b, int it, const Block& blk) {
+    const uint32_t k = blk.keep[it];
+    const u32x4 q = {blk.v[it].x & k, blk.v[it].y & k, blk.v[it].z & k, blk.v[it].w & k};
+    *reinterpret_cast<u32x4*>(&ring[(((b & 3) * kHoldTile) + ur + it * 32) * kLdsRow + kv * 16]) = q;
+  };
+
+  // z of one image as a buffer: an offset of kHoldDrop or more is dropped by the range check.  The
+  // address is wave-uniform; said explicitly, so that the descriptor sits in scalar registers.
+  auto z_rsrc = [&](int img) {
+    const uint64_t a = reinterpret_cast<uint64_t>(z + (int64_t)img * sh.HW * cout);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | (uint64_t)lo), 0,
+                                             z_image_bytes, 0x00020000);
+  };
+  char* my_stage = stage + wv * 32 * kHoldStageRow;
+  // the tile before: its sums, where its four rows per lane go, its image
+  auto stage_chunk = [&](const f32x16 (&accp)[2], int c) {   // chunk c: channels ct*32 + j*8 + gk*4 .. +4
+    const int ct = c >> 2, j = c & 3;
+    const u32x2 q = {pack_bf16x2(accp[ct][4 * j], accp[ct][4 * j + 1]),
+                     pack_bf16x2(accp[ct][4 * j + 2], accp[ct][4 * j + 3])};
+    *reinterpret_cast<u32x2*>(my_stage + xi * kHoldStageRow + (ct * 32 + j * 8 + gk * 4) * 2) = q;
+  };
+  auto stage_row = [&](int it) {
+    return *reinterpret_cast<const u32x4*>(my_stage + (it * 8 + (lane >> 3)) * kHoldStageRow + c8 * 16);
+  };
+
+  u32x4 wr[9][4][2];
+  f32x16 accp[2] = {zero16(), zero16()};
+  uint32_t poff[4] = {kHoldDrop, kHoldDrop, kHoldDrop, kHoldDrop};
+  int pimg = 0;
+  bool have_weights = false;
+
+  for (int unit = blockIdx.x; unit < n_units; unit += gridDim.x) {
+    const int img = unit / per_img, part = unit - img * per_img;
+    const int t0 = part * tiles_per_image / per_img, t1 = (part + 1) * tiles_per_image / per_img;
+    if (t0 >= t1) continue;
+    {
+      int w = 0;
+      while (w + 1 < sh.n_workers && tab.row_off[w + 1] <= img) ++w;
+      ximg = tab.gsrc ? reinterpret_cast<const char*>(tab.gsrc) + gathered_row(tab, img) * sh.HW * 128
+                      : reinterpret_cast<const char*>(tab.x[w]) + (int64_t)(img - tab.row_off[w]) * sh.HW * 128;
+      const int up = t0 * kHoldTile + ur;
+      lhp = up / Wp;
+      lwp = up - lhp * Wp;
+    }
+    // rows of tile t: position r = t*128 + wv*32 + it*8 + lane/8 counted from the first real pixel,
+    // which is padded position Wp + 1 + r
+    int shp, swp;
+    {
+      const int u = Wp + 1 + t0 * kHoldTile + wv * 32 + (lane >> 3);
+      shp = u / Wp;
+      swp = u - shp * Wp;
+    }
+    Block rn;
+    {
+      Block r0, r1;
+      load_block(r0);
+      load_block(r1);
+      load_block(rn);
+      if (!have_weights) {
+        have_weights = true;
+        // The right operand, while the first blocks travel: the workgroup rounds Wc (fp32 in
+        // params, [9 * 64][C_out]) to bf16 into the ring's memory in operand order, vector
+        // ((tap * 2 + ct) * 4 + kk) * 64 + lane = the 8 values Wc[tap*64 + kk*16 + gk*8 + e][ct*32 + xi]
+        // (zero past C_out), and every wavefront takes its 72 vectors from there.  A launch that
+        // prepares this for all workgroups costs more than they spend here.
+        {
+          const int o = tid & 63;
+#pragma unroll 9
+          for (int it = 0; it < 18; ++it) {
+            const int q = it * 4 + (tid >> 6);                    // (tap, kk, gk)
+            const int tap = q >> 3, kk = (q >> 1) & 3, g = q & 1;
+            const float* src = params + (int64_t)(tap * 64 + kk * 16 + g * 8) * cout + min(o, cout - 1);
+            float f[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] = src[e * cout];
+            u32x4 v = {pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7])};
+            if (o >= cout) v = u32x4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4*>(&ring[(((tap * 2 + (o >> 5)) * 4 + kk) * 64 + g * 32 + (o & 31)) * 16]) = v;
+          }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+          for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+              wr[tap][kk][ct] = *reinterpret_cast<const u32x4*>(&ring[(((tap * 2 + ct) * 4 + kk) * 64 + lane) * 16]);
+        // Every vector is named in an empty asm statement: that fixes its register file (64 of the
+        // 72 in the accumulation registers), and it puts the wait for these reads here.
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) {
+            if (tap < 8) {
+              asm volatile("" : "+a"(wr[tap][kk][0]));
+              asm volatile("" : "+a"(wr[tap][kk][1]));
+            } else {
+              asm volatile("" : "+v"(wr[tap][kk][0]));
+              asm volatile("" : "+v"(wr[tap][kk][1]));
+            }
+          }
+        __syncthreads();               // the ring's memory is free for the blocks
+      }
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        store_row(t0, it, r0);
+        store_row(t0 + 1, it, r1);
+      }
+      __syncthreads();
+    }
+
+    for (int t = t0; t < t1; ++t) {
+      f32x16 acc[2] = {zero16(), zero16()};
+      uint32_t coff[4];
+      u32x4 qv[4];
+      const __amdgpu_buffer_rsrc_t prs = z_rsrc(pimg);
+      const int p0 = t * kHoldTile + wv * 32 + xi;      // this lane's position; tap (kh, kw) reads p0 + kh Wp + kw
+      auto read_tap = [&](int tap, u32x4 (&a)[4]) {
+        const int row = (p0 + (tap / 3) * Wp + tap % 3) & (kHoldRing - 1);
+        const char* P = ring + row * kLdsRow + gk * 16;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) a[kk] = *reinterpret_cast<const u32x4*>(P + kk * 32);
+      };
+      int hp_l = lhp, wp_l = lwp, hp_s = shp, wp_s = swp;
+      auto side = [&](int s) {
+        if (s < 8) {
+          const int it = s >> 1;
+          if (!(s & 1)) {
+            store_row(t + 2, it, rn);          // block t+2, asked for one tile ago
+          } else {
+            load_row(it, rn, hp_l, wp_l);      // block t+3
+            adv(hp_l, wp_l, a32h, a32w);
+          }
+        } else if (s < 24) {
+          const int c = (s - 8) >> 1;
+          if (!(s & 1)) {
+            stage_chunk(accp, c);
+          } else if (c < 4) {                  // where this tile's rows go
+            const uint32_t bad = (uint32_t)!((unsigned)(hp_s - 1) < (unsigned)H & (unsigned)(wp_s - 1) < (unsigned)W &
+                                             c8 * 8 < cout);
+            coff[c] = (uint32_t)(((hp_s - 1) * W + (wp_s - 1)) * cout * 2 + c8 * 16) | (bad << 31);
+            adv(hp_s, wp_s, a8h, a8w);
+          }
+        } else if (s < 28) {
+          qv[s - 24] = stage_row(s - 24);
+        } else if (!(s & 1)) {
+          const int it = (s - 28) >> 1;
+          __builtin_amdgcn_raw_buffer_store_b128(qv[it], prs, poff[it], 0, 0);
+        }
+      };
+      // the positions of a tap are read while the tap before it is multiplied
+      u32x4 a[2][4];
+      read_tap(0, a[0]);
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        if (tap + 1 < 9) read_tap(tap + 1, a[(tap + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);       // the reads stay ahead of the MFMAs that hide them
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          acc[0] = mma(bf16_t(), wr[tap][kk][0], a[tap & 1][kk], acc[0]);
+          acc[1] = mma(bf16_t(), wr[tap][kk][1], a[tap & 1][kk], acc[1]);
+          side(tap * 4 + kk);
+          __builtin_amdgcn_sched_barrier(0);     // and every slice stays in its slot
+        }
+      }
+      adv(lhp, lwp, a128h, a128w);
+      adv(shp, swp, a128h, a128w);
+      accp[0] = acc[0];
+      accp[1] = acc[1];
+#pragma unroll
+      for (int it = 0; it < 4; ++it) poff[it] = coff[it];
+      pimg = img;
+      __syncthreads();
+    }
+  }
+
+  // the last tile's rows
+  const __amdgpu_buffer_rsrc_t prs = z_rsrc(pimg);
+#pragma unroll
+  for (int c = 0; c < 8; ++c) stage_chunk(accp, c);
+#pragma unroll
+  for (int it = 0; it < 4; ++it) __builtin_amdgcn_raw_buffer_store_b128(stage_row(it), prs, poff[it], 0, 0);
+}
+
 // -------------------------------------------------- streaming passes over z
 // A workgroup takes up to kChunkRows pixels of one image and all channels:
 // thread = (4 consecutive channels, row group); row groups are folded through
@@ -450,10 +705,10 @@ struct Chunk {
   bool active;
 };
 
-__device__ __forceinline__ Chunk chunk_of(const WorkerTable& tab, const ConvShape& sh) {
+__device__ __forceinline__ Chunk chunk_of(const WorkerTable& tab, const ConvShape& sh, int bid = blockIdx.x) {
   Chunk c;
-  c.img = blockIdx.x / sh.n_chunks;
-  c.chunk = blockIdx.x - c.img * sh.n_chunks;
+  c.img = bid / sh.n_chunks;
+  c.chunk = bid - c.img * sh.n_chunks;
   int w = 0;
   while (w + 1 < sh.n_workers && tab.row_off[w + 1] <= c.img) ++w;
   c.w = w;
@@ -786,25 +1041,25 @@ __global__ __launch_bounds__(kHeadThreads) void head_image_kernel(WorkerTable ta
   }
 }
 
-constexpr int kImgTile = 8;   // images held in registers at a time by head_worker_kernel
+constexpr int kImgTile = 8;   // images held in registers at a time by head_worker_body
 constexpr int kWorkerChans = 64;
 
-// Per worker, class k and group of kWorkerChans channels (blockIdx.z): dWf[group, k]
-// over the worker's images in image order, kImgTile images at a time held in
-// registers; group 0 also writes dbf[k], and its workgroup (0, w) folds the
-// image losses into loss[w].
-__global__ __launch_bounds__(kThreads) void head_worker_kernel(WorkerTable tab, ConvShape sh,
-                                                               const float* __restrict__ pooled,
-                                                               const float* __restrict__ dlogits,
-                                                               const float* __restrict__ row_loss,
-                                                               float* __restrict__ loss) {
+// Per worker w, class k (block bx of 256 classes) and group bz of kWorkerChans channels:
+// dWf[group, k] over the worker's images in image order, kImgTile images at a time held in
+// registers; group 0 also writes dbf[k], and its block (0, w) folds the image losses into
+// loss[w].  Runs as the first workgroups of bn_bwd_chunk_kernel's launch.
+__device__ __forceinline__ void head_worker_body(const WorkerTable& tab, const ConvShape& sh,
+                                                 const float* __restrict__ pooled,
+                                                 const float* __restrict__ dlogits,
+                                                 const float* __restrict__ row_loss, float* __restrict__ loss,
+                                                 int bx, int w, int bz) {
   __shared__ float sp[kImgTile][kWorkerChans];
-  const int w = blockIdx.y, k = blockIdx.x * kThreads + threadIdx.x;
-  const int ch0 = blockIdx.z * kWorkerChans, nch = min(kWorkerChans, sh.cout - ch0);
+  const int k = bx * kThreads + threadIdx.x;
+  const int ch0 = bz * kWorkerChans, nch = min(kWorkerChans, sh.cout - ch0);
   const int i0 = tab.row_off[w], n = tab.rows[w];
   const ParamOff po = param_off(sh.cin, sh.cout, sh.classes);
   float* __restrict__ g = tab.grad[w];
-  if (blockIdx.z == 0 && blockIdx.x == 0 && threadIdx.x == 0) {
+  if (bz == 0 && bx == 0 && threadIdx.x == 0) {
     float a = 0.0f;
     for (int i = 0; i < n; ++i) a += row_loss[i0 + i];
     loss[w] = a;
@@ -835,12 +1090,17 @@ __global__ __launch_bounds__(kThreads) void head_worker_kernel(WorkerTable tab, 
       }
     }
   }
-  if (live && blockIdx.z == 0) g[po.bf + k] = b;
+  if (live && bz == 0) g[po.bf + k] = b;
 }
 
 // ------------------------------------------------------ batch-norm backward
 // dy = (dp / HW) [gamma*xhat + beta > 0].  Per (image, chunk, channel): sum of
 // dy and of dy * xhat.
+// The first head_blocks workgroups of the launch do the head's per-worker sums instead
+// (head_worker_body; block = (class block, worker, channel group), class block fastest): both need
+// only what head_image_kernel left, nothing after this launch but the update reads those sums, and
+// a launch of their own would be one more latency-bound link in the chain (9 us at 8 workers, 64
+// channels and 1000 classes); here they run beside the pass over z.
 template <typename Tz>
 __global__ __launch_bounds__(kThreads) void bn_bwd_chunk_kernel(WorkerTable tab, ConvShape sh,
                                                                 const float* __restrict__ params,
@@ -848,9 +1108,20 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_chunk_kernel(WorkerTable tab,
                                                                 const float* __restrict__ mu,
                                                                 const float* __restrict__ rstd,
                                                                 const float* __restrict__ dpooled,
-                                                                float* __restrict__ bwdp) {
+                                                                float* __restrict__ bwdp,
+                                                                const float* __restrict__ pooled,
+                                                                const float* __restrict__ dlogits,
+                                                                const float* __restrict__ row_loss,
+                                                                float* __restrict__ loss, int head_blocks,
+                                                                int class_blocks) {
+  if ((int)blockIdx.x < head_blocks) {
+    const int bx = blockIdx.x % class_blocks, r = blockIdx.x / class_blocks;
+    head_worker_body(tab, sh, pooled, dlogits, row_loss, loss, bx, r % sh.n_workers, r / sh.n_workers);
+    return;
+  }
+  const int bid = blockIdx.x - head_blocks;
   __shared__ __attribute__((aligned(16))) float red[2 * kThreads * 4];
-  const Chunk c = chunk_of(tab, sh);
+  const Chunk c = chunk_of(tab, sh, bid);
   const ParamOff po = param_off(sh.cin, sh.cout, sh.classes);
   f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
   if (c.active) {
@@ -877,7 +1148,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_chunk_kernel(WorkerTable tab,
   fold_store<2>(red, c, sh.cout, acc);
   __syncthreads();
   for (int ch = threadIdx.x; ch < sh.cout; ch += kThreads) {
-    float* o = bwdp + ((int64_t)blockIdx.x * sh.cout + ch) * 2;
+    float* o = bwdp + ((int64_t)bid * sh.cout + ch) * 2;
     o[0] = fold_sum(red, 0, c.n_rg, sh.cout, ch);
     o[1] = fold_sum(red, 1, c.n_rg, sh.cout, ch);
   }
@@ -1545,6 +1816,9 @@ struct Plan {
 static inline bool patch_kernels_ok(const ConvShape& sh, size_t elem) {
   return elem == 2 && sh.cin % 64 == 0 && sh.W + 2 <= 63;
 }
+static inline bool hold_kernel_ok(const ConvShape& sh, size_t elem) {
+  return patch_kernels_ok(sh, elem) && sh.cin == 64 && sh.cout <= 64;
+}
 static inline bool ring_kernel_ok(const ConvShape& sh, size_t elem) {
   return patch_kernels_ok(sh, elem) && sh.W >= 31;     // rows wide enough to fill most of a 64-position step
 }
@@ -1679,8 +1953,10 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   float* dwp = reinterpret_cast<float*>(ws + p.o_dwp);
 
   const int64_t wn = p.K * sh.cout;
-  const bool patch_ok = patch_kernels_ok(sh, sizeof(T));
-  if (patch_ok) {
+  const bool patch_ok = patch_kernels_ok(sh, sizeof(T)), hold_ok = hold_kernel_ok(sh, sizeof(T));
+  if (hold_ok) {
+    // the forward kernel lays the weights out itself
+  } else if (patch_ok) {
     const int64_t total = p.K * (int64_t)round_up((size_t)sh.cout, 32);
     hipLaunchKernelGGL(conv_weight_frag_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads),
                        0, st, params, reinterpret_cast<uint16_t*>(wmat), sh.cin, sh.cout, total);
@@ -1691,7 +1967,21 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
   SYNK_LAUNCH_CHECK();
   const dim3 gf((unsigned)(((int64_t)p.max_unit_images * sh.HW + kFwdBM - 1) / kFwdBM),
                 (unsigned)((sh.cout + kFwdBN - 1) / kFwdBN), (unsigned)p.n_units);
-  if (patch_ok) {
+  if (hold_ok) {
+    // units: an image's tiles in per_img runs; per_img so that the rounds of units over the CUs,
+    // times a unit's tiles plus one for its start, come out smallest
+    const int tiles_per_image = (sh.H * (sh.W + 2) - 2 + kHoldTile - 1) / kHoldTile;
+    int per_img = 1;
+    int64_t best = -1;
+    for (int g = 1; g <= std::min(tiles_per_image, 16); ++g) {
+      const int64_t rounds = ((int64_t)sh.total_images * g + kNumCU - 1) / kNumCU;
+      const int64_t cost = rounds * ((tiles_per_image + g - 1) / g + 1);
+      if (best < 0 || cost < best) { best = cost; per_img = g; }
+    }
+    const int64_t n_units = (int64_t)sh.total_images * per_img;
+    SYNK_LAUNCH_TIMED(conv3x3_fwd_hold_kernel, dim3((unsigned)std::min<int64_t>(kNumCU, n_units)), dim3(kThreads), 0,
+                      st, tab, sh, params, reinterpret_cast<bf16_t*>(z), tiles_per_image, per_img, (int)n_units);
+  } else if (patch_ok) {
     // 128 positions per workgroup, three workgroups per CU, weights two taps ahead: measured against
     // 256 / two / four (30.7 vs 32.1 us at 64 images of 56 x 56 x 64)
     constexpr int kTile = 128;
@@ -1722,14 +2012,12 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
     hipLaunchKernelGGL(head_image_kernel<false>, dim3((unsigned)sh.total_images), dim3(kHeadThreads), 0, st, tab, sh,
                        params, (const float*)poolp, pooled, dlogits, dpooled, row_loss);
   SYNK_LAUNCH_CHECK();
-  hipLaunchKernelGGL(head_worker_kernel,
-                     dim3((unsigned)((sh.classes + kThreads - 1) / kThreads), (unsigned)sh.n_workers,
-                          (unsigned)((sh.cout + kWorkerChans - 1) / kWorkerChans)),
-                     dim3(kThreads), 0, st, tab, sh, (const float*)pooled, (const float*)dlogits,
-                     (const float*)row_loss, loss);
-  SYNK_LAUNCH_CHECK();
-  hipLaunchKernelGGL(bn_bwd_chunk_kernel<T>, gc, dim3(kThreads), 0, st, tab, sh, params, (const T*)z,
-                     (const float*)mu, (const float*)rstd, (const float*)dpooled, bwdp);
+  const int class_blocks = (sh.classes + kThreads - 1) / kThreads;
+  const int head_blocks = class_blocks * sh.n_workers * ((sh.cout + kWorkerChans - 1) / kWorkerChans);
+  hipLaunchKernelGGL(bn_bwd_chunk_kernel<T>, dim3(gc.x + (unsigned)head_blocks), dim3(kThreads), 0, st, tab, sh, params,
+                     (const T*)z, (const float*)mu, (const float*)rstd, (const float*)dpooled, bwdp,
+                     (const float*)pooled, (const float*)dlogits, (const float*)row_loss, loss, head_blocks,
+                     class_blocks);
   SYNK_LAUNCH_CHECK();
   hipLaunchKernelGGL(bn_bwd_worker_kernel, dim3((unsigned)((sh.n_workers * sh.cout + 3) / 4)), dim3(kThreads), 0, st,
                      tab, sh,
