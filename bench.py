@@ -619,7 +619,8 @@ class ConvStep:
                          "accumulate" % (H, W, cin, cout, classes, self.B, self.N, self.S))
         # dominant kernel: the forward convolution, a [pixels x 9 C_in] . [9 C_in x C_out] contraction (its
         # weight gradient has as many flops and takes about as long)
-        self.dom_name = "conv3x3_fwd_patch_kernel"
+        held = self.bf16 and cin == 64 and cout <= 64 and W + 2 <= 63      # the shapes that kernel takes
+        self.dom_name = "conv3x3_fwd_hold_kernel" if held else "conv3x3_fwd_patch_kernel"
         self.dom_bound, self.dom_unit = "mfma", "TFLOP/s"
         self.dom_peak = 2500.0 if self.bf16 else 157.3
         self.dom_work = 2.0 * self.B * H * W * 9 * cin * cout       # flops per launch
