@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 # HBM bytes per launch of each config's dominant kernel, from rocprofv3 --pmc FETCH_SIZE and
 # --pmc WRITE_SIZE runs of this file (10 steps), scaled by what the same counters read for the
 # plain copy of --config 0 (fetch x2.000, write x1.000).  Summaries: profiles/*_kernel_stats.txt.
-MEASURED_TRAFFIC_BYTES = {2: 210.37e6, 3: 1226.75e6, 4: 192.83e6, 5: 264.56e6, 6: 51.90e6}
+MEASURED_TRAFFIC_BYTES = {2: 210.37e6, 3: 1226.75e6, 4: 192.83e6, 5: 264.56e6, 6: 59.08e6}
 
 
 def parse():
