@@ -86,6 +86,8 @@ def check(cfg, idx, n_workers, n_slices, op, bf16, got_g, got_l, eps=1e-5):
     ((2, 62, 64, 64, 4), 3, 1, 1, "mean"),      # one pixel wider: the general kernels
     ((4, 33, 64, 40, 5), 300, 3, 2, "mean"),    # more images than CUs: a forward workgroup walks several images
     ((30, 40, 64, 24, 5), 3, 2, 1, "sum"),      # ten tiles an image in runs over the CUs, 24 output channels
+    ((1, 1, 64, 8, 3), 5, 2, 1, "mean"),        # one-pixel images of 64 channels: every block is mostly border
+    ((70, 3, 64, 64, 4), 4, 2, 2, "mean"),      # tall narrow images: a padded row is 5 positions
     ((3, 3, 8, 512, 4096), 3, 2, 1, "mean"),    # the largest channel and class counts the call takes
     ((4, 4, 8, 256, 10), 7, 2, 2, "sum"),       # wide block: head workgroups of four images across workers / slices
 ])
