@@ -67,6 +67,29 @@ def test_gather_identity_and_permutation(synk):
     assert np.array_equal(out[0].cpu().numpy(), data[perm])
 
 
+def test_bf16_rounding_over_the_whole_finite_range(synk):
+    """The kernels round with the part's conversion instruction: nearest-even for every finite float32,
+    denormals and the overflow to infinity included (random bit patterns of every exponent, and the
+    edge values), against the oracle's bit arithmetic."""
+    rng = np.random.default_rng(950)
+    bits = rng.integers(0, 1 << 32, 64 * 4096, dtype=np.uint64).astype(np.uint32)
+    bits = bits[(bits & 0x7F800000) != 0x7F800000]                     # finite only
+    edge = np.array([0x00000000, 0x80000000, 0x00000001, 0x80000001, 0x00008000, 0x00018000, 0x00007FFF,
+                     0x007FFFFF, 0x00800000, 0x3F808000, 0x3F818000, 0xBF808000, 0xBF818000, 0x3F807FFF,
+                     0x3F808001, 0x7F7FFFFF, 0xFF7FFFFF, 0x7F7F7FFF, 0x7F7F8000, 0x7F800000, 0xFF800000],
+                    dtype=np.uint32)
+    bits = np.concatenate([edge, bits])
+    n = len(bits) // 64 * 64
+    data = bits[:n].view(np.float32).reshape(-1, 64)
+    idx = np.arange(data.shape[0], dtype=np.int32)
+    dst = [torch.zeros(data.shape, dtype=torch.bfloat16, device="cuda")]
+    synk.synk_gather_rows(dev(data), dev(idx), dst)
+    got = dst[0].view(torch.int16).cpu().numpy().view(np.uint16)
+    with np.errstate(over="ignore"):
+        want = (ogather.round_to_bf16(data).view(np.uint32) >> 16).astype(np.uint16)
+    assert np.array_equal(got, want), np.flatnonzero(got.ravel() != want.ravel())[:8]
+
+
 @pytest.mark.parametrize("row,n_workers", [(3072, 8), (10, 3)])
 def test_gather_to_bf16_bit_exact(synk, row, n_workers):
     rng = np.random.default_rng(row)
