@@ -78,6 +78,14 @@ def test_bf16_rounding_matches_torch_cast():
     ref = torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
     got = gather.round_to_bf16(a)
     assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    # every exponent, denormals and the overflow to infinity: random finite bit patterns and the edges
+    bits = rng.integers(0, 1 << 32, 200000, dtype=np.uint64).astype(np.uint32)
+    bits = bits[(bits & 0x7F800000) != 0x7F800000]
+    bits = np.concatenate([bits, np.array([0x00000001, 0x00008000, 0x00018000, 0x007FFFFF, 0x7F7FFFFF, 0xFF7FFFFF,
+                                           0x7F7F7FFF, 0x7F7F8000, 0x7F800000, 0xFF800000], np.uint32)])
+    b = bits.view(np.float32)
+    ref = torch.from_numpy(b).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(gather.round_to_bf16(b).view(np.uint32), ref.view(np.uint32))
 
 
 # ------------------------------------------------------------------- mlp
