@@ -1777,24 +1777,40 @@ __global__ __launch_bounds__(kRingThreads, 1) void conv3x3_dw_ring_kernel(Worker
   }
 }
 
-__global__ __launch_bounds__(kThreads) void conv_dw_fold_kernel(WorkerTable tab, const float* __restrict__ dwp,
+// A wavefront owns 64 consecutive 16-byte vectors of the gradient; the four wavefronts of a
+// workgroup take a quarter of the runs each (up to eight loads in flight per thread; a run past
+// the quarter's last re-reads it and is dropped), added in run order, and the quarters are added
+// in order through LDS.  With one thread adding all runs of its vector the launch was four
+// dependent rounds of loads in 288 workgroups.
+constexpr int kFoldParts = 4;
+__global__ __launch_bounds__(64 * kFoldParts) void conv_dw_fold_kernel(WorkerTable tab, const float* __restrict__ dwp,
                                                                 int n_runs, int64_t len) {
-  const int w = blockIdx.y;
-  const int64_t i = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
-  if (i >= len) return;
-  const float* p = dwp + (int64_t)w * n_runs * len + i;
-  // eight loads at a time (a run past the last re-reads the last one and is dropped), added in
-  // run order
+  __shared__ __attribute__((aligned(16))) f32x4 part[kFoldParts][64];
+  const int w = blockIdx.y, lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int64_t i = ((int64_t)blockIdx.x * 64 + lane) * 4;
+  const bool live = i < len;
+  const int per = (n_runs + kFoldParts - 1) / kFoldParts;
+  const int r_begin = min(q * per, n_runs), r_end = min(r_begin + per, n_runs);
   f32x4 a = {0.f, 0.f, 0.f, 0.f};
-  for (int r0 = 0; r0 < n_runs; r0 += 8) {
-    f32x4 v[8];
+  if (live && r_begin < r_end) {
+    const float* p = dwp + (int64_t)w * n_runs * len + i;
+    for (int r0 = r_begin; r0 < r_end; r0 += 8) {
+      f32x4 v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4*>(p + (int64_t)min(r0 + u, n_runs - 1) * len);
+      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4*>(p + (int64_t)min(r0 + u, r_end - 1) * len);
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (r0 + u < n_runs) a += v[u];
+      for (int u = 0; u < 8; ++u)
+        if (r0 + u < r_end) a += v[u];
+    }
   }
-  *reinterpret_cast<f32x4*>(tab.grad[w] + i) = a;
+  part[q][lane] = a;
+  __syncthreads();
+  if (q == 0 && live) {
+    f32x4 t = part[0][lane];
+#pragma unroll
+    for (int j = 1; j < kFoldParts; ++j) t += part[j][lane];
+    *reinterpret_cast<f32x4*>(tab.grad[w] + i) = t;
+  }
 }
 
 // ------------------------------------------------------------------- host
@@ -2046,8 +2062,8 @@ int run(const Plan& p, const float* params, float* loss, char* ws, hipStream_t s
                        p.run_rows);
   }
   SYNK_LAUNCH_CHECK();
-  hipLaunchKernelGGL(conv_dw_fold_kernel, dim3((unsigned)((wn / 4 + kThreads - 1) / kThreads), (unsigned)sh.n_workers),
-                     dim3(kThreads), 0, st, tab, (const float*)dwp, fold_runs, wn);
+  hipLaunchKernelGGL(conv_dw_fold_kernel, dim3((unsigned)((wn / 4 + 63) / 64), (unsigned)sh.n_workers),
+                     dim3(64 * kFoldParts), 0, st, tab, (const float*)dwp, fold_runs, wn);
   SYNK_LAUNCH_CHECK();
   return SYNK_OK;
 }
