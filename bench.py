@@ -63,7 +63,10 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="capture the steps (one per rotating input set) into one HIP graph and time its replays; "
                          "the dominant kernel is then timed in a short eager pass before the timed region")
-    ap.add_argument("--probe", default=None, choices=["mfma", "fill", "fetch", "read"],
+    ap.add_argument("--beside", default="valu:0",
+                    help="--probe beside only: kind:count of the other instructions after each MFMA, valu:0|1|2|4|6|8|12 "
+                         "or lds:1|2|4")
+    ap.add_argument("--probe", default=None, choices=["mfma", "fill", "fetch", "read", "beside"],
                     help="config 0 only: instead of the copy, one of the library's peak probes (register-resident bf16 "
                          "MFMA loop; plain 16-byte stores over 1 GiB; operand tiles from L2 straight into LDS)")
     ap.add_argument("--repeats", type=int, default=5,
@@ -680,9 +683,17 @@ class ConvStep:
 class ProbeStep:
     """Config 0 with --probe: a measured peak of the part (timing kernel of the library, nothing of the method)."""
 
-    def __init__(self, torch, synk, which):
+    def __init__(self, torch, synk, which, beside="valu:0"):
         self.s, self.which = synk, which
-        if which == "mfma":
+        if which == "beside":
+            kind, n = beside.split(":")
+            pid = (synk.SYNK_PROBE_MFMA_BESIDE_VALU if kind == "valu" else synk.SYNK_PROBE_MFMA_BESIDE_LDS) + int(n)
+            self.buf, self.iters = torch.zeros(64, device="cuda"), 20000
+            self.unit, self.dom_bound, self.dom_unit, self.dom_peak = "flop/s", "mfma", "TFLOP/s", 2500.0
+            self.workload = ("probe: 256 workgroups x 4 wavefronts (one per SIMD) x 40000 bf16 32x32x16 MFMAs, %s %s "
+                             "after each" % (n, "vector-ALU additions" if kind == "valu" else "4-byte LDS reads"))
+            self.mfmas_per_wave = 2 * self.iters
+        elif which == "mfma":
             self.buf, self.iters, pid = torch.zeros(64, device="cuda"), 20000, synk.SYNK_PROBE_MFMA_BF16
             self.unit, self.dom_bound, self.dom_unit, self.dom_peak = "flop/s", "mfma", "TFLOP/s", 2500.0
             self.workload = "probe: 512 workgroups x 8 wavefronts x 20000 x 4 bf16 32x32x16 MFMAs on registers"
@@ -704,7 +715,7 @@ class ProbeStep:
         self.pid = pid
         self.units = synk.synk_probe_launch(pid, self.buf, self.iters)      # work of one launch
         self.dom_work, self.dom_bytes = self.units, self.units
-        self.dtype = "bf16" if which == "mfma" else "u8"
+        self.dtype = "bf16" if which in ("mfma", "beside") else "u8"
         self.dom_name = "probe_%s_kernel" % which
 
     def step(self, i, timer):
@@ -756,7 +767,7 @@ def main():
     if a.graph:
         # capture needs a stream of its own; the calls below are prepared on it
         torch.cuda.set_stream(torch.cuda.Stream())
-    wl = {0: lambda: (ProbeStep(torch, synk, a.probe) if a.probe else CopyStep(torch, synk)), 1: lambda: MlpStep(torch, synk, 1, a.batch, separate_gather=a.separate_gather), 2: lambda: MlpStep(torch, synk, 2, a.batch, a.rows_per_worker, a.separate_gather),
+    wl = {0: lambda: (ProbeStep(torch, synk, a.probe, a.beside) if a.probe else CopyStep(torch, synk)), 1: lambda: MlpStep(torch, synk, 1, a.batch, separate_gather=a.separate_gather), 2: lambda: MlpStep(torch, synk, 2, a.batch, a.rows_per_worker, a.separate_gather),
           3: lambda: (CollectiveStep(torch, synk, a.collective) if a.collective else ReduceStep(torch, synk, a.rule)), 4: lambda: GatherStep(torch, synk, a.indexing),
           5: lambda: EvalStep(torch, synk), 6: lambda: ConvStep(torch, synk, a.conv_shape, a.separate_gather)}[a.config]()
     steps = a.steps if a.steps is not None else {0: 50, 1: 5000, 2: 4500, 3: 2800, 4: 5000, 5: 5000, 6: 3200}[a.config]   # >= 0.5 s a repeat
@@ -844,6 +855,10 @@ def main():
                      "bytes_per_launch": wl.dom_bytes, "ms_per_launch": dom_ms,
                      "events_on_every_nth_step": timer.every, "launches_timed": timer.used},
     }
+    if hasattr(wl, "mfmas_per_wave"):
+        # the beside probe: a wavefront's MFMAs run one after the other, so the launch over their number is
+        # the time per MFMA with the other instructions beside it
+        out["roofline"]["ns_per_mfma_per_wavefront"] = dom_ms * 1e6 / wl.mfmas_per_wave
     if hasattr(wl, "kernel_report"):
         # every kernel of the step, timed on its own dispatches inside the timed region (one target a step,
         # rotating); the products against the matrix cores' peak for their input type, the streaming kernels

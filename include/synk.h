@@ -146,12 +146,23 @@ int synk_profile_pending(void);
  *                         issued before the first use); buf: read only unless the
  *                         XOR of a workgroup's words is 0x9e3779b9 (fill it with
  *                         one repeated value); iters ignored
+ *   SYNK_PROBE_MFMA_BESIDE_VALU + n (n = 0, 1, 2, 4, 6, 8, 12) and
+ *   SYNK_PROBE_MFMA_BESIDE_LDS + n (n = 1, 2, 4)
+ *                         256 workgroups of 4 wavefronts (one per SIMD), each doing
+ *                         2 * iters bf16 32x32x16 MFMAs (two independent sums) with n
+ *                         vector-ALU additions, or n 4-byte LDS reads, after every
+ *                         MFMA: launch time / (2 * iters) is the time per MFMA with
+ *                         that much other work of the same wavefront beside it;
+ *                         buf_bytes >= 4, never written in practice; other n ->
+ *                         ERR_UNSUPPORTED
  * buf: device, 16-byte aligned.  Errors: NULL -> ERR_NULL; iters < 1, alignment ->
  * ERR_SHAPE; buffer too small -> ERR_WORKSPACE; unknown probe -> ERR_UNSUPPORTED. */
 #define SYNK_PROBE_MFMA_BF16 0
 #define SYNK_PROBE_FILL 1
 #define SYNK_PROBE_LDS_FETCH 2
 #define SYNK_PROBE_READ 3
+#define SYNK_PROBE_MFMA_BESIDE_VALU 16
+#define SYNK_PROBE_MFMA_BESIDE_LDS 32
 int synk_probe_launch(int probe, void* buf, size_t buf_bytes, int iters, double* work, void* stream);
 
 /* Host-side helper: the split rule above.  Writes parts+1 offsets

@@ -26,7 +26,7 @@ __all__ = [
     "synk_broadcast", "synk_all_reduce", "synk_all_gather",
     "synk_gather_slice", "synk_scatter_rows", "synk_gather_resident", "synk_profile_next_launch",
     "synk_profile_next_launch_of", "synk_profile_pending", "synk_probe_launch",
-    "SYNK_PROBE_MFMA_BF16", "SYNK_PROBE_FILL", "SYNK_PROBE_LDS_FETCH", "SYNK_PROBE_READ", "SYNK_KERNEL_MAIN", "SYNK_KERNEL_MLP_HEAD", "SYNK_KERNEL_MLP_BACKWARD_GROUP",
+    "SYNK_PROBE_MFMA_BF16", "SYNK_PROBE_FILL", "SYNK_PROBE_LDS_FETCH", "SYNK_PROBE_READ", "SYNK_PROBE_MFMA_BESIDE_VALU", "SYNK_PROBE_MFMA_BESIDE_LDS", "SYNK_KERNEL_MAIN", "SYNK_KERNEL_MLP_HEAD", "SYNK_KERNEL_MLP_BACKWARD_GROUP",
     "SYNK_KERNEL_MLP_FORWARD", "SYNK_KERNEL_MLP_DW", "SYNK_KERNEL_MLP_DX",
     "synk_convblock_param_count", "synk_sliced_grad_conv_workspace_bytes", "synk_sliced_grad_conv",
 ]
@@ -525,6 +525,7 @@ def synk_profile_next_launch(start, stop):
 
 
 SYNK_PROBE_MFMA_BF16, SYNK_PROBE_FILL, SYNK_PROBE_LDS_FETCH, SYNK_PROBE_READ = 0, 1, 2, 3
+SYNK_PROBE_MFMA_BESIDE_VALU, SYNK_PROBE_MFMA_BESIDE_LDS = 16, 32      # + the number of other instructions
 
 
 def synk_probe_launch(probe, buf, iters, stream=None):

@@ -1,6 +1,7 @@
 // Measured peaks of the part, for the rooflines the benchmark reports: what the
 // matrix cores deliver from registers alone, what plain 16-byte stores and loads
-// reach, and how fast a CU takes operand tiles from L2 straight into LDS.  Timing
+// reach, how fast a CU takes operand tiles from L2 straight into LDS, and what one
+// wavefront hides behind its own MFMAs.  Timing
 // kernels only: they compute nothing of the method.  Every access stays inside
 // the caller's buffer (checked on the host).
 #include "common.h"
@@ -76,6 +77,58 @@ __global__ __launch_bounds__(512) void probe_fetch_kernel(const char* __restrict
   __syncthreads();
 }
 
+// What a lone wavefront hides behind its own MFMAs: 256 workgroups of 4 wavefronts (one per SIMD),
+// each looping over two independent 32x32x16 bf16 MFMAs with NV vector-ALU additions or NL 4-byte LDS
+// reads after each of them.  The time of a launch over 2 * iters is the time per MFMA.
+template <int NV, int NL>
+__global__ __launch_bounds__(256) void probe_beside_kernel(float* __restrict__ sink, int iters) {
+  __shared__ uint32_t lds[4096];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < 4096; i += 256) lds[i] = (uint32_t)i;
+  __syncthreads();
+  // two sums that differ (operands and start), so that neither can stand in for the other
+  bf16x8p a, b, a1, b1;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (__bf16)(0.001f * (float)(tid + i));
+    b[i] = (__bf16)(0.002f * (float)(tid - i));
+    a1[i] = (__bf16)(0.003f * (float)(tid + 2 * i));
+    b1[i] = (__bf16)(0.001f * (float)(3 * i - tid));
+  }
+  f32x16 c0 = {0}, c1 = {0};
+  c1[0] = 1.0f;
+  uint32_t x[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = (uint32_t)(tid + i);
+  const uint32_t one = 1u;
+  auto others = [&]() {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x[i & 7]) : "v"(one));
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      uint32_t r;
+      asm volatile("ds_read_b32 %0, %1" : "=v"(r) : "v"((uint32_t)(tid * 4 + i * 1024)) : "memory");
+      asm volatile("" ::"v"(r));
+    }
+  };
+  for (int it = 0; it < iters; ++it) {
+    c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+    others();
+    __builtin_amdgcn_sched_barrier(0);
+    c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, c1, 0, 0, 0);
+    others();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += c0[i] + c1[i];
+  uint32_t xs = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) xs ^= x[i];
+  if (s == 12345.678f) sink[0] = s + (float)xs;   // keeps the loop alive; never true in practice
+}
+
 }  // namespace synk
 
 using namespace synk;
@@ -107,6 +160,26 @@ extern "C" int synk_probe_launch(int probe, void* buf, size_t buf_bytes, int ite
     SYNK_LAUNCH_TIMED(probe_read_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
                       reinterpret_cast<const u32x4*>(buf), reinterpret_cast<uint32_t*>(buf));
     *work = (double)blocks * 32768.0;                                      // bytes loaded
+  } else if (probe >= SYNK_PROBE_MFMA_BESIDE_VALU && probe < SYNK_PROBE_MFMA_BESIDE_LDS + 16) {
+    if (buf_bytes < 4) return SYNK_ERR_WORKSPACE;
+    float* sink = reinterpret_cast<float*>(buf);
+    const dim3 grid(kNumCU), block(256);
+#define SYNK_BESIDE(NV, NL) SYNK_LAUNCH_TIMED((probe_beside_kernel<NV, NL>), grid, block, 0, s, sink, iters)
+    switch (probe) {
+      case SYNK_PROBE_MFMA_BESIDE_VALU + 0: SYNK_BESIDE(0, 0); break;
+      case SYNK_PROBE_MFMA_BESIDE_VALU + 1: SYNK_BESIDE(1, 0); break;
+      case SYNK_PROBE_MFMA_BESIDE_VALU + 2: SYNK_BESIDE(2, 0); break;
+      case SYNK_PROBE_MFMA_BESIDE_VALU + 4: SYNK_BESIDE(4, 0); break;
+      case SYNK_PROBE_MFMA_BESIDE_VALU + 6: SYNK_BESIDE(6, 0); break;
+      case SYNK_PROBE_MFMA_BESIDE_VALU + 8: SYNK_BESIDE(8, 0); break;
+      case SYNK_PROBE_MFMA_BESIDE_VALU + 12: SYNK_BESIDE(12, 0); break;
+      case SYNK_PROBE_MFMA_BESIDE_LDS + 1: SYNK_BESIDE(0, 1); break;
+      case SYNK_PROBE_MFMA_BESIDE_LDS + 2: SYNK_BESIDE(0, 2); break;
+      case SYNK_PROBE_MFMA_BESIDE_LDS + 4: SYNK_BESIDE(0, 4); break;
+      default: return SYNK_ERR_UNSUPPORTED;
+    }
+#undef SYNK_BESIDE
+    *work = (double)kNumCU * 4.0 * (double)iters * 2.0 * 32768.0;         // flops
   } else {
     return SYNK_ERR_UNSUPPORTED;
   }

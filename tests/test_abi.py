@@ -381,3 +381,6 @@ def test_probe_launch_argument_checks():
     assert f(2, FAKE, 1 << 20, 49, ctypes.byref(work), None) == -6              # more steps than the window holds
     assert f(3, FAKE, 32767, 1, ctypes.byref(work), None) == -2                 # less than one 32 KB workgroup to read
     assert f(7, FAKE, 1 << 20, 1, ctypes.byref(work), None) == -9
+    assert f(synk.SYNK_PROBE_MFMA_BESIDE_VALU + 3, FAKE, 64, 1, ctypes.byref(work), None) == -9     # a count it has no kernel for
+    assert f(synk.SYNK_PROBE_MFMA_BESIDE_LDS + 0, FAKE, 64, 1, ctypes.byref(work), None) == -9
+    assert f(synk.SYNK_PROBE_MFMA_BESIDE_VALU + 4, FAKE, 2, 1, ctypes.byref(work), None) == -6

@@ -67,6 +67,18 @@ def test_gather_identity_and_permutation(synk):
     assert np.array_equal(out[0].cpu().numpy(), data[perm])
 
 
+def test_probe_of_mfmas_beside_other_instructions_runs(synk):
+    """The timing probe (nothing of the method): every variant launches, reports its flops and leaves
+    its buffer alone."""
+    buf = torch.zeros(64, device="cuda")
+    for pid in ([synk.SYNK_PROBE_MFMA_BESIDE_VALU + n for n in (0, 1, 2, 4, 6, 8, 12)] +
+                [synk.SYNK_PROBE_MFMA_BESIDE_LDS + n for n in (1, 2, 4)]):
+        work = synk.synk_probe_launch(pid, buf, 50)
+        assert work == 256 * 4 * 50 * 2 * 32768.0
+    torch.cuda.synchronize()
+    assert float(buf.abs().sum()) == 0.0
+
+
 def test_bf16_rounding_over_the_whole_finite_range(synk):
     """The kernels round with the part's conversion instruction: nearest-even for every finite float32,
     denormals and the overflow to infinity included (random bit patterns of every exponent, and the
