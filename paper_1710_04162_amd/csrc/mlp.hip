@@ -979,16 +979,17 @@ __global__ __launch_bounds__(kGemmThreads, 4) void mlp_dw_persistent_kernel(Gemm
 constexpr int kSmallRows = 8, kSmallCols = 64, kSmallWaves = 16, kSmallBatch = 56;
 constexpr int kSmallMaxK = 2048;   // the x tile (8 rows) stays within 64 KB of LDS
 
+template <int ROWS>
 __global__ __launch_bounds__(64 * kSmallWaves) void mlp_fwd_small_kernel(GemmArgs g, int row_tiles, int col_tiles) {
   extern __shared__ __attribute__((aligned(16))) float small_lds[];
   const int K = (int)g.k_fixed;
   const int Kp = (K + 3) & ~3;                                 // x tile row pitch in LDS: [k][8 rows] is used instead
   float* xs = small_lds;                                       // [Kp][8]
-  float* part = small_lds + (size_t)Kp * kSmallRows;           // [16][8][64]
+  float* part = small_lds + (size_t)Kp * ROWS;           // [16][8][64]
   const int w = blockIdx.y;
   const int rt = blockIdx.x / col_tiles, ct = blockIdx.x % col_tiles;
   const int64_t rows_w = g.row_off[w + 1] - g.row_off[w];
-  const int64_t r0 = (int64_t)rt * kSmallRows;
+  const int64_t r0 = (int64_t)rt * ROWS;
   if (r0 >= rows_w) return;                                    // uniform for the workgroup
   const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
   const int64_t N = g.n;
@@ -998,9 +999,9 @@ __global__ __launch_bounds__(64 * kSmallWaves) void mlp_fwd_small_kernel(GemmArg
   const float* W = reinterpret_cast<const float*>(g.b) + (col_ok ? n : 0);
   // input indexing folded in: the 8 rows come from the resident data through the index
   const bool gather = g.gather_src != nullptr;
-  const float* xrow[kSmallRows];
+  const float* xrow[ROWS];
 #pragma unroll
-  for (int r = 0; r < kSmallRows; ++r) {
+  for (int r = 0; r < ROWS; ++r) {
     const int64_t rr = r0 + r < rows_w ? r0 + r : r0;          // a row past the end repeats row r0
     if (gather) {
       int64_t src = g.gather_idx[g.row_off[w] + rr];
@@ -1019,24 +1020,24 @@ __global__ __launch_bounds__(64 * kSmallWaves) void mlp_fwd_small_kernel(GemmArg
 #pragma unroll
   for (int u = 0; u < kSmallBatch; ++u) wv[u] = W[(int64_t)(kb + u < ke ? kb + u : (kb < K ? kb : 0)) * g.ldb];
   for (int k = threadIdx.x; k < K; k += 64 * kSmallWaves) {
-    float xv[kSmallRows];
+    float xv[ROWS];
 #pragma unroll
-    for (int r = 0; r < kSmallRows; ++r) xv[r] = xrow[r][k];
-    *reinterpret_cast<f32x4*>(xs + k * kSmallRows) = f32x4{xv[0], xv[1], xv[2], xv[3]};
-    *reinterpret_cast<f32x4*>(xs + k * kSmallRows + 4) = f32x4{xv[4], xv[5], xv[6], xv[7]};
+    for (int r = 0; r < ROWS; ++r) xv[r] = xrow[r][k];
+    *reinterpret_cast<f32x4*>(xs + k * ROWS) = f32x4{xv[0], xv[1], xv[2], xv[3]};
+    if (ROWS == 8) *reinterpret_cast<f32x4*>(xs + k * ROWS + 4) = f32x4{xv[ROWS - 4], xv[ROWS - 3], xv[ROWS - 2], xv[ROWS - 1]};
     // the rows are left in a[w] for the weight gradient: of a row tile's workgroups, column tile ct
     // copies the 64-wide column blocks ct, ct + col_tiles, ...
     if (gather && (k >> 6) % col_tiles == ct) {
       float* Xo = const_cast<float*>(X);
 #pragma unroll
-      for (int r = 0; r < kSmallRows; ++r)
+      for (int r = 0; r < ROWS; ++r)
         if (r0 + r < rows_w) Xo[(r0 + r) * g.lda + k] = xv[r];
     }
   }
   __syncthreads();
-  float acc[kSmallRows];
+  float acc[ROWS];
 #pragma unroll
-  for (int r = 0; r < kSmallRows; ++r) acc[r] = 0.0f;
+  for (int r = 0; r < ROWS; ++r) acc[r] = 0.0f;
   for (int k0 = kb; k0 < ke; k0 += kSmallBatch) {
     if (k0 > kb) {
 #pragma unroll
@@ -1045,23 +1046,25 @@ __global__ __launch_bounds__(64 * kSmallWaves) void mlp_fwd_small_kernel(GemmArg
 #pragma unroll
     for (int u = 0; u < kSmallBatch; ++u) {
       if (k0 + u < ke) {
-        const f32x4 lo = *reinterpret_cast<const f32x4*>(xs + (k0 + u) * kSmallRows);
-        const f32x4 hi = *reinterpret_cast<const f32x4*>(xs + (k0 + u) * kSmallRows + 4);
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(xs + (k0 + u) * ROWS);
         acc[0] = fmaf(lo.x, wv[u], acc[0]); acc[1] = fmaf(lo.y, wv[u], acc[1]);
         acc[2] = fmaf(lo.z, wv[u], acc[2]); acc[3] = fmaf(lo.w, wv[u], acc[3]);
-        acc[4] = fmaf(hi.x, wv[u], acc[4]); acc[5] = fmaf(hi.y, wv[u], acc[5]);
-        acc[6] = fmaf(hi.z, wv[u], acc[6]); acc[7] = fmaf(hi.w, wv[u], acc[7]);
+        if (ROWS == 8) {
+          const f32x4 hi = *reinterpret_cast<const f32x4*>(xs + (k0 + u) * ROWS + 4);
+          acc[ROWS - 4] = fmaf(hi.x, wv[u], acc[ROWS - 4]); acc[ROWS - 3] = fmaf(hi.y, wv[u], acc[ROWS - 3]);
+          acc[ROWS - 2] = fmaf(hi.z, wv[u], acc[ROWS - 2]); acc[ROWS - 1] = fmaf(hi.w, wv[u], acc[ROWS - 1]);
+        }
       }
     }
   }
 #pragma unroll
-  for (int r = 0; r < kSmallRows; ++r) part[(q * kSmallRows + r) * kSmallCols + lane] = acc[r];
+  for (int r = 0; r < ROWS; ++r) part[(q * ROWS + r) * kSmallCols + lane] = acc[r];
   __syncthreads();
   // wavefront r (< 8) finishes row r: the 16 partial sums in wavefront order
-  if (q < kSmallRows && col_ok && r0 + q < rows_w) {
+  if (q < ROWS && col_ok && r0 + q < rows_w) {
     float pv[kSmallWaves];
 #pragma unroll
-    for (int qq = 0; qq < kSmallWaves; ++qq) pv[qq] = part[(qq * kSmallRows + q) * kSmallCols + lane];
+    for (int qq = 0; qq < kSmallWaves; ++qq) pv[qq] = part[(qq * ROWS + q) * kSmallCols + lane];
     float v = pv[0];
 #pragma unroll
     for (int qq = 1; qq < kSmallWaves; ++qq) v += pv[qq];
@@ -1071,8 +1074,8 @@ __global__ __launch_bounds__(64 * kSmallWaves) void mlp_fwd_small_kernel(GemmArg
   }
 }
 
-static inline size_t fwd_small_lds_bytes(int64_t K) {
-  return ((size_t)((K + 3) & ~(int64_t)3) * kSmallRows + (size_t)kSmallWaves * kSmallRows * kSmallCols) * 4;
+static inline size_t fwd_small_lds_bytes(int64_t K, int rows) {
+  return ((size_t)((K + 3) & ~(int64_t)3) * rows + (size_t)kSmallWaves * rows * kSmallCols) * 4;
 }
 
 // ------------------------------------------------------- narrow last layer dW
@@ -1842,10 +1845,17 @@ static int run_sliced_grad(const MlpPlan& p, const float* params, const void* pa
       }
     }
     if (small) {
-      const int row_tiles = (int)((p.max_rows + kSmallRows - 1) / kSmallRows);
+      // 8 rows a workgroup, or 4 when that leaves most CUs without one (a row's sum is the same either way)
       const int col_tiles = (int)((N + kSmallCols - 1) / kSmallCols);
-      SYNK_LAUNCH_TIMED_AS(fwd_id, mlp_fwd_small_kernel, dim3((unsigned)(row_tiles * col_tiles), n_workers),
-                           dim3(64 * kSmallWaves), fwd_small_lds_bytes(K), s, g, row_tiles, col_tiles);
+      const bool four = ((p.max_rows + 7) / 8) * col_tiles * n_workers < kNumCU;
+      const int rows_wg = four ? 4 : kSmallRows;
+      const int row_tiles = (int)((p.max_rows + rows_wg - 1) / rows_wg);
+      if (four)
+        SYNK_LAUNCH_TIMED_AS(fwd_id, mlp_fwd_small_kernel<4>, dim3((unsigned)(row_tiles * col_tiles), n_workers),
+                             dim3(64 * kSmallWaves), fwd_small_lds_bytes(K, 4), s, g, row_tiles, col_tiles);
+      else
+        SYNK_LAUNCH_TIMED_AS(fwd_id, mlp_fwd_small_kernel<8>, dim3((unsigned)(row_tiles * col_tiles), n_workers),
+                             dim3(64 * kSmallWaves), fwd_small_lds_bytes(K, 8), s, g, row_tiles, col_tiles);
       SYNK_LAUNCH_CHECK();
       g.gather_src = nullptr;
       continue;
